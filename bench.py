@@ -1,0 +1,170 @@
+#!/usr/bin/env python3
+"""Benchmark of the Fira optimizer step on one MI355X.
+
+A "step" is one fira_step call over ALL weight matrices of the workload (default: the LLaMA-1B
+shape set, 168 matrices, r = 512, bf16 W/G with fp32 state): projection, Adam on the low-rank
+gradient, factor norms, residual norm, limiter, back-projection and weight update.  Inputs are
+synthetic and resident in HBM before the timed region; three gradient sets rotate so that no step
+finds its gradient in the last-level cache.
+
+Prints ONE JSON line: whole-job optimizer steps/s, plus
+  "roofline":     achieved vs peak for the kernel that takes the most time (HIP events recorded by
+                  the library around every kernel of every timed step), and "kernels" with the same
+                  figures for all of them;
+  "cpu_baseline": the CPU oracle timed on this machine's host cores on a bounded sample.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0        # MI355X HBM3E, GB/s
+PEAK_MFMA_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, TFLOP/s
+
+
+def kernel_models(shapes, r):
+    """Algorithmic flops and HBM bytes of each kernel for one step over `shapes` (bf16 W/G, fp32
+    state).  mn: elements of W; Lr: elements of the low-rank arrays; Sr: elements of P."""
+    mn = sum(m * n for m, n in shapes)
+    Lr = sum(max(m, n) * r for m, n in shapes)
+    Sr = sum(min(m, n) * r for m, n in shapes)
+    L = sum(max(m, n) for m, n in shapes)
+    gemm = 2.0 * mn * r
+    return {
+        # R = P^T G: read G and P once, write R (fp32)
+        "project": dict(flops=gemm, bytes=2 * mn + 2 * Sr + 4 * Lr),
+        # read R, M, V (fp32); write M, V (fp32), N and R as bf16 operands, the factors
+        "adam_norms": dict(flops=0.0, bytes=(4 + 8 + 8 + 2 + 2) * Lr + 4 * L),
+        # ||k (G - P R)||: read G, R (bf16), P
+        "residual_norm": dict(flops=gemm, bytes=2 * mn + 2 * Lr + 2 * Sr),
+        "limiter": dict(flops=0.0, bytes=0.0),
+        # Z = N - c k R: read N, R (bf16), write Z
+        "make_z": dict(flops=0.0, bytes=6 * Lr + 4 * L),
+        # W -= lr alpha (P Z + c k G): read G, W, Z, P; write W
+        "update": dict(flops=gemm, bytes=6 * mn + 2 * Lr + 2 * Sr),
+    }
+
+
+def cpu_baseline(wl, sample_mats, steps=1):
+    """The oracle as it stands, on the host cores, on `sample_mats` of the workload."""
+    import numpy as np
+    from oracle import fira_oracle as orc
+    from paper_2410_01623_amd import synth
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    hp = orc.OracleHparams()
+    data = []
+    for i in sample_mats:
+        m, n = wl.shapes[i]
+        W = synth.gen_W(wl, i).astype(np.float64)
+        G = synth.gen_G(wl, i, 0).astype(np.float64)
+        P = synth.store_projector(synth.random_orthonormal_projector(wl, i, min(m, n), wl.rank), wl.dtype)
+        data.append((W, G, P.astype(np.float64), orc.OracleState.zeros(m, n, wl.rank)))
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        for (W, G, P, st) in data:
+            orc.fira_step(W, G, P, st, hp, store_bf16=(wl.dtype == "bf16"))
+    dt = (time.perf_counter() - t0) / steps
+    frac = sum(m * n for m, n in (wl.shapes[i] for i in sample_mats)) / sum(m * n for m, n in wl.shapes)
+    return dict(value=frac / dt, unit="steps/s", cores=int(cores), kind="oracle",
+                sample=f"{len(sample_mats)} of {wl.n_matrices} matrices (one block), {steps} step(s), "
+                       f"{dt:.2f} s measured, scaled by the sample's share of the elements ({frac:.4f})")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default=None)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (no collectives); use --gpus 1")
+
+    import torch
+    from paper_2410_01623_amd import fira, synth
+
+    name = args.workload or synth.HEADLINE
+    wl = synth.WORKLOADS[name]
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    dt_t = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
+    dt_f = fira.FIRA_BF16 if wl.dtype == "bf16" else fira.FIRA_F32
+    shapes = wl.shapes
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(1000 * wl.config_id)
+    ctx = fira.FiraContext(shapes, wl.rank, dt_f, fira.make_hparams(), device=dev)
+    # projectors: one seeded orthonormal basis per distinct short side, installed into every matrix
+    cache = {}
+    for i, (m, n) in enumerate(shapes):
+        key = (min(m, n), m <= n)
+        if key not in cache:
+            P = synth.store_projector(synth.random_orthonormal_projector(wl, len(cache), min(m, n), wl.rank), wl.dtype)
+            cache[key] = torch.from_numpy(P).to(dt_t).to(dev)
+        ctx.fira_set_projector(i, cache[key])
+    W = [(0.02 * torch.randn(s, device=dev, generator=gen)).to(dt_t) for s in shapes]
+    n_sets = 3
+    Gsets = [[(wl.grad_scale * torch.randn(s, device=dev, generator=gen)).to(dt_t) for s in shapes]
+             for _ in range(n_sets)]
+    idx = list(range(len(shapes)))
+    prepared = [ctx.prepare(idx, W, G) for G in Gsets]
+    torch.cuda.synchronize()
+
+    for s in range(args.warmup):
+        ctx.fira_step(prepared=prepared[s % n_sets])
+    torch.cuda.synchronize()
+    ctx.fira_profile_begin(args.steps)
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        ctx.fira_step(prepared=prepared[s % n_sets])
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_sum, rec = ctx.fira_profile_end()
+    finite = all(bool(torch.isfinite(w).all()) for w in W[:7])
+
+    model = kernel_models(shapes, wl.rank)
+    kernels = {}
+    for k, tot in ms_sum.items():
+        avg_ms = tot / max(rec, 1)
+        mdl = model[k]
+        t_mfma = mdl["flops"] / (PEAK_MFMA_BF16_TFLOPS * 1e12)
+        t_hbm = mdl["bytes"] / (PEAK_HBM_GBS * 1e9)
+        bound = "mfma" if t_mfma > t_hbm else "hbm"
+        if bound == "mfma":
+            ach, peak, unit = mdl["flops"] / (avg_ms * 1e-3) / 1e12 if avg_ms > 0 else 0.0, PEAK_MFMA_BF16_TFLOPS, "TFLOP/s"
+        else:
+            ach, peak, unit = mdl["bytes"] / (avg_ms * 1e-3) / 1e9 if avg_ms > 0 else 0.0, PEAK_HBM_GBS, "GB/s"
+        kernels[k] = dict(avg_ms=round(avg_ms, 4), bound=bound, achieved=round(ach, 2), peak=peak, unit=unit,
+                          frac=round(ach / peak, 4), gflop=round(mdl["flops"] / 1e9, 1),
+                          gbyte=round(mdl["bytes"] / 1e9, 3))
+    dom = max((k for k in kernels if k != "limiter"), key=lambda k: kernels[k]["avg_ms"])
+    roof = dict(kernel=dom, bound=kernels[dom]["bound"], achieved=kernels[dom]["achieved"], peak=kernels[dom]["peak"],
+                unit=kernels[dom]["unit"], frac=kernels[dom]["frac"], traffic=None,
+                avg_ms=kernels[dom]["avg_ms"])
+
+    out = {
+        "metric": "fira_optimizer_steps_per_s", "value": round(args.steps / dt, 3), "unit": "steps/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(1e3 * dt / args.steps, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": name, "matrices": len(shapes), "rank": wl.rank,
+                   "params": sum(m * n for m, n in shapes), "state_bytes": ctx.state_bytes,
+                   "gradient_sets": n_sets, "finite": finite},
+        "roofline": roof, "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        nb = len(wl.block_shapes)
+        out["cpu_baseline"] = cpu_baseline(wl, list(range(nb)), steps=1)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,165 @@
+/*
+ * fira.h - C ABI of the MI355X (gfx950) Fira optimizer-step library.
+ *
+ * Fira ("Can We Achieve Full-rank Training of LLMs under Low-rank Constraint?", arXiv 2410.01623)
+ * updates every weight matrix W (m x n) from its gradient G with Algorithm 1 ("Fira with Adam",
+ * Appendix A.1).  With a projector P supplied by the caller the loop body is
+ *
+ *     R  = P^T G                         (Sec. 3.3; R = G Q when m > n, footnote of Sec. 3.3)
+ *     M  = b1 M + (1-b1) R,  V = b2 V + (1-b2) R^2,
+ *     N  = sqrt(1-b2^t)/(1-b1^t) * M / (sqrt(V) + eps)                      (Eqs. 2-4 on R)
+ *     k_i = ||N[:,i]|| / (||R[:,i]|| + eps)                     (Eq. 11, norm-based scaling)
+ *     S  = (G - P R) diag(k)                                                  (Sec. 4.1)
+ *     S  = S * gamma / max(||S|| / (||S_prev|| + eps), gamma)   (Eq. 12, norm-growth limiter)
+ *     W  = W - lr * alpha * (P N + S)                            (Algorithm 1, last two lines)
+ *
+ * When m > n the same algorithm runs on the transposed problem: one factor k_i per *row* of G,
+ * reductions over the rank axis.  m == n is the m <= n case.
+ *
+ * Conventions
+ *   - All `dev_*` pointers are DEVICE (HBM) pointers on the current HIP device; `host_*` pointers
+ *     are host pointers.  The library never takes ownership of caller memory.
+ *   - W and G are row-major m x n with leading dimension ld >= n (elements), dtype wg_dtype.
+ *   - P is row-major min(m,n) x r (P when m <= n, Q when m > n), contiguous.
+ *   - The caller allocates ONE device slab of fira_state_bytes() bytes per context; it holds the
+ *     optimizer state (M, V, the library's operand copies of P, ||S_prev||, t) and the step's
+ *     scratch.  It must stay alive and untouched until fira_destroy().
+ *   - Every call enqueues on the HIP stream given to fira_init_state and, unless stated, returns
+ *     without synchronising.  fira_step performs no device allocation.
+ *   - Every function returns a fira_status (0 = OK, negative = error); errors detectable on the
+ *     host are reported before anything is enqueued and leave the state untouched.
+ *     fira_last_error() gives a message for the last failure (ctx may be NULL for failures of
+ *     fira_init_state).  Non-finite inputs are not checked; they propagate.
+ *   - Not thread-safe per context; two contexts are independent.
+ */
+#ifndef FIRA_H_
+#define FIRA_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define FIRA_API __attribute__((visibility("default")))
+
+typedef struct fira_ctx fira_ctx;
+
+typedef enum {
+  FIRA_OK = 0,
+  FIRA_ERR_INVALID_ARG = -1,  /* null pointer, bad index, duplicate index, bad enum            */
+  FIRA_ERR_SHAPE = -2,        /* m, n, ld, r out of range (need 1 <= r <= min(m,n), ld >= n)   */
+  FIRA_ERR_NO_PROJECTOR = -3, /* fira_step on a matrix whose projector was never set            */
+  FIRA_ERR_DTYPE = -4,        /* unsupported dtype combination                                  */
+  FIRA_ERR_WORKSPACE = -5,    /* dev_state_bytes too small or slab misaligned (256 B)           */
+  FIRA_ERR_HIP = -6           /* a HIP runtime call or kernel launch failed                     */
+} fira_status;
+
+typedef enum { FIRA_F32 = 0, FIRA_BF16 = 1 } fira_dtype;
+
+/* Input line of Algorithm 1: eta, beta1, beta2, (Adam's) epsilon, GaLore scale alpha, limiter
+ * threshold gamma.  gamma = +inf disables the limiter (the "w.o.-limiter" variant, Sec. 5.3). */
+typedef struct {
+  double lr, beta1, beta2, eps, alpha, gamma;
+} fira_hparams;
+
+/* One weight matrix.  wg_dtype is the storage type of W and G (fira_dtype). */
+typedef struct {
+  int64_t m, n, ld;
+  int32_t r;
+  int32_t wg_dtype;
+} fira_matrix_desc;
+
+/* Scaling-factor granularity: FIRA_SCALE_COLUMN is the paper's Fira (Eq. 11); FIRA_SCALE_NONE sets
+ * every factor to 1 (the "GaLore-add" update of Eq. 8 / "Fira-w.o.-scaling" of Sec. 5.3). */
+typedef enum { FIRA_SCALE_COLUMN = 0, FIRA_SCALE_NONE = 2 } fira_scaling;
+
+/* How ||S_t|| (Eq. 12) is obtained.  FIRA_NORM_RESIDUAL forms G - P R tile by tile with an extra
+ * rank-r contraction (exact for any P).  FIRA_NORM_GRAM uses
+ * ||G_i - P R_i||^2 = ||G_i||^2 - 2||R_i||^2 + R_i^T (P^T P) R_i, which holds for any P because
+ * G_i^T P = R_i^T, and saves one contraction and one pass over G; it loses accuracy by
+ * cancellation when the residual is tiny compared with G (r close to min(m,n)). */
+typedef enum { FIRA_NORM_RESIDUAL = 0, FIRA_NORM_GRAM = 1 } fira_norm_mode;
+
+/* Number of optimizer-state values the METHOD keeps for one matrix: m r + 2 n r + 1 for m <= n
+ * (Table "Comparison of different methods"); the transposed count for m > n. */
+FIRA_API int64_t fira_method_state_numel(const fira_matrix_desc* d);
+
+/* Bytes of the device slab for `count` matrices: M and V in fp32, the library's bf16 operand
+ * copies of P, the per-matrix scalars, and the step's scratch (low-rank intermediates, factors,
+ * partial sums, work tables).  Returns 0 on invalid descriptors. */
+FIRA_API size_t fira_state_bytes(const fira_matrix_desc* d, int count);
+
+/* Create a context over `count` matrices.  Zeroes M and V, sets t = 0 and "no previous norm"
+ * (Algorithm 1, initialisation line).  dev_state: device slab, 256-byte aligned, at least
+ * fira_state_bytes(d, count) bytes.  hip_stream: a hipStream_t (NULL = default stream).
+ * Host-side resources of the context are released by fira_destroy. */
+FIRA_API fira_status fira_init_state(fira_ctx** out, const fira_matrix_desc* d, int count,
+                            const fira_hparams* hp, void* dev_state, size_t dev_state_bytes,
+                            void* hip_stream);
+
+/* Install the projector of matrix idx (Eq. 7; built by the caller, e.g. every T steps).
+ * dev_P: min(m,n) x r row-major, dtype p_dtype; it is copied/converted into the slab, so the
+ * caller may free it after the stream has run the call.  For bf16 matrices an fp32 P is rounded
+ * to bf16 (nearest even).  M, V, t and ||S_prev|| are kept (Sec. 4.2, loss-spike analysis). */
+FIRA_API fira_status fira_set_projector(fira_ctx* ctx, int idx, const void* dev_P, fira_dtype p_dtype);
+
+/* One optimizer step (Algorithm 1's loop body below the SVD branch) for `count` distinct
+ * matrices idx[0..count), in one grouped launch sequence.  dev_W[i] is updated in place, dev_G[i]
+ * is read only; both are m x n with the descriptor's ld and dtype.  t advances by one for each
+ * listed matrix.  idx, dev_W, dev_G are host arrays of length count. */
+FIRA_API fira_status fira_step(fira_ctx* ctx, int count, const int* idx, void* const* dev_W,
+                      const void* const* dev_G);
+
+/* Replace the hyper-parameters (e.g. the learning rate under a schedule); takes effect at the
+ * next fira_step. */
+FIRA_API fira_status fira_set_hparams(fira_ctx* ctx, const fira_hparams* hp);
+
+/* Variant switches (Sec. 5.3 ablations) and the way ||S_t|| is computed; both default to 0. */
+FIRA_API fira_status fira_set_options(fira_ctx* ctx, fira_scaling scaling, fira_norm_mode norm_mode);
+
+/* Copy the state of matrix idx to host memory.  Synchronises the stream.
+ * host_M, host_V: fp32, in the paper's orientation (r x n row-major for m <= n, m x r for m > n);
+ * either may be NULL.  *s_prev = ||S_{t-1}|| or -1 when no step has run yet.  *t = steps taken. */
+FIRA_API fira_status fira_get_state(fira_ctx* ctx, int idx, float* host_M, float* host_V, double* s_prev,
+                           int64_t* t);
+
+/* Inverse of fira_get_state (checkpoint restore).  s_prev < 0 means "no previous norm".
+ * Synchronises the stream. */
+FIRA_API fira_status fira_set_state(fira_ctx* ctx, int idx, const float* host_M, const float* host_V,
+                           double s_prev, int64_t t);
+
+/* Limiter diagnostics of the last step of matrix idx: ||S|| before and after limiting and the
+ * factor applied (the "gradient norm" curve of Fig. 3).  Synchronises the stream. */
+FIRA_API fira_status fira_get_diag(fira_ctx* ctx, int idx, double* s_norm_pre, double* s_norm_post,
+                          double* c);
+
+/* Copy the scaling factors k_i of the last step of matrix idx (n values for m <= n, m values for
+ * m > n) to host memory.  Synchronises the stream. */
+FIRA_API fira_status fira_get_factors(fira_ctx* ctx, int idx, float* host_k);
+
+/* Copy the low-rank gradient R_t of the last step of matrix idx to host memory, fp32, in the
+ * paper's orientation (r x n row-major for m <= n, m x r for m > n).  Synchronises the stream. */
+FIRA_API fira_status fira_get_lowrank(fira_ctx* ctx, int idx, float* host_R);
+
+/* Per-kernel timing of the step's launch sequence with HIP events on the context's stream.
+ * fira_profile_begin creates the events for up to max_steps steps (the only allocation; it happens
+ * here, not in fira_step); every following fira_step records one event before its first kernel
+ * and one after each kernel.  fira_profile_end synchronises, adds up the elapsed time of each of
+ * the FIRA_NUM_KERNELS kernels over the recorded steps into ms_sum[0..FIRA_NUM_KERNELS) (host
+ * array, milliseconds), stores the number of recorded steps in *steps, and destroys the events.
+ * Kernel order: fira_kernel_name(k). */
+#define FIRA_NUM_KERNELS 6
+FIRA_API fira_status fira_profile_begin(fira_ctx* ctx, int max_steps);
+FIRA_API fira_status fira_profile_end(fira_ctx* ctx, double* ms_sum, int* steps);
+FIRA_API const char* fira_kernel_name(int k);
+
+FIRA_API const char* fira_last_error(const fira_ctx* ctx);
+
+FIRA_API void fira_destroy(fira_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FIRA_H_ */

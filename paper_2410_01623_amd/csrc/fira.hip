@@ -1,0 +1,563 @@
+// Host side of the Fira optimizer-step library: the C ABI of include/fira.h, the slab planner and
+// the grouped launch sequence.  gfx950 only; no allocation on the step path.
+#include "../../include/fira.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "fira_device.h"
+#include "fira_elementwise.h"
+#include "fira_gemm.h"
+
+namespace {
+
+constexpr size_t kAlign = 256;
+constexpr int kSlots = 4;  // cached work lists (a training loop alternates between very few)
+
+inline size_t align_up(size_t x, size_t a = kAlign) { return (x + a - 1) / a * a; }
+inline int round_up_int(long long x, int a) { return (int)((x + a - 1) / a * a); }
+
+thread_local std::string g_last_error;
+
+struct HostMat {
+  fira_matrix_desc d;
+  FiraMat dev;          // copy of the device description (pointers are device pointers)
+  bool has_projector = false;
+  int tiles_project = 0;      // tiles of the R contraction
+  int tiles_back = 0;         // tiles of the back-projection (and of the residual-norm pass)
+  int ta_project = 0, tb_project = 0, ta_back = 0, tb_back = 0;
+  int rowblocks = 0;
+};
+
+struct ListSlot {
+  std::vector<int> idx;
+  std::vector<void*> W;
+  std::vector<const void*> G;
+  int ntiles_project = 0, ntiles_back = 0, rowblocks = 0;
+  // device views (inside the slab)
+  FiraEnt* d_ents = nullptr;
+  FiraTile* d_tiles_project = nullptr;
+  FiraTile* d_tiles_back = nullptr;
+  // pinned host staging, one contiguous block mirrored to the device block
+  char* h_stage = nullptr;
+  char* d_block = nullptr;
+  size_t block_bytes = 0;
+  hipEvent_t uploaded = nullptr;
+  uint64_t last_use = 0;
+  bool valid = false;
+};
+
+struct Plan {
+  size_t total = 0;
+  size_t off_mats = 0, off_scal = 0, off_partial = 0;
+  size_t off_slots = 0, slot_bytes = 0, slot_off_tiles_project = 0, slot_off_tiles_back = 0;
+  std::vector<HostMat> mats;
+  int max_tiles_project = 0, max_tiles_back = 0;
+};
+
+bool valid_desc(const fira_matrix_desc& d, std::string* why) {
+  if (d.m < 1 || d.n < 1 || d.m > (1 << 24) || d.n > (1 << 24)) { *why = "m, n must be in [1, 2^24]"; return false; }
+  if (d.ld < d.n) { *why = "ld must be >= n"; return false; }
+  if (d.r < 1 || d.r > std::min(d.m, d.n)) { *why = "need 1 <= r <= min(m, n)"; return false; }
+  return true;
+}
+
+// Lays the slab out.  Pointers in Plan::mats[i].dev are offsets from a null base until rebased.
+bool make_plan(const fira_matrix_desc* d, int count, Plan* plan, fira_status* st, std::string* why) {
+  if (!d || count < 1 || count > (1 << 20)) { *st = FIRA_ERR_INVALID_ARG; *why = "descriptor array is null or count out of range"; return false; }
+  plan->mats.resize(count);
+  size_t off = 0;
+  plan->off_mats = off; off = align_up(off + sizeof(FiraMat) * count);
+  plan->off_scal = off; off = align_up(off + sizeof(FiraScal) * count);
+  long long total_tiles_project = 0, total_tiles_back = 0;
+  for (int i = 0; i < count; ++i) {
+    HostMat& h = plan->mats[i];
+    h.d = d[i];
+    if (d[i].wg_dtype != FIRA_F32 && d[i].wg_dtype != FIRA_BF16) { *st = FIRA_ERR_DTYPE; *why = "wg_dtype must be FIRA_F32 or FIRA_BF16"; return false; }
+    if (!valid_desc(d[i], why)) { *st = FIRA_ERR_SHAPE; return false; }
+    FiraMat& m = h.dev;
+    std::memset(&m, 0, sizeof(m));
+    m.m = (int)d[i].m; m.n = (int)d[i].n; m.r = d[i].r; m.left = d[i].m <= d[i].n;
+    m.ld = d[i].ld;
+    m.L = (int)std::max(d[i].m, d[i].n); m.S = (int)std::min(d[i].m, d[i].n);
+    m.rp = round_up_int(m.r, 64); m.Sp = round_up_int(m.S, 64);
+    m.dtype = d[i].wg_dtype;
+    m.kx = (m.dtype == FIRA_F32) ? FIRA_KX_SPLIT : 1;
+    m.gx_ld = round_up_int(m.n, 8);
+    const size_t Lr = (size_t)m.L * m.r;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+    m.M = (float*)take(Lr * 4);
+    m.V = (float*)take(Lr * 4);
+    m.Rt = (float*)take(Lr * 4);
+    m.phi = (float*)take((size_t)m.L * 4);
+    m.g2 = (float*)take((size_t)m.L * 4);
+    m.q = (float*)take((size_t)m.L * 4);
+    m.Nb = (bf16_raw*)take((size_t)m.L * m.kx * m.rp * 2);
+    m.Rb = (bf16_raw*)take((size_t)m.L * m.kx * m.rp * 2);
+    m.Pn = (bf16_raw*)take((size_t)m.S * m.kx * m.rp * 2);
+    m.PT = (bf16_raw*)take((size_t)m.r * m.kx * m.Sp * 2);
+    if (m.kx > 1) {
+      const size_t gx = m.left ? (size_t)m.kx * m.Sp * m.gx_ld : (size_t)m.m * m.kx * m.Sp;
+      m.Gx = (bf16_raw*)take(gx * 2);
+    }
+    m.Dm = (bf16_raw*)take((size_t)m.r * m.rp * 2);
+    h.ta_project = (m.L + FIRA_TA - 1) / FIRA_TA; h.tb_project = (m.r + FIRA_TB - 1) / FIRA_TB;
+    h.ta_back = (m.n + FIRA_TA - 1) / FIRA_TA;    h.tb_back = (m.m + FIRA_TB - 1) / FIRA_TB;
+    h.tiles_project = h.ta_project * h.tb_project;
+    h.tiles_back = h.ta_back * h.tb_back;
+    h.rowblocks = (m.L + FIRA_ROWS_PER_WG - 1) / FIRA_ROWS_PER_WG;
+    total_tiles_project += h.tiles_project;
+    total_tiles_back += h.tiles_back;
+  }
+  if (total_tiles_project > (1 << 28) || total_tiles_back > (1 << 28)) { *st = FIRA_ERR_SHAPE; *why = "too many tiles"; return false; }
+  plan->max_tiles_project = (int)total_tiles_project;
+  plan->max_tiles_back = (int)total_tiles_back;
+  plan->off_partial = off; off = align_up(off + (size_t)total_tiles_back * 4);
+  size_t s = 0;
+  s = align_up(s + sizeof(FiraEnt) * count);
+  plan->slot_off_tiles_project = s; s = align_up(s + sizeof(FiraTile) * (size_t)total_tiles_project);
+  plan->slot_off_tiles_back = s;    s = align_up(s + sizeof(FiraTile) * (size_t)total_tiles_back);
+  plan->slot_bytes = s;
+  plan->off_slots = off; off += s * kSlots;
+  plan->total = off;
+  return true;
+}
+
+}  // namespace
+
+struct fira_ctx {
+  Plan plan;
+  char* slab = nullptr;
+  hipStream_t stream = nullptr;
+  fira_hparams hp{};
+  int scaling = FIRA_SCALE_COLUMN;
+  int norm_mode = FIRA_NORM_RESIDUAL;
+  FiraMat* d_mats = nullptr;
+  FiraScal* d_scal = nullptr;
+  float* d_partial = nullptr;
+  ListSlot slots[kSlots];
+  char* h_stage_all = nullptr;
+  uint64_t use_counter = 0;
+  std::string last_error;
+  // optional per-kernel timing (fira_profile_begin / fira_profile_end)
+  std::vector<hipEvent_t> prof_events;   // (FIRA_NUM_KERNELS + 1) per recorded step
+  int prof_max_steps = 0, prof_steps = 0;
+};
+
+namespace {
+
+fira_status fail(fira_ctx* ctx, fira_status st, const std::string& msg) {
+  g_last_error = msg;
+  if (ctx) ctx->last_error = msg;
+  return st;
+}
+#define FIRA_HIP(ctx, call)                                                                     \
+  do {                                                                                          \
+    hipError_t e_ = (call);                                                                     \
+    if (e_ != hipSuccess)                                                                       \
+      return fail(ctx, FIRA_ERR_HIP, std::string(#call) + ": " + hipGetErrorString(e_));        \
+  } while (0)
+
+FiraHp make_hp(const fira_ctx* ctx) {
+  FiraHp h;
+  h.beta1 = ctx->hp.beta1; h.beta2 = ctx->hp.beta2; h.eps = ctx->hp.eps; h.gamma = ctx->hp.gamma;
+  h.b1 = (float)ctx->hp.beta1; h.b2 = (float)ctx->hp.beta2;
+  h.omb1 = (float)(1.0 - ctx->hp.beta1); h.omb2 = (float)(1.0 - ctx->hp.beta2);
+  h.epsf = (float)ctx->hp.eps;
+  h.lr_alpha = (float)(ctx->hp.lr * ctx->hp.alpha);
+  h.scaling = ctx->scaling;
+  return h;
+}
+
+bool valid_hp(const fira_hparams* hp) {
+  return hp && std::isfinite(hp->lr) && hp->beta1 >= 0 && hp->beta1 < 1 && hp->beta2 >= 0 && hp->beta2 < 1 &&
+         hp->eps >= 0 && std::isfinite(hp->eps) && std::isfinite(hp->alpha) && hp->gamma > 0;
+}
+
+// Builds the work list of one fira_step call in pinned staging and returns its slot.
+ListSlot* acquire_list(fira_ctx* ctx, int count, const int* idx, void* const* W, const void* const* G,
+                       fira_status* st) {
+  *st = FIRA_OK;
+  ctx->use_counter++;
+  for (ListSlot& s : ctx->slots) {
+    if (s.valid && (int)s.idx.size() == count && std::equal(idx, idx + count, s.idx.begin()) &&
+        std::equal(W, W + count, s.W.begin()) && std::equal(G, G + count, s.G.begin())) {
+      s.last_use = ctx->use_counter;
+      return &s;
+    }
+  }
+  ListSlot* s = &ctx->slots[0];
+  for (ListSlot& c : ctx->slots)
+    if (!c.valid) { s = &c; break; } else if (c.last_use < s->last_use) s = &c;
+  // the previous upload from this slot's staging must have been consumed before it is rewritten
+  if (hipEventSynchronize(s->uploaded) != hipSuccess) { *st = FIRA_ERR_HIP; return nullptr; }
+  s->valid = false;
+  s->idx.assign(idx, idx + count);
+  s->W.assign(W, W + count);
+  s->G.assign(G, G + count);
+  const Plan& p = ctx->plan;
+  FiraEnt* ents = reinterpret_cast<FiraEnt*>(s->h_stage);
+  FiraTile* tp = reinterpret_cast<FiraTile*>(s->h_stage + p.slot_off_tiles_project);
+  FiraTile* tb = reinterpret_cast<FiraTile*>(s->h_stage + p.slot_off_tiles_back);
+  int ntp = 0, ntb = 0, rowblocks = 0;
+  for (int e = 0; e < count; ++e) {
+    const HostMat& h = p.mats[idx[e]];
+    FiraEnt& en = ents[e];
+    en.mat = idx[e]; en.part0 = ntb; en.npart = h.tiles_back; en.row0 = rowblocks;
+    en.W = W[e]; en.G = G[e];
+    rowblocks += h.rowblocks;
+    // R contraction: rank tiles innermost, so the tiles that share a panel of G are neighbours
+    for (int ta = 0; ta < h.ta_project; ++ta)
+      for (int tbb = 0; tbb < h.tb_project; ++tbb) tp[ntp++] = FiraTile{e, ta, tbb, 0};
+    // back-projection: groups of 8 column tiles x all row tiles keep both operand panels in L2
+    for (int ta0 = 0; ta0 < h.ta_back; ta0 += 8)
+      for (int t2 = 0; t2 < h.tb_back; ++t2)
+        for (int ta = ta0; ta < std::min(ta0 + 8, h.ta_back); ++ta) { tb[ntb] = FiraTile{e, ta, t2, ntb}; ++ntb; }
+  }
+  s->ntiles_project = ntp; s->ntiles_back = ntb; s->rowblocks = rowblocks;
+  const size_t bytes = p.slot_off_tiles_back + sizeof(FiraTile) * (size_t)ntb;
+  if (hipMemcpyAsync(s->d_block, s->h_stage, bytes, hipMemcpyHostToDevice, ctx->stream) != hipSuccess ||
+      hipEventRecord(s->uploaded, ctx->stream) != hipSuccess) { *st = FIRA_ERR_HIP; return nullptr; }
+  s->valid = true;
+  s->last_use = ctx->use_counter;
+  return s;
+}
+
+}  // namespace
+
+extern "C" {
+
+int64_t fira_method_state_numel(const fira_matrix_desc* d) {
+  std::string why;
+  if (!d || !valid_desc(*d, &why)) return 0;
+  const int64_t S = std::min(d->m, d->n), L = std::max(d->m, d->n);
+  return S * d->r + 2 * L * d->r + 1;
+}
+
+size_t fira_state_bytes(const fira_matrix_desc* d, int count) {
+  Plan p; fira_status st; std::string why;
+  if (!make_plan(d, count, &p, &st, &why)) { g_last_error = why; return 0; }
+  return p.total;
+}
+
+fira_status fira_init_state(fira_ctx** out, const fira_matrix_desc* d, int count, const fira_hparams* hp,
+                            void* dev_state, size_t dev_state_bytes, void* hip_stream) {
+  if (!out) return fail(nullptr, FIRA_ERR_INVALID_ARG, "out is null");
+  *out = nullptr;
+  if (!valid_hp(hp)) return fail(nullptr, FIRA_ERR_INVALID_ARG, "hyper-parameters are null or out of range");
+  fira_ctx* ctx = new fira_ctx();
+  fira_status st = FIRA_OK; std::string why;
+  if (!make_plan(d, count, &ctx->plan, &st, &why)) { delete ctx; return fail(nullptr, st, why); }
+  if (!dev_state) { delete ctx; return fail(nullptr, FIRA_ERR_INVALID_ARG, "dev_state is null"); }
+  if (((uintptr_t)dev_state % kAlign) != 0 || dev_state_bytes < ctx->plan.total) {
+    delete ctx; return fail(nullptr, FIRA_ERR_WORKSPACE, "dev_state must be 256-byte aligned and hold fira_state_bytes() bytes");
+  }
+  ctx->slab = (char*)dev_state;
+  ctx->stream = (hipStream_t)hip_stream;
+  ctx->hp = *hp;
+  Plan& p = ctx->plan;
+  for (HostMat& h : p.mats) {
+    FiraMat& m = h.dev;
+    // offsets were stored in the pointer fields; Gx is null for bf16 matrices and stays null
+    m.M = (float*)(ctx->slab + (size_t)m.M); m.V = (float*)(ctx->slab + (size_t)m.V);
+    m.Rt = (float*)(ctx->slab + (size_t)m.Rt); m.phi = (float*)(ctx->slab + (size_t)m.phi);
+    m.g2 = (float*)(ctx->slab + (size_t)m.g2); m.q = (float*)(ctx->slab + (size_t)m.q);
+    m.Nb = (bf16_raw*)(ctx->slab + (size_t)m.Nb); m.Rb = (bf16_raw*)(ctx->slab + (size_t)m.Rb);
+    m.Pn = (bf16_raw*)(ctx->slab + (size_t)m.Pn); m.PT = (bf16_raw*)(ctx->slab + (size_t)m.PT);
+    if (m.kx > 1) m.Gx = (bf16_raw*)(ctx->slab + (size_t)m.Gx);
+    m.Dm = (bf16_raw*)(ctx->slab + (size_t)m.Dm);
+  }
+  ctx->d_mats = (FiraMat*)(ctx->slab + p.off_mats);
+  ctx->d_scal = (FiraScal*)(ctx->slab + p.off_scal);
+  ctx->d_partial = (float*)(ctx->slab + p.off_partial);
+
+  auto cleanup = [&]() {
+    for (ListSlot& s : ctx->slots) if (s.uploaded) (void)hipEventDestroy(s.uploaded);
+    if (ctx->h_stage_all) (void)hipHostFree(ctx->h_stage_all);
+    delete ctx;
+  };
+#define FIRA_INIT_HIP(call)                                                                          \
+  do {                                                                                               \
+    hipError_t e_ = (call);                                                                          \
+    if (e_ != hipSuccess) {                                                                          \
+      std::string msg_ = std::string(#call) + ": " + hipGetErrorString(e_);                          \
+      cleanup();                                                                                     \
+      return fail(nullptr, FIRA_ERR_HIP, msg_);                                                      \
+    }                                                                                                \
+  } while (0)
+  FIRA_INIT_HIP(hipHostMalloc((void**)&ctx->h_stage_all, p.slot_bytes * kSlots, hipHostMallocDefault));
+  for (int i = 0; i < kSlots; ++i) {
+    ListSlot& s = ctx->slots[i];
+    s.h_stage = ctx->h_stage_all + p.slot_bytes * i;
+    s.d_block = ctx->slab + p.off_slots + p.slot_bytes * i;
+    s.block_bytes = p.slot_bytes;
+    s.d_ents = (FiraEnt*)s.d_block;
+    s.d_tiles_project = (FiraTile*)(s.d_block + p.slot_off_tiles_project);
+    s.d_tiles_back = (FiraTile*)(s.d_block + p.slot_off_tiles_back);
+    FIRA_INIT_HIP(hipEventCreateWithFlags(&s.uploaded, hipEventDisableTiming));
+    FIRA_INIT_HIP(hipEventRecord(s.uploaded, ctx->stream));
+  }
+  // Zero everything: M = V = 0, t = 0, "no previous norm", and the zero padding of every operand.
+  FIRA_INIT_HIP(hipMemsetAsync(ctx->slab, 0, p.total, ctx->stream));
+  std::vector<FiraMat> mats(count);
+  for (int i = 0; i < count; ++i) mats[i] = p.mats[i].dev;
+  FIRA_INIT_HIP(hipMemcpyAsync(ctx->d_mats, mats.data(), sizeof(FiraMat) * count, hipMemcpyHostToDevice, ctx->stream));
+  FIRA_INIT_HIP(hipStreamSynchronize(ctx->stream));   // `mats` is a local
+#undef FIRA_INIT_HIP
+  *out = ctx;
+  return FIRA_OK;
+}
+
+fira_status fira_set_hparams(fira_ctx* ctx, const fira_hparams* hp) {
+  if (!ctx) return fail(nullptr, FIRA_ERR_INVALID_ARG, "ctx is null");
+  if (!valid_hp(hp)) return fail(ctx, FIRA_ERR_INVALID_ARG, "hyper-parameters are null or out of range");
+  ctx->hp = *hp;
+  return FIRA_OK;
+}
+
+fira_status fira_set_options(fira_ctx* ctx, fira_scaling scaling, fira_norm_mode norm_mode) {
+  if (!ctx) return fail(nullptr, FIRA_ERR_INVALID_ARG, "ctx is null");
+  if (scaling != FIRA_SCALE_COLUMN && scaling != FIRA_SCALE_NONE) return fail(ctx, FIRA_ERR_INVALID_ARG, "unknown scaling mode");
+  if (norm_mode != FIRA_NORM_RESIDUAL) return fail(ctx, FIRA_ERR_INVALID_ARG, "unsupported norm mode");
+  ctx->scaling = scaling;
+  ctx->norm_mode = norm_mode;
+  return FIRA_OK;
+}
+
+fira_status fira_set_projector(fira_ctx* ctx, int idx, const void* dev_P, fira_dtype p_dtype) {
+  if (!ctx) return fail(nullptr, FIRA_ERR_INVALID_ARG, "ctx is null");
+  if (idx < 0 || idx >= (int)ctx->plan.mats.size()) return fail(ctx, FIRA_ERR_INVALID_ARG, "matrix index out of range");
+  if (!dev_P) return fail(ctx, FIRA_ERR_INVALID_ARG, "dev_P is null");
+  if (p_dtype != FIRA_F32 && p_dtype != FIRA_BF16) return fail(ctx, FIRA_ERR_DTYPE, "p_dtype must be FIRA_F32 or FIRA_BF16");
+  HostMat& h = ctx->plan.mats[idx];
+  const long long total = (long long)h.dev.S * h.dev.r;
+  const int grid = (int)std::min<long long>((total + 255) / 256, 65535);
+  if (p_dtype == FIRA_F32)
+    hipLaunchKernelGGL(fira_prep_projector_kernel<float>, dim3(grid), dim3(256), 0, ctx->stream, h.dev, (const float*)dev_P);
+  else
+    hipLaunchKernelGGL(fira_prep_projector_kernel<bf16_raw>, dim3(grid), dim3(256), 0, ctx->stream, h.dev, (const bf16_raw*)dev_P);
+  FIRA_HIP(ctx, hipGetLastError());
+  h.has_projector = true;
+  return FIRA_OK;
+}
+
+fira_status fira_step(fira_ctx* ctx, int count, const int* idx, void* const* dev_W, const void* const* dev_G) {
+  if (!ctx) return fail(nullptr, FIRA_ERR_INVALID_ARG, "ctx is null");
+  const int nmat = (int)ctx->plan.mats.size();
+  if (count == 0) return FIRA_OK;
+  if (count < 0 || count > nmat || !idx || !dev_W || !dev_G) return fail(ctx, FIRA_ERR_INVALID_ARG, "bad count or null array");
+  {
+    std::vector<char> seen(nmat, 0);
+    for (int e = 0; e < count; ++e) {
+      if (idx[e] < 0 || idx[e] >= nmat) return fail(ctx, FIRA_ERR_INVALID_ARG, "matrix index out of range");
+      if (seen[idx[e]]) return fail(ctx, FIRA_ERR_INVALID_ARG, "a matrix is listed twice");
+      seen[idx[e]] = 1;
+      if (!dev_W[e] || !dev_G[e]) return fail(ctx, FIRA_ERR_INVALID_ARG, "null W or G pointer");
+      if (!ctx->plan.mats[idx[e]].has_projector) return fail(ctx, FIRA_ERR_NO_PROJECTOR, "fira_set_projector was never called for a listed matrix");
+    }
+  }
+  fira_status st;
+  ListSlot* s = acquire_list(ctx, count, idx, dev_W, dev_G, &st);
+  if (!s) return fail(ctx, st, "building the work list failed");
+  const FiraHp hp = make_hp(ctx);
+  hipStream_t q = ctx->stream;
+  hipEvent_t* pe = nullptr;
+  if (ctx->prof_steps < ctx->prof_max_steps) pe = &ctx->prof_events[(size_t)ctx->prof_steps++ * (FIRA_NUM_KERNELS + 1)];
+  auto mark = [&](int k) { if (pe) (void)hipEventRecord(pe[k], q); };
+  mark(0);
+
+  // fp32 matrices: split the gradient into bf16 planes first
+  for (int e = 0; e < count; ++e) {
+    const HostMat& h = ctx->plan.mats[idx[e]];
+    if (h.dev.kx > 1) {
+      const long long total = (long long)h.dev.m * h.dev.n;
+      const int grid = (int)std::min<long long>((total + 255) / 256, 65535);
+      hipLaunchKernelGGL(fira_split_gradient_kernel, dim3(grid), dim3(256), 0, q, h.dev, (const float*)dev_G[e]);
+    }
+  }
+  auto grid8 = [](int n) { return dim3((unsigned)(((n + 7) / 8) * 8)); };
+  // 1. R = P^T G (long-side major)
+  hipLaunchKernelGGL(fira_project_kernel, grid8(s->ntiles_project), dim3(256), 0, q, ctx->d_mats, s->d_ents,
+                     s->d_tiles_project, s->ntiles_project);
+  mark(1);
+  // 2. Adam on R, factor norms
+  hipLaunchKernelGGL(fira_adam_kernel, dim3(s->rowblocks), dim3(256), 0, q, ctx->d_mats, ctx->d_scal, s->d_ents, count,
+                     s->rowblocks, hp);
+  mark(2);
+  // 3. ||k (G - P R)||^2 per tile
+  hipLaunchKernelGGL(fira_backproject_kernel<0>, grid8(s->ntiles_back), dim3(256), 0, q, ctx->d_mats, ctx->d_scal,
+                     s->d_ents, s->d_tiles_back, s->ntiles_back, ctx->d_partial, hp.lr_alpha);
+  mark(3);
+  // 4. limiter factor, state advance
+  hipLaunchKernelGGL(fira_limiter_kernel, dim3(count), dim3(64), 0, q, ctx->d_scal, s->d_ents, ctx->d_partial, hp);
+  mark(4);
+  // 5. Z = N - c k R
+  hipLaunchKernelGGL(fira_makez_kernel, dim3(s->rowblocks), dim3(256), 0, q, ctx->d_mats, ctx->d_scal, s->d_ents, count,
+                     s->rowblocks);
+  mark(5);
+  // 6. W -= lr alpha (P Z + c k G)
+  hipLaunchKernelGGL(fira_backproject_kernel<1>, grid8(s->ntiles_back), dim3(256), 0, q, ctx->d_mats, ctx->d_scal,
+                     s->d_ents, s->d_tiles_back, s->ntiles_back, ctx->d_partial, hp.lr_alpha);
+  mark(6);
+  FIRA_HIP(ctx, hipGetLastError());
+  return FIRA_OK;
+}
+
+static void destroy_profile_events(fira_ctx* ctx) {
+  for (hipEvent_t e : ctx->prof_events) (void)hipEventDestroy(e);
+  ctx->prof_events.clear();
+  ctx->prof_max_steps = ctx->prof_steps = 0;
+}
+
+fira_status fira_profile_begin(fira_ctx* ctx, int max_steps) {
+  if (!ctx) return fail(nullptr, FIRA_ERR_INVALID_ARG, "ctx is null");
+  if (max_steps < 1 || max_steps > 100000) return fail(ctx, FIRA_ERR_INVALID_ARG, "max_steps out of range");
+  destroy_profile_events(ctx);
+  ctx->prof_events.resize((size_t)max_steps * (FIRA_NUM_KERNELS + 1));
+  for (hipEvent_t& e : ctx->prof_events) {
+    e = nullptr;
+    hipError_t err = hipEventCreate(&e);
+    if (err != hipSuccess) { destroy_profile_events(ctx); return fail(ctx, FIRA_ERR_HIP, std::string("hipEventCreate: ") + hipGetErrorString(err)); }
+  }
+  ctx->prof_max_steps = max_steps;
+  ctx->prof_steps = 0;
+  return FIRA_OK;
+}
+
+fira_status fira_profile_end(fira_ctx* ctx, double* ms_sum, int* steps) {
+  if (!ctx) return fail(nullptr, FIRA_ERR_INVALID_ARG, "ctx is null");
+  if (!ms_sum || !steps) return fail(ctx, FIRA_ERR_INVALID_ARG, "null output");
+  FIRA_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  for (int k = 0; k < FIRA_NUM_KERNELS; ++k) ms_sum[k] = 0.0;
+  for (int s = 0; s < ctx->prof_steps; ++s) {
+    hipEvent_t* pe = &ctx->prof_events[(size_t)s * (FIRA_NUM_KERNELS + 1)];
+    for (int k = 0; k < FIRA_NUM_KERNELS; ++k) {
+      float ms = 0.0f;
+      FIRA_HIP(ctx, hipEventElapsedTime(&ms, pe[k], pe[k + 1]));
+      ms_sum[k] += ms;
+    }
+  }
+  *steps = ctx->prof_steps;
+  destroy_profile_events(ctx);
+  return FIRA_OK;
+}
+
+const char* fira_kernel_name(int k) {
+  static const char* names[FIRA_NUM_KERNELS] = {"project", "adam_norms", "residual_norm", "limiter", "make_z", "update"};
+  return (k >= 0 && k < FIRA_NUM_KERNELS) ? names[k] : "";
+}
+
+fira_status fira_get_state(fira_ctx* ctx, int idx, float* host_M, float* host_V, double* s_prev, int64_t* t) {
+  if (!ctx) return fail(nullptr, FIRA_ERR_INVALID_ARG, "ctx is null");
+  if (idx < 0 || idx >= (int)ctx->plan.mats.size()) return fail(ctx, FIRA_ERR_INVALID_ARG, "matrix index out of range");
+  const FiraMat& m = ctx->plan.mats[idx].dev;
+  const size_t Lr = (size_t)m.L * m.r;
+  FIRA_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  std::vector<float> tmp;
+  for (int which = 0; which < 2; ++which) {
+    float* dst = which ? host_V : host_M;
+    const float* src = which ? m.V : m.M;
+    if (!dst) continue;
+    if (!m.left) {
+      FIRA_HIP(ctx, hipMemcpy(dst, src, Lr * 4, hipMemcpyDeviceToHost));
+    } else {   // device keeps [n][r]; the paper's orientation is r x n
+      tmp.resize(Lr);
+      FIRA_HIP(ctx, hipMemcpy(tmp.data(), src, Lr * 4, hipMemcpyDeviceToHost));
+      for (int i = 0; i < m.L; ++i)
+        for (int a = 0; a < m.r; ++a) dst[(size_t)a * m.L + i] = tmp[(size_t)i * m.r + a];
+    }
+  }
+  FiraScal sc;
+  FIRA_HIP(ctx, hipMemcpy(&sc, ctx->d_scal + idx, sizeof(sc), hipMemcpyDeviceToHost));
+  if (s_prev) *s_prev = sc.has_prev ? sc.s_prev : -1.0;
+  if (t) *t = sc.t;
+  return FIRA_OK;
+}
+
+fira_status fira_set_state(fira_ctx* ctx, int idx, const float* host_M, const float* host_V, double s_prev, int64_t t) {
+  if (!ctx) return fail(nullptr, FIRA_ERR_INVALID_ARG, "ctx is null");
+  if (idx < 0 || idx >= (int)ctx->plan.mats.size()) return fail(ctx, FIRA_ERR_INVALID_ARG, "matrix index out of range");
+  if (!host_M || !host_V || t < 0 || t > INT32_MAX) return fail(ctx, FIRA_ERR_INVALID_ARG, "null state array or bad step count");
+  const FiraMat& m = ctx->plan.mats[idx].dev;
+  const size_t Lr = (size_t)m.L * m.r;
+  FIRA_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  std::vector<float> tmp(Lr);
+  for (int which = 0; which < 2; ++which) {
+    const float* src = which ? host_V : host_M;
+    float* dst = which ? m.V : m.M;
+    if (!m.left) {
+      FIRA_HIP(ctx, hipMemcpy(dst, src, Lr * 4, hipMemcpyHostToDevice));
+    } else {
+      for (int i = 0; i < m.L; ++i)
+        for (int a = 0; a < m.r; ++a) tmp[(size_t)i * m.r + a] = src[(size_t)a * m.L + i];
+      FIRA_HIP(ctx, hipMemcpy(dst, tmp.data(), Lr * 4, hipMemcpyHostToDevice));
+    }
+  }
+  FiraScal sc;
+  FIRA_HIP(ctx, hipMemcpy(&sc, ctx->d_scal + idx, sizeof(sc), hipMemcpyDeviceToHost));
+  sc.has_prev = s_prev >= 0.0;
+  sc.s_prev = sc.has_prev ? s_prev : 0.0;
+  sc.t = (int)t;
+  FIRA_HIP(ctx, hipMemcpy(ctx->d_scal + idx, &sc, sizeof(sc), hipMemcpyHostToDevice));
+  return FIRA_OK;
+}
+
+fira_status fira_get_diag(fira_ctx* ctx, int idx, double* s_norm_pre, double* s_norm_post, double* c) {
+  if (!ctx) return fail(nullptr, FIRA_ERR_INVALID_ARG, "ctx is null");
+  if (idx < 0 || idx >= (int)ctx->plan.mats.size()) return fail(ctx, FIRA_ERR_INVALID_ARG, "matrix index out of range");
+  FIRA_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  FiraScal sc;
+  FIRA_HIP(ctx, hipMemcpy(&sc, ctx->d_scal + idx, sizeof(sc), hipMemcpyDeviceToHost));
+  if (s_norm_pre) *s_norm_pre = sc.s_pre;
+  if (s_norm_post) *s_norm_post = sc.s_post;
+  if (c) *c = sc.c;
+  return FIRA_OK;
+}
+
+fira_status fira_get_factors(fira_ctx* ctx, int idx, float* host_k) {
+  if (!ctx) return fail(nullptr, FIRA_ERR_INVALID_ARG, "ctx is null");
+  if (idx < 0 || idx >= (int)ctx->plan.mats.size()) return fail(ctx, FIRA_ERR_INVALID_ARG, "matrix index out of range");
+  if (!host_k) return fail(ctx, FIRA_ERR_INVALID_ARG, "host_k is null");
+  const FiraMat& m = ctx->plan.mats[idx].dev;
+  FIRA_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  FIRA_HIP(ctx, hipMemcpy(host_k, m.phi, (size_t)m.L * 4, hipMemcpyDeviceToHost));
+  return FIRA_OK;
+}
+
+fira_status fira_get_lowrank(fira_ctx* ctx, int idx, float* host_R) {
+  if (!ctx) return fail(nullptr, FIRA_ERR_INVALID_ARG, "ctx is null");
+  if (idx < 0 || idx >= (int)ctx->plan.mats.size()) return fail(ctx, FIRA_ERR_INVALID_ARG, "matrix index out of range");
+  if (!host_R) return fail(ctx, FIRA_ERR_INVALID_ARG, "host_R is null");
+  const FiraMat& m = ctx->plan.mats[idx].dev;
+  const size_t Lr = (size_t)m.L * m.r;
+  FIRA_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  if (!m.left) {
+    FIRA_HIP(ctx, hipMemcpy(host_R, m.Rt, Lr * 4, hipMemcpyDeviceToHost));
+  } else {
+    std::vector<float> tmp(Lr);
+    FIRA_HIP(ctx, hipMemcpy(tmp.data(), m.Rt, Lr * 4, hipMemcpyDeviceToHost));
+    for (int i = 0; i < m.L; ++i)
+      for (int a = 0; a < m.r; ++a) host_R[(size_t)a * m.L + i] = tmp[(size_t)i * m.r + a];
+  }
+  return FIRA_OK;
+}
+
+const char* fira_last_error(const fira_ctx* ctx) { return ctx ? ctx->last_error.c_str() : g_last_error.c_str(); }
+
+void fira_destroy(fira_ctx* ctx) {
+  if (!ctx) return;
+  (void)hipStreamSynchronize(ctx->stream);
+  destroy_profile_events(ctx);
+  for (ListSlot& s : ctx->slots)
+    if (s.uploaded) (void)hipEventDestroy(s.uploaded);
+  if (ctx->h_stage_all) (void)hipHostFree(ctx->h_stage_all);
+  delete ctx;
+}
+
+}  // extern "C"

@@ -1,0 +1,116 @@
+// Device-side data layout of the Fira step: per-matrix tables that live in the caller's slab,
+// work-list entries, and small numeric helpers.  gfx950 only.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+typedef unsigned short bf16_raw;  // storage of one bf16 value
+
+// Pointers read out of the device tables are generic; the kernels cast them to the global address
+// space so that loads and stores are global_* instructions (flat_* would also tick the LDS counter).
+#define FIRA_GLOBAL __attribute__((address_space(1)))
+template <typename T>
+using gptr = FIRA_GLOBAL T*;
+template <typename T>
+__device__ __forceinline__ gptr<T> as_global(T* p) { return (gptr<T>)p; }
+// vector types with element alignment only: rows of W and G start at any element (odd n, odd ld)
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef u32x4 __attribute__((aligned(2))) u32x4_a2;
+typedef f32x4 __attribute__((aligned(4))) f32x4_a4;
+
+// K-expansion used for fp32 matrices: an fp32 value x is split as x = h + m + l with h, m, l bf16,
+// and a product a*b is summed over the six (a-part, b-part) pairs below, which keeps ~2^-24
+// relative accuracy on the bf16 MFMA pipe.  "Data" operands (G, R, N, Z) use sequence A,
+// projector operands use sequence B; position p of A meets position p of B in the contraction.
+//   A: h h m h l m        B: h m h l h m
+#define FIRA_KX_SPLIT 6
+
+// Immutable description of one weight matrix (device array, one element per matrix).
+struct FiraMat {
+  int m, n, r, left;   // left = (m <= n): P multiplies from the left, one factor per column
+  long long ld;        // leading dimension of W and G, elements
+  int L, S;            // long side max(m,n) (number of factors), short side min(m,n)
+  int rp, Sp;          // rank and short side rounded up to 64 (zero padded operand rows)
+  int kx, dtype;       // K-expansion (1: bf16, 6: fp32 split); dtype of W and G (0 f32, 1 bf16)
+  long long gx_ld;     // leading dimension of the split copy of G (fp32 matrices only)
+  // low-rank arrays, all "long-side major": row i holds the r values of factor i
+  float* M;            // [L][r]   first moment
+  float* V;            // [L][r]   second moment
+  float* Rt;           // [L][r]   low-rank gradient of this step (scratch)
+  float* phi;          // [L]      scaling factors k_i of this step
+  float* g2;           // [L]      ||G_i||^2 (only written in Gram mode)
+  float* q;            // [L]      ||R_i||^2 - 2 R_i.R_i + R_i^T (P^T P) R_i pieces (Gram mode)
+  bf16_raw* Nb;        // [L][kx*rp] N of this step, then Z = N - c k_i R_i in place (MFMA operand)
+  bf16_raw* Rb;        // [L][kx*rp] R of this step as MFMA operand
+  bf16_raw* Pn;        // [S][kx*rp] projector, rank-contiguous (operand of the back-projection)
+  bf16_raw* PT;        // [r][kx*Sp] projector transposed, short-side-contiguous (operand of R)
+  bf16_raw* Gx;        // fp32 matrices: split copy of G ([kx*Sp][gx_ld] if left, [m][kx*Sp] else)
+  bf16_raw* Dm;        // [r][rp]  P^T P - I in bf16 (Gram mode)
+};
+
+// Mutable per-matrix scalars (device array).
+struct FiraScal {
+  double s_prev;   // ||S_{t-1}|| (after limiting)
+  double s_pre;    // ||S_t|| before limiting, last step
+  double s_post;   // ||S_t|| after limiting, last step
+  float c;         // limiter factor of the current step
+  int has_prev;    // 0 until the first step has recorded a norm
+  int t;           // steps taken
+  int pad;
+};
+
+// One entry of a step's work list.
+struct FiraEnt {
+  int mat;          // index into FiraMat / FiraScal
+  int part0;        // first partial-sum slot of this entry
+  int npart;        // number of partial-sum slots
+  int row0;         // first row-block (elementwise kernels) of this entry
+  void* W;
+  const void* G;
+};
+
+// One GEMM tile of a grouped launch.
+struct FiraTile {
+  int ent;  // work-list entry
+  int ta;   // tile index along the MFMA A side (long side for R; n for the back-projection)
+  int tb;   // tile index along the MFMA B side (rank for R; m for the back-projection)
+  int part; // partial-sum slot (residual-norm kernel)
+};
+
+struct FiraHp {     // hyper-parameters as the kernels take them
+  double beta1, beta2, eps, gamma;
+  float b1, b2, omb1, omb2, epsf;
+  float lr_alpha;   // lr * alpha
+  int scaling;      // 0 column, 2 none
+};
+
+// ---- bf16 helpers ---------------------------------------------------------------------------
+__device__ __forceinline__ bf16_raw f32_to_bf16(float x) {
+  unsigned u = __float_as_uint(x);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_raw)((u >> 16) | 0x40u);  // quiet NaN
+  u += 0x7fffu + ((u >> 16) & 1u);                                            // nearest even
+  return (bf16_raw)(u >> 16);
+}
+__device__ __forceinline__ float bf16_to_f32(bf16_raw b) { return __uint_as_float(((unsigned)b) << 16); }
+__device__ __forceinline__ unsigned pack_bf16x2(float lo, float hi) {
+  return (unsigned)f32_to_bf16(lo) | ((unsigned)f32_to_bf16(hi) << 16);
+}
+__device__ __forceinline__ void split3(float x, bf16_raw& h, bf16_raw& m, bf16_raw& l) {
+  h = f32_to_bf16(x);
+  float r1 = x - bf16_to_f32(h);
+  m = f32_to_bf16(r1);
+  float r2 = r1 - bf16_to_f32(m);
+  l = f32_to_bf16(r2);
+}
+
+// XCD-aware mapping of a linear workgroup id onto a logical work index: consecutive workgroup
+// ids are dispatched round-robin over the 8 XCDs (each with its own L2), so XCD x takes the
+// contiguous chunk [x*per, (x+1)*per) of the logical order; neighbours in that order (which share
+// operand panels) then share an L2.  Returns -1 for padding workgroups.
+__device__ __forceinline__ int xcd_chunked_index(int bid, int total) {
+  int per = (total + 7) >> 3;
+  int idx = (bid & 7) * per + (bid >> 3);
+  return (bid >> 3) < per && idx < total ? idx : -1;
+}

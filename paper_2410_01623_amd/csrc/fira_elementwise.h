@@ -1,0 +1,262 @@
+// Fused element-wise / reduction passes of the Fira step (HBM-bound): Adam on the low-rank gradient
+// with the per-factor norms, the limiter scalar, the construction of the back-projection operand,
+// and the operand conversions done when a projector is installed.
+#pragma once
+#include "fira_device.h"
+
+#define FIRA_ROWS_PER_WG 16  // 4 wavefronts x 4 rows
+
+// Work-list lookup for the row-blocked kernels: entry e covers row-blocks [ents[e].row0, ents[e+1].row0).
+__device__ __forceinline__ int find_entry(const FiraEnt* __restrict__ ents, int count, int rowblock) {
+  int lo = 0, hi = count - 1;
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (ents[mid].row0 <= rowblock) lo = mid; else hi = mid - 1;
+  }
+  return lo;
+}
+
+__device__ __forceinline__ float wave_sum(float x) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) x += __shfl_xor(x, off, 64);
+  return x;
+}
+
+// store one low-rank value as an MFMA operand element (plain bf16, or the 6-plane split, sequence A)
+template <int KX>
+__device__ __forceinline__ void store_operand(gptr<bf16_raw> row, int rp, int a, float x) {
+  if (KX == 1) {
+    row[a] = f32_to_bf16(x);
+  } else {
+    bf16_raw h, m, l;
+    split3(x, h, m, l);
+    row[a] = h; row[rp + a] = h; row[2 * rp + a] = m; row[3 * rp + a] = h; row[4 * rp + a] = l; row[5 * rp + a] = m;
+  }
+}
+template <int KX>
+__device__ __forceinline__ float load_operand(gptr<const bf16_raw> row, int rp, int a) {
+  if (KX == 1) return bf16_to_f32(row[a]);
+  return (bf16_to_f32(row[a]) + bf16_to_f32(row[2 * rp + a])) + bf16_to_f32(row[4 * rp + a]);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Adam on R (Eqs. 2-4 applied to R, Algorithm 1's Adam block) fused with the two norms of every
+// factor (Algorithm 1, "Norm-Based Scaling").  One wavefront per long-side row:
+//   M <- b1 M + (1-b1) R;  V <- b2 V + (1-b2) R^2;  N = bias * M / (sqrt(V) + eps)
+//   k_i = ||N_i|| / (||R_i|| + eps);  N and R are also written as bf16 MFMA operands.
+// ------------------------------------------------------------------------------------------------
+template <int KX, int VEC>
+__device__ __forceinline__ void adam_row(const FiraMat& mt, const FiraHp& hp, float bias, long long row) {
+  const int lane = threadIdx.x & 63;
+  const int r = mt.r;
+  gptr<const float> R = as_global<const float>(mt.Rt) + row * r;
+  gptr<float> M = as_global(mt.M) + row * r;
+  gptr<float> V = as_global(mt.V) + row * r;
+  gptr<bf16_raw> Nb = as_global(mt.Nb) + row * ((long long)mt.kx * mt.rp);
+  gptr<bf16_raw> Rb = as_global(mt.Rb) + row * ((long long)mt.kx * mt.rp);
+  float nn = 0.0f, rr = 0.0f;
+  for (int a = lane * VEC; a < r; a += 64 * VEC) {
+    float rv[VEC], mv[VEC], vv[VEC], nv[VEC];
+    if (VEC == 4) {
+      *reinterpret_cast<f32x4*>(rv) = *reinterpret_cast<gptr<const f32x4>>(R + a);
+      *reinterpret_cast<f32x4*>(mv) = *reinterpret_cast<gptr<const f32x4>>(M + a);
+      *reinterpret_cast<f32x4*>(vv) = *reinterpret_cast<gptr<const f32x4>>(V + a);
+    } else {
+      rv[0] = R[a]; mv[0] = M[a]; vv[0] = V[a];
+    }
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+      mv[e] = hp.b1 * mv[e] + hp.omb1 * rv[e];
+      vv[e] = hp.b2 * vv[e] + hp.omb2 * (rv[e] * rv[e]);
+      nv[e] = bias * (mv[e] / (sqrtf(vv[e]) + hp.epsf));
+      nn += nv[e] * nv[e];
+      rr += rv[e] * rv[e];
+    }
+    if (VEC == 4) {
+      *reinterpret_cast<gptr<f32x4>>(M + a) = *reinterpret_cast<const f32x4*>(mv);
+      *reinterpret_cast<gptr<f32x4>>(V + a) = *reinterpret_cast<const f32x4*>(vv);
+    } else {
+      M[a] = mv[0]; V[a] = vv[0];
+    }
+    if (KX == 1 && VEC == 4) {
+      *reinterpret_cast<gptr<u32x2>>(Nb + a) = u32x2{pack_bf16x2(nv[0], nv[1]), pack_bf16x2(nv[2], nv[3])};
+      *reinterpret_cast<gptr<u32x2>>(Rb + a) = u32x2{pack_bf16x2(rv[0], rv[1]), pack_bf16x2(rv[2], rv[3])};
+    } else {
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) {
+        store_operand<KX>(Nb, mt.rp, a + e, nv[e]);
+        store_operand<KX>(Rb, mt.rp, a + e, rv[e]);
+      }
+    }
+  }
+  nn = wave_sum(nn);
+  rr = wave_sum(rr);
+  if (lane == 0) as_global(mt.phi)[row] = (hp.scaling == 2) ? 1.0f : sqrtf(nn) / (sqrtf(rr) + hp.epsf);
+}
+
+__global__ __launch_bounds__(256) void fira_adam_kernel(const FiraMat* __restrict__ mats,
+                                                        const FiraScal* __restrict__ scal,
+                                                        const FiraEnt* __restrict__ ents, int count,
+                                                        int total_rowblocks, FiraHp hp) {
+  const int rb = blockIdx.x;
+  if (rb >= total_rowblocks) return;
+  const int e = find_entry(ents, count, rb);
+  const FiraEnt ent = ents[e];
+  const FiraMat mt = mats[ent.mat];
+  // bias correction with the 1-based step count (Eq. 4), in double: 1 - beta2^t loses all
+  // accuracy in fp32 at small t.
+  const int t = scal[ent.mat].t + 1;
+  const float bias = (float)(sqrt(1.0 - pow(hp.beta2, (double)t)) / (1.0 - pow(hp.beta1, (double)t)));
+  const int wave = threadIdx.x >> 6;
+  const long long row_base = (long long)(rb - ent.row0) * FIRA_ROWS_PER_WG + wave * 4;
+  for (int i = 0; i < 4; ++i) {
+    const long long row = row_base + i;
+    if (row >= mt.L) break;
+    if (mt.kx == 1) {
+      if ((mt.r & 3) == 0) adam_row<1, 4>(mt, hp, bias, row); else adam_row<1, 1>(mt, hp, bias, row);
+    } else {
+      adam_row<FIRA_KX_SPLIT, 1>(mt, hp, bias, row);
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Norm-growth limiter (Eq. 12 in Algorithm 1's form): one workgroup per listed matrix sums the
+// tile partials of ||S||^2 in a fixed order (fp64), derives the factor c, and advances the state.
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(64) void fira_limiter_kernel(FiraScal* __restrict__ scal,
+                                                          const FiraEnt* __restrict__ ents,
+                                                          const float* __restrict__ partial, FiraHp hp) {
+  const FiraEnt ent = ents[blockIdx.x];
+  const int lane = threadIdx.x;
+  double acc = 0.0;
+  for (int i = lane; i < ent.npart; i += 64) acc += (double)partial[ent.part0 + i];
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off, 64);
+  if (lane == 0) {
+    FiraScal s = scal[ent.mat];
+    const double sn = sqrt(acc);
+    double c = 1.0;
+    if (s.has_prev && !isinf(hp.gamma) && sn != 0.0) {
+      const double den = s.s_prev + hp.eps;
+      const double ratio = den > 0.0 ? sn / den : INFINITY;
+      c = hp.gamma / fmax(ratio, hp.gamma);
+    }
+    s.s_pre = sn;
+    s.s_post = c * sn;
+    s.s_prev = s.s_post;      // the remembered norm is the limited one
+    s.has_prev = 1;
+    s.c = (float)c;
+    s.t += 1;
+    scal[ent.mat] = s;
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Back-projection operand: Z_i = N_i - c k_i R_i, so that P N + c k (G - P R) = P Z + c k G.
+// Overwrites N in place.
+// ------------------------------------------------------------------------------------------------
+template <int KX>
+__device__ __forceinline__ void makez_row(const FiraMat& mt, float f, long long row) {
+  const int lane = threadIdx.x & 63;
+  gptr<bf16_raw> Nb = as_global(mt.Nb) + row * ((long long)mt.kx * mt.rp);
+  gptr<const bf16_raw> Rb = as_global<const bf16_raw>(mt.Rb) + row * ((long long)mt.kx * mt.rp);
+  if (KX == 1) {
+    // rp is a multiple of 64 and padded entries are zero: whole 16-byte groups
+    for (int a = lane * 8; a < mt.rp; a += 512) {
+      const u32x4 nv = *reinterpret_cast<gptr<const u32x4>>(Nb + a);
+      const u32x4 rv = *reinterpret_cast<gptr<const u32x4>>(Rb + a);
+      const unsigned nw[4] = {nv.x, nv.y, nv.z, nv.w}, rw[4] = {rv.x, rv.y, rv.z, rv.w};
+      unsigned zw[4];
+#pragma unroll
+      for (int d = 0; d < 4; ++d) {
+        float z0 = __uint_as_float(nw[d] << 16) - f * __uint_as_float(rw[d] << 16);
+        float z1 = __uint_as_float(nw[d] & 0xffff0000u) - f * __uint_as_float(rw[d] & 0xffff0000u);
+        if (a + 2 * d >= mt.r) z0 = 0.0f;       // padding stays zero even for a non-finite factor
+        if (a + 2 * d + 1 >= mt.r) z1 = 0.0f;
+        zw[d] = pack_bf16x2(z0, z1);
+      }
+      *reinterpret_cast<gptr<u32x4>>(Nb + a) = u32x4{zw[0], zw[1], zw[2], zw[3]};
+    }
+  } else {
+    for (int a = lane; a < mt.r; a += 64) {
+      const float z = load_operand<KX>((gptr<const bf16_raw>)Nb, mt.rp, a) - f * load_operand<KX>(Rb, mt.rp, a);
+      store_operand<KX>(Nb, mt.rp, a, z);
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void fira_makez_kernel(const FiraMat* __restrict__ mats,
+                                                         const FiraScal* __restrict__ scal,
+                                                         const FiraEnt* __restrict__ ents, int count,
+                                                         int total_rowblocks) {
+  const int rb = blockIdx.x;
+  if (rb >= total_rowblocks) return;
+  const int e = find_entry(ents, count, rb);
+  const FiraEnt ent = ents[e];
+  const FiraMat mt = mats[ent.mat];
+  const float c = scal[ent.mat].c;
+  const int wave = threadIdx.x >> 6;
+  const long long row_base = (long long)(rb - ent.row0) * FIRA_ROWS_PER_WG + wave * 4;
+  for (int i = 0; i < 4; ++i) {
+    const long long row = row_base + i;
+    if (row >= mt.L) break;
+    const float f = c * as_global<const float>(mt.phi)[row];
+    if (mt.kx == 1) makez_row<1>(mt, f, row); else makez_row<FIRA_KX_SPLIT>(mt, f, row);
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Operand preparation (outside the per-step hot loop)
+// ------------------------------------------------------------------------------------------------
+
+// Projector P[S][r] (fp32 or bf16) -> Pn[S][kx*rp] and PT[r][kx*Sp]; split planes follow sequence B.
+template <typename TP>
+__global__ void fira_prep_projector_kernel(FiraMat mt, const TP* __restrict__ P) {
+  const long long total = (long long)mt.S * mt.r;
+  for (long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
+       idx += (long long)gridDim.x * blockDim.x) {
+    const long long s = idx / mt.r;
+    const int a = (int)(idx - s * mt.r);
+    float x;
+    if (sizeof(TP) == 2) x = bf16_to_f32(*reinterpret_cast<const bf16_raw*>(&P[idx]));
+    else x = *reinterpret_cast<const float*>(&P[idx]);
+    gptr<bf16_raw> pn = as_global(mt.Pn) + s * ((long long)mt.kx * mt.rp);
+    gptr<bf16_raw> pt = as_global(mt.PT) + (long long)a * ((long long)mt.kx * mt.Sp);
+    if (mt.kx == 1) {
+      const bf16_raw b = f32_to_bf16(x);
+      pn[a] = b;
+      pt[s] = b;
+    } else {
+      bf16_raw h, m, l;
+      split3(x, h, m, l);
+      const bf16_raw seq[6] = {h, m, h, l, h, m};
+#pragma unroll
+      for (int p = 0; p < 6; ++p) {
+        pn[p * mt.rp + a] = seq[p];
+        pt[(long long)p * mt.Sp + s] = seq[p];
+      }
+    }
+  }
+}
+
+// fp32 gradient -> split bf16 planes (sequence A), stacked along the contraction axis.
+__global__ void fira_split_gradient_kernel(FiraMat mt, const float* __restrict__ G) {
+  const long long total = (long long)mt.m * mt.n;
+  gptr<bf16_raw> Gx = as_global(mt.Gx);
+  for (long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
+       idx += (long long)gridDim.x * blockDim.x) {
+    const long long i = idx / mt.n;
+    const long long j = idx - i * mt.n;
+    bf16_raw h, m, l;
+    split3(G[i * mt.ld + j], h, m, l);
+    const bf16_raw seq[6] = {h, h, m, h, l, m};
+    if (mt.left) {   // contraction over rows i: plane p occupies rows [p*Sp, p*Sp + m)
+#pragma unroll
+      for (int p = 0; p < 6; ++p) Gx[((long long)p * mt.Sp + i) * mt.gx_ld + j] = seq[p];
+    } else {         // contraction over columns j: plane p occupies columns [p*Sp, p*Sp + n)
+#pragma unroll
+      for (int p = 0; p < 6; ++p) Gx[i * ((long long)mt.kx * mt.Sp) + (long long)p * mt.Sp + j] = seq[p];
+    }
+  }
+}

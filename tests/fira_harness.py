@@ -1,0 +1,155 @@
+"""Shared driver for the GPU parity tests: runs the HIP library (through the C ABI binding) and the
+CPU oracle on the same seeded inputs and reports, stage by stage, how far apart they are.
+
+Stages compared (names follow Algorithm 1): R (low-rank gradient), M and V (Adam moments),
+k (scaling factors), s_pre / c / s_post (limiter), W (weights).
+"""
+from __future__ import annotations
+
+import dataclasses
+from typing import Callable, Dict, List, Optional, Sequence, Tuple
+
+import numpy as np
+import torch
+
+from oracle import fira_oracle as orc
+from paper_2410_01623_amd import fira, synth
+
+DEV = "cuda:0"
+
+
+def to_device(x: np.ndarray, dtype: int, ld: Optional[int] = None) -> torch.Tensor:
+    """float32 numpy (already representable in the storage type) -> device tensor, optional ld."""
+    t = torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32))
+    t = t.to(torch.bfloat16) if dtype == fira.FIRA_BF16 else t
+    if ld is None or ld == x.shape[1]:
+        return t.to(DEV)
+    buf = torch.zeros((x.shape[0], ld), dtype=t.dtype, device=DEV)
+    buf[:, : x.shape[1]] = t.to(DEV)
+    return buf[:, : x.shape[1]]
+
+
+def to_host(t: torch.Tensor) -> np.ndarray:
+    return t.detach().to(torch.float32).cpu().numpy().astype(np.float64)
+
+
+def rel_max(a: np.ndarray, ref: np.ndarray) -> float:
+    """max |a - ref| / max |ref| (the parity metric for W; also used for the other stages)."""
+    den = float(np.max(np.abs(ref)))
+    num = float(np.max(np.abs(np.asarray(a, dtype=np.float64) - ref)))
+    return num / den if den > 0 else num
+
+
+@dataclasses.dataclass
+class CaseResult:
+    w_err: List[float]            # per checked matrix, after the last step
+    worst: Dict[str, float]       # worst error per stage over all steps and matrices
+    c_min: float                  # smallest limiter factor seen (oracle)
+    ctx: fira.FiraContext
+    W_dev: List[torch.Tensor]
+    W_ref: Dict[int, np.ndarray]
+    states: Dict[int, orc.OracleState]
+    diag: List[Tuple]
+
+
+def run_case(shapes: Sequence[Tuple[int, int]], rank, dtype: int, steps: int,
+             gen_W: Callable[[int], np.ndarray], gen_G: Callable[[int, int], np.ndarray],
+             gen_P: Callable[[int, int], Optional[np.ndarray]], hp: orc.OracleHparams,
+             check: Optional[Sequence[int]] = None, lds: Optional[Sequence[int]] = None,
+             stages: bool = True, scaling: str = "column", step_lists: Optional[List[List[int]]] = None,
+             alias: Optional[Dict[int, int]] = None) -> CaseResult:
+    """gen_P(mat, step) returns a projector (float64/float32 values already representable in the
+    storage type) when the projector of `mat` is (re)installed before `step`, else None.
+    `check`: matrices compared against the oracle (default all).  `alias[i] = j`: matrix i is fed
+    the same inputs as matrix j (its own device buffers), for bitwise-equality checks.
+    `step_lists[s]`: matrices stepped at step s (default all)."""
+    nmat = len(shapes)
+    check = list(range(nmat)) if check is None else list(check)
+    alias = alias or {}
+    src = lambda i: alias.get(i, i)
+    ranks = rank if isinstance(rank, (list, tuple)) else [rank] * nmat
+    chp = fira.make_hparams(hp.lr, hp.beta1, hp.beta2, hp.eps, hp.alpha, hp.gamma)
+    ctx = fira.FiraContext(shapes, rank, dtype, chp, device=DEV, lds=lds)
+    if scaling != "column":
+        ctx.fira_set_options(scaling={"none": fira.FIRA_SCALE_NONE}[scaling])
+    bf = dtype == fira.FIRA_BF16
+    W_host = {i: gen_W(i) for i in set(src(i) for i in range(nmat))}
+    W_dev = [to_device(W_host[src(i)], dtype, None if lds is None else lds[i]) for i in range(nmat)]
+    W_ref = {i: W_host[src(i)].astype(np.float64) for i in check}
+    states = {i: orc.OracleState.zeros(shapes[i][0], shapes[i][1], ranks[i]) for i in check}
+    P_cur: Dict[int, np.ndarray] = {}
+    worst = dict(R=0.0, k=0.0, s_pre=0.0, c=0.0, W=0.0, M=0.0, V=0.0)
+    c_min = 1.0
+    diag = []
+    for s in range(steps):
+        listed = list(range(nmat)) if step_lists is None else step_lists[s]
+        G_host = {j: gen_G(j, s) for j in set(src(i) for i in listed)}
+        G_dev = [to_device(G_host[src(i)], dtype, None if lds is None else lds[i]) for i in listed]
+        P_new = {}
+        for i in listed:
+            if src(i) not in P_new:
+                P_new[src(i)] = gen_P(src(i), s)
+            P = P_new[src(i)]
+            if P is not None:
+                P_cur[i] = np.asarray(P, dtype=np.float64)
+                ctx.fira_set_projector(i, to_device(np.asarray(P, dtype=np.float32), dtype))
+        ctx.fira_step(listed, [W_dev[i] for i in listed], G_dev)
+        for i in listed:
+            if i not in check:
+                continue
+            out = orc.fira_step(W_ref[i], G_host[src(i)].astype(np.float64), P_cur[i], states[i], hp,
+                                scaling=scaling, store_bf16=bf)
+            W_ref[i] = out["W"]
+            c_min = min(c_min, out["c"])
+            if stages:
+                R = ctx.fira_get_lowrank(i).numpy().astype(np.float64)
+                k = ctx.fira_get_factors(i).numpy().astype(np.float64)
+                s_pre, s_post, c = ctx.fira_get_diag(i)
+                e = dict(R=rel_max(R, out["R"]), k=rel_max(k, out["k"]),
+                         s_pre=abs(s_pre - out["s_pre"]) / max(out["s_pre"], 1e-300),
+                         c=abs(c - out["c"]), W=rel_max(to_host(W_dev[i]), W_ref[i]))
+                diag.append((s, i, e, dict(s_pre=(s_pre, out["s_pre"]), c=(c, out["c"]))))
+                for key, v in e.items():
+                    worst[key] = max(worst[key], v)
+    torch.cuda.synchronize()
+    w_err = []
+    for i in check:
+        w_err.append(rel_max(to_host(W_dev[i]), W_ref[i]))
+        worst["W"] = max(worst["W"], w_err[-1])
+        if stages:
+            M, V, s_prev, t = ctx.fira_get_state(i)
+            worst["M"] = max(worst["M"], rel_max(M.numpy(), states[i].M))
+            worst["V"] = max(worst["V"], rel_max(V.numpy(), states[i].V))
+            assert t == states[i].t
+    return CaseResult(w_err, worst, c_min, ctx, W_dev, W_ref, states, diag)
+
+
+def workload_generators(wl: synth.Workload, proj: str = "svd"):
+    """(gen_W, gen_G, gen_P) for a synth.Workload.  proj: "svd" (top-r singular vectors of the
+    gradient at the refresh step, Eq. 7) or "random" (seeded orthonormal basis; used for the large
+    workloads where only the step itself is under test)."""
+    dt = wl.dtype
+    shapes = wl.shapes
+
+    def gen_W(i):
+        return synth.gen_W(wl, i)
+
+    def gen_G(i, s):
+        return synth.gen_G(wl, i, s)
+
+    def gen_P(i, s):
+        refresh = s == 0 or (wl.refresh_every and s % wl.refresh_every == 0)
+        if not refresh:
+            return None
+        m, n = shapes[i]
+        if proj == "svd":
+            P = synth.projector_from_gradient(synth.gen_G(wl, i, s), wl.rank)
+        else:
+            P = synth.random_orthonormal_projector(wl, i, min(m, n), wl.rank)
+        return synth.store_projector(P, dt)
+
+    return gen_W, gen_G, gen_P
+
+
+def fmt(res: CaseResult) -> str:
+    return "worst " + ", ".join(f"{k}={v:.3g}" for k, v in res.worst.items()) + f", c_min={res.c_min:.3g}"
