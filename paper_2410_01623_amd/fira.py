@@ -183,6 +183,8 @@ class FiraContext:
 
     def prepare(self, idx, Ws, Gs) -> PreparedList:
         for i, w, g in zip(idx, Ws, Gs):
+            if not 0 <= i < len(self.descs):
+                continue   # the library reports bad indices
             d = self.descs[i]
             want = _TORCH_DTYPE[d.wg_dtype]
             assert w.dtype == want and g.dtype == want, "W/G dtype must match the descriptor"

@@ -50,6 +50,7 @@ class CaseResult:
     W_ref: Dict[int, np.ndarray]
     states: Dict[int, orc.OracleState]
     diag: List[Tuple]
+    w_err_by_step: Dict[int, float] = dataclasses.field(default_factory=dict)   # worst W error after step s+1
 
 
 def run_case(shapes: Sequence[Tuple[int, int]], rank, dtype: int, steps: int,
@@ -121,7 +122,11 @@ def run_case(shapes: Sequence[Tuple[int, int]], rank, dtype: int, steps: int,
             worst["M"] = max(worst["M"], rel_max(M.numpy(), states[i].M))
             worst["V"] = max(worst["V"], rel_max(V.numpy(), states[i].V))
             assert t == states[i].t
-    return CaseResult(w_err, worst, c_min, ctx, W_dev, W_ref, states, diag)
+    by_step: Dict[int, float] = {}
+    for (s, i, e, d) in diag:
+        by_step[s + 1] = max(by_step.get(s + 1, 0.0), e["W"])
+    by_step[steps] = max([by_step.get(steps, 0.0)] + w_err)
+    return CaseResult(w_err, worst, c_min, ctx, W_dev, W_ref, states, diag, by_step)
 
 
 def workload_generators(wl: synth.Workload, proj: str = "svd"):
