@@ -62,8 +62,8 @@ struct Plan {
 };
 
 bool valid_desc(const fira_matrix_desc& d, std::string* why) {
-  if (d.m < 1 || d.n < 1 || d.m > (1 << 24) || d.n > (1 << 24)) { *why = "m, n must be in [1, 2^24]"; return false; }
-  if (d.ld < d.n) { *why = "ld must be >= n"; return false; }
+  if (d.m < 1 || d.n < 1 || d.m > (1 << 22) || d.n > (1 << 22)) { *why = "m, n must be in [1, 2^22]"; return false; }
+  if (d.ld < d.n || d.ld > (1 << 22)) { *why = "ld must be in [n, 2^22]"; return false; }
   if (d.r < 1 || d.r > std::min(d.m, d.n)) { *why = "need 1 <= r <= min(m, n)"; return false; }
   return true;
 }

@@ -125,11 +125,73 @@ __device__ __forceinline__ void gemm_store_tiles(char* lds, const u32x4 (&ra)[8]
   }
 }
 
-// acc[tm][tn]: wave (wm, wn) = (wave & 1, wave >> 1) owns A rows wm*128 + 32*tm + .., B rows wn*64 + 32*tn + ..
+// Unguarded tile loads for interior tiles (every row of the tile valid, KA a multiple of 64): one
+// uniform base pointer per operand that advances along K, plus per-thread element offsets that are
+// computed once.  Rows may start at any element (odd n / ld): the loads only assume 2-byte alignment.
 template <bool AKSLOW>
-__device__ __forceinline__ void gemm_mainloop(f32x16_t (&acc)[4][2], char* lds, const GemmOperands& g) {
+struct FastLoader {
+  gptr<const bf16_raw> pa, pb;
+  unsigned offa[8], offb[4];
+  long long stepa;
+  __device__ __forceinline__ FastLoader(const GemmOperands& g) {
+    const int t = threadIdx.x;
+    const int cc = t & 7, rr = t >> 3;
+    if (AKSLOW) {
+      const int ib = t & 31, kb = t >> 5;
+      pa = g.A + g.a_row0;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) offa[j] = (unsigned)((8 * kb + j) * g.lda + 8 * ib);
+      stepa = FIRA_BK * g.lda;
+    } else {
+      pa = g.A + (long long)g.a_row0 * g.lda;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) offa[i] = (unsigned)((rr + 32 * i) * g.lda + 8 * cc);
+      stepa = FIRA_BK;
+    }
+    pb = g.B + (long long)g.b_row0 * g.ldb;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) offb[i] = (unsigned)((rr + 32 * i) * g.ldb + 8 * cc);
+  }
+  __device__ __forceinline__ void load(u32x4 (&ra)[8], u32x4 (&rb)[4]) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) ra[i] = *reinterpret_cast<gptr<const u32x4_a2>>(pa + offa[i]);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) rb[i] = *reinterpret_cast<gptr<const u32x4_a2>>(pb + offb[i]);
+    pa += stepa;
+    pb += FIRA_BK;
+  }
+};
+
+__device__ __forceinline__ bool gemm_tile_is_interior(const GemmOperands& g) {
+  return g.a_row0 + FIRA_TA <= g.a_rows && g.b_row0 + FIRA_TB <= g.b_rows && (g.KA % FIRA_BK) == 0;
+}
+
+__device__ __forceinline__ void gemm_compute_step(f32x16_t (&acc)[4][2], const char* la, const char* lb) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave & 1, wn = wave >> 1;
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) {
+    const int chunk = 2 * kk + (lane >> 5);
+    bf16x8_t af[4], bfr[2];
+#pragma unroll
+    for (int tm = 0; tm < 4; ++tm)
+      af[tm] = *reinterpret_cast<const bf16x8_t*>(la + lds_tile_off(wm * 128 + 32 * tm + (lane & 31), chunk));
+#pragma unroll
+    for (int tn = 0; tn < 2; ++tn)
+      bfr[tn] = *reinterpret_cast<const bf16x8_t*>(lb + lds_tile_off(wn * 64 + 32 * tn + (lane & 31), chunk));
+#pragma unroll
+    for (int tm = 0; tm < 4; ++tm)
+#pragma unroll
+      for (int tn = 0; tn < 2; ++tn)
+        acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[tm], bfr[tn], acc[tm][tn], 0, 0, 0);
+  }
+}
+
+// acc[tm][tn]: wave (wm, wn) = (wave & 1, wave >> 1) owns A rows wm*128 + 32*tm + .., B rows wn*64 + 32*tn + ..
+// Single LDS buffer, register prefetch: the global loads of step k+1 are in flight while step k is
+// multiplied; two workgroups per CU overlap one another's barriers.
+template <bool AKSLOW>
+__device__ __forceinline__ void gemm_mainloop(f32x16_t (&acc)[4][2], char* lds, const GemmOperands& g) {
 #pragma unroll
   for (int tm = 0; tm < 4; ++tm)
 #pragma unroll
@@ -139,30 +201,27 @@ __device__ __forceinline__ void gemm_mainloop(f32x16_t (&acc)[4][2], char* lds, 
 
   const int KT = (g.KA + FIRA_BK - 1) / FIRA_BK;
   u32x4 ra[8], rb[4];
-  gemm_load_tiles<AKSLOW>(ra, rb, g, 0);
   const char* la = lds;
   const char* lb = lds + FIRA_LDS_A;
-  for (int kt = 0; kt < KT; ++kt) {
-    gemm_store_tiles<AKSLOW>(lds, ra, rb);
-    __syncthreads();
-    if (kt + 1 < KT) gemm_load_tiles<AKSLOW>(ra, rb, g, (kt + 1) * FIRA_BK);
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-      const int chunk = 2 * kk + (lane >> 5);
-      bf16x8_t af[4], bfr[2];
-#pragma unroll
-      for (int tm = 0; tm < 4; ++tm)
-        af[tm] = *reinterpret_cast<const bf16x8_t*>(la + lds_tile_off(wm * 128 + 32 * tm + (lane & 31), chunk));
-#pragma unroll
-      for (int tn = 0; tn < 2; ++tn)
-        bfr[tn] = *reinterpret_cast<const bf16x8_t*>(lb + lds_tile_off(wn * 64 + 32 * tn + (lane & 31), chunk));
-#pragma unroll
-      for (int tm = 0; tm < 4; ++tm)
-#pragma unroll
-        for (int tn = 0; tn < 2; ++tn)
-          acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[tm], bfr[tn], acc[tm][tn], 0, 0, 0);
+  if (gemm_tile_is_interior(g)) {
+    FastLoader<AKSLOW> ld(g);
+    ld.load(ra, rb);
+    for (int kt = 0; kt < KT; ++kt) {
+      gemm_store_tiles<AKSLOW>(lds, ra, rb);
+      __syncthreads();
+      if (kt + 1 < KT) ld.load(ra, rb);
+      gemm_compute_step(acc, la, lb);
+      __syncthreads();
     }
-    __syncthreads();
+  } else {
+    gemm_load_tiles<AKSLOW>(ra, rb, g, 0);
+    for (int kt = 0; kt < KT; ++kt) {
+      gemm_store_tiles<AKSLOW>(lds, ra, rb);
+      __syncthreads();
+      if (kt + 1 < KT) gemm_load_tiles<AKSLOW>(ra, rb, g, (kt + 1) * FIRA_BK);
+      gemm_compute_step(acc, la, lb);
+      __syncthreads();
+    }
   }
 }
 
@@ -232,11 +291,17 @@ __global__ __launch_bounds__(256, 2) void fira_project_kernel(const FiraMat* __r
 //   MODE 1: W -= lr*alpha*(U + c k G)                       with Y/X built from Z = N - c k R
 // ------------------------------------------------------------------------------------------------
 template <typename T>
-struct Elem8;  // 8 consecutive elements of W or G as floats
+struct Elem8;  // 8 consecutive elements of W or G: raw registers, conversion to floats, store
 template <>
 struct Elem8<bf16_raw> {
-  static __device__ __forceinline__ void load(float (&x)[8], gptr<const bf16_raw> row, long long idx, long long limit) {
-    const u32x4 v = load8_bf16(row, idx, limit);
+  typedef u32x4 Raw;
+  template <bool INTERIOR>
+  static __device__ __forceinline__ Raw load_raw(gptr<const bf16_raw> row, long long idx, long long limit) {
+    if (INTERIOR) return *reinterpret_cast<gptr<const u32x4_a2>>(row + idx);
+    return load8_bf16(row, idx, limit);
+  }
+  static __device__ __forceinline__ Raw zero() { return u32x4{0u, 0u, 0u, 0u}; }
+  static __device__ __forceinline__ void unpack(const Raw& v, float (&x)[8]) {
     const unsigned w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
     for (int d = 0; d < 4; ++d) {
@@ -244,10 +309,11 @@ struct Elem8<bf16_raw> {
       x[2 * d + 1] = __uint_as_float(w[d] & 0xffff0000u);
     }
   }
+  template <bool INTERIOR>
   static __device__ __forceinline__ void store(const float (&x)[8], gptr<bf16_raw> row, long long idx, long long limit) {
-    if (idx + 8 <= limit) {
+    if (INTERIOR || idx + 8 <= limit) {
       const u32x4 v = u32x4{pack_bf16x2(x[0], x[1]), pack_bf16x2(x[2], x[3]), pack_bf16x2(x[4], x[5]),
-                                 pack_bf16x2(x[6], x[7])};
+                            pack_bf16x2(x[6], x[7])};
       *reinterpret_cast<gptr<u32x4_a2>>(row + idx) = v;
     } else {
 #pragma unroll
@@ -258,18 +324,29 @@ struct Elem8<bf16_raw> {
 };
 template <>
 struct Elem8<float> {
-  static __device__ __forceinline__ void load(float (&x)[8], gptr<const float> row, long long idx, long long limit) {
-    if (idx + 8 <= limit) {
-      const f32x4 a = *reinterpret_cast<gptr<const f32x4_a4>>(row + idx);
-      const f32x4 b = *reinterpret_cast<gptr<const f32x4_a4>>(row + idx + 4);
-      x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w; x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
+  struct Raw { f32x4 a, b; };
+  template <bool INTERIOR>
+  static __device__ __forceinline__ Raw load_raw(gptr<const float> row, long long idx, long long limit) {
+    Raw r;
+    if (INTERIOR || idx + 8 <= limit) {
+      r.a = *reinterpret_cast<gptr<const f32x4_a4>>(row + idx);
+      r.b = *reinterpret_cast<gptr<const f32x4_a4>>(row + idx + 4);
     } else {
+      float x[8];
 #pragma unroll
       for (int e = 0; e < 8; ++e) x[e] = (idx + e < limit) ? row[idx + e] : 0.0f;
+      r.a = f32x4{x[0], x[1], x[2], x[3]};
+      r.b = f32x4{x[4], x[5], x[6], x[7]};
     }
+    return r;
   }
+  static __device__ __forceinline__ Raw zero() { Raw r; r.a = f32x4{0.f, 0.f, 0.f, 0.f}; r.b = r.a; return r; }
+  static __device__ __forceinline__ void unpack(const Raw& r, float (&x)[8]) {
+    x[0] = r.a.x; x[1] = r.a.y; x[2] = r.a.z; x[3] = r.a.w; x[4] = r.b.x; x[5] = r.b.y; x[6] = r.b.z; x[7] = r.b.w;
+  }
+  template <bool INTERIOR>
   static __device__ __forceinline__ void store(const float (&x)[8], gptr<float> row, long long idx, long long limit) {
-    if (idx + 8 <= limit) {
+    if (INTERIOR || idx + 8 <= limit) {
       *reinterpret_cast<gptr<f32x4_a4>>(row + idx) = f32x4{x[0], x[1], x[2], x[3]};
       *reinterpret_cast<gptr<f32x4_a4>>(row + idx + 4) = f32x4{x[4], x[5], x[6], x[7]};
     } else {
@@ -280,9 +357,13 @@ struct Elem8<float> {
   }
 };
 
-template <int MODE, typename T>
+// Epilogue of the rank-axis contractions.  The wave's 64(i) x 128(j) accumulators are processed as
+// four 32 x 64 slabs; the G (and W) values of slab s+1 are requested from HBM before slab s is
+// re-laid out through LDS and consumed, so their latency overlaps the LDS work.
+template <int MODE, typename T, bool INTERIOR>
 __device__ __forceinline__ float backproject_epilogue(f32x16_t (&acc)[4][2], char* lds, const FiraMat& mt,
                                                       const FiraEnt& ent, int i0, int j0, float c, float lr_alpha) {
+  typedef typename Elem8<T>::Raw Raw;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave & 1, wn = wave >> 1;
   float* buf = reinterpret_cast<float*>(lds) + wave * (32 * FIRA_EPI_STRIDE);
@@ -290,55 +371,70 @@ __device__ __forceinline__ float backproject_epilogue(f32x16_t (&acc)[4][2], cha
   gptr<T> W = as_global(reinterpret_cast<T*>(ent.W));
   gptr<const float> phi = as_global<const float>(mt.phi);
   const int jl = 8 * (lane & 7);              // this lane's 8 columns inside the staged 64
-  float sum = 0.0f;
-#pragma unroll
-  for (int th = 0; th < 2; ++th) {            // halves of the wave's 128 columns (A-side blocks 2th, 2th+1)
+  const int il0 = lane >> 3;                  // this lane's row inside each group of 8 staged rows
+  Raw gbuf[sizeof(T) == 2 ? 2 : 1][4], wbuf[sizeof(T) == 2 ? 2 : 1][4];
+  auto preload = [&](int s, Raw (&gr)[4], Raw (&wr)[4]) {
+    const int th = s >> 1, tn = s & 1;
     const long long j = (long long)j0 + wm * 128 + 64 * th + jl;
-    float cphi[8];
-    if (mt.left) {
 #pragma unroll
-      for (int e = 0; e < 8; ++e) cphi[e] = (j + e < mt.n) ? c * phi[j + e] : 0.0f;
+    for (int p = 0; p < 4; ++p) {
+      const long long i = (long long)i0 + wn * 64 + 32 * tn + 8 * p + il0;
+      const bool ok = INTERIOR || (i < mt.m && j < mt.n);
+      gr[p] = ok ? Elem8<T>::template load_raw<INTERIOR>(G + i * mt.ld, j, mt.n) : Elem8<T>::zero();
+      if (MODE == 1) wr[p] = ok ? Elem8<T>::template load_raw<INTERIOR>(W + i * mt.ld, j, mt.n) : Elem8<T>::zero();
     }
+  };
+  constexpr bool PIPE = sizeof(T) == 2;       // fp32 tiles would need 128 more registers: no prefetch
+  if (PIPE) preload(0, gbuf[0], wbuf[0]);
+  float sum = 0.0f;
+  float cphi[8];
 #pragma unroll
-    for (int tn = 0; tn < 2; ++tn) {
-      __syncthreads();  // previous slab fully consumed (first time: the main loop's LDS reads are done)
+  for (int s = 0; s < 4; ++s) {
+    const int th = s >> 1, tn = s & 1;
+    const long long j = (long long)j0 + wm * 128 + 64 * th + jl;
+    if (PIPE && s + 1 < 4) preload(s + 1, gbuf[PIPE ? ((s + 1) & 1) : 0], wbuf[PIPE ? ((s + 1) & 1) : 0]);
+    if (!PIPE) preload(s, gbuf[0], wbuf[0]);
+    if (mt.left && tn == 0) {
 #pragma unroll
-      for (int t2 = 0; t2 < 2; ++t2)
+      for (int e = 0; e < 8; ++e) cphi[e] = (INTERIOR || j + e < mt.n) ? c * phi[j + e] : 0.0f;
+    }
+    __syncthreads();  // previous slab fully consumed (first time: the main loop's LDS reads are done)
 #pragma unroll
-        for (int vg = 0; vg < 4; ++vg) {
-          const f32x16_t& a = acc[2 * th + t2][tn];
-          const f32x4 val = f32x4{a[4 * vg], a[4 * vg + 1], a[4 * vg + 2], a[4 * vg + 3]};
-          *reinterpret_cast<f32x4*>(buf + (lane & 31) * FIRA_EPI_STRIDE + 32 * t2 + 8 * vg + 4 * (lane >> 5)) = val;
+    for (int t2 = 0; t2 < 2; ++t2)
+#pragma unroll
+      for (int vg = 0; vg < 4; ++vg) {
+        const f32x16_t& a = acc[2 * th + t2][tn];
+        const f32x4 val = f32x4{a[4 * vg], a[4 * vg + 1], a[4 * vg + 2], a[4 * vg + 3]};
+        *reinterpret_cast<f32x4*>(buf + (lane & 31) * FIRA_EPI_STRIDE + 32 * t2 + 8 * vg + 4 * (lane >> 5)) = val;
+      }
+    __syncthreads();
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      const int il = 8 * p + il0;
+      const long long i = (long long)i0 + wn * 64 + 32 * tn + il;
+      if (INTERIOR || (i < mt.m && j < mt.n)) {
+        const f32x4 u0 = *reinterpret_cast<const f32x4*>(buf + il * FIRA_EPI_STRIDE + jl);
+        const f32x4 u1 = *reinterpret_cast<const f32x4*>(buf + il * FIRA_EPI_STRIDE + jl + 4);
+        const float u[8] = {u0.x, u0.y, u0.z, u0.w, u1.x, u1.y, u1.z, u1.w};
+        float g[8];
+        Elem8<T>::unpack(gbuf[PIPE ? (s & 1) : 0][p], g);
+        if (!mt.left) {
+          const float f = c * phi[i];
+#pragma unroll
+          for (int e = 0; e < 8; ++e) cphi[e] = f;
         }
-      __syncthreads();
+        if (MODE == 0) {
 #pragma unroll
-      for (int p = 0; p < 4; ++p) {
-        const int il = 8 * p + (lane >> 3);
-        const long long i = (long long)i0 + wn * 64 + 32 * tn + il;
-        if (i < mt.m && j < mt.n) {
-          const f32x4 u0 = *reinterpret_cast<const f32x4*>(buf + il * FIRA_EPI_STRIDE + jl);
-          const f32x4 u1 = *reinterpret_cast<const f32x4*>(buf + il * FIRA_EPI_STRIDE + jl + 4);
-          const float u[8] = {u0.x, u0.y, u0.z, u0.w, u1.x, u1.y, u1.z, u1.w};
-          float g[8];
-          Elem8<T>::load(g, G + i * mt.ld, j, mt.n);
-          if (!mt.left) {
-            const float f = c * phi[i];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) cphi[e] = f;
+          for (int e = 0; e < 8; ++e) {
+            const float sv = cphi[e] * (g[e] - u[e]);   // c = 1 here: k_i (G - P R)
+            sum += (INTERIOR || j + e < mt.n) ? sv * sv : 0.0f;
           }
-          if (MODE == 0) {
+        } else {
+          float w[8];
+          Elem8<T>::unpack(wbuf[PIPE ? (s & 1) : 0][p], w);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-              const float s = cphi[e] * (g[e] - u[e]);   // c = 1 here: k_i (G - P R)
-              sum += (j + e < mt.n) ? s * s : 0.0f;
-            }
-          } else {
-            float w[8];
-            Elem8<T>::load(w, W + i * mt.ld, j, mt.n);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) w[e] = w[e] - lr_alpha * (u[e] + cphi[e] * g[e]);
-            Elem8<T>::store(w, W + i * mt.ld, j, mt.n);
-          }
+          for (int e = 0; e < 8; ++e) w[e] = w[e] - lr_alpha * (u[e] + cphi[e] * g[e]);
+          Elem8<T>::template store<INTERIOR>(w, W + i * mt.ld, j, mt.n);
         }
       }
     }
@@ -377,10 +473,13 @@ __global__ __launch_bounds__(256, 2) void fira_backproject_kernel(const FiraMat*
 
   const float c = (MODE == 0) ? 1.0f : scal[ent.mat].c;
   float sum;
-  if (mt.dtype == 1)
-    sum = backproject_epilogue<MODE, bf16_raw>(acc, lds, mt, ent, g.b_row0, g.a_row0, c, lr_alpha);
-  else
-    sum = backproject_epilogue<MODE, float>(acc, lds, mt, ent, g.b_row0, g.a_row0, c, lr_alpha);
+  const bool interior = g.b_row0 + FIRA_TB <= mt.m && g.a_row0 + FIRA_TA <= mt.n;
+  if (mt.dtype == 1) {
+    if (interior) sum = backproject_epilogue<MODE, bf16_raw, true>(acc, lds, mt, ent, g.b_row0, g.a_row0, c, lr_alpha);
+    else sum = backproject_epilogue<MODE, bf16_raw, false>(acc, lds, mt, ent, g.b_row0, g.a_row0, c, lr_alpha);
+  } else {
+    sum = backproject_epilogue<MODE, float, false>(acc, lds, mt, ent, g.b_row0, g.a_row0, c, lr_alpha);
+  }
 
   if (MODE == 0) {
     // deterministic workgroup reduction: xor-butterfly inside each wave, then waves in order
