@@ -22,6 +22,13 @@ constexpr int kSlots = 4;  // cached work lists (a training loop alternates betw
 
 inline size_t align_up(size_t x, size_t a = kAlign) { return (x + a - 1) / a * a; }
 inline int round_up_int(long long x, int a) { return (int)((x + a - 1) / a * a); }
+// Row pitch (bf16 elements) for an operand row of k values: a whole number of 256-byte L2-channel
+// lines, and an odd number of them, so that consecutive rows walk through all sixteen channels.
+inline int operand_pitch(long long k) {
+  long long lines = (k * 2 + 255) / 256;
+  if (lines % 2 == 0) ++lines;
+  return (int)(lines * 128);
+}
 
 thread_local std::string g_last_error;
 
@@ -35,15 +42,17 @@ struct HostMat {
   int rowblocks = 0;
 };
 
+enum { kTilesProjectLeft = 0, kTilesProjectRight = 1, kTilesBackBf16 = 2, kTilesBackF32 = 3, kNumTileLists = 4 };
+
 struct ListSlot {
   std::vector<int> idx;
   std::vector<void*> W;
   std::vector<const void*> G;
-  int ntiles_project = 0, ntiles_back = 0, rowblocks = 0;
+  int ntiles[kNumTileLists] = {0, 0, 0, 0};
+  int rowblocks = 0;
   // device views (inside the slab)
   FiraEnt* d_ents = nullptr;
-  FiraTile* d_tiles_project = nullptr;
-  FiraTile* d_tiles_back = nullptr;
+  FiraTile* d_tiles[kNumTileLists] = {nullptr, nullptr, nullptr, nullptr};
   // pinned host staging, one contiguous block mirrored to the device block
   char* h_stage = nullptr;
   char* d_block = nullptr;
@@ -56,9 +65,9 @@ struct ListSlot {
 struct Plan {
   size_t total = 0;
   size_t off_mats = 0, off_scal = 0, off_partial = 0;
-  size_t off_slots = 0, slot_bytes = 0, slot_off_tiles_project = 0, slot_off_tiles_back = 0;
+  size_t off_slots = 0, slot_bytes = 0, slot_off_tiles[kNumTileLists] = {0, 0, 0, 0};
   std::vector<HostMat> mats;
-  int max_tiles_project = 0, max_tiles_back = 0;
+  int max_tiles[kNumTileLists] = {0, 0, 0, 0};
 };
 
 bool valid_desc(const fira_matrix_desc& d, std::string* why) {
@@ -75,7 +84,7 @@ bool make_plan(const fira_matrix_desc* d, int count, Plan* plan, fira_status* st
   size_t off = 0;
   plan->off_mats = off; off = align_up(off + sizeof(FiraMat) * count);
   plan->off_scal = off; off = align_up(off + sizeof(FiraScal) * count);
-  long long total_tiles_project = 0, total_tiles_back = 0;
+  long long total_tiles[kNumTileLists] = {0, 0, 0, 0};
   for (int i = 0; i < count; ++i) {
     HostMat& h = plan->mats[i];
     h.d = d[i];
@@ -89,7 +98,9 @@ bool make_plan(const fira_matrix_desc* d, int count, Plan* plan, fira_status* st
     m.rp = round_up_int(m.r, 64); m.Sp = round_up_int(m.S, 64);
     m.dtype = d[i].wg_dtype;
     m.kx = (m.dtype == FIRA_F32) ? FIRA_KX_SPLIT : 1;
-    m.gx_ld = round_up_int(m.n, 8);
+    m.lr_ld = operand_pitch((long long)m.kx * m.rp);
+    m.pt_ld = operand_pitch((long long)m.kx * m.Sp);
+    m.gx_ld = m.left ? round_up_int(m.n, 8) : operand_pitch((long long)m.kx * m.Sp);
     const size_t Lr = (size_t)m.L * m.r;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
     m.M = (float*)take(Lr * 4);
@@ -98,12 +109,12 @@ bool make_plan(const fira_matrix_desc* d, int count, Plan* plan, fira_status* st
     m.phi = (float*)take((size_t)m.L * 4);
     m.g2 = (float*)take((size_t)m.L * 4);
     m.q = (float*)take((size_t)m.L * 4);
-    m.Nb = (bf16_raw*)take((size_t)m.L * m.kx * m.rp * 2);
-    m.Rb = (bf16_raw*)take((size_t)m.L * m.kx * m.rp * 2);
-    m.Pn = (bf16_raw*)take((size_t)m.S * m.kx * m.rp * 2);
-    m.PT = (bf16_raw*)take((size_t)m.r * m.kx * m.Sp * 2);
+    m.Nb = (bf16_raw*)take((size_t)m.L * m.lr_ld * 2);
+    m.Rb = (bf16_raw*)take((size_t)m.L * m.lr_ld * 2);
+    m.Pn = (bf16_raw*)take((size_t)m.S * m.lr_ld * 2);
+    m.PT = (bf16_raw*)take((size_t)m.r * m.pt_ld * 2);
     if (m.kx > 1) {
-      const size_t gx = m.left ? (size_t)m.kx * m.Sp * m.gx_ld : (size_t)m.m * m.kx * m.Sp;
+      const size_t gx = m.left ? (size_t)m.kx * m.Sp * m.gx_ld : (size_t)m.m * m.gx_ld;
       m.Gx = (bf16_raw*)take(gx * 2);
     }
     m.Dm = (bf16_raw*)take((size_t)m.r * m.rp * 2);
@@ -112,17 +123,21 @@ bool make_plan(const fira_matrix_desc* d, int count, Plan* plan, fira_status* st
     h.tiles_project = h.ta_project * h.tb_project;
     h.tiles_back = h.ta_back * h.tb_back;
     h.rowblocks = (m.L + FIRA_ROWS_PER_WG - 1) / FIRA_ROWS_PER_WG;
-    total_tiles_project += h.tiles_project;
-    total_tiles_back += h.tiles_back;
+    total_tiles[m.left ? kTilesProjectLeft : kTilesProjectRight] += h.tiles_project;
+    total_tiles[m.dtype == FIRA_BF16 ? kTilesBackBf16 : kTilesBackF32] += h.tiles_back;
   }
-  if (total_tiles_project > (1 << 28) || total_tiles_back > (1 << 28)) { *st = FIRA_ERR_SHAPE; *why = "too many tiles"; return false; }
-  plan->max_tiles_project = (int)total_tiles_project;
-  plan->max_tiles_back = (int)total_tiles_back;
-  plan->off_partial = off; off = align_up(off + (size_t)total_tiles_back * 4);
+  for (int l = 0; l < kNumTileLists; ++l) {
+    if (total_tiles[l] > (1 << 28)) { *st = FIRA_ERR_SHAPE; *why = "too many tiles"; return false; }
+    plan->max_tiles[l] = (int)total_tiles[l];
+  }
+  plan->off_partial = off;
+  off = align_up(off + (size_t)(total_tiles[kTilesBackBf16] + total_tiles[kTilesBackF32]) * 4);
   size_t s = 0;
   s = align_up(s + sizeof(FiraEnt) * count);
-  plan->slot_off_tiles_project = s; s = align_up(s + sizeof(FiraTile) * (size_t)total_tiles_project);
-  plan->slot_off_tiles_back = s;    s = align_up(s + sizeof(FiraTile) * (size_t)total_tiles_back);
+  for (int l = 0; l < kNumTileLists; ++l) {
+    plan->slot_off_tiles[l] = s;
+    s = align_up(s + sizeof(FiraTile) * (size_t)total_tiles[l]);
+  }
   plan->slot_bytes = s;
   plan->off_slots = off; off += s * kSlots;
   plan->total = off;
@@ -203,26 +218,29 @@ ListSlot* acquire_list(fira_ctx* ctx, int count, const int* idx, void* const* W,
   s->G.assign(G, G + count);
   const Plan& p = ctx->plan;
   FiraEnt* ents = reinterpret_cast<FiraEnt*>(s->h_stage);
-  FiraTile* tp = reinterpret_cast<FiraTile*>(s->h_stage + p.slot_off_tiles_project);
-  FiraTile* tb = reinterpret_cast<FiraTile*>(s->h_stage + p.slot_off_tiles_back);
-  int ntp = 0, ntb = 0, rowblocks = 0;
+  FiraTile* tl[kNumTileLists];
+  int nt[kNumTileLists] = {0, 0, 0, 0};
+  for (int l = 0; l < kNumTileLists; ++l) tl[l] = reinterpret_cast<FiraTile*>(s->h_stage + p.slot_off_tiles[l]);
+  int nparts = 0, rowblocks = 0;
   for (int e = 0; e < count; ++e) {
     const HostMat& h = p.mats[idx[e]];
     FiraEnt& en = ents[e];
-    en.mat = idx[e]; en.part0 = ntb; en.npart = h.tiles_back; en.row0 = rowblocks;
+    en.mat = idx[e]; en.part0 = nparts; en.npart = h.tiles_back; en.row0 = rowblocks;
     en.W = W[e]; en.G = G[e];
     rowblocks += h.rowblocks;
     // R contraction: rank tiles innermost, so the tiles that share a panel of G are neighbours
+    const int lp = h.dev.left ? kTilesProjectLeft : kTilesProjectRight;
     for (int ta = 0; ta < h.ta_project; ++ta)
-      for (int tbb = 0; tbb < h.tb_project; ++tbb) tp[ntp++] = FiraTile{e, ta, tbb, 0};
+      for (int tbb = 0; tbb < h.tb_project; ++tbb) tl[lp][nt[lp]++] = FiraTile{e, ta, tbb, 0};
     // back-projection: groups of 8 column tiles x all row tiles keep both operand panels in L2
+    const int lb = h.dev.dtype == FIRA_BF16 ? kTilesBackBf16 : kTilesBackF32;
     for (int ta0 = 0; ta0 < h.ta_back; ta0 += 8)
       for (int t2 = 0; t2 < h.tb_back; ++t2)
-        for (int ta = ta0; ta < std::min(ta0 + 8, h.ta_back); ++ta) { tb[ntb] = FiraTile{e, ta, t2, ntb}; ++ntb; }
+        for (int ta = ta0; ta < std::min(ta0 + 8, h.ta_back); ++ta) tl[lb][nt[lb]++] = FiraTile{e, ta, t2, nparts++};
   }
-  s->ntiles_project = ntp; s->ntiles_back = ntb; s->rowblocks = rowblocks;
-  const size_t bytes = p.slot_off_tiles_back + sizeof(FiraTile) * (size_t)ntb;
-  if (hipMemcpyAsync(s->d_block, s->h_stage, bytes, hipMemcpyHostToDevice, ctx->stream) != hipSuccess ||
+  for (int l = 0; l < kNumTileLists; ++l) s->ntiles[l] = nt[l];
+  s->rowblocks = rowblocks;
+  if (hipMemcpyAsync(s->d_block, s->h_stage, p.slot_bytes, hipMemcpyHostToDevice, ctx->stream) != hipSuccess ||
       hipEventRecord(s->uploaded, ctx->stream) != hipSuccess) { *st = FIRA_ERR_HIP; return nullptr; }
   s->valid = true;
   s->last_use = ctx->use_counter;
@@ -291,6 +309,13 @@ fira_status fira_init_state(fira_ctx** out, const fira_matrix_desc* d, int count
       return fail(nullptr, FIRA_ERR_HIP, msg_);                                                      \
     }                                                                                                \
   } while (0)
+  // the contraction kernels use 128 KB of dynamic LDS (gfx950 has 160 KB per workgroup)
+  FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_project_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_LDS_BYTES));
+  FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_project_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_LDS_BYTES));
+  FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_backproject_kernel<0, bf16_raw>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_LDS_BYTES));
+  FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_backproject_kernel<1, bf16_raw>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_LDS_BYTES));
+  FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_backproject_kernel<0, float>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_LDS_BYTES));
+  FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_backproject_kernel<1, float>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_LDS_BYTES));
   FIRA_INIT_HIP(hipHostMalloc((void**)&ctx->h_stage_all, p.slot_bytes * kSlots, hipHostMallocDefault));
   for (int i = 0; i < kSlots; ++i) {
     ListSlot& s = ctx->slots[i];
@@ -298,8 +323,7 @@ fira_status fira_init_state(fira_ctx** out, const fira_matrix_desc* d, int count
     s.d_block = ctx->slab + p.off_slots + p.slot_bytes * i;
     s.block_bytes = p.slot_bytes;
     s.d_ents = (FiraEnt*)s.d_block;
-    s.d_tiles_project = (FiraTile*)(s.d_block + p.slot_off_tiles_project);
-    s.d_tiles_back = (FiraTile*)(s.d_block + p.slot_off_tiles_back);
+    for (int l = 0; l < kNumTileLists; ++l) s.d_tiles[l] = (FiraTile*)(s.d_block + p.slot_off_tiles[l]);
     FIRA_INIT_HIP(hipEventCreateWithFlags(&s.uploaded, hipEventDisableTiming));
     FIRA_INIT_HIP(hipEventRecord(s.uploaded, ctx->stream));
   }
@@ -382,17 +406,28 @@ fira_status fira_step(fira_ctx* ctx, int count, const int* idx, void* const* dev
     }
   }
   auto grid8 = [](int n) { return dim3((unsigned)(((n + 7) / 8) * 8)); };
-  // 1. R = P^T G (long-side major)
-  hipLaunchKernelGGL(fira_project_kernel, grid8(s->ntiles_project), dim3(256), 0, q, ctx->d_mats, s->d_ents,
-                     s->d_tiles_project, s->ntiles_project);
+  const dim3 blk(FIRA_THREADS);
+  // 1. R = P^T G (long-side major), one launch per orientation
+  if (s->ntiles[kTilesProjectLeft])
+    hipLaunchKernelGGL(fira_project_kernel<true>, grid8(s->ntiles[kTilesProjectLeft]), blk, FIRA_LDS_BYTES, q,
+                       ctx->d_mats, s->d_ents, s->d_tiles[kTilesProjectLeft], s->ntiles[kTilesProjectLeft]);
+  if (s->ntiles[kTilesProjectRight])
+    hipLaunchKernelGGL(fira_project_kernel<false>, grid8(s->ntiles[kTilesProjectRight]), blk, FIRA_LDS_BYTES, q,
+                       ctx->d_mats, s->d_ents, s->d_tiles[kTilesProjectRight], s->ntiles[kTilesProjectRight]);
   mark(1);
   // 2. Adam on R, factor norms
   hipLaunchKernelGGL(fira_adam_kernel, dim3(s->rowblocks), dim3(256), 0, q, ctx->d_mats, ctx->d_scal, s->d_ents, count,
                      s->rowblocks, hp);
   mark(2);
   // 3. ||k (G - P R)||^2 per tile
-  hipLaunchKernelGGL(fira_backproject_kernel<0>, grid8(s->ntiles_back), dim3(256), 0, q, ctx->d_mats, ctx->d_scal,
-                     s->d_ents, s->d_tiles_back, s->ntiles_back, ctx->d_partial, hp.lr_alpha);
+  if (s->ntiles[kTilesBackBf16])
+    hipLaunchKernelGGL((fira_backproject_kernel<0, bf16_raw>), grid8(s->ntiles[kTilesBackBf16]), blk, FIRA_LDS_BYTES, q,
+                       ctx->d_mats, ctx->d_scal, s->d_ents, s->d_tiles[kTilesBackBf16], s->ntiles[kTilesBackBf16],
+                       ctx->d_partial, hp.lr_alpha);
+  if (s->ntiles[kTilesBackF32])
+    hipLaunchKernelGGL((fira_backproject_kernel<0, float>), grid8(s->ntiles[kTilesBackF32]), blk, FIRA_LDS_BYTES, q,
+                       ctx->d_mats, ctx->d_scal, s->d_ents, s->d_tiles[kTilesBackF32], s->ntiles[kTilesBackF32],
+                       ctx->d_partial, hp.lr_alpha);
   mark(3);
   // 4. limiter factor, state advance
   hipLaunchKernelGGL(fira_limiter_kernel, dim3(count), dim3(64), 0, q, ctx->d_scal, s->d_ents, ctx->d_partial, hp);
@@ -402,8 +437,14 @@ fira_status fira_step(fira_ctx* ctx, int count, const int* idx, void* const* dev
                      s->rowblocks);
   mark(5);
   // 6. W -= lr alpha (P Z + c k G)
-  hipLaunchKernelGGL(fira_backproject_kernel<1>, grid8(s->ntiles_back), dim3(256), 0, q, ctx->d_mats, ctx->d_scal,
-                     s->d_ents, s->d_tiles_back, s->ntiles_back, ctx->d_partial, hp.lr_alpha);
+  if (s->ntiles[kTilesBackBf16])
+    hipLaunchKernelGGL((fira_backproject_kernel<1, bf16_raw>), grid8(s->ntiles[kTilesBackBf16]), blk, FIRA_LDS_BYTES, q,
+                       ctx->d_mats, ctx->d_scal, s->d_ents, s->d_tiles[kTilesBackBf16], s->ntiles[kTilesBackBf16],
+                       ctx->d_partial, hp.lr_alpha);
+  if (s->ntiles[kTilesBackF32])
+    hipLaunchKernelGGL((fira_backproject_kernel<1, float>), grid8(s->ntiles[kTilesBackF32]), blk, FIRA_LDS_BYTES, q,
+                       ctx->d_mats, ctx->d_scal, s->d_ents, s->d_tiles[kTilesBackF32], s->ntiles[kTilesBackF32],
+                       ctx->d_partial, hp.lr_alpha);
   mark(6);
   FIRA_HIP(ctx, hipGetLastError());
   return FIRA_OK;

@@ -35,6 +35,11 @@ struct FiraMat {
   int rp, Sp;          // rank and short side rounded up to 64 (zero padded operand rows)
   int kx, dtype;       // K-expansion (1: bf16, 6: fp32 split); dtype of W and G (0 f32, 1 bf16)
   long long gx_ld;     // leading dimension of the split copy of G (fp32 matrices only)
+  // Row pitches (elements) of the library's own bf16 operand arrays.  A pitch is never a multiple of
+  // 512 bytes: rows that are a power-of-two number of bytes apart all map to the same L2 channel,
+  // and a 256-row operand tile would then be served by one channel of sixteen.
+  int lr_ld;           // Nb, Rb, Pn rows: kx*rp values + padding
+  int pt_ld;           // PT rows: kx*Sp values + padding
   // low-rank arrays, all "long-side major": row i holds the r values of factor i
   float* M;            // [L][r]   first moment
   float* V;            // [L][r]   second moment
@@ -42,11 +47,11 @@ struct FiraMat {
   float* phi;          // [L]      scaling factors k_i of this step
   float* g2;           // [L]      ||G_i||^2 (only written in Gram mode)
   float* q;            // [L]      ||R_i||^2 - 2 R_i.R_i + R_i^T (P^T P) R_i pieces (Gram mode)
-  bf16_raw* Nb;        // [L][kx*rp] N of this step, then Z = N - c k_i R_i in place (MFMA operand)
-  bf16_raw* Rb;        // [L][kx*rp] R of this step as MFMA operand
-  bf16_raw* Pn;        // [S][kx*rp] projector, rank-contiguous (operand of the back-projection)
-  bf16_raw* PT;        // [r][kx*Sp] projector transposed, short-side-contiguous (operand of R)
-  bf16_raw* Gx;        // fp32 matrices: split copy of G ([kx*Sp][gx_ld] if left, [m][kx*Sp] else)
+  bf16_raw* Nb;        // [L][lr_ld] N of this step, then Z = N - c k_i R_i in place (MFMA operand)
+  bf16_raw* Rb;        // [L][lr_ld] R of this step as MFMA operand
+  bf16_raw* Pn;        // [S][lr_ld] projector, rank-contiguous (operand of the back-projection)
+  bf16_raw* PT;        // [r][pt_ld] projector transposed, short-side-contiguous (operand of R)
+  bf16_raw* Gx;        // fp32 matrices: split copy of G ([kx*Sp][gx_ld] if left, [m][gx_ld] else)
   bf16_raw* Dm;        // [r][rp]  P^T P - I in bf16 (Gram mode)
 };
 

@@ -52,8 +52,8 @@ __device__ __forceinline__ void adam_row(const FiraMat& mt, const FiraHp& hp, fl
   gptr<const float> R = as_global<const float>(mt.Rt) + row * r;
   gptr<float> M = as_global(mt.M) + row * r;
   gptr<float> V = as_global(mt.V) + row * r;
-  gptr<bf16_raw> Nb = as_global(mt.Nb) + row * ((long long)mt.kx * mt.rp);
-  gptr<bf16_raw> Rb = as_global(mt.Rb) + row * ((long long)mt.kx * mt.rp);
+  gptr<bf16_raw> Nb = as_global(mt.Nb) + row * (long long)mt.lr_ld;
+  gptr<bf16_raw> Rb = as_global(mt.Rb) + row * (long long)mt.lr_ld;
   float nn = 0.0f, rr = 0.0f;
   for (int a = lane * VEC; a < r; a += 64 * VEC) {
     float rv[VEC], mv[VEC], vv[VEC], nv[VEC];
@@ -159,8 +159,8 @@ __global__ __launch_bounds__(64) void fira_limiter_kernel(FiraScal* __restrict__
 template <int KX>
 __device__ __forceinline__ void makez_row(const FiraMat& mt, float f, long long row) {
   const int lane = threadIdx.x & 63;
-  gptr<bf16_raw> Nb = as_global(mt.Nb) + row * ((long long)mt.kx * mt.rp);
-  gptr<const bf16_raw> Rb = as_global<const bf16_raw>(mt.Rb) + row * ((long long)mt.kx * mt.rp);
+  gptr<bf16_raw> Nb = as_global(mt.Nb) + row * (long long)mt.lr_ld;
+  gptr<const bf16_raw> Rb = as_global<const bf16_raw>(mt.Rb) + row * (long long)mt.lr_ld;
   if (KX == 1) {
     // rp is a multiple of 64 and padded entries are zero: whole 16-byte groups
     for (int a = lane * 8; a < mt.rp; a += 512) {
@@ -221,8 +221,8 @@ __global__ void fira_prep_projector_kernel(FiraMat mt, const TP* __restrict__ P)
     float x;
     if (sizeof(TP) == 2) x = bf16_to_f32(*reinterpret_cast<const bf16_raw*>(&P[idx]));
     else x = *reinterpret_cast<const float*>(&P[idx]);
-    gptr<bf16_raw> pn = as_global(mt.Pn) + s * ((long long)mt.kx * mt.rp);
-    gptr<bf16_raw> pt = as_global(mt.PT) + (long long)a * ((long long)mt.kx * mt.Sp);
+    gptr<bf16_raw> pn = as_global(mt.Pn) + s * (long long)mt.lr_ld;
+    gptr<bf16_raw> pt = as_global(mt.PT) + (long long)a * (long long)mt.pt_ld;
     if (mt.kx == 1) {
       const bf16_raw b = f32_to_bf16(x);
       pn[a] = b;
@@ -256,7 +256,7 @@ __global__ void fira_split_gradient_kernel(FiraMat mt, const float* __restrict__
       for (int p = 0; p < 6; ++p) Gx[((long long)p * mt.Sp + i) * mt.gx_ld + j] = seq[p];
     } else {         // contraction over columns j: plane p occupies columns [p*Sp, p*Sp + n)
 #pragma unroll
-      for (int p = 0; p < 6; ++p) Gx[i * ((long long)mt.kx * mt.Sp) + (long long)p * mt.Sp + j] = seq[p];
+      for (int p = 0; p < 6; ++p) Gx[i * mt.gx_ld + (long long)p * mt.Sp + j] = seq[p];
     }
   }
 }

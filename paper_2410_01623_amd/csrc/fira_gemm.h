@@ -1,13 +1,22 @@
 // Grouped bf16 MFMA contractions of the Fira step for gfx950 (v_mfma_f32_32x32x16_bf16).
 //
-// One 256-thread workgroup (4 wavefronts, 2 x 2) computes a 256 x 128 tile
+// One 256-thread workgroup (4 wavefronts, 2 x 2) computes a 256 x 256 tile
 //     D[a][b] = sum_k A[a][k] * B[b][k]
-// where "A" is the MFMA A operand (256 rows per tile) and "B" the MFMA B operand (128 rows).
-// Both operands are staged through LDS as [row][64 k] bf16 tiles (128 B per row, 16-byte chunks
-// XOR-swizzled by row so that fragment reads and tile writes spread over all banks).  An operand is
-// either K-contiguous in memory (row pointer + k) or, for the gradient when P multiplies from the
-// left, K-slow (element (a, k) at base[k*ld + a]); the K-slow loader reads 8 x 8 blocks with
-// row-contiguous 16-byte loads and transposes them in registers before the LDS write.
+// where "A" is the MFMA A operand and "B" the MFMA B operand; each wavefront owns 128 (A) x 128 (B),
+// i.e. 256 accumulator registers, which is the largest register tile and therefore the fewest LDS
+// fragment reads per MFMA (0.5).  One workgroup runs per CU, one wavefront per SIMD with the full
+// 512-register budget; latency is hidden inside the wavefront: fragments of the next k-slice are
+// read from LDS while the current slice is multiplied, and global loads run two K steps ahead.
+// Both operands are staged through LDS as
+// [row][64 k] bf16 tiles (128 B per row, 16-byte chunks XOR-swizzled by row so that fragment reads
+// and tile writes spread over all banks).  LDS holds two K stages (2 x 64 KB); two more stages are
+// in flight in registers, so a global load has two full K steps to land before it is needed and
+// there is one barrier per K step.
+//
+// An operand is either K-contiguous in memory (row pointer + k) or, for the gradient when P
+// multiplies from the left, K-slow (element (a, k) at base[k*ld + a]); the K-slow loader reads
+// 4(k) x 8(a) blocks with row-contiguous 16-byte loads and transposes them in registers before the
+// LDS write.
 //
 // Accumulator layout of one 32 x 32 block (per lane, 16 floats v = 0..15):
 //     b (B row) = lane % 32,   a (A row) = 8*(v/4) + 4*(lane/32) + v%4
@@ -21,12 +30,13 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
 
 #define FIRA_BK 64
 #define FIRA_TA 256  // tile rows on the A side
-#define FIRA_TB 128  // tile rows on the B side
+#define FIRA_TB 256  // tile rows on the B side
+#define FIRA_THREADS 256
 #define FIRA_LDS_A (FIRA_TA * 128)
 #define FIRA_LDS_B (FIRA_TB * 128)
+#define FIRA_LDS_STAGE (FIRA_LDS_A + FIRA_LDS_B)
+#define FIRA_LDS_BYTES (2 * FIRA_LDS_STAGE)   // 128 KB of the CU's 160 KB
 #define FIRA_EPI_STRIDE 68   // floats per staged row: 64 + 4 (keeps 16-byte alignment, shifts banks)
-#define FIRA_LDS_EPI (4 * 32 * FIRA_EPI_STRIDE * 4)
-#define FIRA_LDS_BYTES (FIRA_LDS_EPI > (FIRA_LDS_A + FIRA_LDS_B) ? FIRA_LDS_EPI : (FIRA_LDS_A + FIRA_LDS_B))
 
 __device__ __forceinline__ int lds_tile_off(int row, int chunk) {
   return row * 128 + (((chunk ^ row ^ (row >> 3)) & 7) << 4);
@@ -34,18 +44,31 @@ __device__ __forceinline__ int lds_tile_off(int row, int chunk) {
 
 // 8 consecutive bf16 of a row that has `limit` valid elements, starting at element idx; elements
 // outside [0, limit) read as zero and are never touched in memory.  No alignment assumed.
+// Branch-free for limit >= 8: the 16-byte load is moved back so that it ends inside the row and the
+// value is shifted down again, which also shifts zeros into the out-of-range positions.  (A ragged
+// chunk handled with per-element loads costs a serialized memory round trip per element.)
 __device__ __forceinline__ u32x4 load8_bf16(gptr<const bf16_raw> row, long long idx, long long limit) {
-  u32x4 v = u32x4{0u, 0u, 0u, 0u};
-  if (idx + 8 <= limit) {
-    v = *reinterpret_cast<gptr<const u32x4_a2>>(row + idx);
-  } else if (idx < limit) {
-    unsigned w[4] = {0u, 0u, 0u, 0u};
-#pragma unroll
-    for (int e = 0; e < 8; ++e)
-      if (idx + e < limit) w[e >> 1] |= ((unsigned)row[idx + e]) << ((e & 1) * 16);
-    v = u32x4{w[0], w[1], w[2], w[3]};
+  if (limit >= 8) {
+    long long start = idx < limit - 8 ? idx : limit - 8;
+    if (start < 0) start = 0;
+    const u32x4 v = *reinterpret_cast<gptr<const u32x4_a2>>(row + start);
+    const long long d = idx - start;          // elements to shift out at the low end
+    const unsigned sh = d < 8 ? (unsigned)d : 8u;
+    // 128-bit logical shift right by 16*sh bits
+    const unsigned long long lo = ((unsigned long long)v.y << 32) | v.x, hi = ((unsigned long long)v.w << 32) | v.z;
+    const unsigned bits = 16u * sh;
+    unsigned long long rlo, rhi;
+    if (bits == 0) { rlo = lo; rhi = hi; }
+    else if (bits < 64) { rlo = (lo >> bits) | (hi << (64 - bits)); rhi = hi >> bits; }
+    else if (bits < 128) { rlo = hi >> (bits - 64); rhi = 0; }
+    else { rlo = 0; rhi = 0; }
+    return u32x4{(unsigned)rlo, (unsigned)(rlo >> 32), (unsigned)rhi, (unsigned)(rhi >> 32)};
   }
-  return v;
+  unsigned w[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+  for (int e = 0; e < 8; ++e)
+    if (idx + e >= 0 && idx + e < limit) w[e >> 1] |= ((unsigned)row[idx + e]) << ((e & 1) * 16);
+  return u32x4{w[0], w[1], w[2], w[3]};
 }
 
 struct GemmOperands {
@@ -59,69 +82,42 @@ struct GemmOperands {
   int KB;             // readable row length of B (>= KA rounded up to 64)
 };
 
+// Thread -> tile element mapping of the loaders (256 threads, 16-byte chunks of 8 bf16).
+//   K-contiguous: chunk column cc = t & 7, rows rr + 32*i, rr = t >> 3, i = 0..7.
+//   K-slow:       8(k) x 8(a) block per thread: a-block ib = t & 31 (32 lanes read 512 contiguous
+//                 bytes of one gradient row), k-block kb = t >> 5.
+
+// Guarded tile loads (edge tiles, ragged K).  Rows beyond the operand are clamped to its last row
+// (their products land in accumulators that are never stored), so every load is issued on every
+// path; ragged 8-element chunks are realigned in registers (load8_bf16).
 template <bool AKSLOW>
-__device__ __forceinline__ void gemm_load_tiles(u32x4 (&ra)[8], u32x4 (&rb)[4], const GemmOperands& g, int k0) {
+__device__ __forceinline__ void gemm_load_guarded(u32x4 (&ra)[8], u32x4 (&rb)[8], const GemmOperands& g, int k0) {
   const int t = threadIdx.x;
+  const int cc = t & 7, rr = t >> 3;
+  const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
   if (AKSLOW) {
     const int ib = t & 31, kb = t >> 5;
     const long long a = (long long)g.a_row0 + 8 * ib;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       const int k = k0 + 8 * kb + j;
-      ra[j] = (k < g.KA) ? load8_bf16(g.A + (long long)k * g.lda, a, g.a_rows) : u32x4{0u, 0u, 0u, 0u};
+      const int kc = k < g.KA ? k : g.KA - 1;
+      const u32x4 v = load8_bf16(g.A + (long long)kc * g.lda, a, g.a_rows);
+      ra[j] = k < g.KA ? v : zero;
     }
   } else {
-    const int cc = t & 7, rr = t >> 3;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int row = g.a_row0 + rr + 32 * i;
-      ra[i] = (row < g.a_rows) ? load8_bf16(g.A + (long long)row * g.lda, k0 + 8 * cc, g.KA)
-                               : u32x4{0u, 0u, 0u, 0u};
+      const int rc = row < g.a_rows ? row : g.a_rows - 1;
+      ra[i] = load8_bf16(g.A + (long long)rc * g.lda, k0 + 8 * cc, g.KA);
     }
   }
-  {
-    const int cc = t & 7, rr = t >> 3;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int row = g.b_row0 + rr + 32 * i;
-      rb[i] = (row < g.b_rows) ? load8_bf16(g.B + (long long)row * g.ldb, k0 + 8 * cc, g.KB)
-                               : u32x4{0u, 0u, 0u, 0u};
-    }
-  }
-}
-
-template <bool AKSLOW>
-__device__ __forceinline__ void gemm_store_tiles(char* lds, const u32x4 (&ra)[8], const u32x4 (&rb)[4]) {
-  const int t = threadIdx.x;
-  char* la = lds;
-  char* lb = lds + FIRA_LDS_A;
-  if (AKSLOW) {
-    // ra[j] holds row k = 8*kb + j of an 8(k) x 8(a) block; emit, for each a, the 8 k values.
-    const int ib = t & 31, kb = t >> 5;
-    const unsigned* in = reinterpret_cast<const unsigned*>(&ra[0]);  // in[4*j + d]: a = 2d, 2d+1
-#pragma unroll
-    for (int ii = 0; ii < 8; ++ii) {
-      unsigned w[4];
-#pragma unroll
-      for (int d = 0; d < 4; ++d) {
-        const unsigned x = in[4 * (2 * d) + (ii >> 1)];      // k = 2d
-        const unsigned y = in[4 * (2 * d + 1) + (ii >> 1)];  // k = 2d + 1
-        w[d] = (ii & 1) ? ((x >> 16) | (y & 0xffff0000u)) : ((x & 0xffffu) | (y << 16));
-      }
-      const int row = 8 * ib + ii;
-      *reinterpret_cast<u32x4*>(la + lds_tile_off(row, kb)) = u32x4{w[0], w[1], w[2], w[3]};
-    }
-  } else {
-    const int cc = t & 7, rr = t >> 3;
-#pragma unroll
-    for (int i = 0; i < 8; ++i)
-      *reinterpret_cast<u32x4*>(la + lds_tile_off(rr + 32 * i, cc)) = ra[i];
-  }
-  {
-    const int cc = t & 7, rr = t >> 3;
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-      *reinterpret_cast<u32x4*>(lb + lds_tile_off(rr + 32 * i, cc)) = rb[i];
+  for (int i = 0; i < 8; ++i) {
+    const int row = g.b_row0 + rr + 32 * i;
+    const int rc = row < g.b_rows ? row : g.b_rows - 1;
+    rb[i] = load8_bf16(g.B + (long long)rc * g.ldb, k0 + 8 * cc, g.KB);
   }
 }
 
@@ -131,7 +127,7 @@ __device__ __forceinline__ void gemm_store_tiles(char* lds, const u32x4 (&ra)[8]
 template <bool AKSLOW>
 struct FastLoader {
   gptr<const bf16_raw> pa, pb;
-  unsigned offa[8], offb[4];
+  unsigned offa[8], offb[8];
   long long stepa;
   __device__ __forceinline__ FastLoader(const GemmOperands& g) {
     const int t = threadIdx.x;
@@ -150,92 +146,177 @@ struct FastLoader {
     }
     pb = g.B + (long long)g.b_row0 * g.ldb;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) offb[i] = (unsigned)((rr + 32 * i) * g.ldb + 8 * cc);
+    for (int i = 0; i < 8; ++i) offb[i] = (unsigned)((rr + 32 * i) * g.ldb + 8 * cc);
   }
-  __device__ __forceinline__ void load(u32x4 (&ra)[8], u32x4 (&rb)[4]) {
+  // Loads the current stage and advances to the next one while `more` is true.  The loads are
+  // unconditional (a request past the last stage re-reads the last stage and is never used), so
+  // the number of loads in flight is the same on every path and the compiler can wait for exactly
+  // the older of two outstanding stages.
+  __device__ __forceinline__ void load(u32x4 (&ra)[8], u32x4 (&rb)[8], bool more) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) ra[i] = *reinterpret_cast<gptr<const u32x4_a2>>(pa + offa[i]);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) rb[i] = *reinterpret_cast<gptr<const u32x4_a2>>(pb + offb[i]);
-    pa += stepa;
-    pb += FIRA_BK;
+    for (int i = 0; i < 8; ++i) rb[i] = *reinterpret_cast<gptr<const u32x4_a2>>(pb + offb[i]);
+    pa += more ? stepa : 0;
+    pb += more ? FIRA_BK : 0;
   }
 };
+
+template <bool AKSLOW>
+__device__ __forceinline__ void gemm_store_tiles(char* stage, const u32x4 (&ra)[8], const u32x4 (&rb)[8]) {
+  const int t = threadIdx.x;
+  const int cc = t & 7, rr = t >> 3;
+  char* la = stage;
+  char* lb = stage + FIRA_LDS_A;
+  if (AKSLOW) {
+    // ra[j] holds row k = 8*kb + j of an 8(k) x 8(a) block; emit, for each a, the 8 k values.
+    const int ib = t & 31, kb = t >> 5;
+    unsigned in[32];   // in[4*j + d]: row j, a = 2d (low half) and 2d+1 (high half)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) { in[4 * j] = ra[j].x; in[4 * j + 1] = ra[j].y; in[4 * j + 2] = ra[j].z; in[4 * j + 3] = ra[j].w; }
+#pragma unroll
+    for (int ii = 0; ii < 8; ++ii) {
+      unsigned w[4];
+#pragma unroll
+      for (int d = 0; d < 4; ++d) {
+        const unsigned x = in[4 * (2 * d) + (ii >> 1)];      // k = 2d
+        const unsigned y = in[4 * (2 * d + 1) + (ii >> 1)];  // k = 2d + 1
+        w[d] = (ii & 1) ? ((x >> 16) | (y & 0xffff0000u)) : ((x & 0xffffu) | (y << 16));
+      }
+      *reinterpret_cast<u32x4*>(la + lds_tile_off(8 * ib + ii, kb)) = u32x4{w[0], w[1], w[2], w[3]};
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) *reinterpret_cast<u32x4*>(la + lds_tile_off(rr + 32 * i, cc)) = ra[i];
+  }
+#pragma unroll
+  for (int i = 0; i < 8; ++i) *reinterpret_cast<u32x4*>(lb + lds_tile_off(rr + 32 * i, cc)) = rb[i];
+}
 
 __device__ __forceinline__ bool gemm_tile_is_interior(const GemmOperands& g) {
   return g.a_row0 + FIRA_TA <= g.a_rows && g.b_row0 + FIRA_TB <= g.b_rows && (g.KA % FIRA_BK) == 0;
 }
 
-__device__ __forceinline__ void gemm_compute_step(f32x16_t (&acc)[4][2], const char* la, const char* lb) {
+// One K step (64) of the wave's 128 x 128 sub-tile: 4 k-slices of 8 fragment reads and 16 MFMAs;
+// the fragments of slice kk+1 are requested before slice kk is multiplied.
+struct Frags { bf16x8_t a[4], b[4]; };
+__device__ __forceinline__ void gemm_read_frags(Frags& f, const char* stage, int kk) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave & 1, wn = wave >> 1;
+  const char* la = stage;
+  const char* lb = stage + FIRA_LDS_A;
+  const int chunk = 2 * kk + (lane >> 5);
 #pragma unroll
-  for (int kk = 0; kk < 4; ++kk) {
-    const int chunk = 2 * kk + (lane >> 5);
-    bf16x8_t af[4], bfr[2];
-#pragma unroll
-    for (int tm = 0; tm < 4; ++tm)
-      af[tm] = *reinterpret_cast<const bf16x8_t*>(la + lds_tile_off(wm * 128 + 32 * tm + (lane & 31), chunk));
-#pragma unroll
-    for (int tn = 0; tn < 2; ++tn)
-      bfr[tn] = *reinterpret_cast<const bf16x8_t*>(lb + lds_tile_off(wn * 64 + 32 * tn + (lane & 31), chunk));
-#pragma unroll
-    for (int tm = 0; tm < 4; ++tm)
-#pragma unroll
-      for (int tn = 0; tn < 2; ++tn)
-        acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[tm], bfr[tn], acc[tm][tn], 0, 0, 0);
+  for (int t = 0; t < 4; ++t) {
+    f.a[t] = *reinterpret_cast<const bf16x8_t*>(la + lds_tile_off(wm * 128 + 32 * t + (lane & 31), chunk));
+    f.b[t] = *reinterpret_cast<const bf16x8_t*>(lb + lds_tile_off(wn * 128 + 32 * t + (lane & 31), chunk));
   }
 }
-
-// acc[tm][tn]: wave (wm, wn) = (wave & 1, wave >> 1) owns A rows wm*128 + 32*tm + .., B rows wn*64 + 32*tn + ..
-// Single LDS buffer, register prefetch: the global loads of step k+1 are in flight while step k is
-// multiplied; two workgroups per CU overlap one another's barriers.
-template <bool AKSLOW>
-__device__ __forceinline__ void gemm_mainloop(f32x16_t (&acc)[4][2], char* lds, const GemmOperands& g) {
+__device__ __forceinline__ void gemm_mfma_slice(f32x16_t (&acc)[4][4], const Frags& f) {
 #pragma unroll
   for (int tm = 0; tm < 4; ++tm)
 #pragma unroll
-    for (int tn = 0; tn < 2; ++tn)
+    for (int tn = 0; tn < 4; ++tn)
+      acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[tm], f.b[tn], acc[tm][tn], 0, 0, 0);
+}
+__device__ __forceinline__ void gemm_compute_step(f32x16_t (&acc)[4][4], const char* stage) {
+  Frags f0, f1;
+  gemm_read_frags(f0, stage, 0);
+  gemm_read_frags(f1, stage, 1);
+  gemm_mfma_slice(acc, f0);
+  gemm_read_frags(f0, stage, 2);
+  gemm_mfma_slice(acc, f1);
+  gemm_read_frags(f1, stage, 3);
+  gemm_mfma_slice(acc, f0);
+  gemm_mfma_slice(acc, f1);
+}
+
+// acc[tm][tn]: wave (wm, wn) = (wave & 1, wave >> 1) owns A rows wm*128 + 32*tm + .., B rows wn*128 + 32*tn + ..
+//
+// Pipeline (stage s = K range [64 s, 64 s + 64)):
+//   before iteration s: LDS[s & 1] holds stage s; registers R[(s+1)&1] hold stage s+1 (requested one
+//   iteration ago), R[s & 1] hold stage s+2 (just requested).
+//   iteration s: write R[(s+1)&1] into LDS[(s+1)&1]; request stage s+3 into R[(s+1)&1]; multiply
+//   LDS[s&1]; barrier.
+template <bool AKSLOW>
+__device__ __forceinline__ void gemm_pipeline_fast(f32x16_t (&acc)[4][4], char* lds, const GemmOperands& g) {
+  const int KT = g.KA / FIRA_BK;
+  u32x4 ra0[8], rb0[8], ra1[8], rb1[8];
+  FastLoader<AKSLOW> fl(g);
+  int knext = 0;
+  fl.load(ra0, rb0, ++knext < KT);         // stage 0
+  fl.load(ra1, rb1, ++knext < KT);         // stage 1
+  gemm_store_tiles<AKSLOW>(lds, ra0, rb0);
+  fl.load(ra0, rb0, ++knext < KT);         // stage 2
+  __syncthreads();
+  for (int s = 0; s < KT; s += 2) {
+    gemm_store_tiles<AKSLOW>(lds + FIRA_LDS_STAGE, ra1, rb1);      // stage s+1 (unused if s+1 == KT)
+    fl.load(ra1, rb1, ++knext < KT);                               // stage s+3
+    gemm_compute_step(acc, lds);                                   // stage s from LDS[0]
+    __syncthreads();
+    gemm_store_tiles<AKSLOW>(lds, ra0, rb0);                       // stage s+2
+    fl.load(ra0, rb0, ++knext < KT);                               // stage s+4
+    if (s + 1 < KT) gemm_compute_step(acc, lds + FIRA_LDS_STAGE);  // stage s+1 from LDS[1]
+    __syncthreads();
+  }
+}
+
+// Same schedule with bounds-checked loads (edge tiles, ragged K).  A request past the last stage
+// re-reads the last stage and is never used.
+template <bool AKSLOW>
+__device__ __forceinline__ void gemm_pipeline_guarded(f32x16_t (&acc)[4][4], char* lds, const GemmOperands& g) {
+  const int KT = (g.KA + FIRA_BK - 1) / FIRA_BK;
+  u32x4 ra0[8], rb0[8], ra1[8], rb1[8];
+  int knext = 0;
+  auto request = [&](u32x4 (&ra)[8], u32x4 (&rb)[8]) {
+    const int ks = knext < KT ? knext : KT - 1;
+    gemm_load_guarded<AKSLOW>(ra, rb, g, ks * FIRA_BK);
+    ++knext;
+  };
+  request(ra0, rb0);                       // stage 0
+  request(ra1, rb1);                       // stage 1
+  gemm_store_tiles<AKSLOW>(lds, ra0, rb0);
+  request(ra0, rb0);                       // stage 2
+  __syncthreads();
+  for (int s = 0; s < KT; s += 2) {
+    gemm_store_tiles<AKSLOW>(lds + FIRA_LDS_STAGE, ra1, rb1);      // stage s+1 (unused if s+1 == KT)
+    request(ra1, rb1);                                             // stage s+3
+    gemm_compute_step(acc, lds);                                   // stage s from LDS[0]
+    __syncthreads();
+    gemm_store_tiles<AKSLOW>(lds, ra0, rb0);                       // stage s+2
+    request(ra0, rb0);                                             // stage s+4
+    if (s + 1 < KT) gemm_compute_step(acc, lds + FIRA_LDS_STAGE);  // stage s+1 from LDS[1]
+    __syncthreads();
+  }
+}
+
+template <bool AKSLOW>
+__device__ __forceinline__ void gemm_mainloop(f32x16_t (&acc)[4][4], char* lds, const GemmOperands& g) {
+#pragma unroll
+  for (int tm = 0; tm < 4; ++tm)
+#pragma unroll
+    for (int tn = 0; tn < 4; ++tn)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[tm][tn][v] = 0.0f;
-
-  const int KT = (g.KA + FIRA_BK - 1) / FIRA_BK;
-  u32x4 ra[8], rb[4];
-  const char* la = lds;
-  const char* lb = lds + FIRA_LDS_A;
-  if (gemm_tile_is_interior(g)) {
-    FastLoader<AKSLOW> ld(g);
-    ld.load(ra, rb);
-    for (int kt = 0; kt < KT; ++kt) {
-      gemm_store_tiles<AKSLOW>(lds, ra, rb);
-      __syncthreads();
-      if (kt + 1 < KT) ld.load(ra, rb);
-      gemm_compute_step(acc, la, lb);
-      __syncthreads();
-    }
-  } else {
-    gemm_load_tiles<AKSLOW>(ra, rb, g, 0);
-    for (int kt = 0; kt < KT; ++kt) {
-      gemm_store_tiles<AKSLOW>(lds, ra, rb);
-      __syncthreads();
-      if (kt + 1 < KT) gemm_load_tiles<AKSLOW>(ra, rb, g, (kt + 1) * FIRA_BK);
-      gemm_compute_step(acc, la, lb);
-      __syncthreads();
-    }
-  }
+  if (gemm_tile_is_interior(g))
+    gemm_pipeline_fast<AKSLOW>(acc, lds, g);
+  else
+    gemm_pipeline_guarded<AKSLOW>(acc, lds, g);
 }
 
 // ------------------------------------------------------------------------------------------------
 // Kernel 1: low-rank gradient, long-side major:  Rt[i][a] = sum_s G(s, i) P[s][a]
-//   left  (m <= n): i = column of G, s = row of G      -> A side is G read K-slow
-//   right (m >  n): i = row of G,    s = column of G   -> A side is G read K-contiguous
+//   LEFT  (m <= n): i = column of G, s = row of G      -> A side is G read K-slow
+//   RIGHT (m >  n): i = row of G,    s = column of G   -> A side is G read K-contiguous
 //   B side is PT[a][s] (rank rows, short-side contiguous).
-// Also (Gram mode) g2[i] = sum_s G(s, i)^2 is not computed here; see fira_gram.h.
+// One instantiation per orientation; the host keeps one tile list for each.
 // ------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256, 2) void fira_project_kernel(const FiraMat* __restrict__ mats,
-                                                              const FiraEnt* __restrict__ ents,
-                                                              const FiraTile* __restrict__ tiles, int ntiles) {
-  __shared__ __attribute__((aligned(16))) char lds[FIRA_LDS_A + FIRA_LDS_B];
+template <bool LEFT>
+__global__ __launch_bounds__(FIRA_THREADS, 1) void fira_project_kernel(const FiraMat* __restrict__ mats,
+                                                                       const FiraEnt* __restrict__ ents,
+                                                                       const FiraTile* __restrict__ tiles,
+                                                                       int ntiles) {
+  extern __shared__ __attribute__((aligned(16))) char lds[];
   const int ti = xcd_chunked_index(blockIdx.x, ntiles);
   if (ti < 0) return;
   const FiraTile tile = tiles[ti];
@@ -248,7 +329,7 @@ __global__ __launch_bounds__(256, 2) void fira_project_kernel(const FiraMat* __r
   g.b_row0 = tile.tb * FIRA_TB;
   g.b_rows = mt.r;
   g.B = as_global<const bf16_raw>(mt.PT);
-  g.ldb = (long long)mt.kx * mt.Sp;
+  g.ldb = mt.pt_ld;
   g.KB = mt.kx * mt.Sp;
   if (mt.kx == 1) {
     g.A = as_global(reinterpret_cast<const bf16_raw*>(ent.G));
@@ -256,14 +337,11 @@ __global__ __launch_bounds__(256, 2) void fira_project_kernel(const FiraMat* __r
     g.KA = mt.S;
   } else {
     g.A = as_global<const bf16_raw>(mt.Gx);
-    g.lda = mt.left ? mt.gx_ld : (long long)mt.kx * mt.Sp;
+    g.lda = mt.gx_ld;
     g.KA = mt.kx * mt.Sp;
   }
-  f32x16_t acc[4][2];
-  if (mt.left)
-    gemm_mainloop<true>(acc, lds, g);
-  else
-    gemm_mainloop<false>(acc, lds, g);
+  f32x16_t acc[4][4];
+  gemm_mainloop<LEFT>(acc, lds, g);
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave & 1, wn = wave >> 1;
@@ -271,8 +349,8 @@ __global__ __launch_bounds__(256, 2) void fira_project_kernel(const FiraMat* __r
 #pragma unroll
   for (int tm = 0; tm < 4; ++tm)
 #pragma unroll
-    for (int tn = 0; tn < 2; ++tn) {
-      const int col = g.b_row0 + wn * 64 + 32 * tn + (lane & 31);
+    for (int tn = 0; tn < 4; ++tn) {
+      const int col = g.b_row0 + wn * 128 + 32 * tn + (lane & 31);
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int row = g.a_row0 + wm * 128 + 32 * tm + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
@@ -357,13 +435,14 @@ struct Elem8<float> {
   }
 };
 
-// Epilogue of the rank-axis contractions.  The wave's 64(i) x 128(j) accumulators are processed as
-// four 32 x 64 slabs; the G (and W) values of slab s+1 are requested from HBM before slab s is
+// Epilogue of the rank-axis contractions.  The wave's 128(i) x 128(j) accumulators are processed as
+// eight 32 x 64 slabs; the G (and W) values of slab s+1 are requested from HBM before slab s is
 // re-laid out through LDS and consumed, so their latency overlaps the LDS work.
 template <int MODE, typename T, bool INTERIOR>
-__device__ __forceinline__ float backproject_epilogue(f32x16_t (&acc)[4][2], char* lds, const FiraMat& mt,
+__device__ __forceinline__ float backproject_epilogue(f32x16_t (&acc)[4][4], char* lds, const FiraMat& mt,
                                                       const FiraEnt& ent, int i0, int j0, float c, float lr_alpha) {
   typedef typename Elem8<T>::Raw Raw;
+  constexpr bool PIPE = true;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave & 1, wn = wave >> 1;
   float* buf = reinterpret_cast<float*>(lds) + wave * (32 * FIRA_EPI_STRIDE);
@@ -372,27 +451,26 @@ __device__ __forceinline__ float backproject_epilogue(f32x16_t (&acc)[4][2], cha
   gptr<const float> phi = as_global<const float>(mt.phi);
   const int jl = 8 * (lane & 7);              // this lane's 8 columns inside the staged 64
   const int il0 = lane >> 3;                  // this lane's row inside each group of 8 staged rows
-  Raw gbuf[sizeof(T) == 2 ? 2 : 1][4], wbuf[sizeof(T) == 2 ? 2 : 1][4];
+  Raw gbuf[PIPE ? 2 : 1][4], wbuf[PIPE ? 2 : 1][4];
   auto preload = [&](int s, Raw (&gr)[4], Raw (&wr)[4]) {
-    const int th = s >> 1, tn = s & 1;
+    const int th = s >> 2, tn = s & 3;
     const long long j = (long long)j0 + wm * 128 + 64 * th + jl;
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
-      const long long i = (long long)i0 + wn * 64 + 32 * tn + 8 * p + il0;
+      const long long i = (long long)i0 + wn * 128 + 32 * tn + 8 * p + il0;
       const bool ok = INTERIOR || (i < mt.m && j < mt.n);
       gr[p] = ok ? Elem8<T>::template load_raw<INTERIOR>(G + i * mt.ld, j, mt.n) : Elem8<T>::zero();
       if (MODE == 1) wr[p] = ok ? Elem8<T>::template load_raw<INTERIOR>(W + i * mt.ld, j, mt.n) : Elem8<T>::zero();
     }
   };
-  constexpr bool PIPE = sizeof(T) == 2;       // fp32 tiles would need 128 more registers: no prefetch
   if (PIPE) preload(0, gbuf[0], wbuf[0]);
   float sum = 0.0f;
   float cphi[8];
 #pragma unroll
-  for (int s = 0; s < 4; ++s) {
-    const int th = s >> 1, tn = s & 1;
+  for (int s = 0; s < 8; ++s) {
+    const int th = s >> 2, tn = s & 3;
     const long long j = (long long)j0 + wm * 128 + 64 * th + jl;
-    if (PIPE && s + 1 < 4) preload(s + 1, gbuf[PIPE ? ((s + 1) & 1) : 0], wbuf[PIPE ? ((s + 1) & 1) : 0]);
+    if (PIPE && s + 1 < 8) preload(s + 1, gbuf[PIPE ? ((s + 1) & 1) : 0], wbuf[PIPE ? ((s + 1) & 1) : 0]);
     if (!PIPE) preload(s, gbuf[0], wbuf[0]);
     if (mt.left && tn == 0) {
 #pragma unroll
@@ -411,7 +489,7 @@ __device__ __forceinline__ float backproject_epilogue(f32x16_t (&acc)[4][2], cha
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
       const int il = 8 * p + il0;
-      const long long i = (long long)i0 + wn * 64 + 32 * tn + il;
+      const long long i = (long long)i0 + wn * 128 + 32 * tn + il;
       if (INTERIOR || (i < mt.m && j < mt.n)) {
         const f32x4 u0 = *reinterpret_cast<const f32x4*>(buf + il * FIRA_EPI_STRIDE + jl);
         const f32x4 u1 = *reinterpret_cast<const f32x4*>(buf + il * FIRA_EPI_STRIDE + jl + 4);
@@ -442,13 +520,15 @@ __device__ __forceinline__ float backproject_epilogue(f32x16_t (&acc)[4][2], cha
   return sum;
 }
 
-template <int MODE>
-__global__ __launch_bounds__(256, 2) void fira_backproject_kernel(const FiraMat* __restrict__ mats,
-                                                                  const FiraScal* __restrict__ scal,
-                                                                  const FiraEnt* __restrict__ ents,
-                                                                  const FiraTile* __restrict__ tiles, int ntiles,
-                                                                  float* __restrict__ partial, float lr_alpha) {
-  __shared__ __attribute__((aligned(16))) char lds[FIRA_LDS_BYTES];
+// T: storage type of W and G of every matrix in the tile list (the host keeps one list per type).
+template <int MODE, typename T>
+__global__ __launch_bounds__(FIRA_THREADS, 1) void fira_backproject_kernel(const FiraMat* __restrict__ mats,
+                                                                           const FiraScal* __restrict__ scal,
+                                                                           const FiraEnt* __restrict__ ents,
+                                                                           const FiraTile* __restrict__ tiles,
+                                                                           int ntiles, float* __restrict__ partial,
+                                                                           float lr_alpha) {
+  extern __shared__ __attribute__((aligned(16))) char lds[];
   __shared__ float red[4];
   const int ti = xcd_chunked_index(blockIdx.x, ntiles);
   if (ti < 0) return;
@@ -464,22 +544,19 @@ __global__ __launch_bounds__(256, 2) void fira_backproject_kernel(const FiraMat*
   g.a_rows = mt.n;
   g.b_row0 = tile.tb * FIRA_TB;
   g.b_rows = mt.m;
-  g.lda = g.ldb = (long long)mt.kx * mt.rp;
+  g.lda = g.ldb = mt.lr_ld;
   g.KA = g.KB = mt.kx * mt.rp;
   g.A = mt.left ? lowrank : proj;
   g.B = mt.left ? proj : lowrank;
-  f32x16_t acc[4][2];
+  f32x16_t acc[4][4];
   gemm_mainloop<false>(acc, lds, g);
 
   const float c = (MODE == 0) ? 1.0f : scal[ent.mat].c;
+  const int i0 = g.b_row0, j0 = g.a_row0;
+  const bool interior = i0 + FIRA_TB <= mt.m && j0 + FIRA_TA <= mt.n;
   float sum;
-  const bool interior = g.b_row0 + FIRA_TB <= mt.m && g.a_row0 + FIRA_TA <= mt.n;
-  if (mt.dtype == 1) {
-    if (interior) sum = backproject_epilogue<MODE, bf16_raw, true>(acc, lds, mt, ent, g.b_row0, g.a_row0, c, lr_alpha);
-    else sum = backproject_epilogue<MODE, bf16_raw, false>(acc, lds, mt, ent, g.b_row0, g.a_row0, c, lr_alpha);
-  } else {
-    sum = backproject_epilogue<MODE, float, false>(acc, lds, mt, ent, g.b_row0, g.a_row0, c, lr_alpha);
-  }
+  if (interior) sum = backproject_epilogue<MODE, T, true>(acc, lds, mt, ent, i0, j0, c, lr_alpha);
+  else sum = backproject_epilogue<MODE, T, false>(acc, lds, mt, ent, i0, j0, c, lr_alpha);
 
   if (MODE == 0) {
     // deterministic workgroup reduction: xor-butterfly inside each wave, then waves in order
@@ -487,6 +564,7 @@ __global__ __launch_bounds__(256, 2) void fira_backproject_kernel(const FiraMat*
     for (int off = 32; off >= 1; off >>= 1) sum += __shfl_xor(sum, off, 64);
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = sum;
     __syncthreads();
-    if (threadIdx.x == 0) as_global(partial)[tile.part] = (red[0] + red[1]) + (red[2] + red[3]);
+    if (threadIdx.x == 0)
+      as_global(partial)[tile.part] = (red[0] + red[1]) + (red[2] + red[3]);
   }
 }
