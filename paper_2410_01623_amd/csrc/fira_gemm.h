@@ -1,17 +1,15 @@
 // Grouped bf16 MFMA contractions of the Fira step for gfx950 (v_mfma_f32_32x32x16_bf16).
 //
-// One 256-thread workgroup (4 wavefronts, 2 x 2) computes a 256 x 256 tile
+// One 512-thread workgroup (8 wavefronts, 2 x 4) computes a 256 x 256 tile
 //     D[a][b] = sum_k A[a][k] * B[b][k]
-// where "A" is the MFMA A operand and "B" the MFMA B operand; each wavefront owns 128 (A) x 128 (B),
-// i.e. 256 accumulator registers, which is the largest register tile and therefore the fewest LDS
-// fragment reads per MFMA (0.5).  One workgroup runs per CU, one wavefront per SIMD with the full
-// 512-register budget; latency is hidden inside the wavefront: fragments of the next k-slice are
-// read from LDS while the current slice is multiplied, and global loads run two K steps ahead.
+// where "A" is the MFMA A operand and "B" the MFMA B operand; each wavefront owns 128 (A) x 64 (B).
+// One workgroup runs per CU with two wavefronts per SIMD: wavefronts issue in order, so a wavefront
+// that stalls on a full memory queue or on an LDS wait would leave the matrix pipe idle if it were
+// alone on its SIMD.  The 256 x 256 tile keeps the L2 traffic at 64 KB per 8.4 MFLOP.
 // Both operands are staged through LDS as
 // [row][64 k] bf16 tiles (128 B per row, 16-byte chunks XOR-swizzled by row so that fragment reads
-// and tile writes spread over all banks).  LDS holds two K stages (2 x 64 KB); two more stages are
-// in flight in registers, so a global load has two full K steps to land before it is needed and
-// there is one barrier per K step.
+// and tile writes spread over all banks).  LDS holds two K stages (2 x 64 KB) and a third one is in
+// flight in registers, so a global load has a full K step to land and there is one barrier per K step.
 //
 // An operand is either K-contiguous in memory (row pointer + k) or, for the gradient when P
 // multiplies from the left, K-slow (element (a, k) at base[k*ld + a]); the K-slow loader reads
@@ -31,7 +29,7 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
 #define FIRA_BK 64
 #define FIRA_TA 256  // tile rows on the A side
 #define FIRA_TB 256  // tile rows on the B side
-#define FIRA_THREADS 256
+#define FIRA_THREADS 512
 #define FIRA_LDS_A (FIRA_TA * 128)
 #define FIRA_LDS_B (FIRA_TB * 128)
 #define FIRA_LDS_STAGE (FIRA_LDS_A + FIRA_LDS_B)
@@ -39,7 +37,7 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
 #define FIRA_EPI_STRIDE 68   // floats per staged row: 64 + 4 (keeps 16-byte alignment, shifts banks)
 
 __device__ __forceinline__ int lds_tile_off(int row, int chunk) {
-  return row * 128 + (((chunk ^ row ^ (row >> 3)) & 7) << 4);
+  return row * 128 + (((chunk ^ row ^ (row >> 3) ^ (row >> 6)) & 7) << 4);
 }
 
 // 8 consecutive bf16 of a row that has `limit` valid elements, starting at element idx; elements
@@ -82,40 +80,50 @@ struct GemmOperands {
   int KB;             // readable row length of B (>= KA rounded up to 64)
 };
 
-// Thread -> tile element mapping of the loaders (256 threads, 16-byte chunks of 8 bf16).
-//   K-contiguous: chunk column cc = t & 7, rows rr + 32*i, rr = t >> 3, i = 0..7.
-//   K-slow:       8(k) x 8(a) block per thread: a-block ib = t & 31 (32 lanes read 512 contiguous
-//                 bytes of one gradient row), k-block kb = t >> 5.
+// Thread -> tile element mapping of the loaders (512 threads, 16-byte chunks of 8 bf16).
+//   K-contiguous: chunk column cc = t & 7, rows rr + 64*i, rr = t >> 3, i = 0..3.
+//   K-slow:       4(k) x 8(a) block per thread: a-block ib, k-quad kq (4 consecutive k);
+//                 lane bits [0:4) -> ib low, bit 4 -> kq low, bit 5 -> ib high, bits [6:9) -> kq high,
+//                 so that 16 lanes read 256 contiguous bytes of one gradient row and the 32 lanes of a
+//                 half-wave write 16 distinct 8-byte LDS slots.
+struct KSlowMap {
+  int ib, kq;
+  __device__ __forceinline__ KSlowMap() {
+    const int t = threadIdx.x;
+    ib = (t & 15) | ((t >> 1) & 16);
+    kq = ((t >> 4) & 1) | ((t >> 5) & 14);
+  }
+};
 
 // Guarded tile loads (edge tiles, ragged K).  Rows beyond the operand are clamped to its last row
 // (their products land in accumulators that are never stored), so every load is issued on every
 // path; ragged 8-element chunks are realigned in registers (load8_bf16).
 template <bool AKSLOW>
-__device__ __forceinline__ void gemm_load_guarded(u32x4 (&ra)[8], u32x4 (&rb)[8], const GemmOperands& g, int k0) {
+__device__ __forceinline__ void gemm_load_guarded(u32x4 (&ra)[4], u32x4 (&rb)[4], const GemmOperands& g, int k0) {
   const int t = threadIdx.x;
   const int cc = t & 7, rr = t >> 3;
   const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
   if (AKSLOW) {
-    const int ib = t & 31, kb = t >> 5;
-    const long long a = (long long)g.a_row0 + 8 * ib;
+    const KSlowMap mp;
+    const long long a = (long long)g.a_row0 + 8 * mp.ib;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const int k = k0 + 8 * kb + j;
+    for (int j = 0; j < 4; ++j) {
+      const int k = k0 + 4 * mp.kq + j;
       const int kc = k < g.KA ? k : g.KA - 1;
       const u32x4 v = load8_bf16(g.A + (long long)kc * g.lda, a, g.a_rows);
       ra[j] = k < g.KA ? v : zero;
     }
   } else {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int row = g.a_row0 + rr + 32 * i;
+    for (int i = 0; i < 4; ++i) {
+      const int row = g.a_row0 + rr + 64 * i;
       const int rc = row < g.a_rows ? row : g.a_rows - 1;
       ra[i] = load8_bf16(g.A + (long long)rc * g.lda, k0 + 8 * cc, g.KA);
     }
   }
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const int row = g.b_row0 + rr + 32 * i;
+  for (int i = 0; i < 4; ++i) {
+    const int row = g.b_row0 + rr + 64 * i;
     const int rc = row < g.b_rows ? row : g.b_rows - 1;
     rb[i] = load8_bf16(g.B + (long long)rc * g.ldb, k0 + 8 * cc, g.KB);
   }
@@ -127,79 +135,78 @@ __device__ __forceinline__ void gemm_load_guarded(u32x4 (&ra)[8], u32x4 (&rb)[8]
 template <bool AKSLOW>
 struct FastLoader {
   gptr<const bf16_raw> pa, pb;
-  unsigned offa[8], offb[8];
+  unsigned offa[4], offb[4];
   long long stepa;
   __device__ __forceinline__ FastLoader(const GemmOperands& g) {
     const int t = threadIdx.x;
     const int cc = t & 7, rr = t >> 3;
     if (AKSLOW) {
-      const int ib = t & 31, kb = t >> 5;
+      const KSlowMap mp;
       pa = g.A + g.a_row0;
 #pragma unroll
-      for (int j = 0; j < 8; ++j) offa[j] = (unsigned)((8 * kb + j) * g.lda + 8 * ib);
+      for (int j = 0; j < 4; ++j) offa[j] = (unsigned)((4 * mp.kq + j) * g.lda + 8 * mp.ib);
       stepa = FIRA_BK * g.lda;
     } else {
       pa = g.A + (long long)g.a_row0 * g.lda;
 #pragma unroll
-      for (int i = 0; i < 8; ++i) offa[i] = (unsigned)((rr + 32 * i) * g.lda + 8 * cc);
+      for (int i = 0; i < 4; ++i) offa[i] = (unsigned)((rr + 64 * i) * g.lda + 8 * cc);
       stepa = FIRA_BK;
     }
     pb = g.B + (long long)g.b_row0 * g.ldb;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) offb[i] = (unsigned)((rr + 32 * i) * g.ldb + 8 * cc);
+    for (int i = 0; i < 4; ++i) offb[i] = (unsigned)((rr + 64 * i) * g.ldb + 8 * cc);
   }
   // Loads the current stage and advances to the next one while `more` is true.  The loads are
   // unconditional (a request past the last stage re-reads the last stage and is never used), so
-  // the number of loads in flight is the same on every path and the compiler can wait for exactly
-  // the older of two outstanding stages.
-  __device__ __forceinline__ void load(u32x4 (&ra)[8], u32x4 (&rb)[8], bool more) {
+  // the number of loads in flight is the same on every path.
+  __device__ __forceinline__ void load(u32x4 (&ra)[4], u32x4 (&rb)[4], bool more) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) ra[i] = *reinterpret_cast<gptr<const u32x4_a2>>(pa + offa[i]);
+    for (int i = 0; i < 4; ++i) ra[i] = *reinterpret_cast<gptr<const u32x4_a2>>(pa + offa[i]);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) rb[i] = *reinterpret_cast<gptr<const u32x4_a2>>(pb + offb[i]);
+    for (int i = 0; i < 4; ++i) rb[i] = *reinterpret_cast<gptr<const u32x4_a2>>(pb + offb[i]);
     pa += more ? stepa : 0;
     pb += more ? FIRA_BK : 0;
   }
 };
 
 template <bool AKSLOW>
-__device__ __forceinline__ void gemm_store_tiles(char* stage, const u32x4 (&ra)[8], const u32x4 (&rb)[8]) {
+__device__ __forceinline__ void gemm_store_tiles(char* stage, const u32x4 (&ra)[4], const u32x4 (&rb)[4]) {
   const int t = threadIdx.x;
   const int cc = t & 7, rr = t >> 3;
   char* la = stage;
   char* lb = stage + FIRA_LDS_A;
   if (AKSLOW) {
-    // ra[j] holds row k = 8*kb + j of an 8(k) x 8(a) block; emit, for each a, the 8 k values.
-    const int ib = t & 31, kb = t >> 5;
-    unsigned in[32];   // in[4*j + d]: row j, a = 2d (low half) and 2d+1 (high half)
-#pragma unroll
-    for (int j = 0; j < 8; ++j) { in[4 * j] = ra[j].x; in[4 * j + 1] = ra[j].y; in[4 * j + 2] = ra[j].z; in[4 * j + 3] = ra[j].w; }
+    // ra[j] holds row k = 4*kq + j of a 4(k) x 8(a) block; emit, for each a, its 4 k values (8 B).
+    const KSlowMap mp;
+    const unsigned in[16] = {ra[0].x, ra[0].y, ra[0].z, ra[0].w, ra[1].x, ra[1].y, ra[1].z, ra[1].w,
+                             ra[2].x, ra[2].y, ra[2].z, ra[2].w, ra[3].x, ra[3].y, ra[3].z, ra[3].w};  // in[4*j + d]: a = 2d, 2d+1
 #pragma unroll
     for (int ii = 0; ii < 8; ++ii) {
-      unsigned w[4];
+      unsigned w[2];
 #pragma unroll
-      for (int d = 0; d < 4; ++d) {
+      for (int d = 0; d < 2; ++d) {
         const unsigned x = in[4 * (2 * d) + (ii >> 1)];      // k = 2d
         const unsigned y = in[4 * (2 * d + 1) + (ii >> 1)];  // k = 2d + 1
         w[d] = (ii & 1) ? ((x >> 16) | (y & 0xffff0000u)) : ((x & 0xffffu) | (y << 16));
       }
-      *reinterpret_cast<u32x4*>(la + lds_tile_off(8 * ib + ii, kb)) = u32x4{w[0], w[1], w[2], w[3]};
+      const int row = 8 * mp.ib + ii;
+      *reinterpret_cast<u32x2*>(la + lds_tile_off(row, mp.kq >> 1) + 8 * (mp.kq & 1)) = u32x2{w[0], w[1]};
     }
   } else {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) *reinterpret_cast<u32x4*>(la + lds_tile_off(rr + 32 * i, cc)) = ra[i];
+    for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4*>(la + lds_tile_off(rr + 64 * i, cc)) = ra[i];
   }
 #pragma unroll
-  for (int i = 0; i < 8; ++i) *reinterpret_cast<u32x4*>(lb + lds_tile_off(rr + 32 * i, cc)) = rb[i];
+  for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4*>(lb + lds_tile_off(rr + 64 * i, cc)) = rb[i];
 }
 
 __device__ __forceinline__ bool gemm_tile_is_interior(const GemmOperands& g) {
   return g.a_row0 + FIRA_TA <= g.a_rows && g.b_row0 + FIRA_TB <= g.b_rows && (g.KA % FIRA_BK) == 0;
 }
 
-// One K step (64) of the wave's 128 x 128 sub-tile: 4 k-slices of 8 fragment reads and 16 MFMAs;
+// One K step (64) of the wave's 128 x 64 sub-tile: 4 k-slices of 6 fragment reads and 8 MFMAs;
 // the fragments of slice kk+1 are requested before slice kk is multiplied.
-struct Frags { bf16x8_t a[4], b[4]; };
+struct Frags { bf16x8_t a[4], b[2]; };
 __device__ __forceinline__ void gemm_read_frags(Frags& f, const char* stage, int kk) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave & 1, wn = wave >> 1;
@@ -207,19 +214,20 @@ __device__ __forceinline__ void gemm_read_frags(Frags& f, const char* stage, int
   const char* lb = stage + FIRA_LDS_A;
   const int chunk = 2 * kk + (lane >> 5);
 #pragma unroll
-  for (int t = 0; t < 4; ++t) {
+  for (int t = 0; t < 4; ++t)
     f.a[t] = *reinterpret_cast<const bf16x8_t*>(la + lds_tile_off(wm * 128 + 32 * t + (lane & 31), chunk));
-    f.b[t] = *reinterpret_cast<const bf16x8_t*>(lb + lds_tile_off(wn * 128 + 32 * t + (lane & 31), chunk));
-  }
+#pragma unroll
+  for (int t = 0; t < 2; ++t)
+    f.b[t] = *reinterpret_cast<const bf16x8_t*>(lb + lds_tile_off(wn * 64 + 32 * t + (lane & 31), chunk));
 }
-__device__ __forceinline__ void gemm_mfma_slice(f32x16_t (&acc)[4][4], const Frags& f) {
+__device__ __forceinline__ void gemm_mfma_slice(f32x16_t (&acc)[4][2], const Frags& f) {
 #pragma unroll
   for (int tm = 0; tm < 4; ++tm)
 #pragma unroll
-    for (int tn = 0; tn < 4; ++tn)
+    for (int tn = 0; tn < 2; ++tn)
       acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[tm], f.b[tn], acc[tm][tn], 0, 0, 0);
 }
-__device__ __forceinline__ void gemm_compute_step(f32x16_t (&acc)[4][4], const char* stage) {
+__device__ __forceinline__ void gemm_compute_step(f32x16_t (&acc)[4][2], const char* stage) {
   Frags f0, f1;
   gemm_read_frags(f0, stage, 0);
   gemm_read_frags(f1, stage, 1);
@@ -231,77 +239,52 @@ __device__ __forceinline__ void gemm_compute_step(f32x16_t (&acc)[4][4], const c
   gemm_mfma_slice(acc, f1);
 }
 
-// acc[tm][tn]: wave (wm, wn) = (wave & 1, wave >> 1) owns A rows wm*128 + 32*tm + .., B rows wn*128 + 32*tn + ..
+// acc[tm][tn]: wave (wm, wn) = (wave & 1, wave >> 1) owns A rows wm*128 + 32*tm + .., B rows wn*64 + 32*tn + ..
 //
 // Pipeline (stage s = K range [64 s, 64 s + 64)):
-//   before iteration s: LDS[s & 1] holds stage s; registers R[(s+1)&1] hold stage s+1 (requested one
-//   iteration ago), R[s & 1] hold stage s+2 (just requested).
-//   iteration s: write R[(s+1)&1] into LDS[(s+1)&1]; request stage s+3 into R[(s+1)&1]; multiply
-//   LDS[s&1]; barrier.
-template <bool AKSLOW>
-__device__ __forceinline__ void gemm_pipeline_fast(f32x16_t (&acc)[4][4], char* lds, const GemmOperands& g) {
-  const int KT = g.KA / FIRA_BK;
-  u32x4 ra0[8], rb0[8], ra1[8], rb1[8];
+//   before iteration s: LDS[s & 1] holds stage s; the registers hold stage s+1 (requested one
+//   iteration ago).
+//   iteration s: write the registers into LDS[(s+1)&1]; request stage s+2; multiply LDS[s&1]; barrier.
+template <bool AKSLOW, bool FAST>
+__device__ __forceinline__ void gemm_pipeline(f32x16_t (&acc)[4][2], char* lds, const GemmOperands& g) {
+  const int KT = (g.KA + FIRA_BK - 1) / FIRA_BK;
+  u32x4 ra[4], rb[4];
   FastLoader<AKSLOW> fl(g);
   int knext = 0;
-  fl.load(ra0, rb0, ++knext < KT);         // stage 0
-  fl.load(ra1, rb1, ++knext < KT);         // stage 1
-  gemm_store_tiles<AKSLOW>(lds, ra0, rb0);
-  fl.load(ra0, rb0, ++knext < KT);         // stage 2
-  __syncthreads();
-  for (int s = 0; s < KT; s += 2) {
-    gemm_store_tiles<AKSLOW>(lds + FIRA_LDS_STAGE, ra1, rb1);      // stage s+1 (unused if s+1 == KT)
-    fl.load(ra1, rb1, ++knext < KT);                               // stage s+3
-    gemm_compute_step(acc, lds);                                   // stage s from LDS[0]
-    __syncthreads();
-    gemm_store_tiles<AKSLOW>(lds, ra0, rb0);                       // stage s+2
-    fl.load(ra0, rb0, ++knext < KT);                               // stage s+4
-    if (s + 1 < KT) gemm_compute_step(acc, lds + FIRA_LDS_STAGE);  // stage s+1 from LDS[1]
-    __syncthreads();
-  }
-}
-
-// Same schedule with bounds-checked loads (edge tiles, ragged K).  A request past the last stage
-// re-reads the last stage and is never used.
-template <bool AKSLOW>
-__device__ __forceinline__ void gemm_pipeline_guarded(f32x16_t (&acc)[4][4], char* lds, const GemmOperands& g) {
-  const int KT = (g.KA + FIRA_BK - 1) / FIRA_BK;
-  u32x4 ra0[8], rb0[8], ra1[8], rb1[8];
-  int knext = 0;
-  auto request = [&](u32x4 (&ra)[8], u32x4 (&rb)[8]) {
-    const int ks = knext < KT ? knext : KT - 1;
-    gemm_load_guarded<AKSLOW>(ra, rb, g, ks * FIRA_BK);
+  auto request = [&]() {
+    if (FAST) {
+      fl.load(ra, rb, knext + 1 < KT);
+    } else {
+      gemm_load_guarded<AKSLOW>(ra, rb, g, (knext < KT ? knext : KT - 1) * FIRA_BK);
+    }
     ++knext;
   };
-  request(ra0, rb0);                       // stage 0
-  request(ra1, rb1);                       // stage 1
-  gemm_store_tiles<AKSLOW>(lds, ra0, rb0);
-  request(ra0, rb0);                       // stage 2
+  request();                                   // stage 0
+  gemm_store_tiles<AKSLOW>(lds, ra, rb);
+  request();                                   // stage 1
   __syncthreads();
-  for (int s = 0; s < KT; s += 2) {
-    gemm_store_tiles<AKSLOW>(lds + FIRA_LDS_STAGE, ra1, rb1);      // stage s+1 (unused if s+1 == KT)
-    request(ra1, rb1);                                             // stage s+3
-    gemm_compute_step(acc, lds);                                   // stage s from LDS[0]
-    __syncthreads();
-    gemm_store_tiles<AKSLOW>(lds, ra0, rb0);                       // stage s+2
-    request(ra0, rb0);                                             // stage s+4
-    if (s + 1 < KT) gemm_compute_step(acc, lds + FIRA_LDS_STAGE);  // stage s+1 from LDS[1]
+  for (int s = 0; s < KT; ++s) {
+    char* cur = lds + (s & 1) * FIRA_LDS_STAGE;
+    char* nxt = lds + ((s + 1) & 1) * FIRA_LDS_STAGE;
+    gemm_store_tiles<AKSLOW>(nxt, ra, rb);     // stage s+1 (a repeat of the last stage at the end)
+    request();                                 // stage s+2
+    gemm_compute_step(acc, cur);               // stage s
     __syncthreads();
   }
 }
 
 template <bool AKSLOW>
-__device__ __forceinline__ void gemm_mainloop(f32x16_t (&acc)[4][4], char* lds, const GemmOperands& g) {
+__device__ __forceinline__ void gemm_mainloop(f32x16_t (&acc)[4][2], char* lds, const GemmOperands& g) {
 #pragma unroll
   for (int tm = 0; tm < 4; ++tm)
 #pragma unroll
-    for (int tn = 0; tn < 4; ++tn)
+    for (int tn = 0; tn < 2; ++tn)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[tm][tn][v] = 0.0f;
   if (gemm_tile_is_interior(g))
-    gemm_pipeline_fast<AKSLOW>(acc, lds, g);
+    gemm_pipeline<AKSLOW, true>(acc, lds, g);
   else
-    gemm_pipeline_guarded<AKSLOW>(acc, lds, g);
+    gemm_pipeline<AKSLOW, false>(acc, lds, g);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -312,7 +295,7 @@ __device__ __forceinline__ void gemm_mainloop(f32x16_t (&acc)[4][4], char* lds, 
 // One instantiation per orientation; the host keeps one tile list for each.
 // ------------------------------------------------------------------------------------------------
 template <bool LEFT>
-__global__ __launch_bounds__(FIRA_THREADS, 1) void fira_project_kernel(const FiraMat* __restrict__ mats,
+__global__ __launch_bounds__(FIRA_THREADS, 2) void fira_project_kernel(const FiraMat* __restrict__ mats,
                                                                        const FiraEnt* __restrict__ ents,
                                                                        const FiraTile* __restrict__ tiles,
                                                                        int ntiles) {
@@ -340,7 +323,7 @@ __global__ __launch_bounds__(FIRA_THREADS, 1) void fira_project_kernel(const Fir
     g.lda = mt.gx_ld;
     g.KA = mt.kx * mt.Sp;
   }
-  f32x16_t acc[4][4];
+  f32x16_t acc[4][2];
   gemm_mainloop<LEFT>(acc, lds, g);
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -349,8 +332,8 @@ __global__ __launch_bounds__(FIRA_THREADS, 1) void fira_project_kernel(const Fir
 #pragma unroll
   for (int tm = 0; tm < 4; ++tm)
 #pragma unroll
-    for (int tn = 0; tn < 4; ++tn) {
-      const int col = g.b_row0 + wn * 128 + 32 * tn + (lane & 31);
+    for (int tn = 0; tn < 2; ++tn) {
+      const int col = g.b_row0 + wn * 64 + 32 * tn + (lane & 31);
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int row = g.a_row0 + wm * 128 + 32 * tm + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
@@ -435,14 +418,14 @@ struct Elem8<float> {
   }
 };
 
-// Epilogue of the rank-axis contractions.  The wave's 128(i) x 128(j) accumulators are processed as
-// eight 32 x 64 slabs; the G (and W) values of slab s+1 are requested from HBM before slab s is
+// Epilogue of the rank-axis contractions.  The wave's 64(i) x 128(j) accumulators are processed as
+// four 32 x 64 slabs; the G (and W) values of slab s+1 are requested from HBM before slab s is
 // re-laid out through LDS and consumed, so their latency overlaps the LDS work.
 template <int MODE, typename T, bool INTERIOR>
-__device__ __forceinline__ float backproject_epilogue(f32x16_t (&acc)[4][4], char* lds, const FiraMat& mt,
+__device__ __forceinline__ float backproject_epilogue(f32x16_t (&acc)[4][2], char* lds, const FiraMat& mt,
                                                       const FiraEnt& ent, int i0, int j0, float c, float lr_alpha) {
   typedef typename Elem8<T>::Raw Raw;
-  constexpr bool PIPE = true;
+  constexpr bool PIPE = sizeof(T) == 2;       // fp32 tiles would need 64 more registers: no prefetch
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave & 1, wn = wave >> 1;
   float* buf = reinterpret_cast<float*>(lds) + wave * (32 * FIRA_EPI_STRIDE);
@@ -453,11 +436,11 @@ __device__ __forceinline__ float backproject_epilogue(f32x16_t (&acc)[4][4], cha
   const int il0 = lane >> 3;                  // this lane's row inside each group of 8 staged rows
   Raw gbuf[PIPE ? 2 : 1][4], wbuf[PIPE ? 2 : 1][4];
   auto preload = [&](int s, Raw (&gr)[4], Raw (&wr)[4]) {
-    const int th = s >> 2, tn = s & 3;
+    const int th = s >> 1, tn = s & 1;
     const long long j = (long long)j0 + wm * 128 + 64 * th + jl;
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
-      const long long i = (long long)i0 + wn * 128 + 32 * tn + 8 * p + il0;
+      const long long i = (long long)i0 + wn * 64 + 32 * tn + 8 * p + il0;
       const bool ok = INTERIOR || (i < mt.m && j < mt.n);
       gr[p] = ok ? Elem8<T>::template load_raw<INTERIOR>(G + i * mt.ld, j, mt.n) : Elem8<T>::zero();
       if (MODE == 1) wr[p] = ok ? Elem8<T>::template load_raw<INTERIOR>(W + i * mt.ld, j, mt.n) : Elem8<T>::zero();
@@ -467,10 +450,10 @@ __device__ __forceinline__ float backproject_epilogue(f32x16_t (&acc)[4][4], cha
   float sum = 0.0f;
   float cphi[8];
 #pragma unroll
-  for (int s = 0; s < 8; ++s) {
-    const int th = s >> 2, tn = s & 3;
+  for (int s = 0; s < 4; ++s) {
+    const int th = s >> 1, tn = s & 1;
     const long long j = (long long)j0 + wm * 128 + 64 * th + jl;
-    if (PIPE && s + 1 < 8) preload(s + 1, gbuf[PIPE ? ((s + 1) & 1) : 0], wbuf[PIPE ? ((s + 1) & 1) : 0]);
+    if (PIPE && s + 1 < 4) preload(s + 1, gbuf[PIPE ? ((s + 1) & 1) : 0], wbuf[PIPE ? ((s + 1) & 1) : 0]);
     if (!PIPE) preload(s, gbuf[0], wbuf[0]);
     if (mt.left && tn == 0) {
 #pragma unroll
@@ -489,7 +472,7 @@ __device__ __forceinline__ float backproject_epilogue(f32x16_t (&acc)[4][4], cha
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
       const int il = 8 * p + il0;
-      const long long i = (long long)i0 + wn * 128 + 32 * tn + il;
+      const long long i = (long long)i0 + wn * 64 + 32 * tn + il;
       if (INTERIOR || (i < mt.m && j < mt.n)) {
         const f32x4 u0 = *reinterpret_cast<const f32x4*>(buf + il * FIRA_EPI_STRIDE + jl);
         const f32x4 u1 = *reinterpret_cast<const f32x4*>(buf + il * FIRA_EPI_STRIDE + jl + 4);
@@ -522,14 +505,14 @@ __device__ __forceinline__ float backproject_epilogue(f32x16_t (&acc)[4][4], cha
 
 // T: storage type of W and G of every matrix in the tile list (the host keeps one list per type).
 template <int MODE, typename T>
-__global__ __launch_bounds__(FIRA_THREADS, 1) void fira_backproject_kernel(const FiraMat* __restrict__ mats,
+__global__ __launch_bounds__(FIRA_THREADS, 2) void fira_backproject_kernel(const FiraMat* __restrict__ mats,
                                                                            const FiraScal* __restrict__ scal,
                                                                            const FiraEnt* __restrict__ ents,
                                                                            const FiraTile* __restrict__ tiles,
                                                                            int ntiles, float* __restrict__ partial,
                                                                            float lr_alpha) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
-  __shared__ float red[4];
+  __shared__ float red[8];
   const int ti = xcd_chunked_index(blockIdx.x, ntiles);
   if (ti < 0) return;
   const FiraTile tile = tiles[ti];
@@ -548,7 +531,7 @@ __global__ __launch_bounds__(FIRA_THREADS, 1) void fira_backproject_kernel(const
   g.KA = g.KB = mt.kx * mt.rp;
   g.A = mt.left ? lowrank : proj;
   g.B = mt.left ? proj : lowrank;
-  f32x16_t acc[4][4];
+  f32x16_t acc[4][2];
   gemm_mainloop<false>(acc, lds, g);
 
   const float c = (MODE == 0) ? 1.0f : scal[ent.mat].c;
@@ -565,6 +548,6 @@ __global__ __launch_bounds__(FIRA_THREADS, 1) void fira_backproject_kernel(const
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = sum;
     __syncthreads();
     if (threadIdx.x == 0)
-      as_global(partial)[tile.part] = (red[0] + red[1]) + (red[2] + red[3]);
+      as_global(partial)[tile.part] = ((red[0] + red[1]) + (red[2] + red[3])) + ((red[4] + red[5]) + (red[6] + red[7]));
   }
 }
