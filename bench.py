@@ -86,6 +86,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--norm-mode", choices=["gram", "residual"], default="gram",
+                    help="how the limiter norm ||S|| is obtained (both are parity-tested)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives); use --gpus 1")
@@ -103,6 +105,7 @@ def main():
     gen = torch.Generator(device=dev)
     gen.manual_seed(1000 * wl.config_id)
     ctx = fira.FiraContext(shapes, wl.rank, dt_f, fira.make_hparams(), device=dev)
+    ctx.fira_set_options(norm_mode=fira.FIRA_NORM_GRAM if args.norm_mode == "gram" else fira.FIRA_NORM_RESIDUAL)
     # projectors: one seeded orthonormal basis per distinct short side, installed into every matrix
     cache = {}
     for i, (m, n) in enumerate(shapes):
@@ -157,7 +160,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": name, "matrices": len(shapes), "rank": wl.rank,
                    "params": sum(m * n for m, n in shapes), "state_bytes": ctx.state_bytes,
-                   "gradient_sets": n_sets, "finite": finite},
+                   "gradient_sets": n_sets, "norm_mode": args.norm_mode, "finite": finite},
         "roofline": roof, "kernels": kernels,
     }
     if not args.no_cpu_baseline:

@@ -40,6 +40,7 @@ struct HostMat {
   int tiles_back = 0;         // tiles of the back-projection (and of the residual-norm pass)
   int ta_project = 0, tb_project = 0, ta_back = 0, tb_back = 0;
   int rowblocks = 0;
+  int g2blocks = 0;           // blocks of the ||G_i||^2 kernel
 };
 
 enum { kTilesProjectLeft = 0, kTilesProjectRight = 1, kTilesBackBf16 = 2, kTilesBackF32 = 3, kNumTileLists = 4 };
@@ -49,7 +50,7 @@ struct ListSlot {
   std::vector<void*> W;
   std::vector<const void*> G;
   int ntiles[kNumTileLists] = {0, 0, 0, 0};
-  int rowblocks = 0;
+  int rowblocks = 0, g2blocks = 0;
   // device views (inside the slab)
   FiraEnt* d_ents = nullptr;
   FiraTile* d_tiles[kNumTileLists] = {nullptr, nullptr, nullptr, nullptr};
@@ -64,7 +65,7 @@ struct ListSlot {
 
 struct Plan {
   size_t total = 0;
-  size_t off_mats = 0, off_scal = 0, off_partial = 0;
+  size_t off_mats = 0, off_scal = 0, off_partial = 0, off_ortho = 0;
   size_t off_slots = 0, slot_bytes = 0, slot_off_tiles[kNumTileLists] = {0, 0, 0, 0};
   std::vector<HostMat> mats;
   int max_tiles[kNumTileLists] = {0, 0, 0, 0};
@@ -117,12 +118,12 @@ bool make_plan(const fira_matrix_desc* d, int count, Plan* plan, fira_status* st
       const size_t gx = m.left ? (size_t)m.kx * m.Sp * m.gx_ld : (size_t)m.m * m.gx_ld;
       m.Gx = (bf16_raw*)take(gx * 2);
     }
-    m.Dm = (bf16_raw*)take((size_t)m.r * m.rp * 2);
     h.ta_project = (m.L + FIRA_TA - 1) / FIRA_TA; h.tb_project = (m.r + FIRA_TB - 1) / FIRA_TB;
     h.ta_back = (m.n + FIRA_TA - 1) / FIRA_TA;    h.tb_back = (m.m + FIRA_TB - 1) / FIRA_TB;
     h.tiles_project = h.ta_project * h.tb_project;
     h.tiles_back = h.ta_back * h.tb_back;
     h.rowblocks = (m.L + FIRA_ROWS_PER_WG - 1) / FIRA_ROWS_PER_WG;
+    h.g2blocks = m.left ? (m.n + 255) / 256 : (m.m + FIRA_G2_ROWS_PER_WG - 1) / FIRA_G2_ROWS_PER_WG;
     total_tiles[m.left ? kTilesProjectLeft : kTilesProjectRight] += h.tiles_project;
     total_tiles[m.dtype == FIRA_BF16 ? kTilesBackBf16 : kTilesBackF32] += h.tiles_back;
   }
@@ -132,6 +133,10 @@ bool make_plan(const fira_matrix_desc* d, int count, Plan* plan, fira_status* st
   }
   plan->off_partial = off;
   off = align_up(off + (size_t)(total_tiles[kTilesBackBf16] + total_tiles[kTilesBackF32]) * 4);
+  long long max_S = 0;
+  for (const HostMat& h : plan->mats) max_S = std::max<long long>(max_S, h.dev.S);
+  plan->off_ortho = off;                       // scratch of the orthonormality estimate: S x 4 floats
+  off = align_up(off + (size_t)max_S * 16);
   size_t s = 0;
   s = align_up(s + sizeof(FiraEnt) * count);
   for (int l = 0; l < kNumTileLists; ++l) {
@@ -187,6 +192,8 @@ FiraHp make_hp(const fira_ctx* ctx) {
   h.epsf = (float)ctx->hp.eps;
   h.lr_alpha = (float)(ctx->hp.lr * ctx->hp.alpha);
   h.scaling = ctx->scaling;
+  h.norm_mode = ctx->norm_mode;
+  h.ortho_tol = 0.02f;   // bf16-rounded orthonormal projectors measure ~1e-3; 0.02 bounds the error of ||S|| by ~1 %
   return h;
 }
 
@@ -221,13 +228,14 @@ ListSlot* acquire_list(fira_ctx* ctx, int count, const int* idx, void* const* W,
   FiraTile* tl[kNumTileLists];
   int nt[kNumTileLists] = {0, 0, 0, 0};
   for (int l = 0; l < kNumTileLists; ++l) tl[l] = reinterpret_cast<FiraTile*>(s->h_stage + p.slot_off_tiles[l]);
-  int nparts = 0, rowblocks = 0;
+  int nparts = 0, rowblocks = 0, g2blocks = 0;
   for (int e = 0; e < count; ++e) {
     const HostMat& h = p.mats[idx[e]];
     FiraEnt& en = ents[e];
-    en.mat = idx[e]; en.part0 = nparts; en.npart = h.tiles_back; en.row0 = rowblocks;
+    en.mat = idx[e]; en.part0 = nparts; en.npart = h.tiles_back; en.row0 = rowblocks; en.g2b0 = g2blocks; en.pad = 0;
     en.W = W[e]; en.G = G[e];
     rowblocks += h.rowblocks;
+    g2blocks += h.g2blocks;
     // R contraction: rank tiles innermost, so the tiles that share a panel of G are neighbours
     const int lp = h.dev.left ? kTilesProjectLeft : kTilesProjectRight;
     for (int ta = 0; ta < h.ta_project; ++ta)
@@ -240,6 +248,7 @@ ListSlot* acquire_list(fira_ctx* ctx, int count, const int* idx, void* const* W,
   }
   for (int l = 0; l < kNumTileLists; ++l) s->ntiles[l] = nt[l];
   s->rowblocks = rowblocks;
+  s->g2blocks = g2blocks;
   if (hipMemcpyAsync(s->d_block, s->h_stage, p.slot_bytes, hipMemcpyHostToDevice, ctx->stream) != hipSuccess ||
       hipEventRecord(s->uploaded, ctx->stream) != hipSuccess) { *st = FIRA_ERR_HIP; return nullptr; }
   s->valid = true;
@@ -289,7 +298,6 @@ fira_status fira_init_state(fira_ctx** out, const fira_matrix_desc* d, int count
     m.Nb = (bf16_raw*)(ctx->slab + (size_t)m.Nb); m.Rb = (bf16_raw*)(ctx->slab + (size_t)m.Rb);
     m.Pn = (bf16_raw*)(ctx->slab + (size_t)m.Pn); m.PT = (bf16_raw*)(ctx->slab + (size_t)m.PT);
     if (m.kx > 1) m.Gx = (bf16_raw*)(ctx->slab + (size_t)m.Gx);
-    m.Dm = (bf16_raw*)(ctx->slab + (size_t)m.Dm);
   }
   ctx->d_mats = (FiraMat*)(ctx->slab + p.off_mats);
   ctx->d_scal = (FiraScal*)(ctx->slab + p.off_scal);
@@ -348,7 +356,7 @@ fira_status fira_set_hparams(fira_ctx* ctx, const fira_hparams* hp) {
 fira_status fira_set_options(fira_ctx* ctx, fira_scaling scaling, fira_norm_mode norm_mode) {
   if (!ctx) return fail(nullptr, FIRA_ERR_INVALID_ARG, "ctx is null");
   if (scaling != FIRA_SCALE_COLUMN && scaling != FIRA_SCALE_NONE) return fail(ctx, FIRA_ERR_INVALID_ARG, "unknown scaling mode");
-  if (norm_mode != FIRA_NORM_RESIDUAL) return fail(ctx, FIRA_ERR_INVALID_ARG, "unsupported norm mode");
+  if (norm_mode != FIRA_NORM_RESIDUAL && norm_mode != FIRA_NORM_GRAM) return fail(ctx, FIRA_ERR_INVALID_ARG, "unknown norm mode");
   ctx->scaling = scaling;
   ctx->norm_mode = norm_mode;
   return FIRA_OK;
@@ -366,6 +374,10 @@ fira_status fira_set_projector(fira_ctx* ctx, int idx, const void* dev_P, fira_d
     hipLaunchKernelGGL(fira_prep_projector_kernel<float>, dim3(grid), dim3(256), 0, ctx->stream, h.dev, (const float*)dev_P);
   else
     hipLaunchKernelGGL(fira_prep_projector_kernel<bf16_raw>, dim3(grid), dim3(256), 0, ctx->stream, h.dev, (const bf16_raw*)dev_P);
+  // gate of the Gram route: estimate ||P^T P - I|| (stream-ordered, shares one S x 4 float scratch)
+  float* ybuf = reinterpret_cast<float*>(ctx->slab + ctx->plan.off_ortho);
+  hipLaunchKernelGGL(fira_ortho_y_kernel, dim3((h.dev.S + 3) / 4), dim3(256), 0, ctx->stream, h.dev, ybuf);
+  hipLaunchKernelGGL(fira_ortho_z_kernel, dim3(1), dim3(256), 0, ctx->stream, h.dev, (const float*)ybuf, ctx->d_scal, idx);
   FIRA_HIP(ctx, hipGetLastError());
   h.has_projector = true;
   return FIRA_OK;
@@ -407,6 +419,10 @@ fira_status fira_step(fira_ctx* ctx, int count, const int* idx, void* const* dev
   }
   auto grid8 = [](int n) { return dim3((unsigned)(((n + 7) / 8) * 8)); };
   const dim3 blk(FIRA_THREADS);
+  // 0. Gram route only: ||G_i||^2 for every factor (workgroups of other matrices return at once)
+  if (ctx->norm_mode == FIRA_NORM_GRAM)
+    hipLaunchKernelGGL(fira_gradnorm_kernel, dim3(s->g2blocks), dim3(256), 0, q, ctx->d_mats, ctx->d_scal, s->d_ents, count,
+                       s->g2blocks, hp);
   // 1. R = P^T G (long-side major), one launch per orientation
   if (s->ntiles[kTilesProjectLeft])
     hipLaunchKernelGGL(fira_project_kernel<true>, grid8(s->ntiles[kTilesProjectLeft]), blk, FIRA_LDS_BYTES, q,
@@ -423,14 +439,14 @@ fira_status fira_step(fira_ctx* ctx, int count, const int* idx, void* const* dev
   if (s->ntiles[kTilesBackBf16])
     hipLaunchKernelGGL((fira_backproject_kernel<0, bf16_raw>), grid8(s->ntiles[kTilesBackBf16]), blk, FIRA_LDS_BYTES, q,
                        ctx->d_mats, ctx->d_scal, s->d_ents, s->d_tiles[kTilesBackBf16], s->ntiles[kTilesBackBf16],
-                       ctx->d_partial, hp.lr_alpha);
+                       ctx->d_partial, hp);
   if (s->ntiles[kTilesBackF32])
     hipLaunchKernelGGL((fira_backproject_kernel<0, float>), grid8(s->ntiles[kTilesBackF32]), blk, FIRA_LDS_BYTES, q,
                        ctx->d_mats, ctx->d_scal, s->d_ents, s->d_tiles[kTilesBackF32], s->ntiles[kTilesBackF32],
-                       ctx->d_partial, hp.lr_alpha);
+                       ctx->d_partial, hp);
   mark(3);
   // 4. limiter factor, state advance
-  hipLaunchKernelGGL(fira_limiter_kernel, dim3(count), dim3(64), 0, q, ctx->d_scal, s->d_ents, ctx->d_partial, hp);
+  hipLaunchKernelGGL(fira_limiter_kernel, dim3(count), dim3(64), 0, q, ctx->d_mats, ctx->d_scal, s->d_ents, ctx->d_partial, hp);
   mark(4);
   // 5. Z = N - c k R
   hipLaunchKernelGGL(fira_makez_kernel, dim3(s->rowblocks), dim3(256), 0, q, ctx->d_mats, ctx->d_scal, s->d_ents, count,
@@ -440,11 +456,11 @@ fira_status fira_step(fira_ctx* ctx, int count, const int* idx, void* const* dev
   if (s->ntiles[kTilesBackBf16])
     hipLaunchKernelGGL((fira_backproject_kernel<1, bf16_raw>), grid8(s->ntiles[kTilesBackBf16]), blk, FIRA_LDS_BYTES, q,
                        ctx->d_mats, ctx->d_scal, s->d_ents, s->d_tiles[kTilesBackBf16], s->ntiles[kTilesBackBf16],
-                       ctx->d_partial, hp.lr_alpha);
+                       ctx->d_partial, hp);
   if (s->ntiles[kTilesBackF32])
     hipLaunchKernelGGL((fira_backproject_kernel<1, float>), grid8(s->ntiles[kTilesBackF32]), blk, FIRA_LDS_BYTES, q,
                        ctx->d_mats, ctx->d_scal, s->d_ents, s->d_tiles[kTilesBackF32], s->ntiles[kTilesBackF32],
-                       ctx->d_partial, hp.lr_alpha);
+                       ctx->d_partial, hp);
   mark(6);
   FIRA_HIP(ctx, hipGetLastError());
   return FIRA_OK;

@@ -45,14 +45,13 @@ struct FiraMat {
   float* V;            // [L][r]   second moment
   float* Rt;           // [L][r]   low-rank gradient of this step (scratch)
   float* phi;          // [L]      scaling factors k_i of this step
-  float* g2;           // [L]      ||G_i||^2 (only written in Gram mode)
-  float* q;            // [L]      ||R_i||^2 - 2 R_i.R_i + R_i^T (P^T P) R_i pieces (Gram mode)
+  float* g2;           // [L]      ||G_i||^2 (Gram mode)
+  float* q;            // [L]      k_i^2 (||G_i||^2 - ||R_i||^2), the terms of ||S||^2 (Gram mode)
   bf16_raw* Nb;        // [L][lr_ld] N of this step, then Z = N - c k_i R_i in place (MFMA operand)
   bf16_raw* Rb;        // [L][lr_ld] R of this step as MFMA operand
   bf16_raw* Pn;        // [S][lr_ld] projector, rank-contiguous (operand of the back-projection)
   bf16_raw* PT;        // [r][pt_ld] projector transposed, short-side-contiguous (operand of R)
   bf16_raw* Gx;        // fp32 matrices: split copy of G ([kx*Sp][gx_ld] if left, [m][gx_ld] else)
-  bf16_raw* Dm;        // [r][rp]  P^T P - I in bf16 (Gram mode)
 };
 
 // Mutable per-matrix scalars (device array).
@@ -63,7 +62,7 @@ struct FiraScal {
   float c;         // limiter factor of the current step
   int has_prev;    // 0 until the first step has recorded a norm
   int t;           // steps taken
-  int pad;
+  float ortho_err; // estimate of ||P^T P - I|| from the last fira_set_projector (Gram-mode gate)
 };
 
 // One entry of a step's work list.
@@ -72,6 +71,8 @@ struct FiraEnt {
   int part0;        // first partial-sum slot of this entry
   int npart;        // number of partial-sum slots
   int row0;         // first row-block (elementwise kernels) of this entry
+  int g2b0;         // first block of the ||G_i||^2 kernel of this entry
+  int pad;
   void* W;
   const void* G;
 };
@@ -89,7 +90,15 @@ struct FiraHp {     // hyper-parameters as the kernels take them
   float b1, b2, omb1, omb2, epsf;
   float lr_alpha;   // lr * alpha
   int scaling;      // 0 column, 2 none
+  int norm_mode;    // 0: ||S|| from the residual tiles; 1: from ||G_i||^2 - ||R_i||^2 where P passes the gate
+  float ortho_tol;  // gate of the Gram mode on FiraScal::ortho_err
 };
+
+// Whether matrix `sc` takes the Gram route to ||S||^2 in this step.
+__device__ __forceinline__ bool use_gram(const FiraHp& hp, const FiraScal& sc) {
+  return hp.norm_mode == 1 && sc.ortho_err <= hp.ortho_tol;
+}
+
 
 // ---- bf16 helpers ---------------------------------------------------------------------------
 __device__ __forceinline__ bf16_raw f32_to_bf16(float x) {

@@ -46,7 +46,7 @@ __device__ __forceinline__ float load_operand(gptr<const bf16_raw> row, int rp, 
 //   k_i = ||N_i|| / (||R_i|| + eps);  N and R are also written as bf16 MFMA operands.
 // ------------------------------------------------------------------------------------------------
 template <int KX, int VEC>
-__device__ __forceinline__ void adam_row(const FiraMat& mt, const FiraHp& hp, float bias, long long row) {
+__device__ __forceinline__ void adam_row(const FiraMat& mt, const FiraHp& hp, float bias, long long row, bool gram) {
   const int lane = threadIdx.x & 63;
   const int r = mt.r;
   gptr<const float> R = as_global<const float>(mt.Rt) + row * r;
@@ -91,7 +91,12 @@ __device__ __forceinline__ void adam_row(const FiraMat& mt, const FiraHp& hp, fl
   }
   nn = wave_sum(nn);
   rr = wave_sum(rr);
-  if (lane == 0) as_global(mt.phi)[row] = (hp.scaling == 2) ? 1.0f : sqrtf(nn) / (sqrtf(rr) + hp.epsf);
+  if (lane == 0) {
+    const float k = (hp.scaling == 2) ? 1.0f : sqrtf(nn) / (sqrtf(rr) + hp.epsf);
+    as_global(mt.phi)[row] = k;
+    // Gram route: ||G_i - P R_i||^2 = ||G_i||^2 - ||R_i||^2 when P^T P = I (G_i^T P = R_i^T always)
+    if (gram) as_global(mt.q)[row] = k * k * fmaxf(as_global<const float>(mt.g2)[row] - rr, 0.0f);
+  }
 }
 
 __global__ __launch_bounds__(256) void fira_adam_kernel(const FiraMat* __restrict__ mats,
@@ -105,7 +110,9 @@ __global__ __launch_bounds__(256) void fira_adam_kernel(const FiraMat* __restric
   const FiraMat mt = mats[ent.mat];
   // bias correction with the 1-based step count (Eq. 4), in double: 1 - beta2^t loses all
   // accuracy in fp32 at small t.
-  const int t = scal[ent.mat].t + 1;
+  const FiraScal sc = scal[ent.mat];
+  const int t = sc.t + 1;
+  const bool gram = use_gram(hp, sc);
   const float bias = (float)(sqrt(1.0 - pow(hp.beta2, (double)t)) / (1.0 - pow(hp.beta1, (double)t)));
   const int wave = threadIdx.x >> 6;
   const long long row_base = (long long)(rb - ent.row0) * FIRA_ROWS_PER_WG + wave * 4;
@@ -113,9 +120,9 @@ __global__ __launch_bounds__(256) void fira_adam_kernel(const FiraMat* __restric
     const long long row = row_base + i;
     if (row >= mt.L) break;
     if (mt.kx == 1) {
-      if ((mt.r & 3) == 0) adam_row<1, 4>(mt, hp, bias, row); else adam_row<1, 1>(mt, hp, bias, row);
+      if ((mt.r & 3) == 0) adam_row<1, 4>(mt, hp, bias, row, gram); else adam_row<1, 1>(mt, hp, bias, row, gram);
     } else {
-      adam_row<FIRA_KX_SPLIT, 1>(mt, hp, bias, row);
+      adam_row<FIRA_KX_SPLIT, 1>(mt, hp, bias, row, gram);
     }
   }
 }
@@ -124,13 +131,20 @@ __global__ __launch_bounds__(256) void fira_adam_kernel(const FiraMat* __restric
 // Norm-growth limiter (Eq. 12 in Algorithm 1's form): one workgroup per listed matrix sums the
 // tile partials of ||S||^2 in a fixed order (fp64), derives the factor c, and advances the state.
 // ------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(64) void fira_limiter_kernel(FiraScal* __restrict__ scal,
+__global__ __launch_bounds__(64) void fira_limiter_kernel(const FiraMat* __restrict__ mats,
+                                                          FiraScal* __restrict__ scal,
                                                           const FiraEnt* __restrict__ ents,
                                                           const float* __restrict__ partial, FiraHp hp) {
   const FiraEnt ent = ents[blockIdx.x];
   const int lane = threadIdx.x;
   double acc = 0.0;
-  for (int i = lane; i < ent.npart; i += 64) acc += (double)partial[ent.part0 + i];
+  if (use_gram(hp, scal[ent.mat])) {
+    const FiraMat mt = mats[ent.mat];
+    gptr<const float> q = as_global<const float>(mt.q);
+    for (int i = lane; i < mt.L; i += 64) acc += (double)q[i];
+  } else {
+    for (int i = lane; i < ent.npart; i += 64) acc += (double)partial[ent.part0 + i];
+  }
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off, 64);
   if (lane == 0) {
@@ -258,5 +272,167 @@ __global__ void fira_split_gradient_kernel(FiraMat mt, const float* __restrict__
 #pragma unroll
       for (int p = 0; p < 6; ++p) Gx[i * mt.gx_ld + (long long)p * mt.Sp + j] = seq[p];
     }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Gram route to ||S||: g2[i] = sum over the short axis of G(s, i)^2 for every long index i.
+//   left  (m <= n): column sums of squares; one workgroup per 256 columns walks all m rows with
+//                   row-contiguous 16-byte loads (32 lanes = 512 B of one row), 8 row lanes.
+//   right (m >  n): row sums of squares; one wavefront per row.
+// Fixed summation order: deterministic.
+// ------------------------------------------------------------------------------------------------
+#define FIRA_G2_ROWS_PER_WG 32   // right orientation: rows per workgroup (8 per wavefront)
+
+__device__ __forceinline__ int find_g2_entry(const FiraEnt* __restrict__ ents, int count, int blk) {
+  int lo = 0, hi = count - 1;
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (ents[mid].g2b0 <= blk) lo = mid; else hi = mid - 1;
+  }
+  return lo;
+}
+
+template <typename T>
+__device__ __forceinline__ void g2_load8(float (&x)[8], gptr<const T> row, long long idx, long long limit);
+template <>
+__device__ __forceinline__ void g2_load8<bf16_raw>(float (&x)[8], gptr<const bf16_raw> row, long long idx, long long limit) {
+  unsigned w[4] = {0u, 0u, 0u, 0u};
+  if (idx + 8 <= limit) {
+    const u32x4 v = *reinterpret_cast<gptr<const u32x4_a2>>(row + idx);
+    w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
+  } else {
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+      if (idx + e < limit) w[e >> 1] |= ((unsigned)row[idx + e]) << ((e & 1) * 16);
+  }
+#pragma unroll
+  for (int d = 0; d < 4; ++d) { x[2 * d] = __uint_as_float(w[d] << 16); x[2 * d + 1] = __uint_as_float(w[d] & 0xffff0000u); }
+}
+template <>
+__device__ __forceinline__ void g2_load8<float>(float (&x)[8], gptr<const float> row, long long idx, long long limit) {
+#pragma unroll
+  for (int e = 0; e < 8; ++e) x[e] = (idx + e < limit) ? row[idx + e] : 0.0f;
+}
+
+template <typename T>
+__device__ __forceinline__ void g2_block(const FiraMat& mt, const FiraEnt& ent, int blk, float* red) {
+  gptr<const T> G = as_global(reinterpret_cast<const T*>(ent.G));
+  gptr<float> g2 = as_global(mt.g2);
+  const int t = threadIdx.x;
+  if (mt.left) {
+    const int cc = t & 31, rl = t >> 5;                 // 32 column chunks x 8 row lanes
+    const long long j = (long long)blk * 256 + 8 * cc;
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if (j < mt.n) {
+      for (int i = rl; i < mt.m; i += 8) {
+        float x[8];
+        g2_load8<T>(x, G + (long long)i * mt.ld, j, mt.n);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] += x[e] * x[e];
+      }
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) red[(rl * 32 + cc) * 8 + e] = acc[e];
+    __syncthreads();
+    // thread t sums column t of the block over the 8 row lanes, in order
+    const int c = t >> 3, e = t & 7;
+    float s = 0.0f;
+#pragma unroll
+    for (int r8 = 0; r8 < 8; ++r8) s += red[(r8 * 32 + c) * 8 + e];
+    const long long col = (long long)blk * 256 + t;
+    if (col < mt.n) g2[col] = s;
+  } else {
+    const int lane = t & 63, wave = t >> 6;
+    for (int rr = 0; rr < 8; ++rr) {
+      const long long i = (long long)blk * FIRA_G2_ROWS_PER_WG + wave * 8 + rr;
+      if (i >= mt.m) break;
+      float s = 0.0f;
+      for (long long j = 8 * lane; j < mt.n; j += 512) {
+        float x[8];
+        g2_load8<T>(x, G + i * mt.ld, j, mt.n);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) s += x[e] * x[e];
+      }
+      s = wave_sum(s);
+      if (lane == 0) g2[i] = s;
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void fira_gradnorm_kernel(const FiraMat* __restrict__ mats,
+                                                            const FiraScal* __restrict__ scal,
+                                                            const FiraEnt* __restrict__ ents, int count,
+                                                            int total_blocks, FiraHp hp) {
+  __shared__ float red[256 * 8];
+  const int b = blockIdx.x;
+  if (b >= total_blocks) return;
+  const int e = find_g2_entry(ents, count, b);
+  const FiraEnt ent = ents[e];
+  if (!use_gram(hp, scal[ent.mat])) return;
+  const FiraMat mt = mats[ent.mat];
+  if (mt.dtype == 1) g2_block<bf16_raw>(mt, ent, b - ent.g2b0, red);
+  else g2_block<float>(mt, ent, b - ent.g2b0, red);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Gate of the Gram route, evaluated when a projector is installed: a randomized estimate of
+// ||P^T P - I|| from 4 sign vectors x (err = max_t ||P^T (P x_t) - x_t|| / ||x_t||), on the bf16
+// operand copy of P that the contractions use.  Two small kernels: y_t = P x_t (one wavefront per
+// row of P), then z_t = P^T y_t - x_t (one workgroup, threads along the rank axis).
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ float ortho_sign(int a, int trial) {
+  const unsigned h = ((unsigned)a * 2654435761u) ^ ((unsigned)trial * 2246822519u + 374761393u);
+  return ((h >> 15) & 1u) ? 1.0f : -1.0f;
+}
+
+__global__ __launch_bounds__(256) void fira_ortho_y_kernel(FiraMat mt, float* __restrict__ y /* [S][4] */) {
+  gptr<const bf16_raw> Pn = as_global<const bf16_raw>(mt.Pn);
+  const int lane = threadIdx.x & 63;
+  const int s = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (s >= mt.S) return;
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  for (int a = lane; a < mt.r; a += 64) {
+    const float p = bf16_to_f32(Pn[(long long)s * mt.lr_ld + a]);
+#pragma unroll
+    for (int t = 0; t < 4; ++t) acc[t] += p * ortho_sign(a, t);
+  }
+#pragma unroll
+  for (int t = 0; t < 4; ++t) acc[t] = wave_sum(acc[t]);
+  if (lane == 0) {
+#pragma unroll
+    for (int t = 0; t < 4; ++t) as_global(y)[(long long)s * 4 + t] = acc[t];
+  }
+}
+
+__global__ __launch_bounds__(256) void fira_ortho_z_kernel(FiraMat mt, const float* __restrict__ y,
+                                                           FiraScal* __restrict__ scal, int mat) {
+  __shared__ float red[4][4];
+  gptr<const bf16_raw> Pn = as_global<const bf16_raw>(mt.Pn);
+  gptr<const float> yy = as_global(y);
+  const int t = threadIdx.x;
+  float zz[4] = {0.f, 0.f, 0.f, 0.f};
+  for (int a = t; a < mt.r; a += 256) {
+    float z[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int s = 0; s < mt.S; ++s) {
+      const float p = bf16_to_f32(Pn[(long long)s * mt.lr_ld + a]);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) z[k] += p * yy[(long long)s * 4 + k];
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) { const float d = z[k] - ortho_sign(a, k); zz[k] += d * d; }
+  }
+#pragma unroll
+  for (int k = 0; k < 4; ++k) zz[k] = wave_sum(zz[k]);
+  if ((t & 63) == 0) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) red[t >> 6][k] = zz[k];
+  }
+  __syncthreads();
+  if (t == 0) {
+    float worst = 0.0f;
+    for (int k = 0; k < 4; ++k)
+      worst = fmaxf(worst, sqrtf(((red[0][k] + red[1][k]) + (red[2][k] + red[3][k])) / (float)mt.r));
+    as_global(scal)[mat].ortho_err = worst;
   }
 }

@@ -510,14 +510,16 @@ __global__ __launch_bounds__(FIRA_THREADS, 2) void fira_backproject_kernel(const
                                                                            const FiraEnt* __restrict__ ents,
                                                                            const FiraTile* __restrict__ tiles,
                                                                            int ntiles, float* __restrict__ partial,
-                                                                           float lr_alpha) {
+                                                                           FiraHp hp) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
   __shared__ float red[8];
   const int ti = xcd_chunked_index(blockIdx.x, ntiles);
   if (ti < 0) return;
   const FiraTile tile = tiles[ti];
   const FiraEnt ent = ents[tile.ent];
+  if (MODE == 0 && use_gram(hp, scal[ent.mat])) return;   // this matrix takes the Gram route to ||S||
   const FiraMat mt = mats[ent.mat];
+  const float lr_alpha = hp.lr_alpha;
 
   // Y (n side) is the A operand, X (m side) the B operand.
   gptr<const bf16_raw> lowrank = as_global<const bf16_raw>((MODE == 0) ? mt.Rb : mt.Nb);

@@ -58,7 +58,7 @@ def run_case(shapes: Sequence[Tuple[int, int]], rank, dtype: int, steps: int,
              gen_P: Callable[[int, int], Optional[np.ndarray]], hp: orc.OracleHparams,
              check: Optional[Sequence[int]] = None, lds: Optional[Sequence[int]] = None,
              stages: bool = True, scaling: str = "column", step_lists: Optional[List[List[int]]] = None,
-             alias: Optional[Dict[int, int]] = None) -> CaseResult:
+             alias: Optional[Dict[int, int]] = None, norm_mode: int = fira.FIRA_NORM_RESIDUAL) -> CaseResult:
     """gen_P(mat, step) returns a projector (float64/float32 values already representable in the
     storage type) when the projector of `mat` is (re)installed before `step`, else None.
     `check`: matrices compared against the oracle (default all).  `alias[i] = j`: matrix i is fed
@@ -71,8 +71,9 @@ def run_case(shapes: Sequence[Tuple[int, int]], rank, dtype: int, steps: int,
     ranks = rank if isinstance(rank, (list, tuple)) else [rank] * nmat
     chp = fira.make_hparams(hp.lr, hp.beta1, hp.beta2, hp.eps, hp.alpha, hp.gamma)
     ctx = fira.FiraContext(shapes, rank, dtype, chp, device=DEV, lds=lds)
-    if scaling != "column":
-        ctx.fira_set_options(scaling={"none": fira.FIRA_SCALE_NONE}[scaling])
+    if scaling != "column" or norm_mode != fira.FIRA_NORM_RESIDUAL:
+        ctx.fira_set_options(scaling={"none": fira.FIRA_SCALE_NONE, "column": fira.FIRA_SCALE_COLUMN}[scaling],
+                             norm_mode=norm_mode)
     bf = dtype == fira.FIRA_BF16
     W_host = {i: gen_W(i) for i in set(src(i) for i in range(nmat))}
     W_dev = [to_device(W_host[src(i)], dtype, None if lds is None else lds[i]) for i in range(nmat)]

@@ -200,20 +200,54 @@ def test_config3_llama350m_shapes_spike():
         assert torch.equal(res.W_dev[i], res.W_dev[i % 7]), f"matrix {i} differs from its twin"
 
 
-def test_config4_llama1b_full_list():
-    """The headline workload in the launch configuration bench.py times: all 168 matrices of the
-    LLaMA-1B shape set (r = 512, bf16) in one fira_step call, 10 steps.  The oracle follows blocks
-    0 and 23; blocks 1..22 are fed block 0's inputs and must match it bit for bit."""
+@pytest.mark.parametrize("norm_mode", [fira.FIRA_NORM_GRAM, fira.FIRA_NORM_RESIDUAL], ids=["gram", "residual"])
+def test_config4_llama1b_full_list(norm_mode):
+    """The headline workload in the launch configuration bench.py times (both ways of obtaining the
+    limiter norm): all 168 matrices of the LLaMA-1B shape set (r = 512, bf16) in one fira_step call,
+    10 steps.  The oracle follows blocks 0 and 23; blocks 1..22 are fed block 0's inputs and must
+    match it bit for bit."""
     wl = synth.WORKLOADS["llama1b_r512_bf16"]
     gw, gg, gp = H.workload_generators(wl, "random")
     n = wl.n_matrices
     alias = {i: i % 7 for i in range(7, n - 7)}
     chk = list(range(7)) + list(range(n - 7, n))
     res = H.run_case(wl.shapes, wl.rank, fira.FIRA_BF16, wl.steps, gw, gg, gp, orc.OracleHparams(),
-                     check=chk, alias=alias)
+                     check=chk, alias=alias, norm_mode=norm_mode)
     check(res, fira.FIRA_BF16)
     for i in range(7, n - 7):
         assert torch.equal(res.W_dev[i], res.W_dev[i % 7]), f"matrix {i} differs from its twin"
+
+
+@pytest.mark.parametrize("dtype", [fira.FIRA_BF16, fira.FIRA_F32], ids=["bf16", "f32"])
+@pytest.mark.parametrize("m,n,r", [(300, 517, 40), (517, 300, 40), (257, 259, 33), (96, 160, 32)],
+                         ids=["300x517r40", "517x300r40", "257x259r33", "96x160r32"])
+def test_gram_route_to_the_limiter_norm(m, n, r, dtype):
+    """FIRA_NORM_GRAM: ||S||^2 = sum_i k_i^2 (||G_i||^2 - ||R_i||^2), valid when P^T P = I.  With a
+    bf16-rounded orthonormal P the identity holds to ~1e-3 of ||R_i||^2, i.e. ~3e-4 of the norm."""
+    W0, Gs, P = random_case(300 + m + n, m, n, r, dtype, steps=6, spike_at=3)
+    res = H.run_case([(m, n)], r, dtype, 6, lambda i: W0, lambda i, s: Gs[s],
+                     lambda i, s: P if s == 0 else None, orc.OracleHparams(alpha=0.25),
+                     norm_mode=fira.FIRA_NORM_GRAM)
+    assert res.c_min < 1.0
+    msg = H.fmt(res)
+    print(msg, flush=True)
+    assert max(res.w_err) <= TOL_W[dtype], msg
+    tol = dict(TOL_STAGE[dtype], s_pre=1e-3, c=1e-3)
+    for k, v in tol.items():
+        assert res.worst[k] <= v, f"stage {k}: {msg}"
+
+
+def test_gram_route_falls_back_for_a_non_orthonormal_projector():
+    """The gate measured at fira_set_projector sends a P that is far from orthonormal through the
+    residual route, so the result still follows Algorithm 1 for that P."""
+    m, n, r = 200, 330, 24
+    rng = np.random.default_rng(77)
+    W0 = synth.as_bf16_values(0.02 * rng.standard_normal((m, n)))
+    Gs = [synth.as_bf16_values(1e-2 * rng.standard_normal((m, n))) for _ in range(4)]
+    P = synth.as_bf16_values(rng.standard_normal((m, r)) / np.sqrt(m) * 1.3)     # not orthonormal
+    res = H.run_case([(m, n)], r, fira.FIRA_BF16, 4, lambda i: W0, lambda i, s: Gs[s],
+                     lambda i, s: P if s == 0 else None, orc.OracleHparams(), norm_mode=fira.FIRA_NORM_GRAM)
+    check(res, fira.FIRA_BF16)
 
 
 def test_config5_llama7b_block_sample():
