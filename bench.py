@@ -86,6 +86,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB device-to-device copy (for scaling HBM traffic counters)")
     ap.add_argument("--norm-mode", choices=["gram", "residual"], default="gram",
                     help="how the limiter norm ||S|| is obtained (both are parity-tested)")
     args = ap.parse_args()
@@ -122,6 +124,13 @@ def main():
     prepared = [ctx.prepare(idx, W, G) for G in Gsets]
     torch.cuda.synchronize()
 
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for s in range(args.warmup):
         ctx.fira_step(prepared=prepared[s % n_sets])
     torch.cuda.synchronize()

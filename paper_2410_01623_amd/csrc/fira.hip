@@ -65,7 +65,7 @@ struct ListSlot {
 
 struct Plan {
   size_t total = 0;
-  size_t off_mats = 0, off_scal = 0, off_partial = 0, off_ortho = 0;
+  size_t off_mats = 0, off_scal = 0, off_partial = 0, off_ortho = 0, ortho_z = 0;
   size_t off_slots = 0, slot_bytes = 0, slot_off_tiles[kNumTileLists] = {0, 0, 0, 0};
   std::vector<HostMat> mats;
   int max_tiles[kNumTileLists] = {0, 0, 0, 0};
@@ -135,8 +135,11 @@ bool make_plan(const fira_matrix_desc* d, int count, Plan* plan, fira_status* st
   off = align_up(off + (size_t)(total_tiles[kTilesBackBf16] + total_tiles[kTilesBackF32]) * 4);
   long long max_S = 0;
   for (const HostMat& h : plan->mats) max_S = std::max<long long>(max_S, h.dev.S);
-  plan->off_ortho = off;                       // scratch of the orthonormality estimate: S x 4 floats
-  off = align_up(off + (size_t)max_S * 16);
+  long long max_r = 0;
+  for (const HostMat& h : plan->mats) max_r = std::max<long long>(max_r, h.dev.r);
+  plan->off_ortho = off;   // scratch of the orthonormality estimate: S x 4 floats, then splits x r x 4 floats
+  plan->ortho_z = align_up((size_t)max_S * 16);
+  off = align_up(off + plan->ortho_z + (size_t)FIRA_ORTHO_SPLITS * max_r * 16);
   size_t s = 0;
   s = align_up(s + sizeof(FiraEnt) * count);
   for (int l = 0; l < kNumTileLists; ++l) {
@@ -377,7 +380,9 @@ fira_status fira_set_projector(fira_ctx* ctx, int idx, const void* dev_P, fira_d
   // gate of the Gram route: estimate ||P^T P - I|| (stream-ordered, shares one S x 4 float scratch)
   float* ybuf = reinterpret_cast<float*>(ctx->slab + ctx->plan.off_ortho);
   hipLaunchKernelGGL(fira_ortho_y_kernel, dim3((h.dev.S + 3) / 4), dim3(256), 0, ctx->stream, h.dev, ybuf);
-  hipLaunchKernelGGL(fira_ortho_z_kernel, dim3(1), dim3(256), 0, ctx->stream, h.dev, (const float*)ybuf, ctx->d_scal, idx);
+  float* zbuf = reinterpret_cast<float*>(ctx->slab + ctx->plan.off_ortho + ctx->plan.ortho_z);
+  hipLaunchKernelGGL(fira_ortho_z_kernel, dim3(FIRA_ORTHO_SPLITS), dim3(256), 0, ctx->stream, h.dev, (const float*)ybuf, zbuf);
+  hipLaunchKernelGGL(fira_ortho_final_kernel, dim3(1), dim3(256), 0, ctx->stream, h.dev, (const float*)zbuf, ctx->d_scal, idx);
   FIRA_HIP(ctx, hipGetLastError());
   h.has_projector = true;
   return FIRA_OK;
@@ -419,17 +424,17 @@ fira_status fira_step(fira_ctx* ctx, int count, const int* idx, void* const* dev
   }
   auto grid8 = [](int n) { return dim3((unsigned)(((n + 7) / 8) * 8)); };
   const dim3 blk(FIRA_THREADS);
-  // 0. Gram route only: ||G_i||^2 for every factor (workgroups of other matrices return at once)
-  if (ctx->norm_mode == FIRA_NORM_GRAM)
+  // 0. Gram route, fp32 matrices only: ||G_i||^2 for every factor (bf16 matrices get it from step 1)
+  if (ctx->norm_mode == FIRA_NORM_GRAM && s->ntiles[kTilesBackF32] > 0)
     hipLaunchKernelGGL(fira_gradnorm_kernel, dim3(s->g2blocks), dim3(256), 0, q, ctx->d_mats, ctx->d_scal, s->d_ents, count,
                        s->g2blocks, hp);
   // 1. R = P^T G (long-side major), one launch per orientation
   if (s->ntiles[kTilesProjectLeft])
     hipLaunchKernelGGL(fira_project_kernel<true>, grid8(s->ntiles[kTilesProjectLeft]), blk, FIRA_LDS_BYTES, q,
-                       ctx->d_mats, s->d_ents, s->d_tiles[kTilesProjectLeft], s->ntiles[kTilesProjectLeft]);
+                       ctx->d_mats, s->d_ents, s->d_tiles[kTilesProjectLeft], s->ntiles[kTilesProjectLeft], ctx->norm_mode);
   if (s->ntiles[kTilesProjectRight])
     hipLaunchKernelGGL(fira_project_kernel<false>, grid8(s->ntiles[kTilesProjectRight]), blk, FIRA_LDS_BYTES, q,
-                       ctx->d_mats, s->d_ents, s->d_tiles[kTilesProjectRight], s->ntiles[kTilesProjectRight]);
+                       ctx->d_mats, s->d_ents, s->d_tiles[kTilesProjectRight], s->ntiles[kTilesProjectRight], ctx->norm_mode);
   mark(1);
   // 2. Adam on R, factor norms
   hipLaunchKernelGGL(fira_adam_kernel, dim3(s->rowblocks), dim3(256), 0, q, ctx->d_mats, ctx->d_scal, s->d_ents, count,

@@ -371,8 +371,8 @@ __global__ __launch_bounds__(256) void fira_gradnorm_kernel(const FiraMat* __res
   const FiraEnt ent = ents[e];
   if (!use_gram(hp, scal[ent.mat])) return;
   const FiraMat mt = mats[ent.mat];
-  if (mt.dtype == 1) g2_block<bf16_raw>(mt, ent, b - ent.g2b0, red);
-  else g2_block<float>(mt, ent, b - ent.g2b0, red);
+  if (mt.dtype == 1) return;   // bf16 matrices: the projection kernel accumulates ||G_i||^2 itself
+  g2_block<float>(mt, ent, b - ent.g2b0, red);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -405,22 +405,40 @@ __global__ __launch_bounds__(256) void fira_ortho_y_kernel(FiraMat mt, float* __
   }
 }
 
+// z-partials: workgroup b sums rows [b*chunk, (b+1)*chunk) of P^T y for all four trials.
+#define FIRA_ORTHO_SPLITS 64
 __global__ __launch_bounds__(256) void fira_ortho_z_kernel(FiraMat mt, const float* __restrict__ y,
-                                                           FiraScal* __restrict__ scal, int mat) {
-  __shared__ float red[4][4];
+                                                           float* __restrict__ zpart /* [splits][r][4] */) {
   gptr<const bf16_raw> Pn = as_global<const bf16_raw>(mt.Pn);
   gptr<const float> yy = as_global(y);
-  const int t = threadIdx.x;
-  float zz[4] = {0.f, 0.f, 0.f, 0.f};
-  for (int a = t; a < mt.r; a += 256) {
+  const int chunk = (mt.S + FIRA_ORTHO_SPLITS - 1) / FIRA_ORTHO_SPLITS;
+  const int s0 = blockIdx.x * chunk, s1 = min(mt.S, s0 + chunk);
+  for (int a = threadIdx.x; a < mt.r; a += 256) {
     float z[4] = {0.f, 0.f, 0.f, 0.f};
-    for (int s = 0; s < mt.S; ++s) {
+    for (int s = s0; s < s1; ++s) {
       const float p = bf16_to_f32(Pn[(long long)s * mt.lr_ld + a]);
 #pragma unroll
       for (int k = 0; k < 4; ++k) z[k] += p * yy[(long long)s * 4 + k];
     }
 #pragma unroll
-    for (int k = 0; k < 4; ++k) { const float d = z[k] - ortho_sign(a, k); zz[k] += d * d; }
+    for (int k = 0; k < 4; ++k) as_global(zpart)[((long long)blockIdx.x * mt.r + a) * 4 + k] = z[k];
+  }
+}
+
+__global__ __launch_bounds__(256) void fira_ortho_final_kernel(FiraMat mt, const float* __restrict__ zpart,
+                                                               FiraScal* __restrict__ scal, int mat) {
+  __shared__ float red[4][4];
+  gptr<const float> zp = as_global(zpart);
+  const int t = threadIdx.x;
+  float zz[4] = {0.f, 0.f, 0.f, 0.f};
+  for (int a = t; a < mt.r; a += 256) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      float z = 0.0f;
+      for (int b = 0; b < FIRA_ORTHO_SPLITS; ++b) z += zp[((long long)b * mt.r + a) * 4 + k];
+      const float d = z - ortho_sign(a, k);
+      zz[k] += d * d;
+    }
   }
 #pragma unroll
   for (int k = 0; k < 4; ++k) zz[k] = wave_sum(zz[k]);

@@ -227,16 +227,36 @@ __device__ __forceinline__ void gemm_mfma_slice(f32x16_t (&acc)[4][2], const Fra
     for (int tn = 0; tn < 2; ++tn)
       acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[tm], f.b[tn], acc[tm][tn], 0, 0, 0);
 }
-__device__ __forceinline__ void gemm_compute_step(f32x16_t (&acc)[4][2], const char* stage) {
+// Sum of squares of the A fragments (v_dot2c_f32_bf16: two bf16 products per instruction): with the
+// gradient on the A side this accumulates ||G_i||^2 for the wave's A rows at no extra memory traffic.
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ void gemm_sumsq_slice(float (&sq)[4], const Frags& f) {
+#pragma unroll
+  for (int tm = 0; tm < 4; ++tm) {
+    const u32x4 w = __builtin_bit_cast(u32x4, f.a[tm]);
+    const unsigned d[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const bf16x2_t v = __builtin_bit_cast(bf16x2_t, d[e]);
+      sq[tm] = __builtin_amdgcn_fdot2_f32_bf16(v, v, sq[tm], false);
+    }
+  }
+}
+template <bool SUMSQ>
+__device__ __forceinline__ void gemm_compute_step(f32x16_t (&acc)[4][2], const char* stage, float (&sq)[4]) {
   Frags f0, f1;
   gemm_read_frags(f0, stage, 0);
   gemm_read_frags(f1, stage, 1);
   gemm_mfma_slice(acc, f0);
+  if (SUMSQ) gemm_sumsq_slice(sq, f0);
   gemm_read_frags(f0, stage, 2);
   gemm_mfma_slice(acc, f1);
+  if (SUMSQ) gemm_sumsq_slice(sq, f1);
   gemm_read_frags(f1, stage, 3);
   gemm_mfma_slice(acc, f0);
+  if (SUMSQ) gemm_sumsq_slice(sq, f0);
   gemm_mfma_slice(acc, f1);
+  if (SUMSQ) gemm_sumsq_slice(sq, f1);
 }
 
 // acc[tm][tn]: wave (wm, wn) = (wave & 1, wave >> 1) owns A rows wm*128 + 32*tm + .., B rows wn*64 + 32*tn + ..
@@ -245,8 +265,8 @@ __device__ __forceinline__ void gemm_compute_step(f32x16_t (&acc)[4][2], const c
 //   before iteration s: LDS[s & 1] holds stage s; the registers hold stage s+1 (requested one
 //   iteration ago).
 //   iteration s: write the registers into LDS[(s+1)&1]; request stage s+2; multiply LDS[s&1]; barrier.
-template <bool AKSLOW, bool FAST>
-__device__ __forceinline__ void gemm_pipeline(f32x16_t (&acc)[4][2], char* lds, const GemmOperands& g) {
+template <bool AKSLOW, bool FAST, bool SUMSQ>
+__device__ __forceinline__ void gemm_pipeline(f32x16_t (&acc)[4][2], char* lds, const GemmOperands& g, float (&sq)[4]) {
   const int KT = (g.KA + FIRA_BK - 1) / FIRA_BK;
   u32x4 ra[4], rb[4];
   FastLoader<AKSLOW> fl(g);
@@ -268,23 +288,31 @@ __device__ __forceinline__ void gemm_pipeline(f32x16_t (&acc)[4][2], char* lds, 
     char* nxt = lds + ((s + 1) & 1) * FIRA_LDS_STAGE;
     gemm_store_tiles<AKSLOW>(nxt, ra, rb);     // stage s+1 (a repeat of the last stage at the end)
     request();                                 // stage s+2
-    gemm_compute_step(acc, cur);               // stage s
+    gemm_compute_step<SUMSQ>(acc, cur, sq);    // stage s
     __syncthreads();
   }
 }
 
+// sumsq: also accumulate sq[tm] = sum_k A[row][k]^2 for the rows this lane's fragments cover (lane
+// and lane + 32 hold the two halves of each row's sum); wave-uniform.
 template <bool AKSLOW>
-__device__ __forceinline__ void gemm_mainloop(f32x16_t (&acc)[4][2], char* lds, const GemmOperands& g) {
+__device__ __forceinline__ void gemm_mainloop(f32x16_t (&acc)[4][2], char* lds, const GemmOperands& g,
+                                              float (&sq)[4], bool sumsq) {
+#pragma unroll
+  for (int tm = 0; tm < 4; ++tm) sq[tm] = 0.0f;
 #pragma unroll
   for (int tm = 0; tm < 4; ++tm)
 #pragma unroll
     for (int tn = 0; tn < 2; ++tn)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[tm][tn][v] = 0.0f;
-  if (gemm_tile_is_interior(g))
-    gemm_pipeline<AKSLOW, true>(acc, lds, g);
-  else
-    gemm_pipeline<AKSLOW, false>(acc, lds, g);
+  if (gemm_tile_is_interior(g)) {
+    if (sumsq) gemm_pipeline<AKSLOW, true, true>(acc, lds, g, sq);
+    else gemm_pipeline<AKSLOW, true, false>(acc, lds, g, sq);
+  } else {
+    if (sumsq) gemm_pipeline<AKSLOW, false, true>(acc, lds, g, sq);
+    else gemm_pipeline<AKSLOW, false, false>(acc, lds, g, sq);
+  }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -298,7 +326,7 @@ template <bool LEFT>
 __global__ __launch_bounds__(FIRA_THREADS, 2) void fira_project_kernel(const FiraMat* __restrict__ mats,
                                                                        const FiraEnt* __restrict__ ents,
                                                                        const FiraTile* __restrict__ tiles,
-                                                                       int ntiles) {
+                                                                       int ntiles, int norm_mode) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
   const int ti = xcd_chunked_index(blockIdx.x, ntiles);
   if (ti < 0) return;
@@ -324,10 +352,23 @@ __global__ __launch_bounds__(FIRA_THREADS, 2) void fira_project_kernel(const Fir
     g.KA = mt.kx * mt.Sp;
   }
   f32x16_t acc[4][2];
-  gemm_mainloop<LEFT>(acc, lds, g);
-
+  float sq[4];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave & 1, wn = wave >> 1;
+  // Gram route: ||G_i||^2 of the tile's 256 factors falls out of the A fragments of the two waves
+  // with wn == 0, in the first rank tile of each panel.  (fp32 matrices feed split planes through
+  // here; their norms come from fira_gradnorm_kernel.)
+  const bool sumsq = norm_mode == 1 && mt.kx == 1 && tile.tb == 0 && wn == 0;
+  gemm_mainloop<LEFT>(acc, lds, g, sq, sumsq);
+  if (sumsq) {
+    gptr<float> g2 = as_global(mt.g2);
+#pragma unroll
+    for (int tm = 0; tm < 4; ++tm) {
+      const float tot = sq[tm] + __shfl_xor(sq[tm], 32, 64);
+      const int row = g.a_row0 + wm * 128 + 32 * tm + (lane & 31);
+      if (lane < 32 && row < mt.L) g2[row] = tot;
+    }
+  }
   gptr<float> Rt = as_global(mt.Rt);
 #pragma unroll
   for (int tm = 0; tm < 4; ++tm)
@@ -356,9 +397,11 @@ struct Elem8;  // 8 consecutive elements of W or G: raw registers, conversion to
 template <>
 struct Elem8<bf16_raw> {
   typedef u32x4 Raw;
+  // W and G are touched once per step: non-temporal accesses keep them from evicting the operand
+  // panels that the 32 CUs of an XCD share through its L2.
   template <bool INTERIOR>
   static __device__ __forceinline__ Raw load_raw(gptr<const bf16_raw> row, long long idx, long long limit) {
-    if (INTERIOR) return *reinterpret_cast<gptr<const u32x4_a2>>(row + idx);
+    if (INTERIOR) return __builtin_nontemporal_load(reinterpret_cast<gptr<const u32x4_a2>>(row + idx));
     return load8_bf16(row, idx, limit);
   }
   static __device__ __forceinline__ Raw zero() { return u32x4{0u, 0u, 0u, 0u}; }
@@ -375,7 +418,7 @@ struct Elem8<bf16_raw> {
     if (INTERIOR || idx + 8 <= limit) {
       const u32x4 v = u32x4{pack_bf16x2(x[0], x[1]), pack_bf16x2(x[2], x[3]), pack_bf16x2(x[4], x[5]),
                             pack_bf16x2(x[6], x[7])};
-      *reinterpret_cast<gptr<u32x4_a2>>(row + idx) = v;
+      __builtin_nontemporal_store(v, reinterpret_cast<gptr<u32x4_a2>>(row + idx));
     } else {
 #pragma unroll
       for (int e = 0; e < 8; ++e)
@@ -534,7 +577,8 @@ __global__ __launch_bounds__(FIRA_THREADS, 2) void fira_backproject_kernel(const
   g.A = mt.left ? lowrank : proj;
   g.B = mt.left ? proj : lowrank;
   f32x16_t acc[4][2];
-  gemm_mainloop<false>(acc, lds, g);
+  float sq_unused[4];
+  gemm_mainloop<false>(acc, lds, g, sq_unused, false);
 
   const float c = (MODE == 0) ? 1.0f : scal[ent.mat].c;
   const int i0 = g.b_row0, j0 = g.a_row0;
