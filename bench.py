@@ -27,27 +27,48 @@ PEAK_HBM_GBS = 8000.0        # MI355X HBM3E, GB/s
 PEAK_MFMA_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, TFLOP/s
 
 
-def kernel_models(shapes, r):
+def kernel_models(shapes, r, norm_mode):
     """Algorithmic flops and HBM bytes of each kernel for one step over `shapes` (bf16 W/G, fp32
-    state).  mn: elements of W; Lr: elements of the low-rank arrays; Sr: elements of P."""
+    state), and the roofline that bounds it.  mn: elements of W; Lr: elements of each low-rank array;
+    Sr: elements of P; L: number of scaling factors.  Every array is counted once per kernel that
+    must touch it; operand re-reads that hit in L2 are not algorithmic traffic."""
     mn = sum(m * n for m, n in shapes)
     Lr = sum(max(m, n) * r for m, n in shapes)
     Sr = sum(min(m, n) * r for m, n in shapes)
     L = sum(max(m, n) for m, n in shapes)
     gemm = 2.0 * mn * r
+    gram = norm_mode == "gram"
     return {
-        # R = P^T G: read G and P once, write R (fp32)
-        "project": dict(flops=gemm, bytes=2 * mn + 2 * Sr + 4 * Lr),
+        # R = P^T G: read G and P once, write R (fp32); dense contraction -> MFMA roofline
+        "project": dict(flops=gemm, bytes=2 * mn + 2 * Sr + 4 * Lr + (4 * L if gram else 0), bound="mfma"),
         # read R, M, V (fp32); write M, V (fp32), N and R as bf16 operands, the factors
-        "adam_norms": dict(flops=0.0, bytes=(4 + 8 + 8 + 2 + 2) * Lr + 4 * L),
-        # ||k (G - P R)||: read G, R (bf16), P
-        "residual_norm": dict(flops=gemm, bytes=2 * mn + 2 * Lr + 2 * Sr),
-        "limiter": dict(flops=0.0, bytes=0.0),
+        "adam_norms": dict(flops=0.0, bytes=(4 + 8 + 8 + 2 + 2) * Lr + (12 if gram else 4) * L, bound="hbm"),
+        # ||k (G - P R)||: read G, R (bf16), P; dense contraction (skipped on the Gram route)
+        "residual_norm": dict(flops=0.0 if gram else gemm, bytes=0.0 if gram else 2 * mn + 2 * Lr + 2 * Sr,
+                              bound="mfma"),
+        "limiter": dict(flops=0.0, bytes=4 * L if gram else 0.0, bound="hbm"),
         # Z = N - c k R: read N, R (bf16), write Z
-        "make_z": dict(flops=0.0, bytes=6 * Lr + 4 * L),
-        # W -= lr alpha (P Z + c k G): read G, W, Z, P; write W
-        "update": dict(flops=gemm, bytes=6 * mn + 2 * Lr + 2 * Sr),
+        "make_z": dict(flops=0.0, bytes=6 * Lr + 4 * L, bound="hbm"),
+        # W -= lr alpha (P Z + c k G): read G, W, Z, P; write W.  2 mn r flops against 6 mn bytes:
+        # at r = 512 the HBM time (bytes / 8 TB/s) is twice the MFMA time (flops / 2.5 PFLOP/s)
+        "update": dict(flops=gemm, bytes=6 * mn + 2 * Lr + 2 * Sr, bound="hbm"),
     }
+
+
+def read_traffic(workload, norm_mode):
+    """HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by the same
+    counters on a plain 1 GiB copy), as recorded in profiles/; {} when no record matches."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}_{norm_mode}.txt")
+    out = {}
+    if os.path.exists(path):
+        for line in open(path):
+            p = line.split()
+            if len(p) >= 2 and not line.startswith("#"):
+                try:
+                    out[p[0]] = float(p[1])
+                except ValueError:
+                    pass
+    return out
 
 
 def cpu_baseline(wl, sample_mats, steps=1):
@@ -143,24 +164,23 @@ def main():
     ms_sum, rec = ctx.fira_profile_end()
     finite = all(bool(torch.isfinite(w).all()) for w in W[:7])
 
-    model = kernel_models(shapes, wl.rank)
+    model = kernel_models(shapes, wl.rank, args.norm_mode)
+    traffic = read_traffic(name, args.norm_mode)
     kernels = {}
     for k, tot in ms_sum.items():
         avg_ms = tot / max(rec, 1)
         mdl = model[k]
-        t_mfma = mdl["flops"] / (PEAK_MFMA_BF16_TFLOPS * 1e12)
-        t_hbm = mdl["bytes"] / (PEAK_HBM_GBS * 1e9)
-        bound = "mfma" if t_mfma > t_hbm else "hbm"
+        bound = mdl["bound"]
         if bound == "mfma":
-            ach, peak, unit = mdl["flops"] / (avg_ms * 1e-3) / 1e12 if avg_ms > 0 else 0.0, PEAK_MFMA_BF16_TFLOPS, "TFLOP/s"
+            ach, peak, unit = (mdl["flops"] / (avg_ms * 1e-3) / 1e12 if avg_ms > 0 else 0.0), PEAK_MFMA_BF16_TFLOPS, "TFLOP/s"
         else:
-            ach, peak, unit = mdl["bytes"] / (avg_ms * 1e-3) / 1e9 if avg_ms > 0 else 0.0, PEAK_HBM_GBS, "GB/s"
+            ach, peak, unit = (mdl["bytes"] / (avg_ms * 1e-3) / 1e9 if avg_ms > 0 else 0.0), PEAK_HBM_GBS, "GB/s"
         kernels[k] = dict(avg_ms=round(avg_ms, 4), bound=bound, achieved=round(ach, 2), peak=peak, unit=unit,
                           frac=round(ach / peak, 4), gflop=round(mdl["flops"] / 1e9, 1),
-                          gbyte=round(mdl["bytes"] / 1e9, 3))
+                          gbyte=round(mdl["bytes"] / 1e9, 3), traffic=traffic.get(k))
     dom = max((k for k in kernels if k != "limiter"), key=lambda k: kernels[k]["avg_ms"])
     roof = dict(kernel=dom, bound=kernels[dom]["bound"], achieved=kernels[dom]["achieved"], peak=kernels[dom]["peak"],
-                unit=kernels[dom]["unit"], frac=kernels[dom]["frac"], traffic=None,
+                unit=kernels[dom]["unit"], frac=kernels[dom]["frac"], traffic=kernels[dom]["traffic"],
                 avg_ms=kernels[dom]["avg_ms"])
 
     out = {
