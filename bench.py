@@ -109,6 +109,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device-to-device copy (for scaling HBM traffic counters)")
+    ap.add_argument("--pad-ld", type=int, default=0,
+                    help="round the leading dimension of W and G up to a multiple of this many elements "
+                         "(0 = dense rows, ld = n: the headline configuration)")
     ap.add_argument("--norm-mode", choices=["gram", "residual"], default="gram",
                     help="how the limiter norm ||S|| is obtained (both are parity-tested)")
     args = ap.parse_args()
@@ -127,7 +130,8 @@ def main():
     shapes = wl.shapes
     gen = torch.Generator(device=dev)
     gen.manual_seed(1000 * wl.config_id)
-    ctx = fira.FiraContext(shapes, wl.rank, dt_f, fira.make_hparams(), device=dev)
+    lds = [((n + args.pad_ld - 1) // args.pad_ld) * args.pad_ld if args.pad_ld else n for (m, n) in shapes]
+    ctx = fira.FiraContext(shapes, wl.rank, dt_f, fira.make_hparams(), device=dev, lds=lds)
     ctx.fira_set_options(norm_mode=fira.FIRA_NORM_GRAM if args.norm_mode == "gram" else fira.FIRA_NORM_RESIDUAL)
     # projectors: one seeded orthonormal basis per distinct short side, installed into every matrix
     cache = {}
@@ -137,10 +141,13 @@ def main():
             P = synth.store_projector(synth.random_orthonormal_projector(wl, len(cache), min(m, n), wl.rank), wl.dtype)
             cache[key] = torch.from_numpy(P).to(dt_t).to(dev)
         ctx.fira_set_projector(i, cache[key])
-    W = [(0.02 * torch.randn(s, device=dev, generator=gen)).to(dt_t) for s in shapes]
+    def draw(scale, i):
+        m, n = shapes[i]
+        t = (scale * torch.randn((m, lds[i]), device=dev, generator=gen)).to(dt_t)
+        return t[:, :n]
+    W = [draw(0.02, i) for i in range(len(shapes))]
     n_sets = 3
-    Gsets = [[(wl.grad_scale * torch.randn(s, device=dev, generator=gen)).to(dt_t) for s in shapes]
-             for _ in range(n_sets)]
+    Gsets = [[draw(wl.grad_scale, i) for i in range(len(shapes))] for _ in range(n_sets)]
     idx = list(range(len(shapes)))
     prepared = [ctx.prepare(idx, W, G) for G in Gsets]
     torch.cuda.synchronize()
@@ -189,7 +196,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": name, "matrices": len(shapes), "rank": wl.rank,
                    "params": sum(m * n for m, n in shapes), "state_bytes": ctx.state_bytes,
-                   "gradient_sets": n_sets, "norm_mode": args.norm_mode, "finite": finite},
+                   "gradient_sets": n_sets, "norm_mode": args.norm_mode, "ld": "n" if not args.pad_ld else f"n rounded up to {args.pad_ld}", "finite": finite},
         "roofline": roof, "kernels": kernels,
     }
     if not args.no_cpu_baseline:

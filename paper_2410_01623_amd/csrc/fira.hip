@@ -119,7 +119,7 @@ bool make_plan(const fira_matrix_desc* d, int count, Plan* plan, fira_status* st
       m.Gx = (bf16_raw*)take(gx * 2);
     }
     h.ta_project = (m.L + FIRA_TA - 1) / FIRA_TA; h.tb_project = (m.r + FIRA_TB - 1) / FIRA_TB;
-    h.ta_back = (m.n + FIRA_TA - 1) / FIRA_TA;    h.tb_back = (m.m + FIRA_TB - 1) / FIRA_TB;
+    h.ta_back = (m.n + FIRA_TA - 1) / FIRA_TA;    h.tb_back = (m.m + FIRA_TB_HALF - 1) / FIRA_TB_HALF;
     h.tiles_project = h.ta_project * h.tb_project;
     h.tiles_back = h.ta_back * h.tb_back;
     h.rowblocks = (m.L + FIRA_ROWS_PER_WG - 1) / FIRA_ROWS_PER_WG;
@@ -245,9 +245,10 @@ ListSlot* acquire_list(fira_ctx* ctx, int count, const int* idx, void* const* W,
       for (int tbb = 0; tbb < h.tb_project; ++tbb) tl[lp][nt[lp]++] = FiraTile{e, ta, tbb, 0};
     // back-projection: groups of 8 column tiles x all row tiles keep both operand panels in L2
     const int lb = h.dev.dtype == FIRA_BF16 ? kTilesBackBf16 : kTilesBackF32;
-    for (int ta0 = 0; ta0 < h.ta_back; ta0 += 8)
+    const int grp = 8;
+    for (int ta0 = 0; ta0 < h.ta_back; ta0 += grp)
       for (int t2 = 0; t2 < h.tb_back; ++t2)
-        for (int ta = ta0; ta < std::min(ta0 + 8, h.ta_back); ++ta) tl[lb][nt[lb]++] = FiraTile{e, ta, t2, nparts++};
+        for (int ta = ta0; ta < std::min(ta0 + grp, h.ta_back); ++ta) tl[lb][nt[lb]++] = FiraTile{e, ta, t2, nparts++};
   }
   for (int l = 0; l < kNumTileLists; ++l) s->ntiles[l] = nt[l];
   s->rowblocks = rowblocks;
@@ -320,13 +321,13 @@ fira_status fira_init_state(fira_ctx** out, const fira_matrix_desc* d, int count
       return fail(nullptr, FIRA_ERR_HIP, msg_);                                                      \
     }                                                                                                \
   } while (0)
-  // the contraction kernels use 128 KB of dynamic LDS (gfx950 has 160 KB per workgroup)
+  // the contraction kernels use more dynamic LDS than the 64 KB default (gfx950 has 160 KB per CU)
   FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_project_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_LDS_BYTES));
   FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_project_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_LDS_BYTES));
-  FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_backproject_kernel<0, bf16_raw>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_LDS_BYTES));
-  FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_backproject_kernel<1, bf16_raw>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_LDS_BYTES));
-  FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_backproject_kernel<0, float>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_LDS_BYTES));
-  FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_backproject_kernel<1, float>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_LDS_BYTES));
+  FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_backproject_kernel<0, bf16_raw>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_BACK_LDS));
+  FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_backproject_kernel<1, bf16_raw>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_BACK_LDS));
+  FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_backproject_kernel<0, float>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_BACK_LDS));
+  FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_backproject_kernel<1, float>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_BACK_LDS));
   FIRA_INIT_HIP(hipHostMalloc((void**)&ctx->h_stage_all, p.slot_bytes * kSlots, hipHostMallocDefault));
   for (int i = 0; i < kSlots; ++i) {
     ListSlot& s = ctx->slots[i];
@@ -442,11 +443,11 @@ fira_status fira_step(fira_ctx* ctx, int count, const int* idx, void* const* dev
   mark(2);
   // 3. ||k (G - P R)||^2 per tile
   if (s->ntiles[kTilesBackBf16])
-    hipLaunchKernelGGL((fira_backproject_kernel<0, bf16_raw>), grid8(s->ntiles[kTilesBackBf16]), blk, FIRA_LDS_BYTES, q,
+    hipLaunchKernelGGL((fira_backproject_kernel<0, bf16_raw>), grid8(s->ntiles[kTilesBackBf16]), dim3(FIRA_HALF_THREADS), FIRA_BACK_LDS, q,
                        ctx->d_mats, ctx->d_scal, s->d_ents, s->d_tiles[kTilesBackBf16], s->ntiles[kTilesBackBf16],
                        ctx->d_partial, hp);
   if (s->ntiles[kTilesBackF32])
-    hipLaunchKernelGGL((fira_backproject_kernel<0, float>), grid8(s->ntiles[kTilesBackF32]), blk, FIRA_LDS_BYTES, q,
+    hipLaunchKernelGGL((fira_backproject_kernel<0, float>), grid8(s->ntiles[kTilesBackF32]), dim3(FIRA_HALF_THREADS), FIRA_BACK_LDS, q,
                        ctx->d_mats, ctx->d_scal, s->d_ents, s->d_tiles[kTilesBackF32], s->ntiles[kTilesBackF32],
                        ctx->d_partial, hp);
   mark(3);
@@ -459,11 +460,11 @@ fira_status fira_step(fira_ctx* ctx, int count, const int* idx, void* const* dev
   mark(5);
   // 6. W -= lr alpha (P Z + c k G)
   if (s->ntiles[kTilesBackBf16])
-    hipLaunchKernelGGL((fira_backproject_kernel<1, bf16_raw>), grid8(s->ntiles[kTilesBackBf16]), blk, FIRA_LDS_BYTES, q,
+    hipLaunchKernelGGL((fira_backproject_kernel<1, bf16_raw>), grid8(s->ntiles[kTilesBackBf16]), dim3(FIRA_HALF_THREADS), FIRA_BACK_LDS, q,
                        ctx->d_mats, ctx->d_scal, s->d_ents, s->d_tiles[kTilesBackBf16], s->ntiles[kTilesBackBf16],
                        ctx->d_partial, hp);
   if (s->ntiles[kTilesBackF32])
-    hipLaunchKernelGGL((fira_backproject_kernel<1, float>), grid8(s->ntiles[kTilesBackF32]), blk, FIRA_LDS_BYTES, q,
+    hipLaunchKernelGGL((fira_backproject_kernel<1, float>), grid8(s->ntiles[kTilesBackF32]), dim3(FIRA_HALF_THREADS), FIRA_BACK_LDS, q,
                        ctx->d_mats, ctx->d_scal, s->d_ents, s->d_tiles[kTilesBackF32], s->ntiles[kTilesBackF32],
                        ctx->d_partial, hp);
   mark(6);

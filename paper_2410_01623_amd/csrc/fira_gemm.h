@@ -34,7 +34,6 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
 #define FIRA_LDS_B (FIRA_TB * 128)
 #define FIRA_LDS_STAGE (FIRA_LDS_A + FIRA_LDS_B)
 #define FIRA_LDS_BYTES (2 * FIRA_LDS_STAGE)   // 128 KB of the CU's 160 KB
-#define FIRA_EPI_STRIDE 68   // floats per staged row: 64 + 4 (keeps 16-byte alignment, shifts banks)
 
 __device__ __forceinline__ int lds_tile_off(int row, int chunk) {
   return row * 128 + (((chunk ^ row ^ (row >> 3) ^ (row >> 6)) & 7) << 4);
@@ -384,6 +383,100 @@ __global__ __launch_bounds__(FIRA_THREADS, 2) void fira_project_kernel(const Fir
 }
 
 // ------------------------------------------------------------------------------------------------
+// Half-tile core for the rank-axis contractions (K = r is short, the epilogue is long): 256 threads,
+// 256 (A) x 128 (B) tile, one LDS stage (48 KB) with the next stage in flight in registers, two
+// workgroups per CU.  The two workgroups are independent, so one runs its HBM-bound epilogue while the
+// other multiplies, and their bursts of loads do not coincide.  Both operands are K-contiguous.
+// Wave mapping, fragment reads and MFMA slices are those of the full tile (4 waves: wn = 0, 1).
+// ------------------------------------------------------------------------------------------------
+#define FIRA_TB_HALF 128
+#define FIRA_HALF_THREADS 256
+#define FIRA_HALF_LDS (FIRA_LDS_A + FIRA_TB_HALF * 128)
+
+template <bool FAST>
+struct HalfLoader {
+  const GemmOperands& g;
+  gptr<const bf16_raw> pa, pb;
+  unsigned offa[8], offb[4];
+  int k0;
+  __device__ __forceinline__ HalfLoader(const GemmOperands& g_) : g(g_), k0(0) {
+    const int t = threadIdx.x;
+    const int cc = t & 7, rr = t >> 3;
+    pa = g.A + (long long)g.a_row0 * g.lda;
+    pb = g.B + (long long)g.b_row0 * g.ldb;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) offa[i] = (unsigned)((rr + 32 * i) * g.lda + 8 * cc);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) offb[i] = (unsigned)((rr + 32 * i) * g.ldb + 8 * cc);
+  }
+  // loads the stage at the current K offset, then advances while `more` (a request past the last
+  // stage re-reads the last stage and is never used)
+  __device__ __forceinline__ void load(u32x4 (&ra)[8], u32x4 (&rb)[4], bool more) {
+    if (FAST) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) ra[i] = *reinterpret_cast<gptr<const u32x4_a2>>(pa + offa[i]);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) rb[i] = *reinterpret_cast<gptr<const u32x4_a2>>(pb + offb[i]);
+      pa += more ? FIRA_BK : 0;
+      pb += more ? FIRA_BK : 0;
+    } else {
+      const int t = threadIdx.x;
+      const int cc = t & 7, rr = t >> 3;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int row = g.a_row0 + rr + 32 * i;
+        const int rc = row < g.a_rows ? row : g.a_rows - 1;
+        ra[i] = load8_bf16(g.A + (long long)rc * g.lda, k0 + 8 * cc, g.KA);
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int row = g.b_row0 + rr + 32 * i;
+        const int rc = row < g.b_rows ? row : g.b_rows - 1;
+        rb[i] = load8_bf16(g.B + (long long)rc * g.ldb, k0 + 8 * cc, g.KB);
+      }
+      k0 += more ? FIRA_BK : 0;
+    }
+  }
+};
+
+__device__ __forceinline__ void half_store_tiles(char* lds, const u32x4 (&ra)[8], const u32x4 (&rb)[4]) {
+  const int t = threadIdx.x;
+  const int cc = t & 7, rr = t >> 3;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) *reinterpret_cast<u32x4*>(lds + lds_tile_off(rr + 32 * i, cc)) = ra[i];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4*>(lds + FIRA_LDS_A + lds_tile_off(rr + 32 * i, cc)) = rb[i];
+}
+
+template <bool FAST>
+__device__ __forceinline__ void half_pipeline(f32x16_t (&acc)[4][2], char* lds, const GemmOperands& g) {
+  const int KT = (g.KA + FIRA_BK - 1) / FIRA_BK;
+  u32x4 ra[8], rb[4];
+  float sq[4];
+  HalfLoader<FAST> ld(g);
+  ld.load(ra, rb, 1 < KT);
+  for (int s = 0; s < KT; ++s) {
+    half_store_tiles(lds, ra, rb);
+    __syncthreads();
+    ld.load(ra, rb, s + 2 < KT);                 // stage s+1, in flight while stage s is multiplied
+    gemm_compute_step<false>(acc, lds, sq);
+    __syncthreads();
+  }
+}
+
+__device__ __forceinline__ void half_mainloop(f32x16_t (&acc)[4][2], char* lds, const GemmOperands& g) {
+#pragma unroll
+  for (int tm = 0; tm < 4; ++tm)
+#pragma unroll
+    for (int tn = 0; tn < 2; ++tn)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[tm][tn][v] = 0.0f;
+  const bool interior = g.a_row0 + FIRA_TA <= g.a_rows && g.b_row0 + FIRA_TB_HALF <= g.b_rows && (g.KA % FIRA_BK) == 0;
+  if (interior) half_pipeline<true>(acc, lds, g);
+  else half_pipeline<false>(acc, lds, g);
+}
+
+// ------------------------------------------------------------------------------------------------
 // Kernels 2 and 3 share the contraction  U[i][j] = sum_a X[i][a] Y[j][a]  over the rank axis, with
 // X = P (m x r) and Y = Z or R long-side major (n x r) when left, X = Z or R (m x r) and Y = Q (n x r)
 // when right.  The A side is Y (so a lane owns 4 consecutive columns j), the B side is X.
@@ -461,67 +554,83 @@ struct Elem8<float> {
   }
 };
 
-// Epilogue of the rank-axis contractions.  The wave's 64(i) x 128(j) accumulators are processed as
-// four 32 x 64 slabs; the G (and W) values of slab s+1 are requested from HBM before slab s is
-// re-laid out through LDS and consumed, so their latency overlaps the LDS work.
+// Epilogue of the rank-axis contractions.  Two waves that share 64 tile rows (i) own 256 adjacent
+// columns (j) between them; their accumulators are re-laid out through one LDS slab of 32 rows x 256
+// columns per step, so that every global instruction covers two full 256-column row segments
+// (512 B of bf16, 1 KB of fp32, contiguous) instead of 64-column pieces.  That matters most when
+// ld is odd and no 16-byte access is aligned: the number of partially covered 128-byte lines per
+// instruction drops four-fold.  The G (and W) values of the second slab are requested while the
+// first one is consumed.
+#define FIRA_EPI_STRIDE 260   // floats per staged row: 256 + 4 (keeps 16-byte alignment, shifts banks)
+#define FIRA_EPI_LDS (2 * 32 * FIRA_EPI_STRIDE * 4)
+#define FIRA_BACK_LDS (FIRA_EPI_LDS > FIRA_HALF_LDS ? FIRA_EPI_LDS : FIRA_HALF_LDS)
 template <int MODE, typename T, bool INTERIOR>
 __device__ __forceinline__ float backproject_epilogue(f32x16_t (&acc)[4][2], char* lds, const FiraMat& mt,
                                                       const FiraEnt& ent, int i0, int j0, float c, float lr_alpha) {
   typedef typename Elem8<T>::Raw Raw;
-  constexpr bool PIPE = sizeof(T) == 2;       // fp32 tiles would need 64 more registers: no prefetch
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  constexpr bool PIPE = sizeof(T) == 2;       // fp32 tiles would need 128 more registers: no prefetch
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wm = wave & 1, wn = wave >> 1;
-  float* buf = reinterpret_cast<float*>(lds) + wave * (32 * FIRA_EPI_STRIDE);
+  float* buf = reinterpret_cast<float*>(lds) + wn * (32 * FIRA_EPI_STRIDE);
   gptr<const T> G = as_global(reinterpret_cast<const T*>(ent.G));
   gptr<T> W = as_global(reinterpret_cast<T*>(ent.W));
   gptr<const float> phi = as_global<const float>(mt.phi);
-  const int jl = 8 * (lane & 7);              // this lane's 8 columns inside the staged 64
-  const int il0 = lane >> 3;                  // this lane's row inside each group of 8 staged rows
-  Raw gbuf[PIPE ? 2 : 1][4], wbuf[PIPE ? 2 : 1][4];
-  auto preload = [&](int s, Raw (&gr)[4], Raw (&wr)[4]) {
-    const int th = s >> 1, tn = s & 1;
-    const long long j = (long long)j0 + wm * 128 + 64 * th + jl;
-#pragma unroll
-    for (int p = 0; p < 4; ++p) {
-      const long long i = (long long)i0 + wn * 64 + 32 * tn + 8 * p + il0;
-      const bool ok = INTERIOR || (i < mt.m && j < mt.n);
-      gr[p] = ok ? Elem8<T>::template load_raw<INTERIOR>(G + i * mt.ld, j, mt.n) : Elem8<T>::zero();
-      if (MODE == 1) wr[p] = ok ? Elem8<T>::template load_raw<INTERIOR>(W + i * mt.ld, j, mt.n) : Elem8<T>::zero();
+  const int jl = 8 * (lane & 31);             // this lane's 8 columns inside the staged 256
+  const int ih = lane >> 5;                   // which of the two rows of a pass
+  const long long j = (long long)j0 + jl;
+  // slab tn holds tile rows wn*64 + 32*tn .. +31; this wave consumes 16 of them, two per pass.
+  // Interior tiles address a pass as a wave-uniform row pointer plus one 32-bit lane offset.
+  const long long wave_row0 = (long long)i0 + wn * 64 + 16 * wm;
+  const long long lane_off = (unsigned)(ih * (int)mt.ld + jl);
+  auto slab_row = [&](int p) { return 16 * wm + 2 * p + ih; };
+  auto fetch = [&](int tn, int p, Raw& gr, Raw& wr) {
+    if (INTERIOR) {
+      const long long base = (wave_row0 + 32 * tn + 2 * p) * mt.ld + j0;
+      gr = Elem8<T>::template load_raw<true>(G + base, lane_off, 0);
+      if (MODE == 1) wr = Elem8<T>::template load_raw<true>(W + base, lane_off, 0);
+    } else {
+      const long long i = (long long)i0 + wn * 64 + 32 * tn + slab_row(p);
+      const bool ok = i < mt.m && j < mt.n;
+      gr = ok ? Elem8<T>::template load_raw<false>(G + i * mt.ld, j, mt.n) : Elem8<T>::zero();
+      if (MODE == 1) wr = ok ? Elem8<T>::template load_raw<false>(W + i * mt.ld, j, mt.n) : Elem8<T>::zero();
     }
   };
-  if (PIPE) preload(0, gbuf[0], wbuf[0]);
-  float sum = 0.0f;
+  Raw gbuf[PIPE ? 8 : 1], wbuf[PIPE ? 8 : 1];
+  if (PIPE) {
+#pragma unroll
+    for (int p = 0; p < 8; ++p) fetch(0, p, gbuf[p], wbuf[p]);
+  }
   float cphi[8];
+  if (mt.left) {
 #pragma unroll
-  for (int s = 0; s < 4; ++s) {
-    const int th = s >> 1, tn = s & 1;
-    const long long j = (long long)j0 + wm * 128 + 64 * th + jl;
-    if (PIPE && s + 1 < 4) preload(s + 1, gbuf[PIPE ? ((s + 1) & 1) : 0], wbuf[PIPE ? ((s + 1) & 1) : 0]);
-    if (!PIPE) preload(s, gbuf[0], wbuf[0]);
-    if (mt.left && tn == 0) {
+    for (int e = 0; e < 8; ++e) cphi[e] = (INTERIOR || j + e < mt.n) ? c * phi[j + e] : 0.0f;
+  }
+  float sum = 0.0f;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) cphi[e] = (INTERIOR || j + e < mt.n) ? c * phi[j + e] : 0.0f;
-    }
+  for (int tn = 0; tn < 2; ++tn) {
     __syncthreads();  // previous slab fully consumed (first time: the main loop's LDS reads are done)
 #pragma unroll
-    for (int t2 = 0; t2 < 2; ++t2)
+    for (int tm = 0; tm < 4; ++tm)
 #pragma unroll
       for (int vg = 0; vg < 4; ++vg) {
-        const f32x16_t& a = acc[2 * th + t2][tn];
+        const f32x16_t& a = acc[tm][tn];
         const f32x4 val = f32x4{a[4 * vg], a[4 * vg + 1], a[4 * vg + 2], a[4 * vg + 3]};
-        *reinterpret_cast<f32x4*>(buf + (lane & 31) * FIRA_EPI_STRIDE + 32 * t2 + 8 * vg + 4 * (lane >> 5)) = val;
+        *reinterpret_cast<f32x4*>(buf + (lane & 31) * FIRA_EPI_STRIDE + 128 * wm + 32 * tm + 8 * vg + 4 * (lane >> 5)) = val;
       }
     __syncthreads();
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
-      const int il = 8 * p + il0;
+    for (int p = 0; p < 8; ++p) {
+      const int il = slab_row(p);
       const long long i = (long long)i0 + wn * 64 + 32 * tn + il;
+      if (!PIPE) fetch(tn, p, gbuf[0], wbuf[0]);
+      Raw& gr = gbuf[PIPE ? p : 0];
+      Raw& wr = wbuf[PIPE ? p : 0];
       if (INTERIOR || (i < mt.m && j < mt.n)) {
         const f32x4 u0 = *reinterpret_cast<const f32x4*>(buf + il * FIRA_EPI_STRIDE + jl);
         const f32x4 u1 = *reinterpret_cast<const f32x4*>(buf + il * FIRA_EPI_STRIDE + jl + 4);
         const float u[8] = {u0.x, u0.y, u0.z, u0.w, u1.x, u1.y, u1.z, u1.w};
         float g[8];
-        Elem8<T>::unpack(gbuf[PIPE ? (s & 1) : 0][p], g);
+        Elem8<T>::unpack(gr, g);
         if (!mt.left) {
           const float f = c * phi[i];
 #pragma unroll
@@ -535,12 +644,14 @@ __device__ __forceinline__ float backproject_epilogue(f32x16_t (&acc)[4][2], cha
           }
         } else {
           float w[8];
-          Elem8<T>::unpack(wbuf[PIPE ? (s & 1) : 0][p], w);
+          Elem8<T>::unpack(wr, w);
 #pragma unroll
           for (int e = 0; e < 8; ++e) w[e] = w[e] - lr_alpha * (u[e] + cphi[e] * g[e]);
-          Elem8<T>::template store<INTERIOR>(w, W + i * mt.ld, j, mt.n);
+          if (INTERIOR) Elem8<T>::template store<true>(w, W + ((wave_row0 + 32 * tn + 2 * p) * mt.ld + j0), lane_off, 0);
+          else Elem8<T>::template store<false>(w, W + i * mt.ld, j, mt.n);
         }
       }
+      if (PIPE && tn == 0) fetch(1, p, gr, wr);
     }
   }
   return sum;
@@ -548,14 +659,14 @@ __device__ __forceinline__ float backproject_epilogue(f32x16_t (&acc)[4][2], cha
 
 // T: storage type of W and G of every matrix in the tile list (the host keeps one list per type).
 template <int MODE, typename T>
-__global__ __launch_bounds__(FIRA_THREADS, 2) void fira_backproject_kernel(const FiraMat* __restrict__ mats,
+__global__ __launch_bounds__(FIRA_HALF_THREADS, 2) void fira_backproject_kernel(const FiraMat* __restrict__ mats,
                                                                            const FiraScal* __restrict__ scal,
                                                                            const FiraEnt* __restrict__ ents,
                                                                            const FiraTile* __restrict__ tiles,
                                                                            int ntiles, float* __restrict__ partial,
                                                                            FiraHp hp) {
-  extern __shared__ __attribute__((aligned(16))) char lds[];
-  __shared__ float red[8];
+  extern __shared__ __attribute__((aligned(16))) char lds[];   // FIRA_BACK_LDS bytes
+  __shared__ float red[4];
   const int ti = xcd_chunked_index(blockIdx.x, ntiles);
   if (ti < 0) return;
   const FiraTile tile = tiles[ti];
@@ -570,19 +681,18 @@ __global__ __launch_bounds__(FIRA_THREADS, 2) void fira_backproject_kernel(const
   GemmOperands g;
   g.a_row0 = tile.ta * FIRA_TA;
   g.a_rows = mt.n;
-  g.b_row0 = tile.tb * FIRA_TB;
+  g.b_row0 = tile.tb * FIRA_TB_HALF;
   g.b_rows = mt.m;
   g.lda = g.ldb = mt.lr_ld;
   g.KA = g.KB = mt.kx * mt.rp;
   g.A = mt.left ? lowrank : proj;
   g.B = mt.left ? proj : lowrank;
   f32x16_t acc[4][2];
-  float sq_unused[4];
-  gemm_mainloop<false>(acc, lds, g, sq_unused, false);
+  half_mainloop(acc, lds, g);
 
   const float c = (MODE == 0) ? 1.0f : scal[ent.mat].c;
   const int i0 = g.b_row0, j0 = g.a_row0;
-  const bool interior = i0 + FIRA_TB <= mt.m && j0 + FIRA_TA <= mt.n;
+  const bool interior = i0 + FIRA_TB_HALF <= mt.m && j0 + FIRA_TA <= mt.n;
   float sum;
   if (interior) sum = backproject_epilogue<MODE, T, true>(acc, lds, mt, ent, i0, j0, c, lr_alpha);
   else sum = backproject_epilogue<MODE, T, false>(acc, lds, mt, ent, i0, j0, c, lr_alpha);
@@ -594,6 +704,6 @@ __global__ __launch_bounds__(FIRA_THREADS, 2) void fira_backproject_kernel(const
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = sum;
     __syncthreads();
     if (threadIdx.x == 0)
-      as_global(partial)[tile.part] = ((red[0] + red[1]) + (red[2] + red[3])) + ((red[4] + red[5]) + (red[6] + red[7]));
+      as_global(partial)[tile.part] = (red[0] + red[1]) + (red[2] + red[3]);
   }
 }
