@@ -100,6 +100,7 @@ bool make_plan(const fira_matrix_desc* d, int count, Plan* plan, fira_status* st
     m.dtype = d[i].wg_dtype;
     m.kx = (m.dtype == FIRA_F32) ? FIRA_KX_SPLIT : 1;
     m.lr_ld = operand_pitch((long long)m.kx * m.rp);
+    m.zready = (m.kx == 1 && (m.r & 3) == 0 && m.r <= FIRA_ZREADY_MAX_R) ? 1 : 0; m.pad0 = 0;
     m.pt_ld = operand_pitch((long long)m.kx * m.Sp);
     m.gx_ld = m.left ? round_up_int(m.n, 8) : operand_pitch((long long)m.kx * m.Sp);
     const size_t Lr = (size_t)m.L * m.r;

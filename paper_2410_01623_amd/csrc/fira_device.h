@@ -26,6 +26,7 @@ typedef f32x4 __attribute__((aligned(4))) f32x4_a4;
 // projector operands use sequence B; position p of A meets position p of B in the contraction.
 //   A: h h m h l m        B: h m h l h m
 #define FIRA_KX_SPLIT 6
+#define FIRA_ZREADY_MAX_R 1024
 
 // Immutable description of one weight matrix (device array, one element per matrix).
 struct FiraMat {
@@ -40,6 +41,11 @@ struct FiraMat {
   // and a 256-row operand tile would then be served by one channel of sixteen.
   int lr_ld;           // Nb, Rb, Pn rows: kx*rp values + padding
   int pt_ld;           // PT rows: kx*Sp values + padding
+  // 1: the Adam kernel keeps a factor's row in registers and writes Z for c = 1 directly (bf16
+  // matrices with r a multiple of 4, up to FIRA_ZREADY_MAX_R); the Z kernel then only corrects
+  // the matrices whose limiter factor came out below 1.
+  int zready;
+  int pad0;
   // low-rank arrays, all "long-side major": row i holds the r values of factor i
   float* M;            // [L][r]   first moment
   float* V;            // [L][r]   second moment

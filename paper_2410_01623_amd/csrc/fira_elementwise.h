@@ -99,7 +99,60 @@ __device__ __forceinline__ void adam_row(const FiraMat& mt, const FiraHp& hp, fl
   }
 }
 
-__global__ __launch_bounds__(256) void fira_adam_kernel(const FiraMat* __restrict__ mats,
+// Same update for bf16 matrices with r % 4 == 0 and r <= FIRA_ZREADY_MAX_R: the factor's N and R stay
+// in registers until k_i is known, and the row is written once as the back-projection operand for
+// an inactive limiter, Z_i = N_i - k_i R_i, rounded from fp32 a single time.  R is written as an
+// operand only when the residual contraction will need it.
+template <int NIT>   // 256 * NIT >= r
+__device__ __forceinline__ void adam_row_zready(const FiraMat& mt, const FiraHp& hp, float bias, long long row, bool gram) {
+  const int lane = threadIdx.x & 63;
+  const int r = mt.r;
+  gptr<const float> R = as_global<const float>(mt.Rt) + row * r;
+  gptr<float> M = as_global(mt.M) + row * r;
+  gptr<float> V = as_global(mt.V) + row * r;
+  gptr<bf16_raw> Nb = as_global(mt.Nb) + row * (long long)mt.lr_ld;
+  gptr<bf16_raw> Rb = as_global(mt.Rb) + row * (long long)mt.lr_ld;
+  float nn = 0.0f, rr = 0.0f;
+  f32x4 nv[NIT], rv[NIT];
+#pragma unroll
+  for (int it = 0; it < NIT; ++it) {
+    const int a = lane * 4 + 256 * it;
+    if (a < r) {
+      rv[it] = *reinterpret_cast<gptr<const f32x4>>(R + a);
+      f32x4 mv = *reinterpret_cast<gptr<const f32x4>>(M + a);
+      f32x4 vv = *reinterpret_cast<gptr<const f32x4>>(V + a);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        mv[e] = hp.b1 * mv[e] + hp.omb1 * rv[it][e];
+        vv[e] = hp.b2 * vv[e] + hp.omb2 * (rv[it][e] * rv[it][e]);
+        nv[it][e] = bias * (mv[e] / (sqrtf(vv[e]) + hp.epsf));
+        nn += nv[it][e] * nv[it][e];
+        rr += rv[it][e] * rv[it][e];
+      }
+      *reinterpret_cast<gptr<f32x4>>(M + a) = mv;
+      *reinterpret_cast<gptr<f32x4>>(V + a) = vv;
+    }
+  }
+  nn = wave_sum(nn);
+  rr = wave_sum(rr);
+  const float k = (hp.scaling == 2) ? 1.0f : sqrtf(nn) / (sqrtf(rr) + hp.epsf);
+#pragma unroll
+  for (int it = 0; it < NIT; ++it) {
+    const int a = lane * 4 + 256 * it;
+    if (a < r) {
+      const f32x4 z = nv[it] - k * rv[it];
+      *reinterpret_cast<gptr<u32x2>>(Nb + a) = u32x2{pack_bf16x2(z[0], z[1]), pack_bf16x2(z[2], z[3])};
+      if (!gram)
+        *reinterpret_cast<gptr<u32x2>>(Rb + a) = u32x2{pack_bf16x2(rv[it][0], rv[it][1]), pack_bf16x2(rv[it][2], rv[it][3])};
+    }
+  }
+  if (lane == 0) {
+    as_global(mt.phi)[row] = k;
+    if (gram) as_global(mt.q)[row] = k * k * fmaxf(as_global<const float>(mt.g2)[row] - rr, 0.0f);
+  }
+}
+
+__global__ __launch_bounds__(256, 4) void fira_adam_kernel(const FiraMat* __restrict__ mats,
                                                         const FiraScal* __restrict__ scal,
                                                         const FiraEnt* __restrict__ ents, int count,
                                                         int total_rowblocks, FiraHp hp) {
@@ -119,7 +172,11 @@ __global__ __launch_bounds__(256) void fira_adam_kernel(const FiraMat* __restric
   for (int i = 0; i < 4; ++i) {
     const long long row = row_base + i;
     if (row >= mt.L) break;
-    if (mt.kx == 1) {
+    if (mt.zready) {
+      if (mt.r <= 256) adam_row_zready<1>(mt, hp, bias, row, gram);
+      else if (mt.r <= 512) adam_row_zready<2>(mt, hp, bias, row, gram);
+      else adam_row_zready<FIRA_ZREADY_MAX_R / 256>(mt, hp, bias, row, gram);
+    } else if (mt.kx == 1) {
       if ((mt.r & 3) == 0) adam_row<1, 4>(mt, hp, bias, row, gram); else adam_row<1, 1>(mt, hp, bias, row, gram);
     } else {
       adam_row<FIRA_KX_SPLIT, 1>(mt, hp, bias, row, gram);
@@ -168,7 +225,7 @@ __global__ __launch_bounds__(64) void fira_limiter_kernel(const FiraMat* __restr
 
 // ------------------------------------------------------------------------------------------------
 // Back-projection operand: Z_i = N_i - c k_i R_i, so that P N + c k (G - P R) = P Z + c k G.
-// Overwrites N in place.
+// Overwrites N in place.  Matrices flagged zready skip this unless their limiter factor is below 1.
 // ------------------------------------------------------------------------------------------------
 template <int KX>
 __device__ __forceinline__ void makez_row(const FiraMat& mt, float f, long long row) {
@@ -200,6 +257,22 @@ __device__ __forceinline__ void makez_row(const FiraMat& mt, float f, long long 
   }
 }
 
+// Rows that already hold Z for c = 1 (N_i - k_i R_i): add back (1 - c) k_i R_i, with R in fp32.
+__device__ __forceinline__ void fixz_row(const FiraMat& mt, float f, long long row) {
+  const int lane = threadIdx.x & 63;
+  gptr<bf16_raw> Nb = as_global(mt.Nb) + row * (long long)mt.lr_ld;
+  gptr<const float> R = as_global<const float>(mt.Rt) + row * mt.r;
+  for (int a = lane * 4; a < mt.r; a += 256) {
+    const u32x2 zv = *reinterpret_cast<gptr<const u32x2>>(Nb + a);
+    const f32x4 rv = *reinterpret_cast<gptr<const f32x4>>(R + a);
+    const float z0 = __uint_as_float(zv.x << 16) + f * rv[0];
+    const float z1 = __uint_as_float(zv.x & 0xffff0000u) + f * rv[1];
+    const float z2 = __uint_as_float(zv.y << 16) + f * rv[2];
+    const float z3 = __uint_as_float(zv.y & 0xffff0000u) + f * rv[3];
+    *reinterpret_cast<gptr<u32x2>>(Nb + a) = u32x2{pack_bf16x2(z0, z1), pack_bf16x2(z2, z3)};
+  }
+}
+
 __global__ __launch_bounds__(256) void fira_makez_kernel(const FiraMat* __restrict__ mats,
                                                          const FiraScal* __restrict__ scal,
                                                          const FiraEnt* __restrict__ ents, int count,
@@ -210,13 +283,16 @@ __global__ __launch_bounds__(256) void fira_makez_kernel(const FiraMat* __restri
   const FiraEnt ent = ents[e];
   const FiraMat mt = mats[ent.mat];
   const float c = scal[ent.mat].c;
+  if (mt.zready && c == 1.0f) return;          // the Adam kernel already wrote Z for c = 1
   const int wave = threadIdx.x >> 6;
   const long long row_base = (long long)(rb - ent.row0) * FIRA_ROWS_PER_WG + wave * 4;
   for (int i = 0; i < 4; ++i) {
     const long long row = row_base + i;
     if (row >= mt.L) break;
-    const float f = c * as_global<const float>(mt.phi)[row];
-    if (mt.kx == 1) makez_row<1>(mt, f, row); else makez_row<FIRA_KX_SPLIT>(mt, f, row);
+    const float k = as_global<const float>(mt.phi)[row];
+    if (mt.zready) fixz_row(mt, (1.0f - c) * k, row);
+    else if (mt.kx == 1) makez_row<1>(mt, c * k, row);
+    else makez_row<FIRA_KX_SPLIT>(mt, c * k, row);
   }
 }
 

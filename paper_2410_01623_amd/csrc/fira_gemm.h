@@ -383,97 +383,117 @@ __global__ __launch_bounds__(FIRA_THREADS, 2) void fira_project_kernel(const Fir
 }
 
 // ------------------------------------------------------------------------------------------------
-// Half-tile core for the rank-axis contractions (K = r is short, the epilogue is long): 256 threads,
-// 256 (A) x 128 (B) tile, one LDS stage (48 KB) with the next stage in flight in registers, two
-// workgroups per CU.  The two workgroups are independent, so one runs its HBM-bound epilogue while the
-// other multiplies, and their bursts of loads do not coincide.  Both operands are K-contiguous.
-// Wave mapping, fragment reads and MFMA slices are those of the full tile (4 waves: wn = 0, 1).
+// Ring core for the rank-axis contractions (K = r is short, the epilogue is long): 256 threads,
+// 256 (A) x 128 (B) tile, two workgroups per CU, so one runs its HBM-bound epilogue while the other
+// multiplies.  Both operands are K-contiguous with 16-byte aligned, zero-padded rows, so they go
+// from global memory straight into LDS (global_load_lds_dwordx4: lane l of a wave writes 16 bytes at
+// M0 + 16*l) without passing through registers.  LDS holds a ring of three K stages of 32
+// ([row][32 k] bf16, 64 B per row, 24 KB per stage): while stage s is multiplied, stages s+1 and
+// s+2 are in flight, and there is one barrier per stage.
+//
+// The loads are written as inline assembly because the compiler, which cannot tell the ring's
+// buffers apart, would wait for every outstanding LDS-direct load before each fragment read.  The
+// waits are explicit instead: loads retire in order, so vmcnt(6) (one stage = 6 loads per thread)
+// means "everything but the newest stage has landed".  Other vector memory operations the compiler
+// may have in flight only make that wait stricter.
+//
+// Slot layout of a stage: the 16-byte chunk c (8 k) of row r sits at  r*64 + 16*((c ^ f(r)) & 3),
+// f(r) = bit2(r) | (bit3(r) ^ bit1(r)) << 1, which makes the fragment reads (32 consecutive rows,
+// one chunk) hit distinct 16-byte bank groups within every aligned group of 8 and of 16 lanes.
+// Since a lane may fetch any global address, the loader realises the permutation on the global
+// side: lane l of a load covers row l/4 of a 16-row group and fetches chunk (l%4) ^ f(l/4).
 // ------------------------------------------------------------------------------------------------
 #define FIRA_TB_HALF 128
 #define FIRA_HALF_THREADS 256
-#define FIRA_HALF_LDS (FIRA_LDS_A + FIRA_TB_HALF * 128)
+#define FIRA_RK 32
+#define FIRA_RING_A (FIRA_TA * 64)
+#define FIRA_RING_B (FIRA_TB_HALF * 64)
+#define FIRA_RING_STAGE (FIRA_RING_A + FIRA_RING_B)
+#define FIRA_RING_STAGES 3
+#define FIRA_RING_LDS (FIRA_RING_STAGES * FIRA_RING_STAGE)
 
-template <bool FAST>
-struct HalfLoader {
-  const GemmOperands& g;
-  gptr<const bf16_raw> pa, pb;
-  unsigned offa[8], offb[4];
-  int k0;
-  __device__ __forceinline__ HalfLoader(const GemmOperands& g_) : g(g_), k0(0) {
-    const int t = threadIdx.x;
-    const int cc = t & 7, rr = t >> 3;
-    pa = g.A + (long long)g.a_row0 * g.lda;
-    pb = g.B + (long long)g.b_row0 * g.ldb;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) offa[i] = (unsigned)((rr + 32 * i) * g.lda + 8 * cc);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) offb[i] = (unsigned)((rr + 32 * i) * g.ldb + 8 * cc);
-  }
-  // loads the stage at the current K offset, then advances while `more` (a request past the last
-  // stage re-reads the last stage and is never used)
-  __device__ __forceinline__ void load(u32x4 (&ra)[8], u32x4 (&rb)[4], bool more) {
-    if (FAST) {
-#pragma unroll
-      for (int i = 0; i < 8; ++i) ra[i] = *reinterpret_cast<gptr<const u32x4_a2>>(pa + offa[i]);
-#pragma unroll
-      for (int i = 0; i < 4; ++i) rb[i] = *reinterpret_cast<gptr<const u32x4_a2>>(pb + offb[i]);
-      pa += more ? FIRA_BK : 0;
-      pb += more ? FIRA_BK : 0;
-    } else {
-      const int t = threadIdx.x;
-      const int cc = t & 7, rr = t >> 3;
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const int row = g.a_row0 + rr + 32 * i;
-        const int rc = row < g.a_rows ? row : g.a_rows - 1;
-        ra[i] = load8_bf16(g.A + (long long)rc * g.lda, k0 + 8 * cc, g.KA);
-      }
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int row = g.b_row0 + rr + 32 * i;
-        const int rc = row < g.b_rows ? row : g.b_rows - 1;
-        rb[i] = load8_bf16(g.B + (long long)rc * g.ldb, k0 + 8 * cc, g.KB);
-      }
-      k0 += more ? FIRA_BK : 0;
-    }
-  }
-};
+typedef __attribute__((address_space(3))) char* lds_ptr;
 
-__device__ __forceinline__ void half_store_tiles(char* lds, const u32x4 (&ra)[8], const u32x4 (&rb)[4]) {
-  const int t = threadIdx.x;
-  const int cc = t & 7, rr = t >> 3;
-#pragma unroll
-  for (int i = 0; i < 8; ++i) *reinterpret_cast<u32x4*>(lds + lds_tile_off(rr + 32 * i, cc)) = ra[i];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4*>(lds + FIRA_LDS_A + lds_tile_off(rr + 32 * i, cc)) = rb[i];
+__device__ __forceinline__ int ring_swz(int row) { return ((row >> 2) & 1) | ((((row >> 3) ^ (row >> 1)) & 1) << 1); }
+__device__ __forceinline__ int ring_tile_off(int row, int chunk) {
+  return row * 64 + (((chunk ^ ring_swz(row)) & 3) << 4);
 }
 
-template <bool FAST>
-__device__ __forceinline__ void half_pipeline(f32x16_t (&acc)[4][2], char* lds, const GemmOperands& g) {
-  const int KT = (g.KA + FIRA_BK - 1) / FIRA_BK;
-  u32x4 ra[8], rb[4];
-  float sq[4];
-  HalfLoader<FAST> ld(g);
-  ld.load(ra, rb, 1 < KT);
-  for (int s = 0; s < KT; ++s) {
-    half_store_tiles(lds, ra, rb);
-    __syncthreads();
-    ld.load(ra, rb, s + 2 < KT);                 // stage s+1, in flight while stage s is multiplied
-    gemm_compute_step<false>(acc, lds, sq);
-    __syncthreads();
-  }
+// 16 bytes per lane from base + voff (base wave-uniform) to LDS byte address lds_addr + 16*lane.
+// M0 is not preserved; on this target the compiler loads M0 right before each of its own uses.
+__device__ __forceinline__ void lds_dma16(const void* base, unsigned voff, unsigned lds_addr) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+               :: "v"(voff), "s"(base), "s"(lds_addr) : "memory");
 }
 
-__device__ __forceinline__ void half_mainloop(f32x16_t (&acc)[4][2], char* lds, const GemmOperands& g) {
+__device__ __forceinline__ void ring_compute(f32x16_t (&acc)[4][2], const char* stage) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = wave & 1, wn = wave >> 1;
+  const char* la = stage;
+  const char* lb = stage + FIRA_RING_A;
+  Frags f[2];
+#pragma unroll
+  for (int kk = 0; kk < 2; ++kk) {
+    const int chunk = 2 * kk + (lane >> 5);
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+      f[kk].a[t] = *reinterpret_cast<const bf16x8_t*>(la + ring_tile_off(wm * 128 + 32 * t + (lane & 31), chunk));
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+      f[kk].b[t] = *reinterpret_cast<const bf16x8_t*>(lb + ring_tile_off(wn * 64 + 32 * t + (lane & 31), chunk));
+  }
+  gemm_mfma_slice(acc, f[0]);
+  gemm_mfma_slice(acc, f[1]);
+}
+
+// Requires KA == KB, a multiple of 64, readable on every row of both operands (zero padded), and
+// 16-byte aligned rows.  Rows beyond an operand are clamped to its last row; their products land in
+// accumulators that are never stored.
+__device__ __forceinline__ void ring_mainloop(f32x16_t (&acc)[4][2], char* lds, const GemmOperands& g) {
 #pragma unroll
   for (int tm = 0; tm < 4; ++tm)
 #pragma unroll
     for (int tn = 0; tn < 2; ++tn)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[tm][tn][v] = 0.0f;
-  const bool interior = g.a_row0 + FIRA_TA <= g.a_rows && g.b_row0 + FIRA_TB_HALF <= g.b_rows && (g.KA % FIRA_BK) == 0;
-  if (interior) half_pipeline<true>(acc, lds, g);
-  else half_pipeline<false>(acc, lds, g);
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const unsigned lds0 = (unsigned)(size_t)(lds_ptr)lds;
+  const int KT = g.KA / FIRA_RK;
+  const int lrow = lane >> 2;
+  const int chunk = (lane & 3) ^ ring_swz(lrow);
+  unsigned offa[4], offb[2];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int row = g.a_row0 + 16 * (4 * wave + q) + lrow;
+    const int rc = (row < g.a_rows ? row : g.a_rows - 1) - g.a_row0;
+    offa[q] = (unsigned)(rc * (int)g.lda * 2 + chunk * 16);
+  }
+#pragma unroll
+  for (int q = 0; q < 2; ++q) {
+    const int row = g.b_row0 + 16 * (2 * wave + q) + lrow;
+    const int rc = (row < g.b_rows ? row : g.b_rows - 1) - g.b_row0;
+    offb[q] = (unsigned)(rc * (int)g.ldb * 2 + chunk * 16);
+  }
+  const char* pa = reinterpret_cast<const char*>((const bf16_raw*)g.A + (long long)g.a_row0 * g.lda);
+  const char* pb = reinterpret_cast<const char*>((const bf16_raw*)g.B + (long long)g.b_row0 * g.ldb);
+  auto issue = [&](int s) {
+    const unsigned dst = lds0 + (unsigned)((s % FIRA_RING_STAGES) * FIRA_RING_STAGE);
+    const char* ka = pa + (long long)s * (FIRA_RK * 2);
+    const char* kb = pb + (long long)s * (FIRA_RK * 2);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) lds_dma16(ka, offa[q], dst + (unsigned)((4 * wave + q) * 1024));
+#pragma unroll
+    for (int q = 0; q < 2; ++q) lds_dma16(kb, offb[q], dst + (unsigned)(FIRA_RING_A + (2 * wave + q) * 1024));
+  };
+  issue(0);
+  if (KT > 1) issue(1);
+  for (int s = 0; s < KT; ++s) {
+    // stage s has landed (this wave's share), then everybody's; everybody is also done with stage s-1
+    if (s + 1 < KT) asm volatile("s_waitcnt vmcnt(6)\n\ts_barrier" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+    if (s + 2 < KT) issue(s + 2);            // into the buffer of stage s-1
+    ring_compute(acc, lds + (s % FIRA_RING_STAGES) * FIRA_RING_STAGE);
+  }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -563,7 +583,7 @@ struct Elem8<float> {
 // first one is consumed.
 #define FIRA_EPI_STRIDE 260   // floats per staged row: 256 + 4 (keeps 16-byte alignment, shifts banks)
 #define FIRA_EPI_LDS (2 * 32 * FIRA_EPI_STRIDE * 4)
-#define FIRA_BACK_LDS (FIRA_EPI_LDS > FIRA_HALF_LDS ? FIRA_EPI_LDS : FIRA_HALF_LDS)
+#define FIRA_BACK_LDS (FIRA_EPI_LDS > FIRA_RING_LDS ? FIRA_EPI_LDS : FIRA_RING_LDS)
 template <int MODE, typename T, bool INTERIOR>
 __device__ __forceinline__ float backproject_epilogue(f32x16_t (&acc)[4][2], char* lds, const FiraMat& mt,
                                                       const FiraEnt& ent, int i0, int j0, float c, float lr_alpha) {
@@ -688,7 +708,7 @@ __global__ __launch_bounds__(FIRA_HALF_THREADS, 2) void fira_backproject_kernel(
   g.A = mt.left ? lowrank : proj;
   g.B = mt.left ? proj : lowrank;
   f32x16_t acc[4][2];
-  half_mainloop(acc, lds, g);
+  ring_mainloop(acc, lds, g);
 
   const float c = (MODE == 0) ? 1.0f : scal[ent.mat].c;
   const int i0 = g.b_row0, j0 = g.a_row0;
