@@ -119,7 +119,7 @@ bool make_plan(const fira_matrix_desc* d, int count, Plan* plan, fira_status* st
       const size_t gx = m.left ? (size_t)m.kx * m.Sp * m.gx_ld : (size_t)m.m * m.gx_ld;
       m.Gx = (bf16_raw*)take(gx * 2);
     }
-    h.ta_project = (m.L + FIRA_TA - 1) / FIRA_TA; h.tb_project = (m.r + FIRA_TB - 1) / FIRA_TB;
+    h.ta_project = (m.L + FIRA_PA - 1) / FIRA_PA; h.tb_project = (m.r + FIRA_PB - 1) / FIRA_PB;
     h.ta_back = (m.n + FIRA_TA - 1) / FIRA_TA;    h.tb_back = (m.m + FIRA_TB_HALF - 1) / FIRA_TB_HALF;
     h.tiles_project = h.ta_project * h.tb_project;
     h.tiles_back = h.ta_back * h.tb_back;
@@ -323,8 +323,8 @@ fira_status fira_init_state(fira_ctx** out, const fira_matrix_desc* d, int count
     }                                                                                                \
   } while (0)
   // the contraction kernels use more dynamic LDS than the 64 KB default (gfx950 has 160 KB per CU)
-  FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_project_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_LDS_BYTES));
-  FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_project_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_LDS_BYTES));
+  FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_project_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_PROJ_LDS));
+  FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_project_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_PROJ_LDS));
   FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_backproject_kernel<0, bf16_raw>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_BACK_LDS));
   FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_backproject_kernel<1, bf16_raw>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_BACK_LDS));
   FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_backproject_kernel<0, float>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_BACK_LDS));
@@ -425,17 +425,17 @@ fira_status fira_step(fira_ctx* ctx, int count, const int* idx, void* const* dev
     }
   }
   auto grid8 = [](int n) { return dim3((unsigned)(((n + 7) / 8) * 8)); };
-  const dim3 blk(FIRA_THREADS);
+  const dim3 blk(FIRA_PROJ_THREADS);
   // 0. Gram route, fp32 matrices only: ||G_i||^2 for every factor (bf16 matrices get it from step 1)
   if (ctx->norm_mode == FIRA_NORM_GRAM && s->ntiles[kTilesBackF32] > 0)
     hipLaunchKernelGGL(fira_gradnorm_kernel, dim3(s->g2blocks), dim3(256), 0, q, ctx->d_mats, ctx->d_scal, s->d_ents, count,
                        s->g2blocks, hp);
   // 1. R = P^T G (long-side major), one launch per orientation
   if (s->ntiles[kTilesProjectLeft])
-    hipLaunchKernelGGL(fira_project_kernel<true>, grid8(s->ntiles[kTilesProjectLeft]), blk, FIRA_LDS_BYTES, q,
+    hipLaunchKernelGGL(fira_project_kernel<true>, grid8(s->ntiles[kTilesProjectLeft]), blk, FIRA_PROJ_LDS, q,
                        ctx->d_mats, s->d_ents, s->d_tiles[kTilesProjectLeft], s->ntiles[kTilesProjectLeft], ctx->norm_mode);
   if (s->ntiles[kTilesProjectRight])
-    hipLaunchKernelGGL(fira_project_kernel<false>, grid8(s->ntiles[kTilesProjectRight]), blk, FIRA_LDS_BYTES, q,
+    hipLaunchKernelGGL(fira_project_kernel<false>, grid8(s->ntiles[kTilesProjectRight]), blk, FIRA_PROJ_LDS, q,
                        ctx->d_mats, s->d_ents, s->d_tiles[kTilesProjectRight], s->ntiles[kTilesProjectRight], ctx->norm_mode);
   mark(1);
   // 2. Adam on R, factor norms

@@ -322,7 +322,7 @@ __device__ __forceinline__ void gemm_mainloop(f32x16_t (&acc)[4][2], char* lds, 
 // One instantiation per orientation; the host keeps one tile list for each.
 // ------------------------------------------------------------------------------------------------
 template <bool LEFT>
-__global__ __launch_bounds__(FIRA_THREADS, 2) void fira_project_kernel(const FiraMat* __restrict__ mats,
+__global__ __launch_bounds__(FIRA_THREADS, 2) void fira_project_kernel_v4(const FiraMat* __restrict__ mats,
                                                                        const FiraEnt* __restrict__ ents,
                                                                        const FiraTile* __restrict__ tiles,
                                                                        int ntiles, int norm_mode) {
@@ -494,6 +494,284 @@ __device__ __forceinline__ void ring_mainloop(f32x16_t (&acc)[4][2], char* lds, 
     if (s + 2 < KT) issue(s + 2);            // into the buffer of stage s-1
     ring_compute(acc, lds + (s % FIRA_RING_STAGES) * FIRA_RING_STAGE);
   }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Kernel 1 (pipelined form): low-rank gradient, long-side major:  Rt[i][a] = sum_s G(s, i) P[s][a]
+//   LEFT  (m <= n): i = column of G, s = row of G      -> A side is G read K-slow
+//   RIGHT (m >  n): i = row of G,    s = column of G   -> A side is G read K-contiguous
+//   B side is PT[a][s] (rank rows, short-side contiguous, 16-byte aligned, zero padded).
+// 256 threads, 128 (A: gradient side) x 256 (B: rank) tile, two independent workgroups per CU so
+// that the load/store phases of one overlap the multiplies of the other.  Wave w owns all 128 A rows
+// and B rows 64 w .. 64 w + 63.
+//   B goes straight from global memory into a three-stage LDS ring (K stages of 32, as in the ring
+//   core above).
+//   A cannot: a gradient row starts at any 2-byte boundary and the left orientation needs a
+//   transpose.  It passes through registers, one K stage of 64 per two ring stages, into a single
+//   128-B-per-row LDS tile.
+// Per K stage of 64 ("E" half, then "O" half; D(s) = ring stage s of B, A(S) = register stage):
+//   E: wait A(S), D(2S); barrier; registers -> LDS A; request D(2S+2), A(S+1); barrier; multiply
+//      k = 0..31 of the stage
+//   O: wait D(2S+1); barrier; request D(2S+3); multiply k = 32..63
+// All requests of the interior path are inline assembly, so the waits can be exact: loads retire in
+// order, each request group is 4 instructions per thread, and the queue order is
+// A(0) D(0) D(1) | D(2) A(1) | D(3) | D(4) A(2) | D(5) ...; E waits with vmcnt(4) (only the newest
+// D may be in flight), O with vmcnt(8).  Edge tiles load A with ordinary guarded loads at the same
+// points of the sequence; the compiler's own waits for those only wait longer.
+// ------------------------------------------------------------------------------------------------
+#define FIRA_PA 128
+#define FIRA_PB 256
+#define FIRA_PROJ_THREADS 256
+#define FIRA_PROJ_LDS_A (FIRA_PA * 128)
+#define FIRA_PROJ_RING_STAGE (FIRA_PB * 64)
+#define FIRA_PROJ_LDS (FIRA_PROJ_LDS_A + FIRA_RING_STAGES * FIRA_PROJ_RING_STAGE)
+
+// 16 bytes per lane from base + voff into registers; the result may only be read after a wait that
+// names the registers (wait_loads below).
+__device__ __forceinline__ void gload16_async(u32x4& dst, const void* base, unsigned voff) {
+  asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(dst) : "v"(voff), "s"(base) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_loads(u32x4 (&r)[4]) {
+  static_assert(N == 4 || N == 0, "queue depths used by the projection pipeline");
+  if (N == 4) asm volatile("s_waitcnt vmcnt(4)" : "+v"(r[0]), "+v"(r[1]), "+v"(r[2]), "+v"(r[3]) :: "memory");
+  else asm volatile("s_waitcnt vmcnt(0)" : "+v"(r[0]), "+v"(r[1]), "+v"(r[2]), "+v"(r[3]) :: "memory");
+}
+
+// Thread -> element mapping of the A loaders (256 threads, 64 k x 128 rows per stage):
+//   K-contiguous: chunk cc = t & 7, rows rr + 32*q, rr = t >> 3, q = 0..3.
+//   K-slow:       one 4(k) x 8(a) block per thread: a-block ib = t & 15, k-quad kq = t >> 4, so 16
+//                 lanes read 256 contiguous bytes of one gradient row and the 32 lanes of a
+//                 half-wave write 16 distinct 8-byte LDS slots twice.
+template <bool LEFT, bool FAST>
+struct ProjALoader {
+  const GemmOperands& g;
+  const char* base;       // wave-uniform, advances along K
+  unsigned off[4];        // byte offsets of this thread's four 16-byte loads
+  long long step;         // bytes per K stage of 64
+  int k0;
+  __device__ __forceinline__ ProjALoader(const GemmOperands& g_) : g(g_), k0(0) {
+    const int t = threadIdx.x;
+    if (LEFT) {
+      const int ib = t & 15, kq = t >> 4;
+      base = reinterpret_cast<const char*>((const bf16_raw*)g.A + g.a_row0);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) off[j] = (unsigned)(((4 * kq + j) * g.lda + 8 * ib) * 2);
+      step = 64 * g.lda * 2;
+    } else {
+      const int cc = t & 7, rr = t >> 3;
+      base = reinterpret_cast<const char*>((const bf16_raw*)g.A + (long long)g.a_row0 * g.lda);
+#pragma unroll
+      for (int q = 0; q < 4; ++q) off[q] = (unsigned)(((rr + 32 * q) * g.lda + 8 * cc) * 2);
+      step = 64 * 2;
+    }
+  }
+  __device__ __forceinline__ void load(u32x4 (&ra)[4]) {
+    if (FAST) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) gload16_async(ra[j], base, off[j]);
+      base += step;
+    } else {
+      const int t = threadIdx.x;
+      const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
+      if (LEFT) {
+        const int ib = t & 15, kq = t >> 4;
+        const long long a = (long long)g.a_row0 + 8 * ib;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int k = k0 + 4 * kq + j;
+          const int kc = k < g.KA ? k : g.KA - 1;
+          const u32x4 v = load8_bf16(g.A + (long long)kc * g.lda, a, g.a_rows);
+          ra[j] = k < g.KA ? v : zero;
+        }
+      } else {
+        const int cc = t & 7, rr = t >> 3;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int row = g.a_row0 + rr + 32 * q;
+          const int rc = row < g.a_rows ? row : g.a_rows - 1;
+          ra[q] = load8_bf16(g.A + (long long)rc * g.lda, k0 + 8 * cc, g.KA);
+        }
+      }
+      k0 += 64;
+    }
+  }
+};
+
+template <bool LEFT>
+__device__ __forceinline__ void proj_store_a(char* la, const u32x4 (&ra)[4]) {
+  const int t = threadIdx.x;
+  if (LEFT) {
+    // ra[j] holds row k = 4*kq + j of a 4(k) x 8(a) block; emit, for each a, its 4 k values (8 B).
+    const int ib = t & 15, kq = t >> 4;
+    const unsigned in[16] = {ra[0].x, ra[0].y, ra[0].z, ra[0].w, ra[1].x, ra[1].y, ra[1].z, ra[1].w,
+                             ra[2].x, ra[2].y, ra[2].z, ra[2].w, ra[3].x, ra[3].y, ra[3].z, ra[3].w};  // in[4*j + d]: a = 2d, 2d+1
+#pragma unroll
+    for (int ii = 0; ii < 8; ++ii) {
+      unsigned w[2];
+#pragma unroll
+      for (int d = 0; d < 2; ++d) {
+        const unsigned x = in[4 * (2 * d) + (ii >> 1)];      // k = 2d
+        const unsigned y = in[4 * (2 * d + 1) + (ii >> 1)];  // k = 2d + 1
+        w[d] = (ii & 1) ? ((x >> 16) | (y & 0xffff0000u)) : ((x & 0xffffu) | (y << 16));
+      }
+      const int row = 8 * ib + ii;
+      *reinterpret_cast<u32x2*>(la + lds_tile_off(row, kq >> 1) + 8 * (kq & 1)) = u32x2{w[0], w[1]};
+    }
+  } else {
+    const int cc = t & 7, rr = t >> 3;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) *reinterpret_cast<u32x4*>(la + lds_tile_off(rr + 32 * q, cc)) = ra[q];
+  }
+}
+
+// 32 k of the wave's 128 x 64 sub-tile: A fragments from the 128-B-per-row tile (k-slices kk4, kk4+1
+// of its 4), B fragments from a ring stage.
+template <bool SUMSQ>
+__device__ __forceinline__ void proj_compute(f32x16_t (&acc)[4][2], const char* la, const char* lb, int kk4,
+                                             float (&sq)[4]) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  Frags f[2];
+#pragma unroll
+  for (int kk = 0; kk < 2; ++kk) {
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+      f[kk].a[t] = *reinterpret_cast<const bf16x8_t*>(la + lds_tile_off(32 * t + (lane & 31), 2 * (kk4 + kk) + (lane >> 5)));
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+      f[kk].b[t] = *reinterpret_cast<const bf16x8_t*>(lb + ring_tile_off(wave * 64 + 32 * t + (lane & 31), 2 * kk + (lane >> 5)));
+  }
+#pragma unroll
+  for (int kk = 0; kk < 2; ++kk) {
+    gemm_mfma_slice(acc, f[kk]);
+    if (SUMSQ) gemm_sumsq_slice(sq, f[kk]);
+  }
+}
+
+template <bool LEFT, bool FAST, bool SUMSQ>
+__device__ __forceinline__ void proj_pipeline(f32x16_t (&acc)[4][2], char* lds, const GemmOperands& g, float (&sq)[4]) {
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  char* la = lds;
+  char* ring = lds + FIRA_PROJ_LDS_A;
+  const unsigned ring0 = (unsigned)(size_t)(lds_ptr)ring;
+  const int SS = g.KB / 64;                    // K stages of 64; the ring runs 2*SS stages of 32
+  const int lrow = lane >> 2;
+  const int chunk = (lane & 3) ^ ring_swz(lrow);
+  unsigned offb[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int row = g.b_row0 + 16 * (4 * wave + q) + lrow;
+    const int rc = (row < g.b_rows ? row : g.b_rows - 1) - g.b_row0;
+    offb[q] = (unsigned)(rc * (int)g.ldb * 2 + chunk * 16);
+  }
+  const char* pb = reinterpret_cast<const char*>((const bf16_raw*)g.B + (long long)g.b_row0 * g.ldb);
+  auto request_b = [&](int s) {
+    const unsigned dst = ring0 + (unsigned)((s % FIRA_RING_STAGES) * FIRA_PROJ_RING_STAGE);
+    const char* kb = pb + (long long)s * (FIRA_RK * 2);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) lds_dma16(kb, offb[q], dst + (unsigned)((4 * wave + q) * 1024));
+  };
+  ProjALoader<LEFT, FAST> al(g);
+  u32x4 ra[4];
+  al.load(ra);                                 // A(0)
+  request_b(0);
+  request_b(1);
+  for (int S = 0; S < SS; ++S) {
+    // E half
+    wait_loads<4>(ra);                         // A(S) and D(2S) have landed; D(2S+1) may be in flight
+    asm volatile("s_barrier" ::: "memory");    // everybody is done with the previous stage's A tile and ring slot
+    proj_store_a<LEFT>(la, ra);
+    if (S + 1 < SS) {
+      request_b(2 * S + 2);
+      al.load(ra);                             // A(S+1)
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    proj_compute<SUMSQ>(acc, la, ring + ((2 * S) % FIRA_RING_STAGES) * FIRA_PROJ_RING_STAGE, 0, sq);
+    // O half
+    // D(2S+1) has landed.  Guarded A loads are the compiler's and may be fewer than 4 instructions,
+    // so the edge path only lets D(2S+2)'s four stay in flight.
+    if (S + 1 >= SS) asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+    else if (FAST) asm volatile("s_waitcnt vmcnt(8)\n\ts_barrier" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(4)\n\ts_barrier" ::: "memory");
+    if (S + 1 < SS) request_b(2 * S + 3);
+    proj_compute<SUMSQ>(acc, la, ring + ((2 * S + 1) % FIRA_RING_STAGES) * FIRA_PROJ_RING_STAGE, 2, sq);
+  }
+}
+
+template <bool LEFT>
+__global__ __launch_bounds__(FIRA_PROJ_THREADS, 2) void fira_project_kernel(const FiraMat* __restrict__ mats,
+                                                                            const FiraEnt* __restrict__ ents,
+                                                                            const FiraTile* __restrict__ tiles,
+                                                                            int ntiles, int norm_mode) {
+  extern __shared__ __attribute__((aligned(16))) char lds[];   // FIRA_PROJ_LDS bytes
+  const int ti = xcd_chunked_index(blockIdx.x, ntiles);
+  if (ti < 0) return;
+  const FiraTile tile = tiles[ti];
+  const FiraEnt ent = ents[tile.ent];
+  const FiraMat mt = mats[ent.mat];
+
+  GemmOperands g;
+  g.a_row0 = tile.ta * FIRA_PA;
+  g.a_rows = mt.L;
+  g.b_row0 = tile.tb * FIRA_PB;
+  g.b_rows = mt.r;
+  g.B = as_global<const bf16_raw>(mt.PT);
+  g.ldb = mt.pt_ld;
+  g.KB = mt.kx * mt.Sp;
+  if (mt.kx == 1) {
+    g.A = as_global(reinterpret_cast<const bf16_raw*>(ent.G));
+    g.lda = mt.ld;
+    g.KA = mt.S;
+  } else {
+    g.A = as_global<const bf16_raw>(mt.Gx);
+    g.lda = mt.gx_ld;
+    g.KA = mt.kx * mt.Sp;
+  }
+  f32x16_t acc[4][2];
+  float sq[4];
+#pragma unroll
+  for (int tm = 0; tm < 4; ++tm) {
+    sq[tm] = 0.0f;
+#pragma unroll
+    for (int tn = 0; tn < 2; ++tn)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[tm][tn][v] = 0.0f;
+  }
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  // Gram route: ||G_i||^2 of the tile's 128 factors falls out of the A fragments of wave 0 in the
+  // first rank tile of each panel.  (fp32 matrices feed split planes through here; their norms
+  // come from fira_gradnorm_kernel.)
+  const bool sumsq = norm_mode == 1 && mt.kx == 1 && tile.tb == 0 && wave == 0;
+  // LEFT: the k rows of G are whole rows of the matrix (any ld); RIGHT: a row of G holds KA values
+  const bool interior = g.a_row0 + FIRA_PA <= g.a_rows && g.KA == g.KB;
+  if (interior) {
+    if (sumsq) proj_pipeline<LEFT, true, true>(acc, lds, g, sq);
+    else proj_pipeline<LEFT, true, false>(acc, lds, g, sq);
+  } else {
+    if (sumsq) proj_pipeline<LEFT, false, true>(acc, lds, g, sq);
+    else proj_pipeline<LEFT, false, false>(acc, lds, g, sq);
+  }
+  if (sumsq) {
+    gptr<float> g2 = as_global(mt.g2);
+#pragma unroll
+    for (int tm = 0; tm < 4; ++tm) {
+      const float tot = sq[tm] + __shfl_xor(sq[tm], 32, 64);
+      const int row = g.a_row0 + 32 * tm + (lane & 31);
+      if (lane < 32 && row < mt.L) g2[row] = tot;
+    }
+  }
+  gptr<float> Rt = as_global(mt.Rt);
+#pragma unroll
+  for (int tm = 0; tm < 4; ++tm)
+#pragma unroll
+    for (int tn = 0; tn < 2; ++tn) {
+      const int col = g.b_row0 + wave * 64 + 32 * tn + (lane & 31);
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int row = g.a_row0 + 32 * tm + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+        if (row < mt.L && col < mt.r) Rt[(long long)row * mt.r + col] = acc[tm][tn][v];
+      }
+    }
 }
 
 // ------------------------------------------------------------------------------------------------
