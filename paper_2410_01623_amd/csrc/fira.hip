@@ -69,6 +69,7 @@ struct Plan {
   size_t off_slots = 0, slot_bytes = 0, slot_off_tiles[kNumTileLists] = {0, 0, 0, 0};
   std::vector<HostMat> mats;
   int max_tiles[kNumTileLists] = {0, 0, 0, 0};
+  int adam_lds = 0;          // dynamic LDS of the Adam kernel: 16 rows of the widest register-resident matrix
 };
 
 bool valid_desc(const fira_matrix_desc& d, std::string* why) {
@@ -99,9 +100,9 @@ bool make_plan(const fira_matrix_desc* d, int count, Plan* plan, fira_status* st
     m.rp = round_up_int(m.r, 64); m.Sp = round_up_int(m.S, 64);
     m.dtype = d[i].wg_dtype;
     m.kx = (m.dtype == FIRA_F32) ? FIRA_KX_SPLIT : 1;
-    m.lr_ld = operand_pitch((long long)m.kx * m.rp);
-    m.zready = (m.kx == 1 && (m.r & 3) == 0 && m.r <= FIRA_ZREADY_MAX_R) ? 1 : 0; m.pad0 = 0;
-    m.pt_ld = operand_pitch((long long)m.kx * m.Sp);
+    m.Lq = round_up_int(m.L, 256); m.Sq = round_up_int(m.S, 256); m.rq = round_up_int(m.r, 256);
+    m.zready = (m.kx == 1 && (m.r & 3) == 0 && m.r <= FIRA_ZREADY_MAX_R) ? 1 : 0;
+    if (m.zready) plan->adam_lds = std::max(plan->adam_lds, FIRA_ROWS_PER_WG * m.rp * 2);
     m.gx_ld = m.left ? round_up_int(m.n, 8) : operand_pitch((long long)m.kx * m.Sp);
     const size_t Lr = (size_t)m.L * m.r;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
@@ -111,10 +112,10 @@ bool make_plan(const fira_matrix_desc* d, int count, Plan* plan, fira_status* st
     m.phi = (float*)take((size_t)m.L * 4);
     m.g2 = (float*)take((size_t)m.L * 4);
     m.q = (float*)take((size_t)m.L * 4);
-    m.Nb = (bf16_raw*)take((size_t)m.L * m.lr_ld * 2);
-    m.Rb = (bf16_raw*)take((size_t)m.L * m.lr_ld * 2);
-    m.Pn = (bf16_raw*)take((size_t)m.S * m.lr_ld * 2);
-    m.PT = (bf16_raw*)take((size_t)m.r * m.pt_ld * 2);
+    m.Nb = (bf16_raw*)take((size_t)m.Lq * m.kx * m.rp * 2);
+    m.Rb = (bf16_raw*)take((size_t)m.Lq * m.kx * m.rp * 2);
+    m.Pn = (bf16_raw*)take((size_t)m.Sq * m.kx * m.rp * 2);
+    m.PT = (bf16_raw*)take((size_t)m.rq * m.kx * m.Sp * 2);
     if (m.kx > 1) {
       const size_t gx = m.left ? (size_t)m.kx * m.Sp * m.gx_ld : (size_t)m.m * m.gx_ld;
       m.Gx = (bf16_raw*)take(gx * 2);
@@ -439,7 +440,7 @@ fira_status fira_step(fira_ctx* ctx, int count, const int* idx, void* const* dev
                        ctx->d_mats, s->d_ents, s->d_tiles[kTilesProjectRight], s->ntiles[kTilesProjectRight], ctx->norm_mode);
   mark(1);
   // 2. Adam on R, factor norms
-  hipLaunchKernelGGL(fira_adam_kernel, dim3(s->rowblocks), dim3(256), 0, q, ctx->d_mats, ctx->d_scal, s->d_ents, count,
+  hipLaunchKernelGGL(fira_adam_kernel, dim3(s->rowblocks), dim3(256), ctx->plan.adam_lds, q, ctx->d_mats, ctx->d_scal, s->d_ents, count,
                      s->rowblocks, hp);
   mark(2);
   // 3. ||k (G - P R)||^2 per tile

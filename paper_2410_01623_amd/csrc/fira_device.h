@@ -36,16 +36,17 @@ struct FiraMat {
   int rp, Sp;          // rank and short side rounded up to 64 (zero padded operand rows)
   int kx, dtype;       // K-expansion (1: bf16, 6: fp32 split); dtype of W and G (0 f32, 1 bf16)
   long long gx_ld;     // leading dimension of the split copy of G (fp32 matrices only)
-  // Row pitches (elements) of the library's own bf16 operand arrays.  A pitch is never a multiple of
-  // 512 bytes: rows that are a power-of-two number of bytes apart all map to the same L2 channel,
-  // and a 256-row operand tile would then be served by one channel of sixteen.
-  int lr_ld;           // Nb, Rb, Pn rows: kx*rp values + padding
-  int pt_ld;           // PT rows: kx*Sp values + padding
+  // The library's own bf16 operand arrays are stored K-blocked, [K/32][rows][32]: the 32 k of one
+  // row are 64 contiguous bytes and consecutive rows follow each other, so the 16 rows x 32 k that
+  // one LDS-direct load instruction moves are 1 KB of contiguous memory (see kblk_index).  Row
+  // counts are rounded up to 256, a whole tile, so tile loads need no clamping; padding is zero.
+  int Lq;              // rows of Nb and Rb: L rounded up to 256
+  int Sq;              // rows of Pn: S rounded up to 256
+  int rq;              // rows of PT: r rounded up to 256
   // 1: the Adam kernel keeps a factor's row in registers and writes Z for c = 1 directly (bf16
   // matrices with r a multiple of 4, up to FIRA_ZREADY_MAX_R); the Z kernel then only corrects
   // the matrices whose limiter factor came out below 1.
   int zready;
-  int pad0;
   // low-rank arrays, all "long-side major": row i holds the r values of factor i
   float* M;            // [L][r]   first moment
   float* V;            // [L][r]   second moment
@@ -53,12 +54,17 @@ struct FiraMat {
   float* phi;          // [L]      scaling factors k_i of this step
   float* g2;           // [L]      ||G_i||^2 (Gram mode)
   float* q;            // [L]      k_i^2 (||G_i||^2 - ||R_i||^2), the terms of ||S||^2 (Gram mode)
-  bf16_raw* Nb;        // [L][lr_ld] N of this step, then Z = N - c k_i R_i in place (MFMA operand)
-  bf16_raw* Rb;        // [L][lr_ld] R of this step as MFMA operand
-  bf16_raw* Pn;        // [S][lr_ld] projector, rank-contiguous (operand of the back-projection)
-  bf16_raw* PT;        // [r][pt_ld] projector transposed, short-side-contiguous (operand of R)
+  bf16_raw* Nb;        // [kx*rp/32][Lq][32] Z = N - c k_i R_i of this step (MFMA operand)
+  bf16_raw* Rb;        // [kx*rp/32][Lq][32] R of this step as MFMA operand (residual route)
+  bf16_raw* Pn;        // [kx*rp/32][Sq][32] projector, rank along K (operand of the back-projection)
+  bf16_raw* PT;        // [kx*Sp/32][rq][32] projector transposed, short side along K (operand of R)
   bf16_raw* Gx;        // fp32 matrices: split copy of G ([kx*Sp][gx_ld] if left, [m][gx_ld] else)
 };
+
+// Element (row, k) of a K-blocked operand with `rows` (padded) rows.
+__host__ __device__ __forceinline__ long long kblk_index(int rows, long long row, int k) {
+  return ((long long)(k >> 5) * rows + row) * 32 + (k & 31);
+}
 
 // Mutable per-matrix scalars (device array).
 struct FiraScal {

@@ -23,20 +23,24 @@ __device__ __forceinline__ float wave_sum(float x) {
 }
 
 // store one low-rank value as an MFMA operand element (plain bf16, or the 6-plane split, sequence A)
+// (`op` is a K-blocked array with `rows` padded rows; plane p of the split occupies k = p*rp + a.)
 template <int KX>
-__device__ __forceinline__ void store_operand(gptr<bf16_raw> row, int rp, int a, float x) {
+__device__ __forceinline__ void store_operand(gptr<bf16_raw> op, int rows, long long row, int rp, int a, float x) {
   if (KX == 1) {
-    row[a] = f32_to_bf16(x);
+    op[kblk_index(rows, row, a)] = f32_to_bf16(x);
   } else {
     bf16_raw h, m, l;
     split3(x, h, m, l);
-    row[a] = h; row[rp + a] = h; row[2 * rp + a] = m; row[3 * rp + a] = h; row[4 * rp + a] = l; row[5 * rp + a] = m;
+    const bf16_raw seq[6] = {h, h, m, h, l, m};
+#pragma unroll
+    for (int p = 0; p < 6; ++p) op[kblk_index(rows, row, p * rp + a)] = seq[p];
   }
 }
 template <int KX>
-__device__ __forceinline__ float load_operand(gptr<const bf16_raw> row, int rp, int a) {
-  if (KX == 1) return bf16_to_f32(row[a]);
-  return (bf16_to_f32(row[a]) + bf16_to_f32(row[2 * rp + a])) + bf16_to_f32(row[4 * rp + a]);
+__device__ __forceinline__ float load_operand(gptr<const bf16_raw> op, int rows, long long row, int rp, int a) {
+  if (KX == 1) return bf16_to_f32(op[kblk_index(rows, row, a)]);
+  return (bf16_to_f32(op[kblk_index(rows, row, a)]) + bf16_to_f32(op[kblk_index(rows, row, 2 * rp + a)])) +
+         bf16_to_f32(op[kblk_index(rows, row, 4 * rp + a)]);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -52,8 +56,8 @@ __device__ __forceinline__ void adam_row(const FiraMat& mt, const FiraHp& hp, fl
   gptr<const float> R = as_global<const float>(mt.Rt) + row * r;
   gptr<float> M = as_global(mt.M) + row * r;
   gptr<float> V = as_global(mt.V) + row * r;
-  gptr<bf16_raw> Nb = as_global(mt.Nb) + row * (long long)mt.lr_ld;
-  gptr<bf16_raw> Rb = as_global(mt.Rb) + row * (long long)mt.lr_ld;
+  gptr<bf16_raw> Nb = as_global(mt.Nb);
+  gptr<bf16_raw> Rb = as_global(mt.Rb);
   float nn = 0.0f, rr = 0.0f;
   for (int a = lane * VEC; a < r; a += 64 * VEC) {
     float rv[VEC], mv[VEC], vv[VEC], nv[VEC];
@@ -79,13 +83,14 @@ __device__ __forceinline__ void adam_row(const FiraMat& mt, const FiraHp& hp, fl
       M[a] = mv[0]; V[a] = vv[0];
     }
     if (KX == 1 && VEC == 4) {
-      *reinterpret_cast<gptr<u32x2>>(Nb + a) = u32x2{pack_bf16x2(nv[0], nv[1]), pack_bf16x2(nv[2], nv[3])};
-      *reinterpret_cast<gptr<u32x2>>(Rb + a) = u32x2{pack_bf16x2(rv[0], rv[1]), pack_bf16x2(rv[2], rv[3])};
+      const long long o = kblk_index(mt.Lq, row, a);
+      *reinterpret_cast<gptr<u32x2>>(Nb + o) = u32x2{pack_bf16x2(nv[0], nv[1]), pack_bf16x2(nv[2], nv[3])};
+      *reinterpret_cast<gptr<u32x2>>(Rb + o) = u32x2{pack_bf16x2(rv[0], rv[1]), pack_bf16x2(rv[2], rv[3])};
     } else {
 #pragma unroll
       for (int e = 0; e < VEC; ++e) {
-        store_operand<KX>(Nb, mt.rp, a + e, nv[e]);
-        store_operand<KX>(Rb, mt.rp, a + e, rv[e]);
+        store_operand<KX>(Nb, mt.Lq, row, mt.rp, a + e, nv[e]);
+        store_operand<KX>(Rb, mt.Lq, row, mt.rp, a + e, rv[e]);
       }
     }
   }
@@ -102,16 +107,18 @@ __device__ __forceinline__ void adam_row(const FiraMat& mt, const FiraHp& hp, fl
 // Same update for bf16 matrices with r % 4 == 0 and r <= FIRA_ZREADY_MAX_R: the factor's N and R stay
 // in registers until k_i is known, and the row is written once as the back-projection operand for
 // an inactive limiter, Z_i = N_i - k_i R_i, rounded from fp32 a single time.  R is written as an
-// operand only when the residual contraction will need it.
+// operand only when the residual contraction will need it.  Z is K-blocked, 64 B per row and K
+// block, so the workgroup's 16 rows are collected in LDS ([K block][16 rows][32]) and leave as
+// 1 KB contiguous pieces (fira_adam_kernel).
 template <int NIT>   // 256 * NIT >= r
-__device__ __forceinline__ void adam_row_zready(const FiraMat& mt, const FiraHp& hp, float bias, long long row, bool gram) {
+__device__ __forceinline__ void adam_row_zready(const FiraMat& mt, const FiraHp& hp, float bias, long long row, bool gram,
+                                                bf16_raw* zl, int rowlocal) {
   const int lane = threadIdx.x & 63;
   const int r = mt.r;
   gptr<const float> R = as_global<const float>(mt.Rt) + row * r;
   gptr<float> M = as_global(mt.M) + row * r;
   gptr<float> V = as_global(mt.V) + row * r;
-  gptr<bf16_raw> Nb = as_global(mt.Nb) + row * (long long)mt.lr_ld;
-  gptr<bf16_raw> Rb = as_global(mt.Rb) + row * (long long)mt.lr_ld;
+  gptr<bf16_raw> Rb = as_global(mt.Rb);
   float nn = 0.0f, rr = 0.0f;
   f32x4 nv[NIT], rv[NIT];
 #pragma unroll
@@ -139,11 +146,16 @@ __device__ __forceinline__ void adam_row_zready(const FiraMat& mt, const FiraHp&
 #pragma unroll
   for (int it = 0; it < NIT; ++it) {
     const int a = lane * 4 + 256 * it;
-    if (a < r) {
-      const f32x4 z = nv[it] - k * rv[it];
-      *reinterpret_cast<gptr<u32x2>>(Nb + a) = u32x2{pack_bf16x2(z[0], z[1]), pack_bf16x2(z[2], z[3])};
-      if (!gram)
-        *reinterpret_cast<gptr<u32x2>>(Rb + a) = u32x2{pack_bf16x2(rv[it][0], rv[it][1]), pack_bf16x2(rv[it][2], rv[it][3])};
+    if (a < mt.rp) {
+      u32x2 zv = u32x2{0u, 0u};
+      if (a < r) {
+        const f32x4 z = nv[it] - k * rv[it];
+        zv = u32x2{pack_bf16x2(z[0], z[1]), pack_bf16x2(z[2], z[3])};
+        if (!gram)
+          *reinterpret_cast<gptr<u32x2>>(Rb + kblk_index(mt.Lq, row, a)) =
+              u32x2{pack_bf16x2(rv[it][0], rv[it][1]), pack_bf16x2(rv[it][2], rv[it][3])};
+      }
+      *reinterpret_cast<u32x2*>(zl + (a >> 5) * (FIRA_ROWS_PER_WG * 32) + rowlocal * 32 + (a & 31)) = zv;
     }
   }
   if (lane == 0) {
@@ -156,11 +168,13 @@ __global__ __launch_bounds__(256, 4) void fira_adam_kernel(const FiraMat* __rest
                                                         const FiraScal* __restrict__ scal,
                                                         const FiraEnt* __restrict__ ents, int count,
                                                         int total_rowblocks, FiraHp hp) {
+  extern __shared__ __attribute__((aligned(16))) char adam_lds[];   // zready matrices: 16 rows x rp bf16
   const int rb = blockIdx.x;
   if (rb >= total_rowblocks) return;
   const int e = find_entry(ents, count, rb);
   const FiraEnt ent = ents[e];
   const FiraMat mt = mats[ent.mat];
+  bf16_raw* zl = reinterpret_cast<bf16_raw*>(adam_lds);
   // bias correction with the 1-based step count (Eq. 4), in double: 1 - beta2^t loses all
   // accuracy in fp32 at small t.
   const FiraScal sc = scal[ent.mat];
@@ -171,15 +185,32 @@ __global__ __launch_bounds__(256, 4) void fira_adam_kernel(const FiraMat* __rest
   const long long row_base = (long long)(rb - ent.row0) * FIRA_ROWS_PER_WG + wave * 4;
   for (int i = 0; i < 4; ++i) {
     const long long row = row_base + i;
-    if (row >= mt.L) break;
+    if (row >= mt.L) {
+      if (mt.zready)   // rows of the padding: zeros
+        for (int a = (threadIdx.x & 63) * 4; a < mt.rp; a += 256)
+          *reinterpret_cast<u32x2*>(zl + (a >> 5) * (FIRA_ROWS_PER_WG * 32) + (wave * 4 + i) * 32 + (a & 31)) = u32x2{0u, 0u};
+      continue;
+    }
     if (mt.zready) {
-      if (mt.r <= 256) adam_row_zready<1>(mt, hp, bias, row, gram);
-      else if (mt.r <= 512) adam_row_zready<2>(mt, hp, bias, row, gram);
-      else adam_row_zready<FIRA_ZREADY_MAX_R / 256>(mt, hp, bias, row, gram);
+      if (mt.r <= 256) adam_row_zready<1>(mt, hp, bias, row, gram, zl, wave * 4 + i);
+      else if (mt.r <= 512) adam_row_zready<2>(mt, hp, bias, row, gram, zl, wave * 4 + i);
+      else adam_row_zready<FIRA_ZREADY_MAX_R / 256>(mt, hp, bias, row, gram, zl, wave * 4 + i);
     } else if (mt.kx == 1) {
       if ((mt.r & 3) == 0) adam_row<1, 4>(mt, hp, bias, row, gram); else adam_row<1, 1>(mt, hp, bias, row, gram);
     } else {
       adam_row<FIRA_KX_SPLIT, 1>(mt, hp, bias, row, gram);
+    }
+  }
+  if (mt.zready) {
+    __syncthreads();
+    // the 16 rows of one K block are 1 KB of contiguous memory
+    gptr<char> nb = reinterpret_cast<gptr<char>>(as_global(mt.Nb));
+    const long long row0 = (long long)(rb - ent.row0) * FIRA_ROWS_PER_WG;
+    const int nbytes = (mt.rp >> 5) * (FIRA_ROWS_PER_WG * 64);
+    for (int o = threadIdx.x * 16; o < nbytes; o += 256 * 16) {
+      const int kb = o / (FIRA_ROWS_PER_WG * 64), w = o % (FIRA_ROWS_PER_WG * 64);
+      *reinterpret_cast<gptr<u32x4>>(nb + ((long long)kb * mt.Lq + row0) * 64 + w) =
+          *reinterpret_cast<const u32x4*>(adam_lds + o);
     }
   }
 }
@@ -230,13 +261,14 @@ __global__ __launch_bounds__(64) void fira_limiter_kernel(const FiraMat* __restr
 template <int KX>
 __device__ __forceinline__ void makez_row(const FiraMat& mt, float f, long long row) {
   const int lane = threadIdx.x & 63;
-  gptr<bf16_raw> Nb = as_global(mt.Nb) + row * (long long)mt.lr_ld;
-  gptr<const bf16_raw> Rb = as_global<const bf16_raw>(mt.Rb) + row * (long long)mt.lr_ld;
+  gptr<bf16_raw> Nb = as_global(mt.Nb);
+  gptr<const bf16_raw> Rb = as_global<const bf16_raw>(mt.Rb);
   if (KX == 1) {
     // rp is a multiple of 64 and padded entries are zero: whole 16-byte groups
     for (int a = lane * 8; a < mt.rp; a += 512) {
-      const u32x4 nv = *reinterpret_cast<gptr<const u32x4>>(Nb + a);
-      const u32x4 rv = *reinterpret_cast<gptr<const u32x4>>(Rb + a);
+      const long long o = kblk_index(mt.Lq, row, a);
+      const u32x4 nv = *reinterpret_cast<gptr<const u32x4>>(Nb + o);
+      const u32x4 rv = *reinterpret_cast<gptr<const u32x4>>(Rb + o);
       const unsigned nw[4] = {nv.x, nv.y, nv.z, nv.w}, rw[4] = {rv.x, rv.y, rv.z, rv.w};
       unsigned zw[4];
 #pragma unroll
@@ -247,12 +279,13 @@ __device__ __forceinline__ void makez_row(const FiraMat& mt, float f, long long 
         if (a + 2 * d + 1 >= mt.r) z1 = 0.0f;
         zw[d] = pack_bf16x2(z0, z1);
       }
-      *reinterpret_cast<gptr<u32x4>>(Nb + a) = u32x4{zw[0], zw[1], zw[2], zw[3]};
+      *reinterpret_cast<gptr<u32x4>>(Nb + o) = u32x4{zw[0], zw[1], zw[2], zw[3]};
     }
   } else {
     for (int a = lane; a < mt.r; a += 64) {
-      const float z = load_operand<KX>((gptr<const bf16_raw>)Nb, mt.rp, a) - f * load_operand<KX>(Rb, mt.rp, a);
-      store_operand<KX>(Nb, mt.rp, a, z);
+      const float z = load_operand<KX>((gptr<const bf16_raw>)Nb, mt.Lq, row, mt.rp, a) -
+                      f * load_operand<KX>(Rb, mt.Lq, row, mt.rp, a);
+      store_operand<KX>(Nb, mt.Lq, row, mt.rp, a, z);
     }
   }
 }
@@ -260,16 +293,17 @@ __device__ __forceinline__ void makez_row(const FiraMat& mt, float f, long long 
 // Rows that already hold Z for c = 1 (N_i - k_i R_i): add back (1 - c) k_i R_i, with R in fp32.
 __device__ __forceinline__ void fixz_row(const FiraMat& mt, float f, long long row) {
   const int lane = threadIdx.x & 63;
-  gptr<bf16_raw> Nb = as_global(mt.Nb) + row * (long long)mt.lr_ld;
+  gptr<bf16_raw> Nb = as_global(mt.Nb);
   gptr<const float> R = as_global<const float>(mt.Rt) + row * mt.r;
   for (int a = lane * 4; a < mt.r; a += 256) {
-    const u32x2 zv = *reinterpret_cast<gptr<const u32x2>>(Nb + a);
+    const long long o = kblk_index(mt.Lq, row, a);
+    const u32x2 zv = *reinterpret_cast<gptr<const u32x2>>(Nb + o);
     const f32x4 rv = *reinterpret_cast<gptr<const f32x4>>(R + a);
     const float z0 = __uint_as_float(zv.x << 16) + f * rv[0];
     const float z1 = __uint_as_float(zv.x & 0xffff0000u) + f * rv[1];
     const float z2 = __uint_as_float(zv.y << 16) + f * rv[2];
     const float z3 = __uint_as_float(zv.y & 0xffff0000u) + f * rv[3];
-    *reinterpret_cast<gptr<u32x2>>(Nb + a) = u32x2{pack_bf16x2(z0, z1), pack_bf16x2(z2, z3)};
+    *reinterpret_cast<gptr<u32x2>>(Nb + o) = u32x2{pack_bf16x2(z0, z1), pack_bf16x2(z2, z3)};
   }
 }
 
@@ -311,20 +345,20 @@ __global__ void fira_prep_projector_kernel(FiraMat mt, const TP* __restrict__ P)
     float x;
     if (sizeof(TP) == 2) x = bf16_to_f32(*reinterpret_cast<const bf16_raw*>(&P[idx]));
     else x = *reinterpret_cast<const float*>(&P[idx]);
-    gptr<bf16_raw> pn = as_global(mt.Pn) + s * (long long)mt.lr_ld;
-    gptr<bf16_raw> pt = as_global(mt.PT) + (long long)a * (long long)mt.pt_ld;
+    gptr<bf16_raw> pn = as_global(mt.Pn);
+    gptr<bf16_raw> pt = as_global(mt.PT);
     if (mt.kx == 1) {
       const bf16_raw b = f32_to_bf16(x);
-      pn[a] = b;
-      pt[s] = b;
+      pn[kblk_index(mt.Sq, s, a)] = b;
+      pt[kblk_index(mt.rq, a, (int)s)] = b;
     } else {
       bf16_raw h, m, l;
       split3(x, h, m, l);
       const bf16_raw seq[6] = {h, m, h, l, h, m};
 #pragma unroll
       for (int p = 0; p < 6; ++p) {
-        pn[p * mt.rp + a] = seq[p];
-        pt[(long long)p * mt.Sp + s] = seq[p];
+        pn[kblk_index(mt.Sq, s, p * mt.rp + a)] = seq[p];
+        pt[kblk_index(mt.rq, a, p * mt.Sp + (int)s)] = seq[p];
       }
     }
   }
@@ -469,7 +503,7 @@ __global__ __launch_bounds__(256) void fira_ortho_y_kernel(FiraMat mt, float* __
   if (s >= mt.S) return;
   float acc[4] = {0.f, 0.f, 0.f, 0.f};
   for (int a = lane; a < mt.r; a += 64) {
-    const float p = bf16_to_f32(Pn[(long long)s * mt.lr_ld + a]);
+    const float p = bf16_to_f32(Pn[kblk_index(mt.Sq, s, a)]);
 #pragma unroll
     for (int t = 0; t < 4; ++t) acc[t] += p * ortho_sign(a, t);
   }
@@ -492,7 +526,7 @@ __global__ __launch_bounds__(256) void fira_ortho_z_kernel(FiraMat mt, const flo
   for (int a = threadIdx.x; a < mt.r; a += 256) {
     float z[4] = {0.f, 0.f, 0.f, 0.f};
     for (int s = s0; s < s1; ++s) {
-      const float p = bf16_to_f32(Pn[(long long)s * mt.lr_ld + a]);
+      const float p = bf16_to_f32(Pn[kblk_index(mt.Sq, s, a)]);
 #pragma unroll
       for (int k = 0; k < 4; ++k) z[k] += p * yy[(long long)s * 4 + k];
     }

@@ -1,40 +1,31 @@
 // Grouped bf16 MFMA contractions of the Fira step for gfx950 (v_mfma_f32_32x32x16_bf16).
 //
-// One 512-thread workgroup (8 wavefronts, 2 x 4) computes a 256 x 256 tile
-//     D[a][b] = sum_k A[a][k] * B[b][k]
-// where "A" is the MFMA A operand and "B" the MFMA B operand; each wavefront owns 128 (A) x 64 (B).
-// One workgroup runs per CU with two wavefronts per SIMD: wavefronts issue in order, so a wavefront
-// that stalls on a full memory queue or on an LDS wait would leave the matrix pipe idle if it were
-// alone on its SIMD.  The 256 x 256 tile keeps the L2 traffic at 64 KB per 8.4 MFLOP.
-// Both operands are staged through LDS as
-// [row][64 k] bf16 tiles (128 B per row, 16-byte chunks XOR-swizzled by row so that fragment reads
-// and tile writes spread over all banks).  LDS holds two K stages (2 x 64 KB) and a third one is in
-// flight in registers, so a global load has a full K step to land and there is one barrier per K step.
+// Every contraction has the form  D[a][b] = sum_k A[a][k] * B[b][k]  ("A" is the MFMA A operand,
+// "B" the MFMA B operand) and runs in 256-thread workgroups, two per CU, each wavefront owning a
+// 128 (A) x 64 (B) block of accumulators.  Two independent workgroups per CU matter more than a
+// bigger tile: the phases of one (operand requests, LDS traffic, the HBM-bound epilogue) overlap the
+// multiplies of the other, which a single workgroup in lockstep on its barriers cannot do.
 //
-// An operand is either K-contiguous in memory (row pointer + k) or, for the gradient when P
-// multiplies from the left, K-slow (element (a, k) at base[k*ld + a]); the K-slow loader reads
-// 4(k) x 8(a) blocks with row-contiguous 16-byte loads and transposes them in registers before the
-// LDS write.
+// Operands that the library stores itself (P in both orientations, Z, R) are K-blocked
+// ([K/32][rows][32], see kblk_index) and go from global memory straight into an LDS ring with
+// LDS-direct loads.  The gradient is the caller's: its rows start at any 2-byte boundary and, when P
+// multiplies from the left, it is K-slow (element (a, k) at base[k*ld + a]); it passes through
+// registers (K-slow: 4(k) x 8(a) blocks, row-contiguous 16-byte loads, transposed in registers
+// before the LDS write).
 //
 // Accumulator layout of one 32 x 32 block (per lane, 16 floats v = 0..15):
 //     b (B row) = lane % 32,   a (A row) = 8*(v/4) + 4*(lane/32) + v%4
-// so a lane owns 4 consecutive A rows per group of 4 registers.  The kernels choose which side of
-// each product plays A so that this run of 4 lies along the contiguous axis of what they touch.
+// so a lane owns 4 consecutive A rows per group of 4 registers.
 #pragma once
 #include "fira_device.h"
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
 
-#define FIRA_BK 64
-#define FIRA_TA 256  // tile rows on the A side
-#define FIRA_TB 256  // tile rows on the B side
-#define FIRA_THREADS 512
-#define FIRA_LDS_A (FIRA_TA * 128)
-#define FIRA_LDS_B (FIRA_TB * 128)
-#define FIRA_LDS_STAGE (FIRA_LDS_A + FIRA_LDS_B)
-#define FIRA_LDS_BYTES (2 * FIRA_LDS_STAGE)   // 128 KB of the CU's 160 KB
+#define FIRA_TA 256  // rank-axis contractions: tile rows on the A side
 
+// [row][64 k] bf16 tile, 128 B per row, 16-byte chunks XOR-swizzled by row so that fragment reads
+// and tile writes spread over all banks.
 __device__ __forceinline__ int lds_tile_off(int row, int chunk) {
   return row * 128 + (((chunk ^ row ^ (row >> 3) ^ (row >> 6)) & 7) << 4);
 }
@@ -70,155 +61,18 @@ __device__ __forceinline__ u32x4 load8_bf16(gptr<const bf16_raw> row, long long 
 
 struct GemmOperands {
   gptr<const bf16_raw> A;  // A side
-  long long lda;      // elements between consecutive A rows (K-contiguous) or K steps (K-slow)
+  long long lda;      // gradient operand: elements between consecutive A rows (K-contiguous) or K steps
+                      // (K-slow); K-blocked operand: its padded row count
   int a_row0, a_rows; // first A row of this tile, number of valid A rows
   int KA;             // valid contraction length on the A side (elements beyond read as zero)
-  gptr<const bf16_raw> B;  // B side: always K-contiguous, rows zero-padded to a multiple of 64 in K
-  long long ldb;
+  gptr<const bf16_raw> B;  // B side: always K-blocked, zero padded to a multiple of 64 in K
+  long long ldb;      // padded row count of B
   int b_row0, b_rows;
-  int KB;             // readable row length of B (>= KA rounded up to 64)
+  int KB;             // stored contraction length of B (>= KA, a multiple of 64)
 };
 
-// Thread -> tile element mapping of the loaders (512 threads, 16-byte chunks of 8 bf16).
-//   K-contiguous: chunk column cc = t & 7, rows rr + 64*i, rr = t >> 3, i = 0..3.
-//   K-slow:       4(k) x 8(a) block per thread: a-block ib, k-quad kq (4 consecutive k);
-//                 lane bits [0:4) -> ib low, bit 4 -> kq low, bit 5 -> ib high, bits [6:9) -> kq high,
-//                 so that 16 lanes read 256 contiguous bytes of one gradient row and the 32 lanes of a
-//                 half-wave write 16 distinct 8-byte LDS slots.
-struct KSlowMap {
-  int ib, kq;
-  __device__ __forceinline__ KSlowMap() {
-    const int t = threadIdx.x;
-    ib = (t & 15) | ((t >> 1) & 16);
-    kq = ((t >> 4) & 1) | ((t >> 5) & 14);
-  }
-};
-
-// Guarded tile loads (edge tiles, ragged K).  Rows beyond the operand are clamped to its last row
-// (their products land in accumulators that are never stored), so every load is issued on every
-// path; ragged 8-element chunks are realigned in registers (load8_bf16).
-template <bool AKSLOW>
-__device__ __forceinline__ void gemm_load_guarded(u32x4 (&ra)[4], u32x4 (&rb)[4], const GemmOperands& g, int k0) {
-  const int t = threadIdx.x;
-  const int cc = t & 7, rr = t >> 3;
-  const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
-  if (AKSLOW) {
-    const KSlowMap mp;
-    const long long a = (long long)g.a_row0 + 8 * mp.ib;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int k = k0 + 4 * mp.kq + j;
-      const int kc = k < g.KA ? k : g.KA - 1;
-      const u32x4 v = load8_bf16(g.A + (long long)kc * g.lda, a, g.a_rows);
-      ra[j] = k < g.KA ? v : zero;
-    }
-  } else {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int row = g.a_row0 + rr + 64 * i;
-      const int rc = row < g.a_rows ? row : g.a_rows - 1;
-      ra[i] = load8_bf16(g.A + (long long)rc * g.lda, k0 + 8 * cc, g.KA);
-    }
-  }
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int row = g.b_row0 + rr + 64 * i;
-    const int rc = row < g.b_rows ? row : g.b_rows - 1;
-    rb[i] = load8_bf16(g.B + (long long)rc * g.ldb, k0 + 8 * cc, g.KB);
-  }
-}
-
-// Unguarded tile loads for interior tiles (every row of the tile valid, KA a multiple of 64): one
-// uniform base pointer per operand that advances along K, plus per-thread element offsets that are
-// computed once.  Rows may start at any element (odd n / ld): the loads only assume 2-byte alignment.
-template <bool AKSLOW>
-struct FastLoader {
-  gptr<const bf16_raw> pa, pb;
-  unsigned offa[4], offb[4];
-  long long stepa;
-  __device__ __forceinline__ FastLoader(const GemmOperands& g) {
-    const int t = threadIdx.x;
-    const int cc = t & 7, rr = t >> 3;
-    if (AKSLOW) {
-      const KSlowMap mp;
-      pa = g.A + g.a_row0;
-#pragma unroll
-      for (int j = 0; j < 4; ++j) offa[j] = (unsigned)((4 * mp.kq + j) * g.lda + 8 * mp.ib);
-      stepa = FIRA_BK * g.lda;
-    } else {
-      pa = g.A + (long long)g.a_row0 * g.lda;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) offa[i] = (unsigned)((rr + 64 * i) * g.lda + 8 * cc);
-      stepa = FIRA_BK;
-    }
-    pb = g.B + (long long)g.b_row0 * g.ldb;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) offb[i] = (unsigned)((rr + 64 * i) * g.ldb + 8 * cc);
-  }
-  // Loads the current stage and advances to the next one while `more` is true.  The loads are
-  // unconditional (a request past the last stage re-reads the last stage and is never used), so
-  // the number of loads in flight is the same on every path.
-  __device__ __forceinline__ void load(u32x4 (&ra)[4], u32x4 (&rb)[4], bool more) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) ra[i] = *reinterpret_cast<gptr<const u32x4_a2>>(pa + offa[i]);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) rb[i] = *reinterpret_cast<gptr<const u32x4_a2>>(pb + offb[i]);
-    pa += more ? stepa : 0;
-    pb += more ? FIRA_BK : 0;
-  }
-};
-
-template <bool AKSLOW>
-__device__ __forceinline__ void gemm_store_tiles(char* stage, const u32x4 (&ra)[4], const u32x4 (&rb)[4]) {
-  const int t = threadIdx.x;
-  const int cc = t & 7, rr = t >> 3;
-  char* la = stage;
-  char* lb = stage + FIRA_LDS_A;
-  if (AKSLOW) {
-    // ra[j] holds row k = 4*kq + j of a 4(k) x 8(a) block; emit, for each a, its 4 k values (8 B).
-    const KSlowMap mp;
-    const unsigned in[16] = {ra[0].x, ra[0].y, ra[0].z, ra[0].w, ra[1].x, ra[1].y, ra[1].z, ra[1].w,
-                             ra[2].x, ra[2].y, ra[2].z, ra[2].w, ra[3].x, ra[3].y, ra[3].z, ra[3].w};  // in[4*j + d]: a = 2d, 2d+1
-#pragma unroll
-    for (int ii = 0; ii < 8; ++ii) {
-      unsigned w[2];
-#pragma unroll
-      for (int d = 0; d < 2; ++d) {
-        const unsigned x = in[4 * (2 * d) + (ii >> 1)];      // k = 2d
-        const unsigned y = in[4 * (2 * d + 1) + (ii >> 1)];  // k = 2d + 1
-        w[d] = (ii & 1) ? ((x >> 16) | (y & 0xffff0000u)) : ((x & 0xffffu) | (y << 16));
-      }
-      const int row = 8 * mp.ib + ii;
-      *reinterpret_cast<u32x2*>(la + lds_tile_off(row, mp.kq >> 1) + 8 * (mp.kq & 1)) = u32x2{w[0], w[1]};
-    }
-  } else {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4*>(la + lds_tile_off(rr + 64 * i, cc)) = ra[i];
-  }
-#pragma unroll
-  for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4*>(lb + lds_tile_off(rr + 64 * i, cc)) = rb[i];
-}
-
-__device__ __forceinline__ bool gemm_tile_is_interior(const GemmOperands& g) {
-  return g.a_row0 + FIRA_TA <= g.a_rows && g.b_row0 + FIRA_TB <= g.b_rows && (g.KA % FIRA_BK) == 0;
-}
-
-// One K step (64) of the wave's 128 x 64 sub-tile: 4 k-slices of 6 fragment reads and 8 MFMAs;
-// the fragments of slice kk+1 are requested before slice kk is multiplied.
+// Fragments of one k-slice (16) of a wave's 128 (A) x 64 (B) block and its 8 MFMAs.
 struct Frags { bf16x8_t a[4], b[2]; };
-__device__ __forceinline__ void gemm_read_frags(Frags& f, const char* stage, int kk) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int wm = wave & 1, wn = wave >> 1;
-  const char* la = stage;
-  const char* lb = stage + FIRA_LDS_A;
-  const int chunk = 2 * kk + (lane >> 5);
-#pragma unroll
-  for (int t = 0; t < 4; ++t)
-    f.a[t] = *reinterpret_cast<const bf16x8_t*>(la + lds_tile_off(wm * 128 + 32 * t + (lane & 31), chunk));
-#pragma unroll
-  for (int t = 0; t < 2; ++t)
-    f.b[t] = *reinterpret_cast<const bf16x8_t*>(lb + lds_tile_off(wn * 64 + 32 * t + (lane & 31), chunk));
-}
 __device__ __forceinline__ void gemm_mfma_slice(f32x16_t (&acc)[4][2], const Frags& f) {
 #pragma unroll
   for (int tm = 0; tm < 4; ++tm)
@@ -241,153 +95,14 @@ __device__ __forceinline__ void gemm_sumsq_slice(float (&sq)[4], const Frags& f)
     }
   }
 }
-template <bool SUMSQ>
-__device__ __forceinline__ void gemm_compute_step(f32x16_t (&acc)[4][2], const char* stage, float (&sq)[4]) {
-  Frags f0, f1;
-  gemm_read_frags(f0, stage, 0);
-  gemm_read_frags(f1, stage, 1);
-  gemm_mfma_slice(acc, f0);
-  if (SUMSQ) gemm_sumsq_slice(sq, f0);
-  gemm_read_frags(f0, stage, 2);
-  gemm_mfma_slice(acc, f1);
-  if (SUMSQ) gemm_sumsq_slice(sq, f1);
-  gemm_read_frags(f1, stage, 3);
-  gemm_mfma_slice(acc, f0);
-  if (SUMSQ) gemm_sumsq_slice(sq, f0);
-  gemm_mfma_slice(acc, f1);
-  if (SUMSQ) gemm_sumsq_slice(sq, f1);
-}
-
-// acc[tm][tn]: wave (wm, wn) = (wave & 1, wave >> 1) owns A rows wm*128 + 32*tm + .., B rows wn*64 + 32*tn + ..
-//
-// Pipeline (stage s = K range [64 s, 64 s + 64)):
-//   before iteration s: LDS[s & 1] holds stage s; the registers hold stage s+1 (requested one
-//   iteration ago).
-//   iteration s: write the registers into LDS[(s+1)&1]; request stage s+2; multiply LDS[s&1]; barrier.
-template <bool AKSLOW, bool FAST, bool SUMSQ>
-__device__ __forceinline__ void gemm_pipeline(f32x16_t (&acc)[4][2], char* lds, const GemmOperands& g, float (&sq)[4]) {
-  const int KT = (g.KA + FIRA_BK - 1) / FIRA_BK;
-  u32x4 ra[4], rb[4];
-  FastLoader<AKSLOW> fl(g);
-  int knext = 0;
-  auto request = [&]() {
-    if (FAST) {
-      fl.load(ra, rb, knext + 1 < KT);
-    } else {
-      gemm_load_guarded<AKSLOW>(ra, rb, g, (knext < KT ? knext : KT - 1) * FIRA_BK);
-    }
-    ++knext;
-  };
-  request();                                   // stage 0
-  gemm_store_tiles<AKSLOW>(lds, ra, rb);
-  request();                                   // stage 1
-  __syncthreads();
-  for (int s = 0; s < KT; ++s) {
-    char* cur = lds + (s & 1) * FIRA_LDS_STAGE;
-    char* nxt = lds + ((s + 1) & 1) * FIRA_LDS_STAGE;
-    gemm_store_tiles<AKSLOW>(nxt, ra, rb);     // stage s+1 (a repeat of the last stage at the end)
-    request();                                 // stage s+2
-    gemm_compute_step<SUMSQ>(acc, cur, sq);    // stage s
-    __syncthreads();
-  }
-}
-
-// sumsq: also accumulate sq[tm] = sum_k A[row][k]^2 for the rows this lane's fragments cover (lane
-// and lane + 32 hold the two halves of each row's sum); wave-uniform.
-template <bool AKSLOW>
-__device__ __forceinline__ void gemm_mainloop(f32x16_t (&acc)[4][2], char* lds, const GemmOperands& g,
-                                              float (&sq)[4], bool sumsq) {
-#pragma unroll
-  for (int tm = 0; tm < 4; ++tm) sq[tm] = 0.0f;
-#pragma unroll
-  for (int tm = 0; tm < 4; ++tm)
-#pragma unroll
-    for (int tn = 0; tn < 2; ++tn)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[tm][tn][v] = 0.0f;
-  if (gemm_tile_is_interior(g)) {
-    if (sumsq) gemm_pipeline<AKSLOW, true, true>(acc, lds, g, sq);
-    else gemm_pipeline<AKSLOW, true, false>(acc, lds, g, sq);
-  } else {
-    if (sumsq) gemm_pipeline<AKSLOW, false, true>(acc, lds, g, sq);
-    else gemm_pipeline<AKSLOW, false, false>(acc, lds, g, sq);
-  }
-}
-
-// ------------------------------------------------------------------------------------------------
-// Kernel 1: low-rank gradient, long-side major:  Rt[i][a] = sum_s G(s, i) P[s][a]
-//   LEFT  (m <= n): i = column of G, s = row of G      -> A side is G read K-slow
-//   RIGHT (m >  n): i = row of G,    s = column of G   -> A side is G read K-contiguous
-//   B side is PT[a][s] (rank rows, short-side contiguous).
-// One instantiation per orientation; the host keeps one tile list for each.
-// ------------------------------------------------------------------------------------------------
-template <bool LEFT>
-__global__ __launch_bounds__(FIRA_THREADS, 2) void fira_project_kernel_v4(const FiraMat* __restrict__ mats,
-                                                                       const FiraEnt* __restrict__ ents,
-                                                                       const FiraTile* __restrict__ tiles,
-                                                                       int ntiles, int norm_mode) {
-  extern __shared__ __attribute__((aligned(16))) char lds[];
-  const int ti = xcd_chunked_index(blockIdx.x, ntiles);
-  if (ti < 0) return;
-  const FiraTile tile = tiles[ti];
-  const FiraEnt ent = ents[tile.ent];
-  const FiraMat mt = mats[ent.mat];
-
-  GemmOperands g;
-  g.a_row0 = tile.ta * FIRA_TA;
-  g.a_rows = mt.L;
-  g.b_row0 = tile.tb * FIRA_TB;
-  g.b_rows = mt.r;
-  g.B = as_global<const bf16_raw>(mt.PT);
-  g.ldb = mt.pt_ld;
-  g.KB = mt.kx * mt.Sp;
-  if (mt.kx == 1) {
-    g.A = as_global(reinterpret_cast<const bf16_raw*>(ent.G));
-    g.lda = mt.ld;
-    g.KA = mt.S;
-  } else {
-    g.A = as_global<const bf16_raw>(mt.Gx);
-    g.lda = mt.gx_ld;
-    g.KA = mt.kx * mt.Sp;
-  }
-  f32x16_t acc[4][2];
-  float sq[4];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int wm = wave & 1, wn = wave >> 1;
-  // Gram route: ||G_i||^2 of the tile's 256 factors falls out of the A fragments of the two waves
-  // with wn == 0, in the first rank tile of each panel.  (fp32 matrices feed split planes through
-  // here; their norms come from fira_gradnorm_kernel.)
-  const bool sumsq = norm_mode == 1 && mt.kx == 1 && tile.tb == 0 && wn == 0;
-  gemm_mainloop<LEFT>(acc, lds, g, sq, sumsq);
-  if (sumsq) {
-    gptr<float> g2 = as_global(mt.g2);
-#pragma unroll
-    for (int tm = 0; tm < 4; ++tm) {
-      const float tot = sq[tm] + __shfl_xor(sq[tm], 32, 64);
-      const int row = g.a_row0 + wm * 128 + 32 * tm + (lane & 31);
-      if (lane < 32 && row < mt.L) g2[row] = tot;
-    }
-  }
-  gptr<float> Rt = as_global(mt.Rt);
-#pragma unroll
-  for (int tm = 0; tm < 4; ++tm)
-#pragma unroll
-    for (int tn = 0; tn < 2; ++tn) {
-      const int col = g.b_row0 + wn * 64 + 32 * tn + (lane & 31);
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int row = g.a_row0 + wm * 128 + 32 * tm + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-        if (row < mt.L && col < mt.r) Rt[(long long)row * mt.r + col] = acc[tm][tn][v];
-      }
-    }
-}
-
 // ------------------------------------------------------------------------------------------------
 // Ring core for the rank-axis contractions (K = r is short, the epilogue is long): 256 threads,
 // 256 (A) x 128 (B) tile, two workgroups per CU, so one runs its HBM-bound epilogue while the other
-// multiplies.  Both operands are K-contiguous with 16-byte aligned, zero-padded rows, so they go
-// from global memory straight into LDS (global_load_lds_dwordx4: lane l of a wave writes 16 bytes at
-// M0 + 16*l) without passing through registers.  LDS holds a ring of three K stages of 32
+// multiplies.  Both operands are K-blocked, so they go from global memory straight into LDS
+// (global_load_lds_dwordx4: lane l of a wave writes 16 bytes at M0 + 16*l) without passing through
+// registers, and one load instruction (16 rows x 32 k) reads 1 KB of contiguous memory: row
+// segments of 64 B spread over 16 separate rows reach only two thirds of that L2 bandwidth.
+// LDS holds a ring of three K stages of 32
 // ([row][32 k] bf16, 64 B per row, 24 KB per stage): while stage s is multiplied, stages s+1 and
 // s+2 are in flight, and there is one barrier per stage.
 //
@@ -402,6 +117,8 @@ __global__ __launch_bounds__(FIRA_THREADS, 2) void fira_project_kernel_v4(const 
 // one chunk) hit distinct 16-byte bank groups within every aligned group of 8 and of 16 lanes.
 // Since a lane may fetch any global address, the loader realises the permutation on the global
 // side: lane l of a load covers row l/4 of a 16-row group and fetches chunk (l%4) ^ f(l/4).
+// Operand rows are padded to whole tiles (zeros), so no row index needs clamping; what the padding
+// rows produce lands in accumulators that are never stored.
 // ------------------------------------------------------------------------------------------------
 #define FIRA_TB_HALF 128
 #define FIRA_HALF_THREADS 256
@@ -446,9 +163,8 @@ __device__ __forceinline__ void ring_compute(f32x16_t (&acc)[4][2], const char* 
   gemm_mfma_slice(acc, f[1]);
 }
 
-// Requires KA == KB, a multiple of 64, readable on every row of both operands (zero padded), and
-// 16-byte aligned rows.  Rows beyond an operand are clamped to its last row; their products land in
-// accumulators that are never stored.
+// Both operands K-blocked with lda / ldb padded rows (multiples of 256) and KB stored k (a multiple
+// of 64).
 __device__ __forceinline__ void ring_mainloop(f32x16_t (&acc)[4][2], char* lds, const GemmOperands& g) {
 #pragma unroll
   for (int tm = 0; tm < 4; ++tm)
@@ -458,32 +174,21 @@ __device__ __forceinline__ void ring_mainloop(f32x16_t (&acc)[4][2], char* lds, 
       for (int v = 0; v < 16; ++v) acc[tm][tn][v] = 0.0f;
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const unsigned lds0 = (unsigned)(size_t)(lds_ptr)lds;
-  const int KT = g.KA / FIRA_RK;
+  const int KT = g.KB / FIRA_RK;
   const int lrow = lane >> 2;
   const int chunk = (lane & 3) ^ ring_swz(lrow);
-  unsigned offa[4], offb[2];
-#pragma unroll
-  for (int q = 0; q < 4; ++q) {
-    const int row = g.a_row0 + 16 * (4 * wave + q) + lrow;
-    const int rc = (row < g.a_rows ? row : g.a_rows - 1) - g.a_row0;
-    offa[q] = (unsigned)(rc * (int)g.lda * 2 + chunk * 16);
-  }
-#pragma unroll
-  for (int q = 0; q < 2; ++q) {
-    const int row = g.b_row0 + 16 * (2 * wave + q) + lrow;
-    const int rc = (row < g.b_rows ? row : g.b_rows - 1) - g.b_row0;
-    offb[q] = (unsigned)(rc * (int)g.ldb * 2 + chunk * 16);
-  }
-  const char* pa = reinterpret_cast<const char*>((const bf16_raw*)g.A + (long long)g.a_row0 * g.lda);
-  const char* pb = reinterpret_cast<const char*>((const bf16_raw*)g.B + (long long)g.b_row0 * g.ldb);
+  const unsigned off = (unsigned)(lrow * 64 + chunk * 16);   // inside a 16-row group (1 KB, contiguous)
+  // this wave's first group of each operand in K block 0; a K block is rows * 64 bytes further
+  const char* pa = reinterpret_cast<const char*>((const bf16_raw*)g.A) + ((long long)g.a_row0 + 64 * wave) * 64;
+  const char* pb = reinterpret_cast<const char*>((const bf16_raw*)g.B) + ((long long)g.b_row0 + 32 * wave) * 64;
   auto issue = [&](int s) {
     const unsigned dst = lds0 + (unsigned)((s % FIRA_RING_STAGES) * FIRA_RING_STAGE);
-    const char* ka = pa + (long long)s * (FIRA_RK * 2);
-    const char* kb = pb + (long long)s * (FIRA_RK * 2);
+    const char* ka = pa + (long long)s * g.lda * 64;
+    const char* kb = pb + (long long)s * g.ldb * 64;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) lds_dma16(ka, offa[q], dst + (unsigned)((4 * wave + q) * 1024));
+    for (int q = 0; q < 4; ++q) lds_dma16(ka + q * 1024, off, dst + (unsigned)((4 * wave + q) * 1024));
 #pragma unroll
-    for (int q = 0; q < 2; ++q) lds_dma16(kb, offb[q], dst + (unsigned)(FIRA_RING_A + (2 * wave + q) * 1024));
+    for (int q = 0; q < 2; ++q) lds_dma16(kb + q * 1024, off, dst + (unsigned)(FIRA_RING_A + (2 * wave + q) * 1024));
   };
   issue(0);
   if (KT > 1) issue(1);
@@ -500,7 +205,7 @@ __device__ __forceinline__ void ring_mainloop(f32x16_t (&acc)[4][2], char* lds, 
 // Kernel 1 (pipelined form): low-rank gradient, long-side major:  Rt[i][a] = sum_s G(s, i) P[s][a]
 //   LEFT  (m <= n): i = column of G, s = row of G      -> A side is G read K-slow
 //   RIGHT (m >  n): i = row of G,    s = column of G   -> A side is G read K-contiguous
-//   B side is PT[a][s] (rank rows, short-side contiguous, 16-byte aligned, zero padded).
+//   B side is PT (rank rows, short side along K, K-blocked).
 // 256 threads, 128 (A: gradient side) x 256 (B: rank) tile, two independent workgroups per CU so
 // that the load/store phases of one overlap the multiplies of the other.  Wave w owns all 128 A rows
 // and B rows 64 w .. 64 w + 63.
@@ -657,19 +362,13 @@ __device__ __forceinline__ void proj_pipeline(f32x16_t (&acc)[4][2], char* lds, 
   const int SS = g.KB / 64;                    // K stages of 64; the ring runs 2*SS stages of 32
   const int lrow = lane >> 2;
   const int chunk = (lane & 3) ^ ring_swz(lrow);
-  unsigned offb[4];
-#pragma unroll
-  for (int q = 0; q < 4; ++q) {
-    const int row = g.b_row0 + 16 * (4 * wave + q) + lrow;
-    const int rc = (row < g.b_rows ? row : g.b_rows - 1) - g.b_row0;
-    offb[q] = (unsigned)(rc * (int)g.ldb * 2 + chunk * 16);
-  }
-  const char* pb = reinterpret_cast<const char*>((const bf16_raw*)g.B + (long long)g.b_row0 * g.ldb);
+  const unsigned offb = (unsigned)(lrow * 64 + chunk * 16);
+  const char* pb = reinterpret_cast<const char*>((const bf16_raw*)g.B) + ((long long)g.b_row0 + 64 * wave) * 64;
   auto request_b = [&](int s) {
     const unsigned dst = ring0 + (unsigned)((s % FIRA_RING_STAGES) * FIRA_PROJ_RING_STAGE);
-    const char* kb = pb + (long long)s * (FIRA_RK * 2);
+    const char* kb = pb + (long long)s * g.ldb * 64;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) lds_dma16(kb, offb[q], dst + (unsigned)((4 * wave + q) * 1024));
+    for (int q = 0; q < 4; ++q) lds_dma16(kb + q * 1024, offb, dst + (unsigned)((4 * wave + q) * 1024));
   };
   ProjALoader<LEFT, FAST> al(g);
   u32x4 ra[4];
@@ -716,7 +415,7 @@ __global__ __launch_bounds__(FIRA_PROJ_THREADS, 2) void fira_project_kernel(cons
   g.b_row0 = tile.tb * FIRA_PB;
   g.b_rows = mt.r;
   g.B = as_global<const bf16_raw>(mt.PT);
-  g.ldb = mt.pt_ld;
+  g.ldb = mt.rq;
   g.KB = mt.kx * mt.Sp;
   if (mt.kx == 1) {
     g.A = as_global(reinterpret_cast<const bf16_raw*>(ent.G));
@@ -981,10 +680,11 @@ __global__ __launch_bounds__(FIRA_HALF_THREADS, 2) void fira_backproject_kernel(
   g.a_rows = mt.n;
   g.b_row0 = tile.tb * FIRA_TB_HALF;
   g.b_rows = mt.m;
-  g.lda = g.ldb = mt.lr_ld;
   g.KA = g.KB = mt.kx * mt.rp;
   g.A = mt.left ? lowrank : proj;
   g.B = mt.left ? proj : lowrank;
+  g.lda = mt.left ? mt.Lq : mt.Sq;
+  g.ldb = mt.left ? mt.Sq : mt.Lq;
   f32x16_t acc[4][2];
   ring_mainloop(acc, lds, g);
 
