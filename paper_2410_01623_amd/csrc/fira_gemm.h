@@ -17,6 +17,7 @@
 //     b (B row) = lane % 32,   a (A row) = 8*(v/4) + 4*(lane/32) + v%4
 // so a lane owns 4 consecutive A rows per group of 4 registers.
 #pragma once
+#include <type_traits>
 #include "fira_device.h"
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
@@ -232,15 +233,16 @@ __device__ __forceinline__ void ring_mainloop(f32x16_t (&acc)[4][2], char* lds, 
 #define FIRA_PROJ_LDS (FIRA_PROJ_LDS_A + FIRA_RING_STAGES * FIRA_PROJ_RING_STAGE)
 
 // 16 bytes per lane from base + voff into registers; the result may only be read after a wait that
-// names the registers (wait_loads below).
+// names the registers (wait_loads below; the names also go into a comment on the instruction, which
+// is what the static check of the compiled code keys on).
 __device__ __forceinline__ void gload16_async(u32x4& dst, const void* base, unsigned voff) {
   asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(dst) : "v"(voff), "s"(base) : "memory");
 }
 template <int N>
 __device__ __forceinline__ void wait_loads(u32x4 (&r)[4]) {
   static_assert(N == 4 || N == 0, "queue depths used by the projection pipeline");
-  if (N == 4) asm volatile("s_waitcnt vmcnt(4)" : "+v"(r[0]), "+v"(r[1]), "+v"(r[2]), "+v"(r[3]) :: "memory");
-  else asm volatile("s_waitcnt vmcnt(0)" : "+v"(r[0]), "+v"(r[1]), "+v"(r[2]), "+v"(r[3]) :: "memory");
+  if (N == 4) asm volatile("s_waitcnt vmcnt(4) ; %0 %1 %2 %3" : "+v"(r[0]), "+v"(r[1]), "+v"(r[2]), "+v"(r[3]) :: "memory");
+  else asm volatile("s_waitcnt vmcnt(0) ; %0 %1 %2 %3" : "+v"(r[0]), "+v"(r[1]), "+v"(r[2]), "+v"(r[3]) :: "memory");
 }
 
 // Thread -> element mapping of the A loaders (256 threads, 64 k x 128 rows per stage):
@@ -375,12 +377,15 @@ __device__ __forceinline__ void proj_pipeline(f32x16_t (&acc)[4][2], char* lds, 
   al.load(ra);                                 // A(0)
   request_b(0);
   request_b(1);
-  for (int S = 0; S < SS; ++S) {
+  // LAST: the final K stage requests nothing more.  It is written out separately rather than
+  // guarded inside the loop, so that on every path a request is followed by the wait that covers it.
+  auto stage = [&](auto last, int S) {
+    constexpr bool LAST = decltype(last)::value;
     // E half
     wait_loads<4>(ra);                         // A(S) and D(2S) have landed; D(2S+1) may be in flight
     asm volatile("s_barrier" ::: "memory");    // everybody is done with the previous stage's A tile and ring slot
     proj_store_a<LEFT>(la, ra);
-    if (S + 1 < SS) {
+    if (!LAST) {
       request_b(2 * S + 2);
       al.load(ra);                             // A(S+1)
     }
@@ -389,12 +394,14 @@ __device__ __forceinline__ void proj_pipeline(f32x16_t (&acc)[4][2], char* lds, 
     // O half
     // D(2S+1) has landed.  Guarded A loads are the compiler's and may be fewer than 4 instructions,
     // so the edge path only lets D(2S+2)'s four stay in flight.
-    if (S + 1 >= SS) asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+    if (LAST) asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
     else if (FAST) asm volatile("s_waitcnt vmcnt(8)\n\ts_barrier" ::: "memory");
     else asm volatile("s_waitcnt vmcnt(4)\n\ts_barrier" ::: "memory");
-    if (S + 1 < SS) request_b(2 * S + 3);
+    if (!LAST) request_b(2 * S + 3);
     proj_compute<SUMSQ>(acc, la, ring + ((2 * S + 1) % FIRA_RING_STAGES) * FIRA_PROJ_RING_STAGE, 2, sq);
-  }
+  };
+  for (int S = 0; S + 1 < SS; ++S) stage(std::false_type{}, S);
+  stage(std::true_type{}, SS - 1);
 }
 
 template <bool LEFT>
