@@ -247,9 +247,14 @@ __device__ __forceinline__ void wait_loads(u32x4 (&r)[4]) {
 
 // Thread -> element mapping of the A loaders (256 threads, 64 k x 128 rows per stage):
 //   K-contiguous: chunk cc = t & 7, rows rr + 32*q, rr = t >> 3, q = 0..3.
-//   K-slow:       one 4(k) x 8(a) block per thread: a-block ib = t & 15, k-quad kq = t >> 4, so 16
-//                 lanes read 256 contiguous bytes of one gradient row and the 32 lanes of a
-//                 half-wave write 16 distinct 8-byte LDS slots twice.
+//   K-slow:       one 4(k) x 8(a) block per thread: a-block ib (16), k-quad kq (16).  Thread bits
+//                 [0:3) -> ib low, bit 3 -> kq low, bit 4 -> ib high, bits [5:8) -> kq high: 8 lanes
+//                 read 128 contiguous bytes of one gradient row, and any 16 consecutive lanes write
+//                 16 distinct 8-byte LDS slots of a 128-byte bank window (8 chunk positions from the
+//                 row swizzle x the two halves of a chunk from kq's low bit).
+__device__ __forceinline__ int proj_kslow_ib(int t) { return (t & 7) | ((t >> 1) & 8); }
+__device__ __forceinline__ int proj_kslow_kq(int t) { return ((t >> 3) & 1) | ((t >> 4) & ~1); }
+
 template <bool LEFT, bool FAST>
 struct ProjALoader {
   const GemmOperands& g;
@@ -260,7 +265,7 @@ struct ProjALoader {
   __device__ __forceinline__ ProjALoader(const GemmOperands& g_) : g(g_), k0(0) {
     const int t = threadIdx.x;
     if (LEFT) {
-      const int ib = t & 15, kq = t >> 4;
+      const int ib = proj_kslow_ib(t), kq = proj_kslow_kq(t);
       base = reinterpret_cast<const char*>((const bf16_raw*)g.A + g.a_row0);
 #pragma unroll
       for (int j = 0; j < 4; ++j) off[j] = (unsigned)(((4 * kq + j) * g.lda + 8 * ib) * 2);
@@ -282,7 +287,7 @@ struct ProjALoader {
       const int t = threadIdx.x;
       const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
       if (LEFT) {
-        const int ib = t & 15, kq = t >> 4;
+        const int ib = proj_kslow_ib(t), kq = proj_kslow_kq(t);
         const long long a = (long long)g.a_row0 + 8 * ib;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -310,7 +315,7 @@ __device__ __forceinline__ void proj_store_a(char* la, const u32x4 (&ra)[4]) {
   const int t = threadIdx.x;
   if (LEFT) {
     // ra[j] holds row k = 4*kq + j of a 4(k) x 8(a) block; emit, for each a, its 4 k values (8 B).
-    const int ib = t & 15, kq = t >> 4;
+    const int ib = proj_kslow_ib(t), kq = proj_kslow_kq(t);
     const unsigned in[16] = {ra[0].x, ra[0].y, ra[0].z, ra[0].w, ra[1].x, ra[1].y, ra[1].z, ra[1].w,
                              ra[2].x, ra[2].y, ra[2].z, ra[2].w, ra[3].x, ra[3].y, ra[3].z, ra[3].w};  // in[4*j + d]: a = 2d, 2d+1
 #pragma unroll
