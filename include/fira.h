@@ -71,9 +71,11 @@ typedef struct {
   int32_t wg_dtype;
 } fira_matrix_desc;
 
-/* Scaling-factor granularity: FIRA_SCALE_COLUMN is the paper's Fira (Eq. 11); FIRA_SCALE_NONE sets
- * every factor to 1 (the "GaLore-add" update of Eq. 8 / "Fira-w.o.-scaling" of Sec. 5.3). */
-typedef enum { FIRA_SCALE_COLUMN = 0, FIRA_SCALE_NONE = 2 } fira_scaling;
+/* Scaling-factor granularity: FIRA_SCALE_COLUMN is the paper's Fira (one factor per column, Eq. 11);
+ * FIRA_SCALE_MATRIX uses one factor ||N|| / (||R|| + eps) for the whole matrix (Eqs. 9-10, the
+ * "Fira-matrix" variant of Sec. 5.3); FIRA_SCALE_NONE sets every factor to 1 (the "GaLore-add" update
+ * of Eq. 8 / "Fira-w.o.-scaling" of Sec. 5.3). */
+typedef enum { FIRA_SCALE_COLUMN = 0, FIRA_SCALE_MATRIX = 1, FIRA_SCALE_NONE = 2 } fira_scaling;
 
 /* How ||S_t|| (Eq. 12) is obtained.  FIRA_NORM_RESIDUAL forms G - P R tile by tile with an extra
  * rank-r contraction (exact for any P).  FIRA_NORM_GRAM uses

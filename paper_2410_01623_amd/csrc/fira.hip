@@ -361,7 +361,7 @@ fira_status fira_set_hparams(fira_ctx* ctx, const fira_hparams* hp) {
 
 fira_status fira_set_options(fira_ctx* ctx, fira_scaling scaling, fira_norm_mode norm_mode) {
   if (!ctx) return fail(nullptr, FIRA_ERR_INVALID_ARG, "ctx is null");
-  if (scaling != FIRA_SCALE_COLUMN && scaling != FIRA_SCALE_NONE) return fail(ctx, FIRA_ERR_INVALID_ARG, "unknown scaling mode");
+  if (scaling != FIRA_SCALE_COLUMN && scaling != FIRA_SCALE_MATRIX && scaling != FIRA_SCALE_NONE) return fail(ctx, FIRA_ERR_INVALID_ARG, "unknown scaling mode");
   if (norm_mode != FIRA_NORM_RESIDUAL && norm_mode != FIRA_NORM_GRAM) return fail(ctx, FIRA_ERR_INVALID_ARG, "unknown norm mode");
   ctx->scaling = scaling;
   ctx->norm_mode = norm_mode;
@@ -458,7 +458,7 @@ fira_status fira_step(fira_ctx* ctx, int count, const int* idx, void* const* dev
   mark(4);
   // 5. Z = N - c k R
   hipLaunchKernelGGL(fira_makez_kernel, dim3(s->rowblocks), dim3(256), 0, q, ctx->d_mats, ctx->d_scal, s->d_ents, count,
-                     s->rowblocks);
+                     s->rowblocks, hp);
   mark(5);
   // 6. W -= lr alpha (P Z + c k G)
   if (s->ntiles[kTilesBackBf16])

@@ -97,10 +97,17 @@ __device__ __forceinline__ void adam_row(const FiraMat& mt, const FiraHp& hp, fl
   nn = wave_sum(nn);
   rr = wave_sum(rr);
   if (lane == 0) {
-    const float k = (hp.scaling == 2) ? 1.0f : sqrtf(nn) / (sqrtf(rr) + hp.epsf);
-    as_global(mt.phi)[row] = k;
-    // Gram route: ||G_i - P R_i||^2 = ||G_i||^2 - ||R_i||^2 when P^T P = I (G_i^T P = R_i^T always)
-    if (gram) as_global(mt.q)[row] = k * k * fmaxf(as_global<const float>(mt.g2)[row] - rr, 0.0f);
+    if (hp.scaling == 1) {
+      // one factor per matrix: leave the row's ||N_i||^2 and ||R_i||^2 for the limiter kernel, which
+      // sums them, forms the factor and writes it over phi
+      as_global(mt.phi)[row] = nn;
+      as_global(mt.q)[row] = rr;
+    } else {
+      const float k = (hp.scaling == 2) ? 1.0f : sqrtf(nn) / (sqrtf(rr) + hp.epsf);
+      as_global(mt.phi)[row] = k;
+      // Gram route: ||G_i - P R_i||^2 = ||G_i||^2 - ||R_i||^2 when P^T P = I (G_i^T P = R_i^T always)
+      if (gram) as_global(mt.q)[row] = k * k * fmaxf(as_global<const float>(mt.g2)[row] - rr, 0.0f);
+    }
   }
 }
 
@@ -175,6 +182,7 @@ __global__ __launch_bounds__(256, 4) void fira_adam_kernel(const FiraMat* __rest
   const FiraEnt ent = ents[e];
   const FiraMat mt = mats[ent.mat];
   bf16_raw* zl = reinterpret_cast<bf16_raw*>(adam_lds);
+  const bool zready = mt.zready && hp.scaling != 1;   // the matrix-level factor is not known in this kernel
   // bias correction with the 1-based step count (Eq. 4), in double: 1 - beta2^t loses all
   // accuracy in fp32 at small t.
   const FiraScal sc = scal[ent.mat];
@@ -186,12 +194,12 @@ __global__ __launch_bounds__(256, 4) void fira_adam_kernel(const FiraMat* __rest
   for (int i = 0; i < 4; ++i) {
     const long long row = row_base + i;
     if (row >= mt.L) {
-      if (mt.zready)   // rows of the padding: zeros
+      if (zready)   // rows of the padding: zeros
         for (int a = (threadIdx.x & 63) * 4; a < mt.rp; a += 256)
           *reinterpret_cast<u32x2*>(zl + (a >> 5) * (FIRA_ROWS_PER_WG * 32) + (wave * 4 + i) * 32 + (a & 31)) = u32x2{0u, 0u};
       continue;
     }
-    if (mt.zready) {
+    if (zready) {
       if (mt.r <= 256) adam_row_zready<1>(mt, hp, bias, row, gram, zl, wave * 4 + i);
       else if (mt.r <= 512) adam_row_zready<2>(mt, hp, bias, row, gram, zl, wave * 4 + i);
       else adam_row_zready<FIRA_ZREADY_MAX_R / 256>(mt, hp, bias, row, gram, zl, wave * 4 + i);
@@ -201,7 +209,7 @@ __global__ __launch_bounds__(256, 4) void fira_adam_kernel(const FiraMat* __rest
       adam_row<FIRA_KX_SPLIT, 1>(mt, hp, bias, row, gram);
     }
   }
-  if (mt.zready) {
+  if (zready) {
     __syncthreads();
     // the 16 rows of one K block are 1 KB of contiguous memory
     gptr<char> nb = reinterpret_cast<gptr<char>>(as_global(mt.Nb));
@@ -225,8 +233,32 @@ __global__ __launch_bounds__(64) void fira_limiter_kernel(const FiraMat* __restr
                                                           const float* __restrict__ partial, FiraHp hp) {
   const FiraEnt ent = ents[blockIdx.x];
   const int lane = threadIdx.x;
+  const bool gram = use_gram(hp, scal[ent.mat]);
   double acc = 0.0;
-  if (use_gram(hp, scal[ent.mat])) {
+  if (hp.scaling == 1) {
+    // Matrix-level factor (Eq. 9): k = ||N|| / (||R|| + eps) from the row sums the Adam kernel left in
+    // phi and q; ||S||^2 = k^2 * (sum_i ||G_i - P R_i||^2), the sum taken with unit factors by either route.
+    const FiraMat mt = mats[ent.mat];
+    gptr<float> phi = as_global(mt.phi);
+    gptr<const float> q = as_global<const float>(mt.q);
+    gptr<const float> g2 = as_global<const float>(mt.g2);
+    double nn = 0.0, rr = 0.0;
+    for (int i = lane; i < mt.L; i += 64) {
+      nn += (double)phi[i];
+      rr += (double)q[i];
+      if (gram) acc += (double)fmaxf(g2[i] - q[i], 0.0f);
+    }
+    if (!gram)
+      for (int i = lane; i < ent.npart; i += 64) acc += (double)partial[ent.part0 + i];
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+      nn += __shfl_xor(nn, off, 64);
+      rr += __shfl_xor(rr, off, 64);
+    }
+    const float k = (float)(sqrt(nn) / (sqrt(rr) + hp.eps));
+    acc *= (double)k * (double)k;
+    for (int i = lane; i < mt.L; i += 64) phi[i] = k;   // every lane has finished reading phi (the shuffles above)
+  } else if (gram) {
     const FiraMat mt = mats[ent.mat];
     gptr<const float> q = as_global<const float>(mt.q);
     for (int i = lane; i < mt.L; i += 64) acc += (double)q[i];
@@ -310,21 +342,22 @@ __device__ __forceinline__ void fixz_row(const FiraMat& mt, float f, long long r
 __global__ __launch_bounds__(256) void fira_makez_kernel(const FiraMat* __restrict__ mats,
                                                          const FiraScal* __restrict__ scal,
                                                          const FiraEnt* __restrict__ ents, int count,
-                                                         int total_rowblocks) {
+                                                         int total_rowblocks, FiraHp hp) {
   const int rb = blockIdx.x;
   if (rb >= total_rowblocks) return;
   const int e = find_entry(ents, count, rb);
   const FiraEnt ent = ents[e];
   const FiraMat mt = mats[ent.mat];
   const float c = scal[ent.mat].c;
-  if (mt.zready && c == 1.0f) return;          // the Adam kernel already wrote Z for c = 1
+  const bool zready = mt.zready && hp.scaling != 1;
+  if (zready && c == 1.0f) return;             // the Adam kernel already wrote Z for c = 1
   const int wave = threadIdx.x >> 6;
   const long long row_base = (long long)(rb - ent.row0) * FIRA_ROWS_PER_WG + wave * 4;
   for (int i = 0; i < 4; ++i) {
     const long long row = row_base + i;
     if (row >= mt.L) break;
     const float k = as_global<const float>(mt.phi)[row];
-    if (mt.zready) fixz_row(mt, (1.0f - c) * k, row);
+    if (zready) fixz_row(mt, (1.0f - c) * k, row);
     else if (mt.kx == 1) makez_row<1>(mt, c * k, row);
     else makez_row<FIRA_KX_SPLIT>(mt, c * k, row);
   }

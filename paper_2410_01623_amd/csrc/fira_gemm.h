@@ -575,7 +575,7 @@ struct Elem8<float> {
 #define FIRA_BACK_LDS (FIRA_EPI_LDS > FIRA_RING_LDS ? FIRA_EPI_LDS : FIRA_RING_LDS)
 template <int MODE, typename T, bool INTERIOR>
 __device__ __forceinline__ float backproject_epilogue(f32x16_t (&acc)[4][2], char* lds, const FiraMat& mt,
-                                                      const FiraEnt& ent, int i0, int j0, float c, float lr_alpha) {
+                                                      const FiraEnt& ent, int i0, int j0, float c, float lr_alpha, bool unitk) {
   typedef typename Elem8<T>::Raw Raw;
   constexpr bool PIPE = sizeof(T) == 2;       // fp32 tiles would need 128 more registers: no prefetch
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -612,7 +612,7 @@ __device__ __forceinline__ float backproject_epilogue(f32x16_t (&acc)[4][2], cha
   float cphi[8];
   if (mt.left) {
 #pragma unroll
-    for (int e = 0; e < 8; ++e) cphi[e] = (INTERIOR || j + e < mt.n) ? c * phi[j + e] : 0.0f;
+    for (int e = 0; e < 8; ++e) cphi[e] = (INTERIOR || j + e < mt.n) ? (unitk ? c : c * phi[j + e]) : 0.0f;
   }
   float sum = 0.0f;
 #pragma unroll
@@ -641,7 +641,7 @@ __device__ __forceinline__ float backproject_epilogue(f32x16_t (&acc)[4][2], cha
         float g[8];
         Elem8<T>::unpack(gr, g);
         if (!mt.left) {
-          const float f = c * phi[i];
+          const float f = unitk ? c : c * phi[i];
 #pragma unroll
           for (int e = 0; e < 8; ++e) cphi[e] = f;
         }
@@ -704,8 +704,10 @@ __global__ __launch_bounds__(FIRA_HALF_THREADS, 2) void fira_backproject_kernel(
   const int i0 = g.b_row0, j0 = g.a_row0;
   const bool interior = i0 + FIRA_TB_HALF <= mt.m && j0 + FIRA_TA <= mt.n;
   float sum;
-  if (interior) sum = backproject_epilogue<MODE, T, true>(acc, lds, mt, ent, i0, j0, c, lr_alpha);
-  else sum = backproject_epilogue<MODE, T, false>(acc, lds, mt, ent, i0, j0, c, lr_alpha);
+  // matrix-level factor: the residual norm is taken with unit factors and scaled by the limiter kernel
+  const bool unitk = MODE == 0 && hp.scaling == 1;
+  if (interior) sum = backproject_epilogue<MODE, T, true>(acc, lds, mt, ent, i0, j0, c, lr_alpha, unitk);
+  else sum = backproject_epilogue<MODE, T, false>(acc, lds, mt, ent, i0, j0, c, lr_alpha, unitk);
 
   if (MODE == 0) {
     // deterministic workgroup reduction: xor-butterfly inside each wave, then waves in order

@@ -24,7 +24,7 @@ FIRA_ERR_DTYPE = -4
 FIRA_ERR_WORKSPACE = -5
 FIRA_ERR_HIP = -6
 FIRA_F32, FIRA_BF16 = 0, 1
-FIRA_SCALE_COLUMN, FIRA_SCALE_NONE = 0, 2
+FIRA_SCALE_COLUMN, FIRA_SCALE_MATRIX, FIRA_SCALE_NONE = 0, 1, 2
 FIRA_NORM_RESIDUAL, FIRA_NORM_GRAM = 0, 1
 FIRA_NUM_KERNELS = 6
 

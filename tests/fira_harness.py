@@ -72,7 +72,8 @@ def run_case(shapes: Sequence[Tuple[int, int]], rank, dtype: int, steps: int,
     chp = fira.make_hparams(hp.lr, hp.beta1, hp.beta2, hp.eps, hp.alpha, hp.gamma)
     ctx = fira.FiraContext(shapes, rank, dtype, chp, device=DEV, lds=lds)
     if scaling != "column" or norm_mode != fira.FIRA_NORM_RESIDUAL:
-        ctx.fira_set_options(scaling={"none": fira.FIRA_SCALE_NONE, "column": fira.FIRA_SCALE_COLUMN}[scaling],
+        ctx.fira_set_options(scaling={"none": fira.FIRA_SCALE_NONE, "column": fira.FIRA_SCALE_COLUMN,
+                                      "matrix": fira.FIRA_SCALE_MATRIX}[scaling],
                              norm_mode=norm_mode)
     bf = dtype == fira.FIRA_BF16
     W_host = {i: gen_W(i) for i in set(src(i) for i in range(nmat))}

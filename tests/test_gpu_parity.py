@@ -154,6 +154,28 @@ def test_no_scaling_variant():
     check(res, fira.FIRA_BF16)
 
 
+@pytest.mark.parametrize("norm_mode", [fira.FIRA_NORM_RESIDUAL, fira.FIRA_NORM_GRAM], ids=["residual", "gram"])
+@pytest.mark.parametrize("dtype", [fira.FIRA_BF16, fira.FIRA_F32], ids=["bf16", "f32"])
+@pytest.mark.parametrize("m,n,r", [(120, 260, 24), (300, 200, 40)], ids=["120x260r24", "300x200r40"])
+def test_matrix_level_factor_variant(m, n, r, dtype, norm_mode):
+    """FIRA_SCALE_MATRIX: one factor ||N|| / (||R|| + eps) for the whole matrix (Eqs. 9-10, the
+    "Fira-matrix" variant), both orientations, both routes to the limiter norm, with a spike that the
+    limiter must cut."""
+    W0, Gs, P = random_case(11 + m, m, n, r, dtype, 5, spike_at=3)
+    res = H.run_case([(m, n)], r, dtype, 5, lambda i: W0, lambda i, s: Gs[s],
+                     lambda i, s: P if s == 0 else None, orc.OracleHparams(), scaling="matrix",
+                     norm_mode=norm_mode)
+    assert res.c_min < 1.0
+    msg = H.fmt(res)
+    print(msg, flush=True)
+    assert max(res.w_err) <= TOL_W[dtype], msg
+    tol = dict(TOL_STAGE[dtype])
+    if norm_mode == fira.FIRA_NORM_GRAM:
+        tol.update(s_pre=1e-3, c=1e-3)
+    for k, v in tol.items():
+        assert res.worst[k] <= v, f"stage {k}: {msg}"
+
+
 def test_limiter_off_and_degenerate_columns():
     """gamma = inf disables the limiter; an all-zero column gives k = 0 and no NaN."""
     m, n, r = 64, 96, 16
