@@ -7,6 +7,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstdio>
+#include <cstddef>
 #include <cstring>
 #include <string>
 #include <vector>
@@ -168,6 +169,11 @@ struct fira_ctx {
   float* d_partial = nullptr;
   ListSlot slots[kSlots];
   char* h_stage_all = nullptr;
+  // Host copy of every matrix's FiraScal::ortho_err (pinned; +inf until known), so that a step on the
+  // Gram route can leave out the residual launch when no listed matrix needs it.
+  float* h_ortho = nullptr;
+  hipEvent_t ortho_event = nullptr;
+  bool ortho_pending = false;
   uint64_t use_counter = 0;
   std::string last_error;
   // optional per-kernel timing (fira_profile_begin / fira_profile_end)
@@ -312,6 +318,8 @@ fira_status fira_init_state(fira_ctx** out, const fira_matrix_desc* d, int count
   auto cleanup = [&]() {
     for (ListSlot& s : ctx->slots) if (s.uploaded) (void)hipEventDestroy(s.uploaded);
     if (ctx->h_stage_all) (void)hipHostFree(ctx->h_stage_all);
+    if (ctx->h_ortho) (void)hipHostFree(ctx->h_ortho);
+    if (ctx->ortho_event) (void)hipEventDestroy(ctx->ortho_event);
     delete ctx;
   };
 #define FIRA_INIT_HIP(call)                                                                          \
@@ -331,6 +339,9 @@ fira_status fira_init_state(fira_ctx** out, const fira_matrix_desc* d, int count
   FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_backproject_kernel<0, float>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_BACK_LDS));
   FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_backproject_kernel<1, float>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_BACK_LDS));
   FIRA_INIT_HIP(hipHostMalloc((void**)&ctx->h_stage_all, p.slot_bytes * kSlots, hipHostMallocDefault));
+  FIRA_INIT_HIP(hipHostMalloc((void**)&ctx->h_ortho, sizeof(float) * count, hipHostMallocDefault));
+  for (int i = 0; i < count; ++i) ctx->h_ortho[i] = INFINITY;
+  FIRA_INIT_HIP(hipEventCreateWithFlags(&ctx->ortho_event, hipEventDisableTiming));
   for (int i = 0; i < kSlots; ++i) {
     ListSlot& s = ctx->slots[i];
     s.h_stage = ctx->h_stage_all + p.slot_bytes * i;
@@ -387,6 +398,11 @@ fira_status fira_set_projector(fira_ctx* ctx, int idx, const void* dev_P, fira_d
   hipLaunchKernelGGL(fira_ortho_z_kernel, dim3(FIRA_ORTHO_SPLITS), dim3(256), 0, ctx->stream, h.dev, (const float*)ybuf, zbuf);
   hipLaunchKernelGGL(fira_ortho_final_kernel, dim3(1), dim3(256), 0, ctx->stream, h.dev, (const float*)zbuf, ctx->d_scal, idx);
   FIRA_HIP(ctx, hipGetLastError());
+  ctx->h_ortho[idx] = INFINITY;
+  FIRA_HIP(ctx, hipMemcpyAsync(&ctx->h_ortho[idx], reinterpret_cast<char*>(&ctx->d_scal[idx]) + offsetof(FiraScal, ortho_err),
+                               sizeof(float), hipMemcpyDeviceToHost, ctx->stream));
+  FIRA_HIP(ctx, hipEventRecord(ctx->ortho_event, ctx->stream));
+  ctx->ortho_pending = true;
   h.has_projector = true;
   return FIRA_OK;
 }
@@ -443,22 +459,31 @@ fira_status fira_step(fira_ctx* ctx, int count, const int* idx, void* const* dev
   hipLaunchKernelGGL(fira_adam_kernel, dim3(s->rowblocks), dim3(256), ctx->plan.adam_lds, q, ctx->d_mats, ctx->d_scal, s->d_ents, count,
                      s->rowblocks, hp);
   mark(2);
-  // 3. ||k (G - P R)||^2 per tile
-  if (s->ntiles[kTilesBackBf16])
+  // 3. ||k (G - P R)||^2 per tile, unless every listed matrix takes the Gram route (the kernels apply
+  //    the same test per matrix: FiraScal::ortho_err <= FiraHp::ortho_tol)
+  bool need_residual = true;
+  if (ctx->norm_mode == FIRA_NORM_GRAM) {
+    if (ctx->ortho_pending) {   // a projector was installed since the last step: wait for its gate value
+      FIRA_HIP(ctx, hipEventSynchronize(ctx->ortho_event));
+      ctx->ortho_pending = false;
+    }
+    need_residual = false;
+    for (int e = 0; e < count; ++e) need_residual = need_residual || !(ctx->h_ortho[idx[e]] <= hp.ortho_tol);
+  }
+  if (need_residual && s->ntiles[kTilesBackBf16])
     hipLaunchKernelGGL((fira_backproject_kernel<0, bf16_raw>), grid8(s->ntiles[kTilesBackBf16]), dim3(FIRA_HALF_THREADS), FIRA_BACK_LDS, q,
                        ctx->d_mats, ctx->d_scal, s->d_ents, s->d_tiles[kTilesBackBf16], s->ntiles[kTilesBackBf16],
                        ctx->d_partial, hp);
-  if (s->ntiles[kTilesBackF32])
+  if (need_residual && s->ntiles[kTilesBackF32])
     hipLaunchKernelGGL((fira_backproject_kernel<0, float>), grid8(s->ntiles[kTilesBackF32]), dim3(FIRA_HALF_THREADS), FIRA_BACK_LDS, q,
                        ctx->d_mats, ctx->d_scal, s->d_ents, s->d_tiles[kTilesBackF32], s->ntiles[kTilesBackF32],
                        ctx->d_partial, hp);
   mark(3);
   // 4. limiter factor, state advance
-  hipLaunchKernelGGL(fira_limiter_kernel, dim3(count), dim3(64), 0, q, ctx->d_mats, ctx->d_scal, s->d_ents, ctx->d_partial, hp);
+  hipLaunchKernelGGL(fira_limiter_kernel, dim3(count), dim3(FIRA_LIMITER_THREADS), 0, q, ctx->d_mats, ctx->d_scal, s->d_ents, ctx->d_partial, hp);
   mark(4);
   // 5. Z = N - c k R
-  hipLaunchKernelGGL(fira_makez_kernel, dim3(s->rowblocks), dim3(256), 0, q, ctx->d_mats, ctx->d_scal, s->d_ents, count,
-                     s->rowblocks, hp);
+  hipLaunchKernelGGL(fira_makez_kernel, dim3(count * FIRA_MAKEZ_PARTS), dim3(256), 0, q, ctx->d_mats, ctx->d_scal, s->d_ents, hp);
   mark(5);
   // 6. W -= lr alpha (P Z + c k G)
   if (s->ntiles[kTilesBackBf16])
@@ -622,6 +647,8 @@ void fira_destroy(fira_ctx* ctx) {
   for (ListSlot& s : ctx->slots)
     if (s.uploaded) (void)hipEventDestroy(s.uploaded);
   if (ctx->h_stage_all) (void)hipHostFree(ctx->h_stage_all);
+  if (ctx->h_ortho) (void)hipHostFree(ctx->h_ortho);
+  if (ctx->ortho_event) (void)hipEventDestroy(ctx->ortho_event);
   delete ctx;
 }
 

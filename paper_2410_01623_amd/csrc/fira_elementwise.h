@@ -171,6 +171,58 @@ __device__ __forceinline__ void adam_row_zready(const FiraMat& mt, const FiraHp&
   }
 }
 
+// Small ranks (r <= 64, e.g. the fine-tuning setting's r = 32): a factor's row is at most 256 bytes, so
+// a wavefront takes its four rows at once, 16 lanes per row, instead of one after the other.
+__device__ __forceinline__ void adam_rows4_small(const FiraMat& mt, const FiraHp& hp, float bias, long long row_base,
+                                                 bool gram, bf16_raw* zl, int wave) {
+  const int lane = threadIdx.x & 63;
+  const int g = lane >> 4, a = (lane & 15) * 4;
+  const int r = mt.r;
+  const long long row = row_base + g;
+  const bool live = row < mt.L && a < r;
+  gptr<const float> R = as_global<const float>(mt.Rt) + row * r;
+  gptr<float> M = as_global(mt.M) + row * r;
+  gptr<float> V = as_global(mt.V) + row * r;
+  f32x4 nv = f32x4{0.f, 0.f, 0.f, 0.f}, rv = nv;
+  float nn = 0.0f, rr = 0.0f;
+  if (live) {
+    rv = *reinterpret_cast<gptr<const f32x4>>(R + a);
+    f32x4 mv = *reinterpret_cast<gptr<const f32x4>>(M + a);
+    f32x4 vv = *reinterpret_cast<gptr<const f32x4>>(V + a);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      mv[e] = hp.b1 * mv[e] + hp.omb1 * rv[e];
+      vv[e] = hp.b2 * vv[e] + hp.omb2 * (rv[e] * rv[e]);
+      nv[e] = bias * (mv[e] / (sqrtf(vv[e]) + hp.epsf));
+      nn += nv[e] * nv[e];
+      rr += rv[e] * rv[e];
+    }
+    *reinterpret_cast<gptr<f32x4>>(M + a) = mv;
+    *reinterpret_cast<gptr<f32x4>>(V + a) = vv;
+  }
+#pragma unroll
+  for (int off = 8; off >= 1; off >>= 1) {   // sums within the 16 lanes of a row
+    nn += __shfl_xor(nn, off, 64);
+    rr += __shfl_xor(rr, off, 64);
+  }
+  const float k = (hp.scaling == 2) ? 1.0f : sqrtf(nn) / (sqrtf(rr) + hp.epsf);
+  if (a < mt.rp) {
+    u32x2 zv = u32x2{0u, 0u};   // rows beyond L and columns beyond r: the operand's zero padding
+    if (live) {
+      const f32x4 z = nv - k * rv;
+      zv = u32x2{pack_bf16x2(z[0], z[1]), pack_bf16x2(z[2], z[3])};
+      if (!gram)
+        *reinterpret_cast<gptr<u32x2>>(as_global(mt.Rb) + kblk_index(mt.Lq, row, a)) =
+            u32x2{pack_bf16x2(rv[0], rv[1]), pack_bf16x2(rv[2], rv[3])};
+    }
+    *reinterpret_cast<u32x2*>(zl + (a >> 5) * (FIRA_ROWS_PER_WG * 32) + (wave * 4 + g) * 32 + (a & 31)) = zv;
+  }
+  if ((lane & 15) == 0 && row < mt.L) {
+    as_global(mt.phi)[row] = k;
+    if (gram) as_global(mt.q)[row] = k * k * fmaxf(as_global<const float>(mt.g2)[row] - rr, 0.0f);
+  }
+}
+
 __global__ __launch_bounds__(256, 4) void fira_adam_kernel(const FiraMat* __restrict__ mats,
                                                         const FiraScal* __restrict__ scal,
                                                         const FiraEnt* __restrict__ ents, int count,
@@ -191,7 +243,8 @@ __global__ __launch_bounds__(256, 4) void fira_adam_kernel(const FiraMat* __rest
   const float bias = (float)(sqrt(1.0 - pow(hp.beta2, (double)t)) / (1.0 - pow(hp.beta1, (double)t)));
   const int wave = threadIdx.x >> 6;
   const long long row_base = (long long)(rb - ent.row0) * FIRA_ROWS_PER_WG + wave * 4;
-  for (int i = 0; i < 4; ++i) {
+  if (zready && mt.r <= 64) adam_rows4_small(mt, hp, bias, row_base, gram, zl, wave);
+  else for (int i = 0; i < 4; ++i) {
     const long long row = row_base + i;
     if (row >= mt.L) {
       if (zready)   // rows of the padding: zeros
@@ -227,12 +280,24 @@ __global__ __launch_bounds__(256, 4) void fira_adam_kernel(const FiraMat* __rest
 // Norm-growth limiter (Eq. 12 in Algorithm 1's form): one workgroup per listed matrix sums the
 // tile partials of ||S||^2 in a fixed order (fp64), derives the factor c, and advances the state.
 // ------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(64) void fira_limiter_kernel(const FiraMat* __restrict__ mats,
-                                                          FiraScal* __restrict__ scal,
-                                                          const FiraEnt* __restrict__ ents,
-                                                          const float* __restrict__ partial, FiraHp hp) {
+#define FIRA_LIMITER_THREADS 256
+// Workgroup sum in a fixed order: butterfly inside each wavefront, then the four wavefronts in order.
+__device__ __forceinline__ double limiter_block_sum(double x, double* red) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) x += __shfl_xor(x, off, 64);
+  __syncthreads();                       // red may still be read from the previous call
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = x;
+  __syncthreads();
+  return (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+__global__ __launch_bounds__(FIRA_LIMITER_THREADS) void fira_limiter_kernel(const FiraMat* __restrict__ mats,
+                                                                            FiraScal* __restrict__ scal,
+                                                                            const FiraEnt* __restrict__ ents,
+                                                                            const float* __restrict__ partial, FiraHp hp) {
+  __shared__ double red[4];
   const FiraEnt ent = ents[blockIdx.x];
-  const int lane = threadIdx.x;
+  const int tid = threadIdx.x;
   const bool gram = use_gram(hp, scal[ent.mat]);
   double acc = 0.0;
   if (hp.scaling == 1) {
@@ -243,31 +308,27 @@ __global__ __launch_bounds__(64) void fira_limiter_kernel(const FiraMat* __restr
     gptr<const float> q = as_global<const float>(mt.q);
     gptr<const float> g2 = as_global<const float>(mt.g2);
     double nn = 0.0, rr = 0.0;
-    for (int i = lane; i < mt.L; i += 64) {
+    for (int i = tid; i < mt.L; i += FIRA_LIMITER_THREADS) {
       nn += (double)phi[i];
       rr += (double)q[i];
       if (gram) acc += (double)fmaxf(g2[i] - q[i], 0.0f);
     }
     if (!gram)
-      for (int i = lane; i < ent.npart; i += 64) acc += (double)partial[ent.part0 + i];
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {
-      nn += __shfl_xor(nn, off, 64);
-      rr += __shfl_xor(rr, off, 64);
-    }
+      for (int i = tid; i < ent.npart; i += FIRA_LIMITER_THREADS) acc += (double)partial[ent.part0 + i];
+    nn = limiter_block_sum(nn, red);     // (the barriers inside also order the reads of phi before its rewrite)
+    rr = limiter_block_sum(rr, red);
     const float k = (float)(sqrt(nn) / (sqrt(rr) + hp.eps));
     acc *= (double)k * (double)k;
-    for (int i = lane; i < mt.L; i += 64) phi[i] = k;   // every lane has finished reading phi (the shuffles above)
+    for (int i = tid; i < mt.L; i += FIRA_LIMITER_THREADS) phi[i] = k;
   } else if (gram) {
     const FiraMat mt = mats[ent.mat];
     gptr<const float> q = as_global<const float>(mt.q);
-    for (int i = lane; i < mt.L; i += 64) acc += (double)q[i];
+    for (int i = tid; i < mt.L; i += FIRA_LIMITER_THREADS) acc += (double)q[i];
   } else {
-    for (int i = lane; i < ent.npart; i += 64) acc += (double)partial[ent.part0 + i];
+    for (int i = tid; i < ent.npart; i += FIRA_LIMITER_THREADS) acc += (double)partial[ent.part0 + i];
   }
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off, 64);
-  if (lane == 0) {
+  acc = limiter_block_sum(acc, red);
+  if (tid == 0) {
     FiraScal s = scal[ent.mat];
     const double sn = sqrt(acc);
     double c = 1.0;
@@ -339,27 +400,30 @@ __device__ __forceinline__ void fixz_row(const FiraMat& mt, float f, long long r
   }
 }
 
+#define FIRA_MAKEZ_PARTS 32   // workgroups per listed matrix
+// One workgroup per (listed matrix, part): it reads the matrix's c once and, in the common case, exits;
+// otherwise it takes every FIRA_MAKEZ_PARTS-th block of 16 rows.
 __global__ __launch_bounds__(256) void fira_makez_kernel(const FiraMat* __restrict__ mats,
                                                          const FiraScal* __restrict__ scal,
-                                                         const FiraEnt* __restrict__ ents, int count,
-                                                         int total_rowblocks, FiraHp hp) {
-  const int rb = blockIdx.x;
-  if (rb >= total_rowblocks) return;
-  const int e = find_entry(ents, count, rb);
-  const FiraEnt ent = ents[e];
-  const FiraMat mt = mats[ent.mat];
+                                                         const FiraEnt* __restrict__ ents, FiraHp hp) {
+  const FiraEnt ent = ents[blockIdx.x / FIRA_MAKEZ_PARTS];
+  const int part = blockIdx.x % FIRA_MAKEZ_PARTS;
   const float c = scal[ent.mat].c;
+  const FiraMat mt = mats[ent.mat];
   const bool zready = mt.zready && hp.scaling != 1;
   if (zready && c == 1.0f) return;             // the Adam kernel already wrote Z for c = 1
   const int wave = threadIdx.x >> 6;
-  const long long row_base = (long long)(rb - ent.row0) * FIRA_ROWS_PER_WG + wave * 4;
-  for (int i = 0; i < 4; ++i) {
-    const long long row = row_base + i;
-    if (row >= mt.L) break;
-    const float k = as_global<const float>(mt.phi)[row];
-    if (zready) fixz_row(mt, (1.0f - c) * k, row);
-    else if (mt.kx == 1) makez_row<1>(mt, c * k, row);
-    else makez_row<FIRA_KX_SPLIT>(mt, c * k, row);
+  const int rowblocks = (mt.L + FIRA_ROWS_PER_WG - 1) / FIRA_ROWS_PER_WG;
+  for (int rb = part; rb < rowblocks; rb += FIRA_MAKEZ_PARTS) {
+    const long long row_base = (long long)rb * FIRA_ROWS_PER_WG + wave * 4;
+    for (int i = 0; i < 4; ++i) {
+      const long long row = row_base + i;
+      if (row >= mt.L) break;
+      const float k = as_global<const float>(mt.phi)[row];
+      if (zready) fixz_row(mt, (1.0f - c) * k, row);
+      else if (mt.kx == 1) makez_row<1>(mt, c * k, row);
+      else makez_row<FIRA_KX_SPLIT>(mt, c * k, row);
+    }
   }
 }
 

@@ -106,6 +106,11 @@ WORKLOADS = {
         "llama1b_r512_bf16", 4, 24, _llama_block(2048, 5461), 512, "bf16", "gauss", 1e-3, 10),
     "llama7b_r1024_bf16": Workload(
         "llama7b_r1024_bf16", 5, 32, _llama_block(4096, 11008), 1024, "bf16", "gauss", 1e-3, 3),
+    # Fine-tuning shape set (Appendix "Detailed Fine-Tuning Setting": rank 32 on Q, K, V, Up, Down of a
+    # 4096-wide model): a very skinny R, the step is almost pure streaming of G and W.
+    "llama7b_finetune_r32_bf16": Workload(
+        "llama7b_finetune_r32_bf16", 6, 32, ((4096, 4096), (4096, 4096), (4096, 4096), (4096, 11008), (11008, 4096)),
+        32, "bf16", "gauss", 1e-3, 3),
 }
 HEADLINE = "llama1b_r512_bf16"
 

@@ -283,6 +283,17 @@ def test_config5_llama7b_block_sample():
     check(res, fira.FIRA_BF16, stages=False)
 
 
+def test_finetune_shapes_block_sample():
+    """One block of the fine-tuning shape set (r = 32 on 4096-wide Q, K, V, Up, Down; bf16), 3 steps;
+    the oracle follows one square matrix and both rectangular ones."""
+    wl = synth.WORKLOADS["llama7b_finetune_r32_bf16"]
+    gw, gg, gp = H.workload_generators(wl, "random")
+    shapes = wl.shapes[:5]
+    res = H.run_case(shapes, wl.rank, fira.FIRA_BF16, wl.steps, gw, gg, gp, orc.OracleHparams(alpha=0.25),
+                     check=[0, 3, 4], stages=False, norm_mode=fira.FIRA_NORM_GRAM)
+    check(res, fira.FIRA_BF16, stages=False)
+
+
 # ------------------------------------------------------------------------------------------
 # boundary behaviour
 # ------------------------------------------------------------------------------------------
