@@ -145,6 +145,28 @@ FIRA_API fira_status fira_get_factors(fira_ctx* ctx, int idx, float* host_k);
  * paper's orientation (r x n row-major for m <= n, m x r for m > n).  Synchronises the stream. */
 FIRA_API fira_status fira_get_lowrank(fira_ctx* ctx, int idx, float* host_R);
 
+/* Copy the projector of matrix idx as the kernels use it (rounded to bf16 for bf16 matrices, to the
+ * three-way bf16 split for fp32 ones) to host memory: min(m,n) x r fp32, row-major.  Synchronises
+ * the stream.  FIRA_ERR_NO_PROJECTOR if none was installed. */
+FIRA_API fira_status fira_get_projector(fira_ctx* ctx, int idx, float* host_P);
+
+/* Projector refresh on the device (Sec. 3.3, Eq. 7; Algorithm 1's "if t mod T = 0" branch): for every
+ * listed matrix, replaces P by an orthonormal basis of an approximation to the span of the leading r
+ * left singular vectors of its gradient (right singular vectors when m > n) and installs it exactly
+ * as fira_set_projector would (M, V, t and the remembered norm are kept).  The basis comes from
+ * `iters` >= 1 rounds of subspace iteration, Q <- orth(G G^T Q) (or G^T G for m > n), from a random
+ * start that is a function of (seed, matrix index) only; it is a rotation of the singular vectors
+ * inside that subspace, not the vectors themselves.  bf16 matrices only (FIRA_ERR_DTYPE otherwise).
+ *   dev_G[e]       gradient of matrix idx[e], same layout as in fira_step; read only
+ *   dev_workspace  device scratch of fira_refresh_workspace_bytes(ctx, count, idx) bytes, 256-byte
+ *                  aligned, owned by the caller, free to reuse once the stream has passed this call
+ * Enqueues on the context's stream and returns; the small work lists are uploaded with blocking
+ * copies, so the call is not meant for the step's inner loop.  Uses the listed matrices' step
+ * scratch (not their state). */
+FIRA_API size_t fira_refresh_workspace_bytes(const fira_ctx* ctx, int count, const int* idx);
+FIRA_API fira_status fira_refresh_projectors(fira_ctx* ctx, int count, const int* idx, const void* const* dev_G,
+                                             int iters, uint64_t seed, void* dev_workspace, size_t workspace_bytes);
+
 /* Per-kernel timing of the step's launch sequence with HIP events on the context's stream.
  * fira_profile_begin creates the events for up to max_steps steps (the only allocation; it happens
  * here, not in fira_step); every following fira_step records one event before its first kernel

@@ -179,3 +179,32 @@ def run(W0, grads, P_for_step, hp: OracleHparams, r: int, *, scaling: str = "col
         W = out["W"]
         trace.append(out)
     return W, st, trace
+
+
+# --------------------------------------------------------------------------------------------------
+# Projector refresh (Sec. 3.3, Eq. 7; the "if t mod T = 0" branch of Algorithm 1)
+# --------------------------------------------------------------------------------------------------
+
+def top_r_projector(G: np.ndarray, r: int) -> np.ndarray:
+    """Eq. 7: the first r left singular vectors of G (m <= n), or the first r right singular vectors
+    (m > n, footnote of Sec. 3.3), from LAPACK's SVD.  Returns min(m, n) x r."""
+    G = np.asarray(G, dtype=np.float64)
+    U, _, Vt = np.linalg.svd(G, full_matrices=False)
+    return U[:, :r] if G.shape[0] <= G.shape[1] else Vt[:r, :].T
+
+
+def subspace_sines(P: np.ndarray, Q: np.ndarray) -> np.ndarray:
+    """Sines of the principal angles between span(P) and span(Q) (both S x r, any bases): the
+    singular values of (I - Pq Pq^T) Qq with orthonormalised Pq, Qq.  All zero iff the spans agree."""
+    Pq, _ = np.linalg.qr(np.asarray(P, dtype=np.float64))
+    Qq, _ = np.linalg.qr(np.asarray(Q, dtype=np.float64))
+    return np.linalg.svd(Qq - Pq @ (Pq.T @ Qq), compute_uv=False)
+
+
+def captured_energy(G: np.ndarray, P: np.ndarray) -> float:
+    """||R||_F^2 / ||G||_F^2 for R = P^T G (or G P when m > n), with P orthonormalised first: the share
+    of the gradient that the projection keeps.  Maximal, over all r-dimensional P, for Eq. 7's choice."""
+    G = np.asarray(G, dtype=np.float64)
+    Pq, _ = np.linalg.qr(np.asarray(P, dtype=np.float64))
+    R = Pq.T @ G if G.shape[0] <= G.shape[1] else G @ Pq
+    return float(np.sum(R * R) / np.sum(G * G))

@@ -14,6 +14,7 @@
 
 #include "fira_device.h"
 #include "fira_elementwise.h"
+#include "fira_refresh.h"
 #include "fira_gemm.h"
 
 namespace {
@@ -634,6 +635,216 @@ fira_status fira_get_lowrank(fira_ctx* ctx, int idx, float* host_R) {
     FIRA_HIP(ctx, hipMemcpy(tmp.data(), m.Rt, Lr * 4, hipMemcpyDeviceToHost));
     for (int i = 0; i < m.L; ++i)
       for (int a = 0; a < m.r; ++a) host_R[(size_t)a * m.L + i] = tmp[(size_t)i * m.r + a];
+  }
+  return FIRA_OK;
+}
+
+fira_status fira_get_projector(fira_ctx* ctx, int idx, float* host_P) {
+  if (!ctx) return fail(nullptr, FIRA_ERR_INVALID_ARG, "ctx is null");
+  if (idx < 0 || idx >= (int)ctx->plan.mats.size()) return fail(ctx, FIRA_ERR_INVALID_ARG, "matrix index out of range");
+  if (!host_P) return fail(ctx, FIRA_ERR_INVALID_ARG, "host_P is null");
+  const HostMat& h = ctx->plan.mats[idx];
+  if (!h.has_projector) return fail(ctx, FIRA_ERR_NO_PROJECTOR, "fira_set_projector was never called for this matrix");
+  const FiraMat& m = h.dev;
+  const size_t n = (size_t)m.Sq * m.kx * m.rp;
+  std::vector<uint16_t> tmp(n);
+  FIRA_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  FIRA_HIP(ctx, hipMemcpy(tmp.data(), m.Pn, n * 2, hipMemcpyDeviceToHost));
+  auto bf = [](uint16_t b) { uint32_t u = (uint32_t)b << 16; float f; std::memcpy(&f, &u, 4); return f; };
+  for (int s = 0; s < m.S; ++s)
+    for (int a = 0; a < m.r; ++a) {
+      if (m.kx == 1) {
+        host_P[(size_t)s * m.r + a] = bf(tmp[(size_t)kblk_index(m.Sq, s, a)]);
+      } else {   // planes of sequence B: h m h l h m
+        host_P[(size_t)s * m.r + a] = (bf(tmp[(size_t)kblk_index(m.Sq, s, a)]) + bf(tmp[(size_t)kblk_index(m.Sq, s, m.rp + a)])) +
+                                      bf(tmp[(size_t)kblk_index(m.Sq, s, 3 * m.rp + a)]);
+      }
+    }
+  return FIRA_OK;
+}
+
+namespace {
+
+struct RefreshPlan {
+  size_t total = 0;
+  size_t off_ents = 0, off_ents2 = 0, off_vmats = 0, off_vents = 0, off_vtiles[2] = {0, 0};
+  int ntiles[2] = {0, 0};                 // virtual launches: [0] K-contiguous (real left), [1] K-slow (real right)
+  std::vector<size_t> off_top, off_y, off_q, off_c, off_linv;
+  size_t top_begin = 0, top_end = 0;
+};
+
+bool make_refresh_plan(const fira_ctx* ctx, int count, const int* idx, RefreshPlan* rp) {
+  const int nmat = (int)ctx->plan.mats.size();
+  if (count < 1 || count > nmat || !idx) return false;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+  rp->off_ents = take(sizeof(FiraRefreshEnt) * count);
+  rp->off_ents2 = take(sizeof(FiraRefreshEnt) * count);
+  rp->off_vmats = take(sizeof(FiraMat) * count);
+  rp->off_vents = take(sizeof(FiraEnt) * count);
+  rp->ntiles[0] = rp->ntiles[1] = 0;
+  for (int e = 0; e < count; ++e) {
+    if (idx[e] < 0 || idx[e] >= nmat) return false;
+    const FiraMat& m = ctx->plan.mats[idx[e]].dev;
+    rp->ntiles[m.left ? 0 : 1] += ((m.S + FIRA_PA - 1) / FIRA_PA) * ((m.r + FIRA_PB - 1) / FIRA_PB);
+  }
+  rp->off_vtiles[0] = take(sizeof(FiraTile) * std::max(rp->ntiles[0], 1));
+  rp->off_vtiles[1] = take(sizeof(FiraTile) * std::max(rp->ntiles[1], 1));
+  rp->off_top.resize(count); rp->off_y.resize(count); rp->off_q.resize(count); rp->off_c.resize(count); rp->off_linv.resize(count);
+  rp->top_begin = off;
+  for (int e = 0; e < count; ++e) {
+    const FiraMat& m = ctx->plan.mats[idx[e]].dev;
+    rp->off_top[e] = take((size_t)round_up_int(m.L, 64) * m.rq * 2);
+  }
+  rp->top_end = off;
+  for (int e = 0; e < count; ++e) {
+    const FiraMat& m = ctx->plan.mats[idx[e]].dev;
+    rp->off_y[e] = take((size_t)m.S * m.r * 4);
+    rp->off_q[e] = take((size_t)m.S * m.r * 4);
+    rp->off_c[e] = take((size_t)m.r * m.r * 8);
+    rp->off_linv[e] = take((size_t)m.r * m.r * 8);
+  }
+  rp->total = off;
+  return true;
+}
+
+}  // namespace
+
+size_t fira_refresh_workspace_bytes(const fira_ctx* ctx, int count, const int* idx) {
+  RefreshPlan rp;
+  if (!ctx || !make_refresh_plan(ctx, count, idx, &rp)) return 0;
+  return rp.total;
+}
+
+fira_status fira_refresh_projectors(fira_ctx* ctx, int count, const int* idx, const void* const* dev_G,
+                                    int iters, uint64_t seed, void* dev_workspace, size_t workspace_bytes) {
+  if (!ctx) return fail(nullptr, FIRA_ERR_INVALID_ARG, "ctx is null");
+  if (count == 0) return FIRA_OK;
+  const int nmat = (int)ctx->plan.mats.size();
+  if (count < 0 || count > nmat || !idx || !dev_G) return fail(ctx, FIRA_ERR_INVALID_ARG, "bad count or null array");
+  if (iters < 1 || iters > 64) return fail(ctx, FIRA_ERR_INVALID_ARG, "iters must be in [1, 64]");
+  {
+    std::vector<char> seen(nmat, 0);
+    for (int e = 0; e < count; ++e) {
+      if (idx[e] < 0 || idx[e] >= nmat) return fail(ctx, FIRA_ERR_INVALID_ARG, "matrix index out of range");
+      if (seen[idx[e]]) return fail(ctx, FIRA_ERR_INVALID_ARG, "a matrix is listed twice");
+      seen[idx[e]] = 1;
+      if (!dev_G[e]) return fail(ctx, FIRA_ERR_INVALID_ARG, "null G pointer");
+      if (ctx->plan.mats[idx[e]].dev.kx != 1) return fail(ctx, FIRA_ERR_DTYPE, "the device refresh handles bf16 matrices only");
+    }
+  }
+  RefreshPlan rp;
+  if (!make_refresh_plan(ctx, count, idx, &rp)) return fail(ctx, FIRA_ERR_INVALID_ARG, "bad list");
+  if (!dev_workspace || ((uintptr_t)dev_workspace % kAlign) != 0 || workspace_bytes < rp.total)
+    return fail(ctx, FIRA_ERR_WORKSPACE, "dev_workspace must be 256-byte aligned and hold fira_refresh_workspace_bytes() bytes");
+  char* ws = (char*)dev_workspace;
+  hipStream_t q = ctx->stream;
+
+  // host images of the small tables
+  std::vector<FiraRefreshEnt> ents(count), ents2(count);
+  std::vector<FiraMat> vmats(count);
+  std::vector<FiraEnt> vents(count);
+  std::vector<FiraTile> vtiles[2];
+  int max_S = 0, max_r = 0, max_Lp = 0;
+  for (int e = 0; e < count; ++e) {
+    const FiraMat& m = ctx->plan.mats[idx[e]].dev;
+    FiraRefreshEnt& re = ents[e];
+    std::memset(&re, 0, sizeof(re));
+    re.S = m.S; re.L = m.L; re.r = m.r; re.left = m.left; re.Lp = round_up_int(m.L, 64); re.rq = m.rq; re.mat = idx[e];
+    re.T = m.Rt;
+    re.Top = (bf16_raw*)(ws + rp.off_top[e]);
+    re.Y = (float*)(ws + rp.off_y[e]);
+    re.Q = (float*)(ws + rp.off_q[e]);
+    re.C = (double*)(ws + rp.off_c[e]);
+    re.Linv = (double*)(ws + rp.off_linv[e]);
+    ents2[e] = re;                       // second orthonormalisation pass of the last round: Q -> Y
+    std::swap(ents2[e].Y, ents2[e].Q);
+    max_S = std::max(max_S, m.S); max_r = std::max(max_r, m.r); max_Lp = std::max(max_Lp, re.Lp);
+    // The way back, Y[s][a] = sum_i G(s, i) T[i][a], is the projection kernel on the other orientation
+    // of the same gradient: long side L' = S, contraction over S' = L, operand "PT" = Top, output "Rt" = Y.
+    FiraMat& v = vmats[e];
+    std::memset(&v, 0, sizeof(v));
+    v.m = m.m; v.n = m.n; v.r = m.r; v.left = !m.left; v.ld = m.ld;
+    v.L = m.S; v.S = m.L; v.rp = m.rp; v.Sp = re.Lp; v.kx = 1; v.dtype = m.dtype;
+    v.Lq = round_up_int(m.S, 256); v.Sq = round_up_int(m.L, 256); v.rq = m.rq;
+    v.PT = re.Top; v.Rt = re.Y;
+    FiraEnt& ve = vents[e];
+    std::memset(&ve, 0, sizeof(ve));
+    ve.mat = e; ve.W = nullptr; ve.G = dev_G[e];
+    const int ta_n = (m.S + FIRA_PA - 1) / FIRA_PA, tb_n = (m.r + FIRA_PB - 1) / FIRA_PB;
+    for (int ta = 0; ta < ta_n; ++ta)
+      for (int tb = 0; tb < tb_n; ++tb) vtiles[m.left ? 0 : 1].push_back(FiraTile{e, ta, tb, 0});
+  }
+  FIRA_HIP(ctx, hipMemcpyAsync(ws + rp.off_ents, ents.data(), sizeof(FiraRefreshEnt) * count, hipMemcpyHostToDevice, q));
+  FIRA_HIP(ctx, hipMemcpyAsync(ws + rp.off_ents2, ents2.data(), sizeof(FiraRefreshEnt) * count, hipMemcpyHostToDevice, q));
+  FIRA_HIP(ctx, hipMemcpyAsync(ws + rp.off_vmats, vmats.data(), sizeof(FiraMat) * count, hipMemcpyHostToDevice, q));
+  FIRA_HIP(ctx, hipMemcpyAsync(ws + rp.off_vents, vents.data(), sizeof(FiraEnt) * count, hipMemcpyHostToDevice, q));
+  for (int l = 0; l < 2; ++l)
+    if (!vtiles[l].empty())
+      FIRA_HIP(ctx, hipMemcpyAsync(ws + rp.off_vtiles[l], vtiles[l].data(), sizeof(FiraTile) * vtiles[l].size(), hipMemcpyHostToDevice, q));
+  // the host vectors go away when this function returns: the copies above must have been made
+  FIRA_HIP(ctx, hipStreamSynchronize(q));
+  FIRA_HIP(ctx, hipMemsetAsync(ws + rp.top_begin, 0, rp.top_end - rp.top_begin, q));   // padding rows of the packed operand
+
+  const FiraRefreshEnt* d_ents = (const FiraRefreshEnt*)(ws + rp.off_ents);
+  const FiraRefreshEnt* d_ents2 = (const FiraRefreshEnt*)(ws + rp.off_ents2);
+  const FiraMat* d_vmats = (const FiraMat*)(ws + rp.off_vmats);
+  const FiraEnt* d_vents = (const FiraEnt*)(ws + rp.off_vents);
+  auto grid8 = [](int n) { return dim3((unsigned)(((n + 7) / 8) * 8)); };
+
+  // the forward product uses the step's own work-list machinery (W is not touched by the projection)
+  std::vector<void*> fakeW(count);
+  for (int e = 0; e < count; ++e) fakeW[e] = const_cast<void*>(dev_G[e]);
+  fira_status st;
+  ListSlot* s = acquire_list(ctx, count, idx, fakeW.data(), dev_G, &st);
+  if (!s) return fail(ctx, st, "building the work list failed");
+
+  {
+    const long long mx = (long long)max_S * max_r;
+    hipLaunchKernelGGL(fira_refresh_init_kernel, dim3((unsigned)std::min<long long>((mx + 255) / 256, 4096), count), dim3(256), 0, q,
+                       d_ents, (unsigned long long)seed);
+  }
+  const int nt64 = (max_r + 63) / 64;
+  auto orthonormalise = [&](const FiraRefreshEnt* de) {
+    hipLaunchKernelGGL(fira_refresh_gram_kernel, dim3(nt64 * (nt64 + 1) / 2, count), dim3(256), 0, q, de);
+    hipLaunchKernelGGL(fira_refresh_chol_kernel, dim3(count), dim3(FIRA_CHOL_THREADS), 0, q, de);
+    hipLaunchKernelGGL(fira_refresh_trinv_kernel, dim3((max_r + 255) / 256, count), dim3(256), 0, q, de);
+    hipLaunchKernelGGL(fira_refresh_apply_kernel, dim3(((max_S + 63) / 64) * nt64, count), dim3(256), 0, q, de);
+  };
+  for (int it = 0; it < iters; ++it) {
+    // operands of Q (the fp32 Q becomes the matrix's projector copies; no gate estimate needed here)
+    for (int e = 0; e < count; ++e) {
+      const HostMat& h = ctx->plan.mats[idx[e]];
+      const long long total = (long long)h.dev.S * h.dev.r;
+      const int grid = (int)std::min<long long>((total + 255) / 256, 65535);
+      hipLaunchKernelGGL(fira_prep_projector_kernel<float>, dim3(grid), dim3(256), 0, q, h.dev, (const float*)ents[e].Q);
+    }
+    // T = G^T Q (or G Q): the projection kernel, norm route off
+    if (s->ntiles[kTilesProjectLeft])
+      hipLaunchKernelGGL(fira_project_kernel<true>, grid8(s->ntiles[kTilesProjectLeft]), dim3(FIRA_PROJ_THREADS), FIRA_PROJ_LDS, q,
+                         ctx->d_mats, s->d_ents, s->d_tiles[kTilesProjectLeft], s->ntiles[kTilesProjectLeft], 0);
+    if (s->ntiles[kTilesProjectRight])
+      hipLaunchKernelGGL(fira_project_kernel<false>, grid8(s->ntiles[kTilesProjectRight]), dim3(FIRA_PROJ_THREADS), FIRA_PROJ_LDS, q,
+                         ctx->d_mats, s->d_ents, s->d_tiles[kTilesProjectRight], s->ntiles[kTilesProjectRight], 0);
+    // pack T as the K-blocked operand of the way back
+    hipLaunchKernelGGL(fira_refresh_pack_kernel, dim3((max_Lp / 32) * nt64, count), dim3(256), 0, q, d_ents);
+    // Y = G T (or G^T T): the projection kernel on the other orientation
+    if (rp.ntiles[0])
+      hipLaunchKernelGGL(fira_project_kernel<false>, grid8(rp.ntiles[0]), dim3(FIRA_PROJ_THREADS), FIRA_PROJ_LDS, q,
+                         d_vmats, d_vents, (const FiraTile*)(ws + rp.off_vtiles[0]), rp.ntiles[0], 0);
+    if (rp.ntiles[1])
+      hipLaunchKernelGGL(fira_project_kernel<true>, grid8(rp.ntiles[1]), dim3(FIRA_PROJ_THREADS), FIRA_PROJ_LDS, q,
+                         d_vmats, d_vents, (const FiraTile*)(ws + rp.off_vtiles[1]), rp.ntiles[1], 0);
+    // Q = orth(Y): CholeskyQR in fp64
+    orthonormalise(d_ents);
+  }
+  // A second pass over the final basis (CholeskyQR2) brings ||Q^T Q - I|| down to rounding level even
+  // when Y was ill conditioned; its result lands in the Y buffers.
+  orthonormalise(d_ents2);
+  FIRA_HIP(ctx, hipGetLastError());
+  for (int e = 0; e < count; ++e) {
+    const fira_status ps = fira_set_projector(ctx, idx[e], ents2[e].Q, FIRA_F32);
+    if (ps != FIRA_OK) return ps;
   }
   return FIRA_OK;
 }

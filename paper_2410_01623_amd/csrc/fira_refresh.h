@@ -1,0 +1,295 @@
+// Projector refresh on the device (Sec. 3.3, Eq. 7 and the "if t mod T = 0" branch of Algorithm 1: every
+// T steps P is replaced by the leading r singular vectors of the current gradient, on the short side).
+// The paper calls an SVD; only the subspace spanned by the leading vectors enters the step (the step is
+// invariant to a rotation of P inside that subspace up to the Adam state's coordinates, which the paper
+// resets to nothing: M and V carry over), so the basis is computed by subspace iteration:
+//
+//     Q <- orth( G G^T Q )   (m <= n),        Q <- orth( G^T G Q )   (m > n),
+//
+// a fixed number of times from a seeded random start.  The two big products are the projection
+// kernel itself: T = (G applied along the short side) is exactly R for the projector Q, and the way
+// back is the same kernel run on the other orientation of G with T packed as its K-blocked operand.
+// The small dense algebra of the orthonormalisation (CholeskyQR: C = Y^T Y, C = L L^T, Q = Y L^-T) is
+// done in fp64 so that it survives gradients with a steep spectrum; the kernels below are plain
+// (no MFMA): r^2 S flops per matrix, every listed matrix in one grouped launch.
+#pragma once
+#include "fira_device.h"
+
+struct FiraRefreshEnt {
+  int S, L, r, left;   // short side, long side, rank, orientation of the real matrix
+  int Lp;              // L rounded up to 64: contraction length of the packed operand
+  int rq;              // r rounded up to 256: rows of the packed operand
+  int mat, pad0;
+  const float* T;      // [L][r]            the matrix's Rt
+  bf16_raw* Top;       // [Lp/32][rq][32]   T transposed, K-blocked along the long side
+  float* Y;            // [S][r]
+  float* Q;            // [S][r]
+  double* C;           // [r][r]            Gram matrix, then its Cholesky factor (lower triangle)
+  double* Linv;        // [r][r]            inverse of the factor (lower triangle)
+};
+
+// splitmix64 finaliser: one independent 64-bit value per counter
+__device__ __forceinline__ unsigned long long refresh_mix64(unsigned long long z) {
+  z += 0x9e3779b97f4a7c15ull;
+  z = (z ^ (z >> 30)) * 0xbf58476d1ce4e5b9ull;
+  z = (z ^ (z >> 27)) * 0x94d049bb133111ebull;
+  return z ^ (z >> 31);
+}
+
+// Q0: uniform(-1, 1) entries, a function of (seed, matrix, element) only.
+__global__ __launch_bounds__(256) void fira_refresh_init_kernel(const FiraRefreshEnt* __restrict__ ents, unsigned long long seed) {
+  const FiraRefreshEnt e = ents[blockIdx.y];
+  const long long total = (long long)e.S * e.r;
+  gptr<float> Q = as_global(e.Q);
+  const unsigned long long key = refresh_mix64(seed ^ ((unsigned long long)(unsigned)e.mat << 32));
+  for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long long)gridDim.x * 256) {
+    const unsigned long long h = refresh_mix64(key + (unsigned long long)i);
+    Q[i] = (float)((double)(h >> 11) * (2.0 / 9007199254740992.0) - 1.0);
+  }
+}
+
+// Top[a][i] = bf16(T[i][a]) in the K-blocked layout; k >= L is zero.  (Rows a >= r stay zero from the
+// workspace clear.)  One workgroup per 32 (i) x 64 (a) tile.
+__global__ __launch_bounds__(256) void fira_refresh_pack_kernel(const FiraRefreshEnt* __restrict__ ents) {
+  __shared__ float tile[32][65];
+  const FiraRefreshEnt e = ents[blockIdx.y];
+  const int atiles = (e.r + 63) / 64;
+  const int ib = blockIdx.x / atiles, ab = blockIdx.x % atiles;
+  if (ib * 32 >= e.Lp) return;
+  gptr<const float> T = as_global<const float>(e.T);
+  const int t = threadIdx.x;
+#pragma unroll
+  for (int p = 0; p < 8; ++p) {
+    const int il = (t >> 6) + 4 * p, al = t & 63;
+    const int i = ib * 32 + il, a = ab * 64 + al;
+    tile[il][al] = (i < e.L && a < e.r) ? T[(long long)i * e.r + a] : 0.0f;
+  }
+  __syncthreads();
+  const int al = t >> 2, i8 = (t & 3) * 8;
+  const int a = ab * 64 + al;
+  if (a < e.r) {
+    unsigned w[4];
+#pragma unroll
+    for (int d = 0; d < 4; ++d) w[d] = pack_bf16x2(tile[i8 + 2 * d][al], tile[i8 + 2 * d + 1][al]);
+    gptr<bf16_raw> Top = as_global(e.Top);
+    *reinterpret_cast<gptr<u32x4>>(Top + kblk_index(e.rq, a, ib * 32 + i8)) = u32x4{w[0], w[1], w[2], w[3]};
+  }
+}
+
+// 64 x 64 tile of a product accumulated in fp64, 256 threads, 4 x 4 outputs per thread.
+// A[k][i] and B[k][j] come from row-major arrays with leading dimension r (k is the slow index).
+struct RefreshAcc { double v[4][4]; };
+
+// C = Y^T Y (lower triangle tiles only), fp64.
+__global__ __launch_bounds__(256) void fira_refresh_gram_kernel(const FiraRefreshEnt* __restrict__ ents) {
+  __shared__ float sa[16][64], sb[16][64];
+  const FiraRefreshEnt e = ents[blockIdx.y];
+  const int nt = (e.r + 63) / 64;
+  // linear index -> (ta >= tb)
+  int ta = 0, rem = blockIdx.x;
+  while (ta < nt && rem > ta) { rem -= ta + 1; ++ta; }
+  if (ta >= nt) return;
+  const int tb = rem;
+  gptr<const float> Y = as_global<const float>(e.Y);
+  const int t = threadIdx.x, tx = t & 15, ty = t >> 4;
+  RefreshAcc acc;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc.v[i][j] = 0.0;
+  for (int s0 = 0; s0 < e.S; s0 += 16) {
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      const int sl = (t >> 6) + 4 * p, c = t & 63;
+      const int s = s0 + sl;
+      const int ca = ta * 64 + c, cb = tb * 64 + c;
+      sa[sl][c] = (s < e.S && ca < e.r) ? Y[(long long)s * e.r + ca] : 0.0f;
+      sb[sl][c] = (s < e.S && cb < e.r) ? Y[(long long)s * e.r + cb] : 0.0f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int sl = 0; sl < 16; ++sl) {
+      double a[4], b[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { a[i] = (double)sa[sl][4 * ty + i]; b[i] = (double)sb[sl][4 * tx + i]; }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc.v[i][j] += a[i] * b[j];
+    }
+    __syncthreads();
+  }
+  gptr<double> C = as_global(e.C);
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int ra = ta * 64 + 4 * ty + i, cb = tb * 64 + 4 * tx + j;
+      if (ra < e.r && cb < e.r && cb <= ra) C[(long long)ra * e.r + cb] = acc.v[i][j];
+    }
+}
+
+// In-place Cholesky factorisation of the lower triangle of C (fp64), one workgroup per matrix,
+// blocked by 32 columns: factor the diagonal block in LDS, solve the panel below it one row per
+// thread, update the trailing triangle from the panel.  A pivot that is not safely positive (Y
+// numerically rank deficient) is replaced by a small multiple of the largest diagonal entry, which
+// keeps the factor finite; the directions it affects carry no energy of G.
+#define FIRA_CHOL_THREADS 512
+#define FIRA_CHOL_NB 32
+__global__ __launch_bounds__(FIRA_CHOL_THREADS) void fira_refresh_chol_kernel(const FiraRefreshEnt* __restrict__ ents) {
+  __shared__ double D[FIRA_CHOL_NB][FIRA_CHOL_NB + 1];
+  __shared__ double dmax_s;
+  const FiraRefreshEnt e = ents[blockIdx.x];
+  const int r = e.r, t = threadIdx.x;
+  gptr<double> C = as_global(e.C);
+  if (t == 0) {
+    double mx = 0.0;
+    for (int i = 0; i < r; ++i) mx = fmax(mx, C[(long long)i * r + i]);
+    dmax_s = mx;
+  }
+  __syncthreads();
+  const double floor_piv = dmax_s * 1e-24 + 1e-300;
+  for (int jb = 0; jb < r; jb += FIRA_CHOL_NB) {
+    const int nb = min(FIRA_CHOL_NB, r - jb);
+    // (1) diagonal block -> LDS, factor with the first 32 threads (column by column)
+    for (int x = t; x < nb * nb; x += FIRA_CHOL_THREADS) {
+      const int i = x / nb, k = x % nb;
+      D[i][k] = (k <= i) ? C[(long long)(jb + i) * r + jb + k] : 0.0;
+    }
+    __syncthreads();
+    if (t < 64) {
+      for (int j = 0; j < nb; ++j) {
+        // every lane computes the same pivot from LDS
+        const double piv = sqrt(fmax(D[j][j], floor_piv));
+        const double inv = 1.0 / piv;
+        __builtin_amdgcn_wave_barrier();
+        if (t == j) D[j][j] = piv;
+        if (t > j && t < nb) D[t][j] *= inv;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        // trailing update inside the block: row t, columns j+1..t
+        if (t > j && t < nb) {
+          const double lt = D[t][j];
+          for (int k = j + 1; k <= t; ++k) D[t][k] -= lt * D[k][j];
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      }
+    }
+    __syncthreads();
+    for (int x = t; x < nb * nb; x += FIRA_CHOL_THREADS) {
+      const int i = x / nb, k = x % nb;
+      if (k <= i) C[(long long)(jb + i) * r + jb + k] = D[i][k];
+    }
+    // (2) panel: rows below the block, X D^T = C_panel  (forward substitution along the block's columns)
+    const int below = r - (jb + nb);
+    for (int i = t; i < below; i += FIRA_CHOL_THREADS) {
+      gptr<double> row = C + (long long)(jb + nb + i) * r + jb;
+      // the row's own earlier results are read back from memory (a thread sees its own stores)
+      for (int k = 0; k < nb; ++k) {
+        double sacc = row[k];
+        for (int p = 0; p < k; ++p) sacc -= row[p] * D[k][p];
+        row[k] = sacc / D[k][k];
+      }
+    }
+    __syncthreads();   // (HIP's barrier also waits for this wave's global stores)
+    // (3) trailing triangle: C[i][k] -= sum_p P[i][p] P[k][p],  jb+nb <= k <= i < r,  P = the panel
+    const int nt4 = (below + 3) / 4;
+    for (int x = t; x < nt4 * nt4; x += FIRA_CHOL_THREADS) {
+      const int bi = x / nt4, bk = x % nt4;
+      if (bk > bi) continue;
+      const int i0 = jb + nb + 4 * bi, k0 = jb + nb + 4 * bk;
+      double acc[4][4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int k = 0; k < 4; ++k) acc[i][k] = 0.0;
+      for (int p = 0; p < nb; ++p) {
+        double a[4], b[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          a[i] = (i0 + i < r) ? C[(long long)(i0 + i) * r + jb + p] : 0.0;
+          b[i] = (k0 + i < r) ? C[(long long)(k0 + i) * r + jb + p] : 0.0;
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int k = 0; k < 4; ++k) acc[i][k] += a[i] * b[k];
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+          if (i0 + i < r && k0 + k <= i0 + i) C[(long long)(i0 + i) * r + k0 + k] -= acc[i][k];
+    }
+    __syncthreads();
+  }
+}
+
+// Linv = L^-1 (lower triangular), one workgroup per matrix, one thread per column b (looping when
+// r exceeds the workgroup): x_b = 1 / L_bb,  x_i = -(sum_{p=b}^{i-1} L_ip x_p) / L_ii.
+__global__ __launch_bounds__(256) void fira_refresh_trinv_kernel(const FiraRefreshEnt* __restrict__ ents) {
+  const FiraRefreshEnt e = ents[blockIdx.y];
+  const int r = e.r;
+  const int b = blockIdx.x * 256 + threadIdx.x;
+  if (b >= r) return;
+  gptr<const double> Lm = as_global<const double>(e.C);
+  gptr<double> X = as_global(e.Linv);
+  for (int i = 0; i < b; ++i) X[(long long)i * r + b] = 0.0;
+  X[(long long)b * r + b] = 1.0 / Lm[(long long)b * r + b];
+  for (int i = b + 1; i < r; ++i) {
+    double s = 0.0;
+    for (int p = b; p < i; ++p) s += Lm[(long long)i * r + p] * X[(long long)p * r + b];
+    X[(long long)i * r + b] = -s / Lm[(long long)i * r + i];
+  }
+}
+
+// Q = Y Linv^T: Q[s][a] = sum_{b <= a} Y[s][b] Linv[a][b], fp64 accumulation, fp32 result.
+__global__ __launch_bounds__(256) void fira_refresh_apply_kernel(const FiraRefreshEnt* __restrict__ ents) {
+  __shared__ float sy[64][17];
+  __shared__ double sl[64][17];
+  const FiraRefreshEnt e = ents[blockIdx.y];
+  const int nta = (e.r + 63) / 64;
+  const int ts = blockIdx.x / nta, ta = blockIdx.x % nta;
+  if (ts * 64 >= e.S) return;
+  gptr<const float> Y = as_global<const float>(e.Y);
+  gptr<const double> X = as_global<const double>(e.Linv);
+  const int t = threadIdx.x, tx = t & 15, ty = t >> 4;
+  double acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[i][j] = 0.0;
+  const int bend = min(e.r, ta * 64 + 64);      // Linv is lower triangular: b <= a
+  for (int b0 = 0; b0 < bend; b0 += 16) {
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      const int row = (t >> 4) + 16 * p, c = t & 15;
+      const int s = ts * 64 + row, a = ta * 64 + row, b = b0 + c;
+      sy[row][c] = (s < e.S && b < e.r) ? Y[(long long)s * e.r + b] : 0.0f;
+      sl[row][c] = (a < e.r && b <= a) ? X[(long long)a * e.r + b] : 0.0;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int c = 0; c < 16; ++c) {
+      double yv[4], lv[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { yv[i] = (double)sy[4 * ty + i][c]; lv[i] = sl[4 * tx + i][c]; }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] += yv[i] * lv[j];
+    }
+    __syncthreads();
+  }
+  gptr<float> Q = as_global(e.Q);
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int s = ts * 64 + 4 * ty + i, a = ta * 64 + 4 * tx + j;
+      if (s < e.S && a < e.r) Q[(long long)s * e.r + a] = (float)acc[i][j];
+    }
+}

@@ -31,7 +31,8 @@ FIRA_NUM_KERNELS = 6
 EXPORTS = (
     "fira_method_state_numel", "fira_state_bytes", "fira_init_state", "fira_set_projector", "fira_step",
     "fira_set_hparams", "fira_set_options", "fira_get_state", "fira_set_state", "fira_get_diag",
-    "fira_get_factors", "fira_get_lowrank", "fira_profile_begin", "fira_profile_end", "fira_kernel_name",
+    "fira_get_factors", "fira_get_lowrank", "fira_get_projector", "fira_refresh_workspace_bytes",
+    "fira_refresh_projectors", "fira_profile_begin", "fira_profile_end", "fira_kernel_name",
     "fira_last_error", "fira_destroy",
 )
 
@@ -92,6 +93,13 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.fira_get_factors.argtypes = [vp, ci, vp]
     lib.fira_get_lowrank.restype = ci
     lib.fira_get_lowrank.argtypes = [vp, ci, vp]
+    lib.fira_get_projector.restype = ci
+    lib.fira_get_projector.argtypes = [vp, ci, vp]
+    lib.fira_refresh_workspace_bytes.restype = ctypes.c_size_t
+    lib.fira_refresh_workspace_bytes.argtypes = [vp, ci, ctypes.POINTER(ci)]
+    lib.fira_refresh_projectors.restype = ci
+    lib.fira_refresh_projectors.argtypes = [vp, ci, ctypes.POINTER(ci), ctypes.POINTER(vp), ci, ctypes.c_uint64, vp,
+                                            ctypes.c_size_t]
     lib.fira_profile_begin.restype = ci
     lib.fira_profile_begin.argtypes = [vp, ci]
     lib.fira_profile_end.restype = ci
@@ -238,6 +246,38 @@ class FiraContext:
         R = torch.empty((r, n) if m <= n else (m, r), dtype=torch.float32)
         _check(self.lib, self.ctx, self.lib.fira_get_lowrank(self.ctx, idx, ctypes.c_void_p(R.data_ptr())))
         return R
+
+    def fira_get_projector(self, idx: int) -> torch.Tensor:
+        m, n = self.shapes[idx]
+        P = torch.empty((min(m, n), self.descs[idx].r), dtype=torch.float32)
+        _check(self.lib, self.ctx, self.lib.fira_get_projector(self.ctx, idx, ctypes.c_void_p(P.data_ptr())))
+        return P
+
+    def fira_refresh_workspace_bytes(self, idx: Sequence[int]) -> int:
+        arr = (ctypes.c_int * len(idx))(*idx)
+        return int(self.lib.fira_refresh_workspace_bytes(self.ctx, len(idx), arr))
+
+    def fira_refresh_projectors(self, idx: Sequence[int], G: Sequence[torch.Tensor], iters: int = 2, seed: int = 0,
+                                workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+        """Recomputes and installs the projectors of the listed matrices from their gradients on the
+        device.  Returns the workspace tensor (keep it until the stream has passed the call)."""
+        count = len(idx)
+        assert len(G) == count
+        need = self.fira_refresh_workspace_bytes(idx)
+        if workspace is None or workspace.numel() < need:
+            workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=self.slab.device)
+        assert workspace.data_ptr() % 256 == 0
+        for e, i in enumerate(idx):
+            m, n = self.shapes[i]
+            g = G[e]
+            d = self.descs[i]
+            assert g.device == self.slab.device and g.dtype == _TORCH_DTYPE[d.wg_dtype] and tuple(g.shape) == (m, n)
+            assert g.stride(1) == 1 and g.stride(0) == d.ld
+        ci = (ctypes.c_int * count)(*idx)
+        cg = (ctypes.c_void_p * count)(*[g.data_ptr() for g in G])
+        _check(self.lib, self.ctx, self.lib.fira_refresh_projectors(self.ctx, count, ci, cg, iters, seed,
+                                                                    ctypes.c_void_p(workspace.data_ptr()), need))
+        return workspace
 
     def fira_profile_begin(self, max_steps: int):
         _check(self.lib, self.ctx, self.lib.fira_profile_begin(self.ctx, max_steps))

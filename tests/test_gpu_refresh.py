@@ -1,0 +1,122 @@
+"""Projector refresh on the device (Sec. 3.3, Eq. 7; the "if t mod T = 0" branch of Algorithm 1) against
+the oracle's LAPACK SVD.  Singular vectors are not unique (signs, rotations inside clusters), and the
+library returns a basis of the subspace rather than the vectors, so the comparison is between subspaces:
+principal angles where the spectrum has a gap at r, and the share of the gradient's energy that the
+projector keeps (which Eq. 7's choice maximises) in every case."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import fira_oracle as orc
+from paper_2410_01623_amd import fira, synth
+
+import fira_harness as H
+
+pytestmark = pytest.mark.gpu
+
+
+def _gapped_gradient(rng, m, n, r, tail=0.05):
+    """G = U diag(s) V^T: r leading values in [1, 2], the rest `tail` times smaller (a gap at r)."""
+    S = min(m, n)
+    U, _ = np.linalg.qr(rng.standard_normal((m, S)))
+    V, _ = np.linalg.qr(rng.standard_normal((n, S)))
+    s = np.concatenate([np.linspace(2.0, 1.0, r), tail * np.linspace(1.0, 0.2, S - r)])
+    return synth.as_bf16_values(1e-2 * (U * s) @ V.T)
+
+
+@pytest.mark.parametrize("m,n,r", [(300, 517, 40), (517, 300, 40), (256, 256, 64), (1024, 2736, 128), (2736, 1024, 128)],
+                         ids=["300x517r40", "517x300r40", "256x256r64", "1024x2736r128", "2736x1024r128"])
+def test_refreshed_projector_spans_the_leading_singular_subspace(m, n, r):
+    rng = np.random.default_rng(1000 + m + n)
+    G = _gapped_gradient(rng, m, n, r)
+    ctx = fira.FiraContext([(m, n)], r, fira.FIRA_BF16, device=H.DEV)
+    Gd = H.to_device(G, fira.FIRA_BF16)
+    ws = ctx.fira_refresh_projectors([0], [Gd], iters=3, seed=7)
+    torch.cuda.synchronize()
+    P = ctx.fira_get_projector(0).numpy().astype(np.float64)
+    assert P.shape == (min(m, n), r) and np.all(np.isfinite(P))
+    # orthonormal to the bf16 rounding of its entries
+    assert np.max(np.abs(P.T @ P - np.eye(r))) < 2e-2
+    Pref = orc.top_r_projector(G, r)
+    sines = orc.subspace_sines(Pref, P)
+    e_ref, e_gpu = orc.captured_energy(G, Pref), orc.captured_energy(G, P)
+    print(f"max sine {sines.max():.3e}  energy kept: svd {e_ref:.6f} device {e_gpu:.6f}", flush=True)
+    # tail/head = 0.05: three rounds leave (0.05)^6 of the tail in the basis; bf16 entries of P add ~4e-3
+    assert sines.max() < 1e-2
+    assert e_gpu > e_ref - 1e-4
+    # the installed projector is the one the step uses: one step reproduces the oracle fed the same P
+    W0 = synth.as_bf16_values(0.02 * rng.standard_normal((m, n)))
+    Wd = H.to_device(W0, fira.FIRA_BF16)
+    ctx.fira_step([0], [Wd], [Gd])
+    st = orc.OracleState.zeros(m, n, r)
+    out = orc.fira_step(W0.astype(np.float64), G.astype(np.float64), P, st, orc.OracleHparams(), store_bf16=True)
+    assert H.rel_max(H.to_host(Wd), out["W"]) <= 2e-2
+    del ws
+
+
+def test_refresh_of_a_gradient_without_a_gap_keeps_nearly_the_optimal_energy():
+    """Gaussian gradient (the benchmark's recipe): the singular values crowd together and the leading
+    subspace is not determined, but the kept energy must approach the optimum of Eq. 7 (four rounds of
+    subspace iteration reach about 96 % of it when sigma_{r+1} / sigma_r is close to 1; a random
+    subspace keeps r / min(m, n) = 25 %)."""
+    m, n, r = 512, 1376, 128
+    rng = np.random.default_rng(5)
+    G = synth.as_bf16_values(1e-3 * rng.standard_normal((m, n)))
+    ctx = fira.FiraContext([(m, n), (n, m)], r, fira.FIRA_BF16, device=H.DEV)
+    Gd = [H.to_device(G, fira.FIRA_BF16), H.to_device(np.ascontiguousarray(G.T), fira.FIRA_BF16)]
+    ws = ctx.fira_refresh_projectors([0, 1], Gd, iters=4, seed=3)
+    torch.cuda.synchronize()
+    e_ref = orc.captured_energy(G, orc.top_r_projector(G, r))
+    for i, g in enumerate((G, G.T)):
+        P = ctx.fira_get_projector(i).numpy().astype(np.float64)
+        assert np.max(np.abs(P.T @ P - np.eye(r))) < 2e-2
+        e = orc.captured_energy(g, P)
+        print(f"matrix {i}: energy kept {e:.4f} (optimum {e_ref:.4f})", flush=True)
+        assert e > 0.95 * e_ref
+    del ws
+
+
+def test_refresh_survives_a_steep_spectrum():
+    """Singular values falling by eight decades across the short side: Y = G G^T Q then has a
+    condition number near 1e4 after one round, whose Gram matrix (1e8) an fp32 Cholesky would not
+    survive; the fp64 CholeskyQR must still return an orthonormal basis that keeps the optimal energy."""
+    m, n, r = 256, 700, 64
+    rng = np.random.default_rng(9)
+    U, _ = np.linalg.qr(rng.standard_normal((m, m)))
+    V, _ = np.linalg.qr(rng.standard_normal((n, m)))
+    s = 10.0 ** (-8.0 * np.arange(m) / m)
+    G = synth.as_bf16_values((U * s) @ V.T)
+    ctx = fira.FiraContext([(m, n)], r, fira.FIRA_BF16, device=H.DEV)
+    ws = ctx.fira_refresh_projectors([0], [H.to_device(G, fira.FIRA_BF16)], iters=3, seed=1)
+    torch.cuda.synchronize()
+    P = ctx.fira_get_projector(0).numpy().astype(np.float64)
+    assert np.all(np.isfinite(P))
+    assert np.max(np.abs(P.T @ P - np.eye(r))) < 2e-2
+    e_ref, e_gpu = orc.captured_energy(G, orc.top_r_projector(G, r)), orc.captured_energy(G, P)
+    print(f"energy kept: svd {e_ref:.8f} device {e_gpu:.8f}", flush=True)
+    assert e_gpu > e_ref - 1e-5
+    del ws
+
+
+def test_refresh_argument_errors():
+    ctx = fira.FiraContext([(96, 160), (64, 64)], 16, fira.FIRA_BF16, device=H.DEV)
+    g0 = torch.zeros((96, 160), dtype=torch.bfloat16, device=H.DEV)
+    need = ctx.fira_refresh_workspace_bytes([0])
+    assert need > 0
+    small = torch.empty(256, dtype=torch.uint8, device=H.DEV)
+    with pytest.raises(fira.FiraError) as ei:
+        ctx.lib.fira_refresh_projectors.restype  # keep the binding loaded
+        import ctypes
+        ci = (ctypes.c_int * 1)(0)
+        cg = (ctypes.c_void_p * 1)(g0.data_ptr())
+        fira._check(ctx.lib, ctx.ctx, ctx.lib.fira_refresh_projectors(ctx.ctx, 1, ci, cg, 2, 0,
+                                                                      ctypes.c_void_p(small.data_ptr()), 256))
+    assert ei.value.status == fira.FIRA_ERR_WORKSPACE
+    with pytest.raises(fira.FiraError) as ei:
+        ctx.fira_refresh_projectors([0], [g0], iters=0)
+    assert ei.value.status == fira.FIRA_ERR_INVALID_ARG
+    f32 = fira.FiraContext([(64, 96)], 8, fira.FIRA_F32, device=H.DEV)
+    gf = torch.zeros((64, 96), dtype=torch.float32, device=H.DEV)
+    with pytest.raises(fira.FiraError) as ei:
+        f32.fira_refresh_projectors([0], [gf], iters=1)
+    assert ei.value.status == fira.FIRA_ERR_DTYPE

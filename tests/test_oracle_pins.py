@@ -466,11 +466,50 @@ def pin_bf16_rounding(o):
     assert np.max(np.abs(out["W"] - out["W_unrounded"])) <= 2.0 ** -8 * np.max(np.abs(out["W"]))
 
 
+def pin_projector_refresh_helpers(o):
+    """Eq. 7 and the subspace measures used to judge a refreshed projector.
+    * a matrix of exact rank r: the projector spans its column (row) space and keeps all its energy;
+    * known singular vectors: G = U diag(s) V^T with a decreasing s gives back U[:, :r] (V[:, :r] for
+      m > n) up to sign, and the kept energy is sum(s[:r]^2) / sum(s^2) (Eckart-Young);
+    * principal angles: equal spans -> 0 whatever the bases; orthogonal spans -> 1; a plane rotated
+      by theta against another about a common axis -> (sin theta, 0)."""
+    rng = np.random.default_rng(31)
+    for (m, n) in ((9, 14), (14, 9)):
+        r = 3
+        S = min(m, n)
+        U = _orth(rng, m, S); V = _orth(rng, n, S)
+        s = np.array([5.0, 4.0, 3.0, 0.5, 0.4, 0.3, 0.2, 0.1, 0.05])[:S]
+        G = (U * s) @ V.T
+        P = o.top_r_projector(G, r)
+        assert P.shape == (S, r)
+        ref = U[:, :r] if m <= n else V[:, :r]
+        np.testing.assert_allclose(np.abs(ref.T @ P), np.eye(r), atol=1e-10)      # same vectors up to sign
+        assert np.max(o.subspace_sines(P, ref)) < 1e-10
+        np.testing.assert_allclose(o.captured_energy(G, P), np.sum(s[:r] ** 2) / np.sum(s ** 2), rtol=1e-12)
+        # any other r-dimensional subspace keeps less
+        other = _orth(rng, S, r)
+        assert o.captured_energy(G, other) < o.captured_energy(G, P)
+        # exact rank r: all the energy, and the span is the column/row space
+        G0 = (U[:, :r] * s[:r]) @ V[:, :r].T
+        P0 = o.top_r_projector(G0, r)
+        np.testing.assert_allclose(o.captured_energy(G0, P0), 1.0, rtol=1e-12)
+        assert np.max(o.subspace_sines(P0, ref)) < 1e-9
+    # principal angles
+    B = _orth(rng, 7, 7)
+    A1 = B[:, :2]
+    Rm = np.array([[2.0, 1.0], [-1.0, 3.0]])
+    assert np.max(o.subspace_sines(A1, A1 @ Rm)) < 1e-12                      # basis change
+    np.testing.assert_allclose(o.subspace_sines(A1, B[:, 2:4]), [1.0, 1.0], atol=1e-12)
+    th = 0.3
+    A2 = np.stack([B[:, 0], np.cos(th) * B[:, 1] + np.sin(th) * B[:, 2]], axis=1)
+    np.testing.assert_allclose(np.sort(o.subspace_sines(A1, A2)), [0.0, np.sin(th)], atol=1e-12)
+
+
 PINS = [pin_hand_case, pin_brute_force, pin_full_rank_identity_is_adam, pin_full_rank_rotation,
         pin_orthonormal_split, pin_limiter_bound, pin_first_step_and_constant_gradient,
         pin_scale_invariance, pin_permutation_equivariance, pin_norm_identity, pin_transpose,
         pin_gradient_in_subspace_and_switches, pin_degenerate_columns,
-        pin_projector_switch_keeps_state, pin_bf16_rounding]
+        pin_projector_switch_keeps_state, pin_bf16_rounding, pin_projector_refresh_helpers]
 
 
 @pytest.mark.parametrize("pin", PINS, ids=lambda p: p.__name__)
@@ -512,6 +551,13 @@ MUTANTS = [
     ("m > n handled as m <= n", "    if m <= n:\n        out = _step_short_rows", "    if True:\n        out = _step_short_rows"),
     ("bf16 rounding truncates", "np.rint(mant * 256.0)", "np.trunc(mant * 256.0)"),
     ("bf16 keeps 9 bits", "np.rint(mant * 256.0) / 256.0", "np.rint(mant * 512.0) / 512.0"),
+    ("refresh takes the trailing vectors", "return U[:, :r] if G.shape[0] <= G.shape[1] else Vt[:r, :].T",
+     "return U[:, -r:] if G.shape[0] <= G.shape[1] else Vt[-r:, :].T"),
+    ("refresh takes the wrong side", "return U[:, :r] if G.shape[0] <= G.shape[1] else Vt[:r, :].T",
+     "return U[:, :r] if G.shape[0] > G.shape[1] else Vt[:r, :].T"),
+    ("principal angles return cosines", "return np.linalg.svd(Qq - Pq @ (Pq.T @ Qq), compute_uv=False)",
+     "return np.linalg.svd(Pq.T @ Qq, compute_uv=False)"),
+    ("kept energy not normalised", "return float(np.sum(R * R) / np.sum(G * G))", "return float(np.sum(R * R))"),
 ]
 
 
