@@ -115,6 +115,9 @@ def main():
     ap.add_argument("--pad-ld", type=int, default=0,
                     help="round the leading dimension of W and G up to a multiple of this many elements "
                          "(0 = dense rows, ld = n: the headline configuration)")
+    ap.add_argument("--refresh-iters", type=int, default=0,
+                    help="also time fira_refresh_projectors over all matrices with this many rounds of subspace "
+                         "iteration (after the timed steps; reported under \"refresh\", not part of value)")
     ap.add_argument("--norm-mode", choices=["gram", "residual"], default="gram",
                     help="how the limiter norm ||S|| is obtained (both are parity-tested)")
     args = ap.parse_args()
@@ -204,6 +207,21 @@ def main():
                    "matrices_limited_last_step": limited},
         "roofline": roof, "kernels": kernels,
     }
+    if args.refresh_iters > 0:
+        # projector refresh (Algorithm 1's "if t mod T = 0" branch) over every matrix, from the first gradient set
+        idx_all = list(range(len(shapes)))
+        ws = torch.empty(ctx.fira_refresh_workspace_bytes(idx_all), dtype=torch.uint8, device=dev)
+        ctx.fira_refresh_projectors(idx_all, Gsets[0], iters=args.refresh_iters, seed=1, workspace=ws)   # warm-up
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        ctx.fira_refresh_projectors(idx_all, Gsets[0], iters=args.refresh_iters, seed=2, workspace=ws)
+        torch.cuda.synchronize()
+        rms = 1e3 * (time.perf_counter() - t1)
+        # the subspace iteration multiplies by G four times per round (two contractions of 2 mn r flops each way)
+        out["refresh"] = dict(ms=round(rms, 2), iters=args.refresh_iters, workspace_bytes=int(ws.numel()),
+                              ms_per_step_at_T200=round(rms / 200.0, 4),
+                              contraction_tflops=round(args.refresh_iters * 2 * 2.0 * sum(m * n for m, n in shapes) * wl.rank / (rms * 1e-3) / 1e12, 1))
+        del ws
     if not args.no_cpu_baseline:
         nb = len(wl.block_shapes)
         out["cpu_baseline"] = cpu_baseline(wl, list(range(nb)), steps=1)

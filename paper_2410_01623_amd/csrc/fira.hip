@@ -808,8 +808,7 @@ fira_status fira_refresh_projectors(fira_ctx* ctx, int count, const int* idx, co
   auto orthonormalise = [&](const FiraRefreshEnt* de) {
     hipLaunchKernelGGL(fira_refresh_gram_kernel, dim3(nt64 * (nt64 + 1) / 2, count), dim3(256), 0, q, de);
     hipLaunchKernelGGL(fira_refresh_chol_kernel, dim3(count), dim3(FIRA_CHOL_THREADS), 0, q, de);
-    hipLaunchKernelGGL(fira_refresh_trinv_kernel, dim3((max_r + 255) / 256, count), dim3(256), 0, q, de);
-    hipLaunchKernelGGL(fira_refresh_apply_kernel, dim3(((max_S + 63) / 64) * nt64, count), dim3(256), 0, q, de);
+    hipLaunchKernelGGL(fira_refresh_solve_kernel, dim3((max_S + 63) / 64, count), dim3(256), 0, q, de);
   };
   for (int it = 0; it < iters; ++it) {
     // operands of Q (the fp32 Q becomes the matrix's projector copies; no gate estimate needed here)

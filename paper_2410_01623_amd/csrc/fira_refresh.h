@@ -9,7 +9,7 @@
 // a fixed number of times from a seeded random start.  The two big products are the projection
 // kernel itself: T = (G applied along the short side) is exactly R for the projector Q, and the way
 // back is the same kernel run on the other orientation of G with T packed as its K-blocked operand.
-// The small dense algebra of the orthonormalisation (CholeskyQR: C = Y^T Y, C = L L^T, Q = Y L^-T) is
+// The small dense algebra of the orthonormalisation (CholeskyQR: C = Y^T Y, C = L L^T, Q = Y L^-T by forward substitution) is
 // done in fp64 so that it survives gradients with a steep spectrum; the kernels below are plain
 // (no MFMA): r^2 S flops per matrix, every listed matrix in one grouped launch.
 #pragma once
@@ -25,7 +25,7 @@ struct FiraRefreshEnt {
   float* Y;            // [S][r]
   float* Q;            // [S][r]
   double* C;           // [r][r]            Gram matrix, then its Cholesky factor (lower triangle)
-  double* Linv;        // [r][r]            inverse of the factor (lower triangle)
+  double* Linv;        // (unused; kept so that the layout of the workspace does not depend on the solver)
 };
 
 // splitmix64 finaliser: one independent 64-bit value per counter
@@ -228,68 +228,74 @@ __global__ __launch_bounds__(FIRA_CHOL_THREADS) void fira_refresh_chol_kernel(co
   }
 }
 
-// Linv = L^-1 (lower triangular), one workgroup per matrix, one thread per column b (looping when
-// r exceeds the workgroup): x_b = 1 / L_bb,  x_i = -(sum_{p=b}^{i-1} L_ip x_p) / L_ii.
-__global__ __launch_bounds__(256) void fira_refresh_trinv_kernel(const FiraRefreshEnt* __restrict__ ents) {
+// Q = Y L^-T, i.e. every row solves  q L^T = y  by forward substitution:
+//     q_a = (y_a - sum_{b < a} q_b L[a][b]) / L[a][a].
+// Rows are independent, so one workgroup takes 64 rows and walks over the columns in blocks of 16:
+// the contribution of the columns already solved is a 64 x 16 x (16 jb) product accumulated in fp64
+// (4 outputs per thread, operands staged through LDS), then 64 threads finish their row's 16 values
+// against the diagonal block.  Solved values are written as fp32 and read back from there.
+#define FIRA_SOLVE_NB 16
+__global__ __launch_bounds__(256) void fira_refresh_solve_kernel(const FiraRefreshEnt* __restrict__ ents) {
+  __shared__ float sq[64][FIRA_SOLVE_NB + 1];                   // Q[s][b0 .. b0+16)
+  __shared__ double slt[FIRA_SOLVE_NB][FIRA_SOLVE_NB + 1];      // L[jb + j][b0 + c]
+  __shared__ double sacc[64][FIRA_SOLVE_NB + 1];
   const FiraRefreshEnt e = ents[blockIdx.y];
+  const int s0 = blockIdx.x * 64;
+  if (s0 >= e.S) return;
   const int r = e.r;
-  const int b = blockIdx.x * 256 + threadIdx.x;
-  if (b >= r) return;
-  gptr<const double> Lm = as_global<const double>(e.C);
-  gptr<double> X = as_global(e.Linv);
-  for (int i = 0; i < b; ++i) X[(long long)i * r + b] = 0.0;
-  X[(long long)b * r + b] = 1.0 / Lm[(long long)b * r + b];
-  for (int i = b + 1; i < r; ++i) {
-    double s = 0.0;
-    for (int p = b; p < i; ++p) s += Lm[(long long)i * r + p] * X[(long long)p * r + b];
-    X[(long long)i * r + b] = -s / Lm[(long long)i * r + i];
-  }
-}
-
-// Q = Y Linv^T: Q[s][a] = sum_{b <= a} Y[s][b] Linv[a][b], fp64 accumulation, fp32 result.
-__global__ __launch_bounds__(256) void fira_refresh_apply_kernel(const FiraRefreshEnt* __restrict__ ents) {
-  __shared__ float sy[64][17];
-  __shared__ double sl[64][17];
-  const FiraRefreshEnt e = ents[blockIdx.y];
-  const int nta = (e.r + 63) / 64;
-  const int ts = blockIdx.x / nta, ta = blockIdx.x % nta;
-  if (ts * 64 >= e.S) return;
   gptr<const float> Y = as_global<const float>(e.Y);
-  gptr<const double> X = as_global<const double>(e.Linv);
-  const int t = threadIdx.x, tx = t & 15, ty = t >> 4;
-  double acc[4][4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j) acc[i][j] = 0.0;
-  const int bend = min(e.r, ta * 64 + 64);      // Linv is lower triangular: b <= a
-  for (int b0 = 0; b0 < bend; b0 += 16) {
-#pragma unroll
-    for (int p = 0; p < 4; ++p) {
-      const int row = (t >> 4) + 16 * p, c = t & 15;
-      const int s = ts * 64 + row, a = ta * 64 + row, b = b0 + c;
-      sy[row][c] = (s < e.S && b < e.r) ? Y[(long long)s * e.r + b] : 0.0f;
-      sl[row][c] = (a < e.r && b <= a) ? X[(long long)a * e.r + b] : 0.0;
-    }
-    __syncthreads();
-#pragma unroll
-    for (int c = 0; c < 16; ++c) {
-      double yv[4], lv[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) { yv[i] = (double)sy[4 * ty + i][c]; lv[i] = sl[4 * tx + i][c]; }
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] += yv[i] * lv[j];
-    }
-    __syncthreads();
-  }
+  gptr<const double> Lm = as_global<const double>(e.C);
   gptr<float> Q = as_global(e.Q);
+  const int t = threadIdx.x;
+  const int row = t >> 2, c4 = (t & 3) * 4;                     // this thread's 4 outputs of the 64 x 16 tile
+  for (int jb = 0; jb < r; jb += FIRA_SOLVE_NB) {
+    double acc[4] = {0.0, 0.0, 0.0, 0.0};
+    for (int b0 = 0; b0 < jb; b0 += FIRA_SOLVE_NB) {
+      // stage Q[s0 .. s0+64)[b0 .. b0+16) and L[jb .. jb+16)[b0 .. b0+16)
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+      for (int p = 0; p < 4; ++p) {
+        const int x = t + 256 * p, rr = x >> 4, cc = x & 15;
+        sq[rr][cc] = (s0 + rr < e.S) ? Q[(long long)(s0 + rr) * r + b0 + cc] : 0.0f;
+      }
+      {
+        const int j = t >> 4, cc = t & 15;
+        slt[j][cc] = (jb + j < r) ? Lm[(long long)(jb + j) * r + b0 + cc] : 0.0;
+      }
+      __syncthreads();
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int s = ts * 64 + 4 * ty + i, a = ta * 64 + 4 * tx + j;
-      if (s < e.S && a < e.r) Q[(long long)s * e.r + a] = (float)acc[i][j];
+      for (int cc = 0; cc < FIRA_SOLVE_NB; ++cc) {
+        const double qv = (double)sq[row][cc];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) acc[k] += qv * slt[c4 + k][cc];
+      }
+      __syncthreads();
     }
+    // right-hand side minus the solved part, and the diagonal block of L
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int a = jb + c4 + k;
+      const double y = (s0 + row < e.S && a < r) ? (double)Y[(long long)(s0 + row) * r + a] : 0.0;
+      sacc[row][c4 + k] = y - acc[k];
+    }
+    {
+      const int j = t >> 4, cc = t & 15;
+      slt[j][cc] = (jb + j < r && jb + cc < r && cc <= j) ? Lm[(long long)(jb + j) * r + jb + cc] : (cc == j ? 1.0 : 0.0);
+    }
+    __syncthreads();
+    if (t < 64 && s0 + t < e.S) {
+      double q[FIRA_SOLVE_NB];
+#pragma unroll
+      for (int k = 0; k < FIRA_SOLVE_NB; ++k) {
+        double v = sacc[t][k];
+#pragma unroll
+        for (int p = 0; p < FIRA_SOLVE_NB; ++p)
+          if (p < k) v -= q[p] * slt[k][p];
+        q[k] = v / slt[k][k];
+      }
+#pragma unroll
+      for (int k = 0; k < FIRA_SOLVE_NB; ++k)
+        if (jb + k < r) Q[(long long)(s0 + t) * r + jb + k] = (float)q[k];
+    }
+    __syncthreads();   // the block's Q values are in memory before the next block reads them
+  }
 }
