@@ -120,3 +120,41 @@ def test_refresh_argument_errors():
     with pytest.raises(fira.FiraError) as ei:
         f32.fira_refresh_projectors([0], [gf], iters=1)
     assert ei.value.status == fira.FIRA_ERR_DTYPE
+
+
+def test_algorithm1_with_the_refresh_branch_on_the_device():
+    """Algorithm 1 end to end, including its "if t mod T = 0" branch: every T steps the projectors are
+    recomputed on the device from the current gradient; the oracle is fed the projector the device
+    installed (read back through the ABI) and must reproduce W, with the optimizer state carried
+    across the switches (Sec. 4.2)."""
+    shapes = [(192, 320), (320, 192)]
+    r, T, steps = 32, 4, 12
+    rng = np.random.default_rng(77)
+    hp = orc.OracleHparams(alpha=0.25)
+    ctx = fira.FiraContext(shapes, r, fira.FIRA_BF16, fira.make_hparams(hp.lr, hp.beta1, hp.beta2, hp.eps, hp.alpha, hp.gamma),
+                           device=H.DEV)
+    W0 = [synth.as_bf16_values(0.02 * rng.standard_normal(s)) for s in shapes]
+    Wd = [H.to_device(w, fira.FIRA_BF16) for w in W0]
+    Wref = [w.astype(np.float64) for w in W0]
+    st = [orc.OracleState.zeros(m, n, r) for (m, n) in shapes]
+    P = [None, None]
+    worst = 0.0
+    for t in range(steps):
+        G = [_gapped_gradient(rng, m, n, r, tail=0.2) for (m, n) in shapes]
+        Gd = [H.to_device(g, fira.FIRA_BF16) for g in G]
+        if t % T == 0:
+            ws = ctx.fira_refresh_projectors([0, 1], Gd, iters=2, seed=100 + t)
+            torch.cuda.synchronize()
+            P = [ctx.fira_get_projector(i).numpy().astype(np.float64) for i in range(2)]
+            del ws
+        ctx.fira_step([0, 1], Wd, Gd)
+        for i in range(2):
+            out = orc.fira_step(Wref[i], G[i].astype(np.float64), P[i], st[i], hp, store_bf16=True)
+            Wref[i] = out["W"]
+            worst = max(worst, H.rel_max(H.to_host(Wd[i]), Wref[i]))
+    for i in range(2):
+        M, V, s_prev, tt = ctx.fira_get_state(i)
+        assert tt == steps == st[i].t
+        assert H.rel_max(M.numpy(), st[i].M) <= 1e-4 and H.rel_max(V.numpy(), st[i].V) <= 1e-4
+    print(f"worst W error over {steps} steps with a refresh every {T}: {worst:.3e}", flush=True)
+    assert worst <= 2e-2
