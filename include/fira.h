@@ -121,6 +121,13 @@ FIRA_API fira_status fira_set_hparams(fira_ctx* ctx, const fira_hparams* hp);
 /* Variant switches (Sec. 5.3 ablations) and the way ||S_t|| is computed; both default to 0. */
 FIRA_API fira_status fira_set_options(fira_ctx* ctx, fira_scaling scaling, fira_norm_mode norm_mode);
 
+/* FIRA_VARIANT_FULL is Algorithm 1.  FIRA_VARIANT_ONLY_SCALING is the appendix's "Fira-only-scaling"
+ * (Eq. "only-scaling"): the factors are applied to the full gradient and the Adam term is dropped,
+ * W <- W - lr * alpha * c * (G diag(k)); the limiter acts on ||G diag(k)||, which needs only the
+ * ||G_i||^2 (no back-projection and no orthonormality condition on P).  M, V and t advance as usual. */
+typedef enum { FIRA_VARIANT_FULL = 0, FIRA_VARIANT_ONLY_SCALING = 1 } fira_variant;
+FIRA_API fira_status fira_set_variant(fira_ctx* ctx, fira_variant variant);
+
 /* Copy the state of matrix idx to host memory.  Synchronises the stream.
  * host_M, host_V: fp32, in the paper's orientation (r x n row-major for m <= n, m x r for m > n);
  * either may be NULL.  *s_prev = ||S_{t-1}|| or -1 when no step has run yet.  *t = steps taken. */

@@ -109,7 +109,7 @@ def limiter_factor(s, s_prev, gamma, eps):
     return gamma / max(ratio, gamma)
 
 
-def _step_short_rows(W, G, P, st: OracleState, hp: OracleHparams, scaling: str) -> Dict:
+def _step_short_rows(W, G, P, st: OracleState, hp: OracleHparams, scaling: str, variant: str = "full") -> Dict:
     """Algorithm 1's loop body for m <= n.  W, G: m x n.  P: m x r.  Mutates st; returns the new
     W and every intermediate."""
     t = st.t + 1
@@ -125,11 +125,17 @@ def _step_short_rows(W, G, P, st: OracleState, hp: OracleHparams, scaling: str) 
     else:
         raise ValueError(scaling)
     S = E * k[None, :]                           # S_t[:, i] = k_i S_t[:, i]
+    if variant == "only_scaling":                # Appendix "Fira-only-scaling": the factors on the full gradient,
+        S = G * k[None, :]                       # W_{t+1} = W_t - eta phi_t(R_t) G_t (limiter as in Algorithm 1)
+    elif variant != "full":
+        raise ValueError(variant)
     s_pre = float(np.sqrt(np.sum(S * S)))
     c = limiter_factor(s_pre, st.s_prev, hp.gamma, hp.eps)
     S = c * S
     s_post = c * s_pre
     G_tilde = hp.alpha * (P @ N + S)             # project back, complete the gradient
+    if variant == "only_scaling":
+        G_tilde = hp.alpha * S                   # no Adam term P psi(R)
     W_new = W - hp.lr * G_tilde
     st.M, st.V, st.s_prev, st.t = M, V, s_post, t
     return dict(W=W_new, R=R, E=E, N=N, k=k, S=S, s_pre=s_pre, c=c, s_post=s_post,
@@ -137,7 +143,7 @@ def _step_short_rows(W, G, P, st: OracleState, hp: OracleHparams, scaling: str) 
 
 
 def fira_step(W, G, P, st: OracleState, hp: OracleHparams, *, scaling: str = "column",
-              store_bf16: bool = False) -> Dict:
+              store_bf16: bool = False, variant: str = "full") -> Dict:
     """One Fira step for one weight matrix.
 
     W, G: m x n.  P: min(m, n) x r (P of Eq. 7 when m <= n, Q of the Sec. 3.3 footnote when
@@ -151,11 +157,11 @@ def fira_step(W, G, P, st: OracleState, hp: OracleHparams, *, scaling: str = "co
     if W.shape != G.shape or P.shape[0] != min(m, n) or P.shape[1] > min(m, n):
         raise ValueError("shape mismatch")
     if m <= n:
-        out = _step_short_rows(W, G, P, st, hp, scaling)
+        out = _step_short_rows(W, G, P, st, hp, scaling, variant)
     else:
         # transposed problem: (G^T, W^T) is n x m with n < m; state arrays are kept as m x r
         tst = OracleState(st.M.T, st.V.T, st.s_prev, st.t)
-        out = _step_short_rows(W.T, G.T, P, tst, hp, scaling)
+        out = _step_short_rows(W.T, G.T, P, tst, hp, scaling, variant)
         st.M, st.V, st.s_prev, st.t = tst.M.T, tst.V.T, tst.s_prev, tst.t
         for key in ("W", "R", "E", "N", "S", "update"):
             out[key] = out[key].T

@@ -123,7 +123,7 @@ bool make_plan(const fira_matrix_desc* d, int count, Plan* plan, fira_status* st
       m.Gx = (bf16_raw*)take(gx * 2);
     }
     h.ta_project = (m.L + FIRA_PA - 1) / FIRA_PA; h.tb_project = (m.r + FIRA_PB - 1) / FIRA_PB;
-    h.ta_back = (m.n + FIRA_TA - 1) / FIRA_TA;    h.tb_back = (m.m + FIRA_TB_HALF - 1) / FIRA_TB_HALF;
+    h.ta_back = (m.n + FIRA_BA - 1) / FIRA_BA;    h.tb_back = (m.m + FIRA_BB - 1) / FIRA_BB;
     h.tiles_project = h.ta_project * h.tb_project;
     h.tiles_back = h.ta_back * h.tb_back;
     h.rowblocks = (m.L + FIRA_ROWS_PER_WG - 1) / FIRA_ROWS_PER_WG;
@@ -165,6 +165,7 @@ struct fira_ctx {
   fira_hparams hp{};
   int scaling = FIRA_SCALE_COLUMN;
   int norm_mode = FIRA_NORM_RESIDUAL;
+  int variant = FIRA_VARIANT_FULL;
   FiraMat* d_mats = nullptr;
   FiraScal* d_scal = nullptr;
   float* d_partial = nullptr;
@@ -205,6 +206,7 @@ FiraHp make_hp(const fira_ctx* ctx) {
   h.lr_alpha = (float)(ctx->hp.lr * ctx->hp.alpha);
   h.scaling = ctx->scaling;
   h.norm_mode = ctx->norm_mode;
+  h.variant = ctx->variant;
   h.ortho_tol = 0.02f;   // bf16-rounded orthonormal projectors measure ~1e-3; 0.02 bounds the error of ||S|| by ~1 %
   return h;
 }
@@ -380,6 +382,13 @@ fira_status fira_set_options(fira_ctx* ctx, fira_scaling scaling, fira_norm_mode
   return FIRA_OK;
 }
 
+fira_status fira_set_variant(fira_ctx* ctx, fira_variant variant) {
+  if (!ctx) return fail(nullptr, FIRA_ERR_INVALID_ARG, "ctx is null");
+  if (variant != FIRA_VARIANT_FULL && variant != FIRA_VARIANT_ONLY_SCALING) return fail(ctx, FIRA_ERR_INVALID_ARG, "unknown variant");
+  ctx->variant = variant;
+  return FIRA_OK;
+}
+
 fira_status fira_set_projector(fira_ctx* ctx, int idx, const void* dev_P, fira_dtype p_dtype) {
   if (!ctx) return fail(nullptr, FIRA_ERR_INVALID_ARG, "ctx is null");
   if (idx < 0 || idx >= (int)ctx->plan.mats.size()) return fail(ctx, FIRA_ERR_INVALID_ARG, "matrix index out of range");
@@ -445,16 +454,18 @@ fira_status fira_step(fira_ctx* ctx, int count, const int* idx, void* const* dev
   auto grid8 = [](int n) { return dim3((unsigned)(((n + 7) / 8) * 8)); };
   const dim3 blk(FIRA_PROJ_THREADS);
   // 0. Gram route, fp32 matrices only: ||G_i||^2 for every factor (bf16 matrices get it from step 1)
-  if (ctx->norm_mode == FIRA_NORM_GRAM && s->ntiles[kTilesBackF32] > 0)
+  const bool only_scaling = ctx->variant == FIRA_VARIANT_ONLY_SCALING;
+  const int want_g2 = (ctx->norm_mode == FIRA_NORM_GRAM || only_scaling) ? 1 : 0;   // ||G_i||^2 per factor
+  if (want_g2 && s->ntiles[kTilesBackF32] > 0)
     hipLaunchKernelGGL(fira_gradnorm_kernel, dim3(s->g2blocks), dim3(256), 0, q, ctx->d_mats, ctx->d_scal, s->d_ents, count,
                        s->g2blocks, hp);
   // 1. R = P^T G (long-side major), one launch per orientation
   if (s->ntiles[kTilesProjectLeft])
     hipLaunchKernelGGL(fira_project_kernel<true>, grid8(s->ntiles[kTilesProjectLeft]), blk, FIRA_PROJ_LDS, q,
-                       ctx->d_mats, s->d_ents, s->d_tiles[kTilesProjectLeft], s->ntiles[kTilesProjectLeft], ctx->norm_mode);
+                       ctx->d_mats, s->d_ents, s->d_tiles[kTilesProjectLeft], s->ntiles[kTilesProjectLeft], want_g2);
   if (s->ntiles[kTilesProjectRight])
     hipLaunchKernelGGL(fira_project_kernel<false>, grid8(s->ntiles[kTilesProjectRight]), blk, FIRA_PROJ_LDS, q,
-                       ctx->d_mats, s->d_ents, s->d_tiles[kTilesProjectRight], s->ntiles[kTilesProjectRight], ctx->norm_mode);
+                       ctx->d_mats, s->d_ents, s->d_tiles[kTilesProjectRight], s->ntiles[kTilesProjectRight], want_g2);
   mark(1);
   // 2. Adam on R, factor norms
   hipLaunchKernelGGL(fira_adam_kernel, dim3(s->rowblocks), dim3(256), ctx->plan.adam_lds, q, ctx->d_mats, ctx->d_scal, s->d_ents, count,
@@ -462,8 +473,8 @@ fira_status fira_step(fira_ctx* ctx, int count, const int* idx, void* const* dev
   mark(2);
   // 3. ||k (G - P R)||^2 per tile, unless every listed matrix takes the Gram route (the kernels apply
   //    the same test per matrix: FiraScal::ortho_err <= FiraHp::ortho_tol)
-  bool need_residual = true;
-  if (ctx->norm_mode == FIRA_NORM_GRAM) {
+  bool need_residual = !only_scaling;
+  if (need_residual && ctx->norm_mode == FIRA_NORM_GRAM) {
     if (ctx->ortho_pending) {   // a projector was installed since the last step: wait for its gate value
       FIRA_HIP(ctx, hipEventSynchronize(ctx->ortho_event));
       ctx->ortho_pending = false;
@@ -472,11 +483,11 @@ fira_status fira_step(fira_ctx* ctx, int count, const int* idx, void* const* dev
     for (int e = 0; e < count; ++e) need_residual = need_residual || !(ctx->h_ortho[idx[e]] <= hp.ortho_tol);
   }
   if (need_residual && s->ntiles[kTilesBackBf16])
-    hipLaunchKernelGGL((fira_backproject_kernel<0, bf16_raw>), grid8(s->ntiles[kTilesBackBf16]), dim3(FIRA_HALF_THREADS), FIRA_BACK_LDS, q,
+    hipLaunchKernelGGL((fira_backproject_kernel<0, bf16_raw>), grid8(s->ntiles[kTilesBackBf16]), dim3(FIRA_BACK_THREADS), FIRA_BACK_LDS, q,
                        ctx->d_mats, ctx->d_scal, s->d_ents, s->d_tiles[kTilesBackBf16], s->ntiles[kTilesBackBf16],
                        ctx->d_partial, hp);
   if (need_residual && s->ntiles[kTilesBackF32])
-    hipLaunchKernelGGL((fira_backproject_kernel<0, float>), grid8(s->ntiles[kTilesBackF32]), dim3(FIRA_HALF_THREADS), FIRA_BACK_LDS, q,
+    hipLaunchKernelGGL((fira_backproject_kernel<0, float>), grid8(s->ntiles[kTilesBackF32]), dim3(FIRA_BACK_THREADS), FIRA_BACK_LDS, q,
                        ctx->d_mats, ctx->d_scal, s->d_ents, s->d_tiles[kTilesBackF32], s->ntiles[kTilesBackF32],
                        ctx->d_partial, hp);
   mark(3);
@@ -484,17 +495,27 @@ fira_status fira_step(fira_ctx* ctx, int count, const int* idx, void* const* dev
   hipLaunchKernelGGL(fira_limiter_kernel, dim3(count), dim3(FIRA_LIMITER_THREADS), 0, q, ctx->d_mats, ctx->d_scal, s->d_ents, ctx->d_partial, hp);
   mark(4);
   // 5. Z = N - c k R
-  hipLaunchKernelGGL(fira_makez_kernel, dim3(count * FIRA_MAKEZ_PARTS), dim3(256), 0, q, ctx->d_mats, ctx->d_scal, s->d_ents, hp);
+  if (!only_scaling)
+    hipLaunchKernelGGL(fira_makez_kernel, dim3(count * FIRA_MAKEZ_PARTS), dim3(256), 0, q, ctx->d_mats, ctx->d_scal, s->d_ents, hp);
   mark(5);
-  // 6. W -= lr alpha (P Z + c k G)
-  if (s->ntiles[kTilesBackBf16])
-    hipLaunchKernelGGL((fira_backproject_kernel<1, bf16_raw>), grid8(s->ntiles[kTilesBackBf16]), dim3(FIRA_HALF_THREADS), FIRA_BACK_LDS, q,
-                       ctx->d_mats, ctx->d_scal, s->d_ents, s->d_tiles[kTilesBackBf16], s->ntiles[kTilesBackBf16],
-                       ctx->d_partial, hp);
-  if (s->ntiles[kTilesBackF32])
-    hipLaunchKernelGGL((fira_backproject_kernel<1, float>), grid8(s->ntiles[kTilesBackF32]), dim3(FIRA_HALF_THREADS), FIRA_BACK_LDS, q,
-                       ctx->d_mats, ctx->d_scal, s->d_ents, s->d_tiles[kTilesBackF32], s->ntiles[kTilesBackF32],
-                       ctx->d_partial, hp);
+  // 6. W -= lr alpha (P Z + c k G)    (only-scaling variant: W -= lr alpha c k G, a plain stream)
+  if (only_scaling) {
+    if (s->ntiles[kTilesBackBf16])
+      hipLaunchKernelGGL(fira_scale_update_kernel<bf16_raw>, grid8(s->ntiles[kTilesBackBf16]), dim3(256), 0, q,
+                         ctx->d_mats, ctx->d_scal, s->d_ents, s->d_tiles[kTilesBackBf16], s->ntiles[kTilesBackBf16], hp);
+    if (s->ntiles[kTilesBackF32])
+      hipLaunchKernelGGL(fira_scale_update_kernel<float>, grid8(s->ntiles[kTilesBackF32]), dim3(256), 0, q,
+                         ctx->d_mats, ctx->d_scal, s->d_ents, s->d_tiles[kTilesBackF32], s->ntiles[kTilesBackF32], hp);
+  } else {
+    if (s->ntiles[kTilesBackBf16])
+      hipLaunchKernelGGL((fira_backproject_kernel<1, bf16_raw>), grid8(s->ntiles[kTilesBackBf16]), dim3(FIRA_BACK_THREADS), FIRA_BACK_LDS, q,
+                         ctx->d_mats, ctx->d_scal, s->d_ents, s->d_tiles[kTilesBackBf16], s->ntiles[kTilesBackBf16],
+                         ctx->d_partial, hp);
+    if (s->ntiles[kTilesBackF32])
+      hipLaunchKernelGGL((fira_backproject_kernel<1, float>), grid8(s->ntiles[kTilesBackF32]), dim3(FIRA_BACK_THREADS), FIRA_BACK_LDS, q,
+                         ctx->d_mats, ctx->d_scal, s->d_ents, s->d_tiles[kTilesBackF32], s->ntiles[kTilesBackF32],
+                         ctx->d_partial, hp);
+  }
   mark(6);
   FIRA_HIP(ctx, hipGetLastError());
   return FIRA_OK;

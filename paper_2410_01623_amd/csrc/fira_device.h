@@ -104,11 +104,14 @@ struct FiraHp {     // hyper-parameters as the kernels take them
   int scaling;      // 0 column, 1 matrix, 2 none
   int norm_mode;    // 0: ||S|| from the residual tiles; 1: from ||G_i||^2 - ||R_i||^2 where P passes the gate
   float ortho_tol;  // gate of the Gram mode on FiraScal::ortho_err
+  int variant;      // 0: Algorithm 1; 1: factors on the full gradient, no Adam term ("Fira-only-scaling")
 };
 
 // Whether matrix `sc` takes the Gram route to ||S||^2 in this step.
+// (The only-scaling variant needs ||G diag(k)||^2 = sum_i k_i^2 ||G_i||^2, which is this route's data
+// without any condition on P.)
 __device__ __forceinline__ bool use_gram(const FiraHp& hp, const FiraScal& sc) {
-  return hp.norm_mode == 1 && sc.ortho_err <= hp.ortho_tol;
+  return hp.variant == 1 || (hp.norm_mode == 1 && sc.ortho_err <= hp.ortho_tol);
 }
 
 

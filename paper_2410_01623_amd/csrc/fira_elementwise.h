@@ -16,6 +16,12 @@ __device__ __forceinline__ int find_entry(const FiraEnt* __restrict__ ents, int 
   return lo;
 }
 
+// ||G_i - P R_i||^2 from ||G_i||^2 and ||R_i||^2 (Gram route), or ||G_i||^2 itself for the variant that
+// scales the full gradient.
+__device__ __forceinline__ float residual_sq(const FiraHp& hp, float g2, float rr) {
+  return hp.variant == 1 ? g2 : fmaxf(g2 - rr, 0.0f);
+}
+
 __device__ __forceinline__ float wave_sum(float x) {
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) x += __shfl_xor(x, off, 64);
@@ -106,7 +112,7 @@ __device__ __forceinline__ void adam_row(const FiraMat& mt, const FiraHp& hp, fl
       const float k = (hp.scaling == 2) ? 1.0f : sqrtf(nn) / (sqrtf(rr) + hp.epsf);
       as_global(mt.phi)[row] = k;
       // Gram route: ||G_i - P R_i||^2 = ||G_i||^2 - ||R_i||^2 when P^T P = I (G_i^T P = R_i^T always)
-      if (gram) as_global(mt.q)[row] = k * k * fmaxf(as_global<const float>(mt.g2)[row] - rr, 0.0f);
+      if (gram) as_global(mt.q)[row] = k * k * residual_sq(hp, as_global<const float>(mt.g2)[row], rr);
     }
   }
 }
@@ -167,7 +173,7 @@ __device__ __forceinline__ void adam_row_zready(const FiraMat& mt, const FiraHp&
   }
   if (lane == 0) {
     as_global(mt.phi)[row] = k;
-    if (gram) as_global(mt.q)[row] = k * k * fmaxf(as_global<const float>(mt.g2)[row] - rr, 0.0f);
+    if (gram) as_global(mt.q)[row] = k * k * residual_sq(hp, as_global<const float>(mt.g2)[row], rr);
   }
 }
 
@@ -219,7 +225,7 @@ __device__ __forceinline__ void adam_rows4_small(const FiraMat& mt, const FiraHp
   }
   if ((lane & 15) == 0 && row < mt.L) {
     as_global(mt.phi)[row] = k;
-    if (gram) as_global(mt.q)[row] = k * k * fmaxf(as_global<const float>(mt.g2)[row] - rr, 0.0f);
+    if (gram) as_global(mt.q)[row] = k * k * residual_sq(hp, as_global<const float>(mt.g2)[row], rr);
   }
 }
 
@@ -311,7 +317,7 @@ __global__ __launch_bounds__(FIRA_LIMITER_THREADS) void fira_limiter_kernel(cons
     for (int i = tid; i < mt.L; i += FIRA_LIMITER_THREADS) {
       nn += (double)phi[i];
       rr += (double)q[i];
-      if (gram) acc += (double)fmaxf(g2[i] - q[i], 0.0f);
+      if (gram) acc += (double)residual_sq(hp, g2[i], q[i]);
     }
     if (!gram)
       for (int i = tid; i < ent.npart; i += FIRA_LIMITER_THREADS) acc += (double)partial[ent.part0 + i];
@@ -423,6 +429,70 @@ __global__ __launch_bounds__(256) void fira_makez_kernel(const FiraMat* __restri
       if (zready) fixz_row(mt, (1.0f - c) * k, row);
       else if (mt.kx == 1) makez_row<1>(mt, c * k, row);
       else makez_row<FIRA_KX_SPLIT>(mt, c * k, row);
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// "Fira-only-scaling" update: W -= lr*alpha * c * k_i * G over the tiles of the back-projection list
+// (256 columns x 128 rows per workgroup), a pure stream: 16 bytes per lane, 512 contiguous bytes per
+// row piece, factors per column (m <= n) or per row (m > n).
+// ------------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void fira_scale_update_kernel(const FiraMat* __restrict__ mats,
+                                                                const FiraScal* __restrict__ scal,
+                                                                const FiraEnt* __restrict__ ents,
+                                                                const FiraTile* __restrict__ tiles, int ntiles, FiraHp hp) {
+  const int ti = xcd_chunked_index(blockIdx.x, ntiles);
+  if (ti < 0) return;
+  const FiraTile tile = tiles[ti];
+  const FiraEnt ent = ents[tile.ent];
+  const FiraMat mt = mats[ent.mat];
+  const float f = hp.lr_alpha * scal[ent.mat].c;
+  gptr<const T> G = as_global(reinterpret_cast<const T*>(ent.G));
+  gptr<T> W = as_global(reinterpret_cast<T*>(ent.W));
+  gptr<const float> phi = as_global<const float>(mt.phi);
+  const int t = threadIdx.x;
+  const long long j = (long long)tile.ta * 256 + 8 * (t & 31);
+  if (j >= mt.n) return;
+  float kc[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) kc[e] = (mt.left && j + e < mt.n) ? f * phi[j + e] : 0.0f;
+  for (int p = 0; p < 16; ++p) {
+    const long long i = (long long)tile.tb * 128 + (t >> 5) + 8 * p;
+    if (i >= mt.m) break;
+    if (!mt.left) {
+      const float fr = f * phi[i];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) kc[e] = fr;
+    }
+    if (sizeof(T) == 2) {
+      gptr<const bf16_raw> gr = reinterpret_cast<gptr<const bf16_raw>>(G) + i * mt.ld + j;
+      gptr<bf16_raw> wr = reinterpret_cast<gptr<bf16_raw>>(W) + i * mt.ld + j;
+      if (j + 8 <= mt.n) {       // rows may start at any element: 2-byte alignment only
+        const u32x4 gv = __builtin_nontemporal_load(reinterpret_cast<gptr<const u32x4_a2>>(gr));
+        const u32x4 wv = __builtin_nontemporal_load(reinterpret_cast<gptr<const u32x4_a2>>(wr));
+        const unsigned gw[4] = {gv.x, gv.y, gv.z, gv.w}, ww[4] = {wv.x, wv.y, wv.z, wv.w};
+        unsigned o[4];
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+          const float w0 = __uint_as_float(ww[d] << 16) - kc[2 * d] * __uint_as_float(gw[d] << 16);
+          const float w1 = __uint_as_float(ww[d] & 0xffff0000u) - kc[2 * d + 1] * __uint_as_float(gw[d] & 0xffff0000u);
+          o[d] = pack_bf16x2(w0, w1);
+        }
+        __builtin_nontemporal_store(u32x4{o[0], o[1], o[2], o[3]}, reinterpret_cast<gptr<u32x4_a2>>(wr));
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+          if (j + e < mt.n) wr[e] = f32_to_bf16(bf16_to_f32(wr[e]) - kc[e] * bf16_to_f32(gr[e]));
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e)
+        if (j + e < mt.n) {
+          gptr<float> wp = reinterpret_cast<gptr<float>>(W) + i * mt.ld + j + e;
+          *wp = *wp - kc[e] * reinterpret_cast<gptr<const float>>(G)[i * mt.ld + j + e];
+        }
     }
   }
 }

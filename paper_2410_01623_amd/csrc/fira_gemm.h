@@ -23,7 +23,7 @@
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
 
-#define FIRA_TA 256  // rank-axis contractions: tile rows on the A side
+#define FIRA_BA 256  // rank-axis contractions (back-projection): tile rows on the A side (n)
 
 // [row][64 k] bf16 tile, 128 B per row, 16-byte chunks XOR-swizzled by row so that fragment reads
 // and tile writes spread over all banks.
@@ -121,11 +121,11 @@ __device__ __forceinline__ void gemm_sumsq_slice(float (&sq)[4], const Frags& f)
 // Operand rows are padded to whole tiles (zeros), so no row index needs clamping; what the padding
 // rows produce lands in accumulators that are never stored.
 // ------------------------------------------------------------------------------------------------
-#define FIRA_TB_HALF 128
-#define FIRA_HALF_THREADS 256
+#define FIRA_BB 128   // ... and on the B side (m)
+#define FIRA_BACK_THREADS 256
 #define FIRA_RK 32
-#define FIRA_RING_A (FIRA_TA * 64)
-#define FIRA_RING_B (FIRA_TB_HALF * 64)
+#define FIRA_RING_A (FIRA_BA * 64)
+#define FIRA_RING_B (FIRA_BB * 64)
 #define FIRA_RING_STAGE (FIRA_RING_A + FIRA_RING_B)
 #define FIRA_RING_STAGES 3
 #define FIRA_RING_LDS (FIRA_RING_STAGES * FIRA_RING_STAGE)
@@ -668,7 +668,7 @@ __device__ __forceinline__ float backproject_epilogue(f32x16_t (&acc)[4][2], cha
 
 // T: storage type of W and G of every matrix in the tile list (the host keeps one list per type).
 template <int MODE, typename T>
-__global__ __launch_bounds__(FIRA_HALF_THREADS, 2) void fira_backproject_kernel(const FiraMat* __restrict__ mats,
+__global__ __launch_bounds__(FIRA_BACK_THREADS, 2) void fira_backproject_kernel(const FiraMat* __restrict__ mats,
                                                                            const FiraScal* __restrict__ scal,
                                                                            const FiraEnt* __restrict__ ents,
                                                                            const FiraTile* __restrict__ tiles,
@@ -688,9 +688,9 @@ __global__ __launch_bounds__(FIRA_HALF_THREADS, 2) void fira_backproject_kernel(
   gptr<const bf16_raw> lowrank = as_global<const bf16_raw>((MODE == 0) ? mt.Rb : mt.Nb);
   gptr<const bf16_raw> proj = as_global<const bf16_raw>(mt.Pn);
   GemmOperands g;
-  g.a_row0 = tile.ta * FIRA_TA;
+  g.a_row0 = tile.ta * FIRA_BA;
   g.a_rows = mt.n;
-  g.b_row0 = tile.tb * FIRA_TB_HALF;
+  g.b_row0 = tile.tb * FIRA_BB;
   g.b_rows = mt.m;
   g.KA = g.KB = mt.kx * mt.rp;
   g.A = mt.left ? lowrank : proj;
@@ -702,7 +702,7 @@ __global__ __launch_bounds__(FIRA_HALF_THREADS, 2) void fira_backproject_kernel(
 
   const float c = (MODE == 0) ? 1.0f : scal[ent.mat].c;
   const int i0 = g.b_row0, j0 = g.a_row0;
-  const bool interior = i0 + FIRA_TB_HALF <= mt.m && j0 + FIRA_TA <= mt.n;
+  const bool interior = i0 + FIRA_BB <= mt.m && j0 + FIRA_BA <= mt.n;
   float sum;
   // matrix-level factor: the residual norm is taken with unit factors and scaled by the limiter kernel
   const bool unitk = MODE == 0 && hp.scaling == 1;

@@ -25,12 +25,13 @@ FIRA_ERR_WORKSPACE = -5
 FIRA_ERR_HIP = -6
 FIRA_F32, FIRA_BF16 = 0, 1
 FIRA_SCALE_COLUMN, FIRA_SCALE_MATRIX, FIRA_SCALE_NONE = 0, 1, 2
+FIRA_VARIANT_FULL, FIRA_VARIANT_ONLY_SCALING = 0, 1
 FIRA_NORM_RESIDUAL, FIRA_NORM_GRAM = 0, 1
 FIRA_NUM_KERNELS = 6
 
 EXPORTS = (
     "fira_method_state_numel", "fira_state_bytes", "fira_init_state", "fira_set_projector", "fira_step",
-    "fira_set_hparams", "fira_set_options", "fira_get_state", "fira_set_state", "fira_get_diag",
+    "fira_set_hparams", "fira_set_options", "fira_set_variant", "fira_get_state", "fira_set_state", "fira_get_diag",
     "fira_get_factors", "fira_get_lowrank", "fira_get_projector", "fira_refresh_workspace_bytes",
     "fira_refresh_projectors", "fira_profile_begin", "fira_profile_end", "fira_kernel_name",
     "fira_last_error", "fira_destroy",
@@ -83,6 +84,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.fira_set_hparams.argtypes = [vp, ctypes.POINTER(fira_hparams)]
     lib.fira_set_options.restype = ci
     lib.fira_set_options.argtypes = [vp, ci, ci]
+    lib.fira_set_variant.restype = ci
+    lib.fira_set_variant.argtypes = [vp, ci]
     lib.fira_get_state.restype = ci
     lib.fira_get_state.argtypes = [vp, ci, vp, vp, ctypes.POINTER(cd), ctypes.POINTER(ctypes.c_int64)]
     lib.fira_set_state.restype = ci
@@ -210,6 +213,9 @@ class FiraContext:
 
     def fira_set_options(self, scaling=FIRA_SCALE_COLUMN, norm_mode=FIRA_NORM_RESIDUAL):
         _check(self.lib, self.ctx, self.lib.fira_set_options(self.ctx, scaling, norm_mode))
+
+    def fira_set_variant(self, variant: int):
+        _check(self.lib, self.ctx, self.lib.fira_set_variant(self.ctx, variant))
 
     def fira_get_state(self, idx: int):
         m, n = self.shapes[idx]

@@ -58,7 +58,8 @@ def run_case(shapes: Sequence[Tuple[int, int]], rank, dtype: int, steps: int,
              gen_P: Callable[[int, int], Optional[np.ndarray]], hp: orc.OracleHparams,
              check: Optional[Sequence[int]] = None, lds: Optional[Sequence[int]] = None,
              stages: bool = True, scaling: str = "column", step_lists: Optional[List[List[int]]] = None,
-             alias: Optional[Dict[int, int]] = None, norm_mode: int = fira.FIRA_NORM_RESIDUAL) -> CaseResult:
+             alias: Optional[Dict[int, int]] = None, norm_mode: int = fira.FIRA_NORM_RESIDUAL,
+             variant: str = "full") -> CaseResult:
     """gen_P(mat, step) returns a projector (float64/float32 values already representable in the
     storage type) when the projector of `mat` is (re)installed before `step`, else None.
     `check`: matrices compared against the oracle (default all).  `alias[i] = j`: matrix i is fed
@@ -75,6 +76,8 @@ def run_case(shapes: Sequence[Tuple[int, int]], rank, dtype: int, steps: int,
         ctx.fira_set_options(scaling={"none": fira.FIRA_SCALE_NONE, "column": fira.FIRA_SCALE_COLUMN,
                                       "matrix": fira.FIRA_SCALE_MATRIX}[scaling],
                              norm_mode=norm_mode)
+    if variant != "full":
+        ctx.fira_set_variant({"only_scaling": fira.FIRA_VARIANT_ONLY_SCALING}[variant])
     bf = dtype == fira.FIRA_BF16
     W_host = {i: gen_W(i) for i in set(src(i) for i in range(nmat))}
     W_dev = [to_device(W_host[src(i)], dtype, None if lds is None else lds[i]) for i in range(nmat)]
@@ -101,7 +104,7 @@ def run_case(shapes: Sequence[Tuple[int, int]], rank, dtype: int, steps: int,
             if i not in check:
                 continue
             out = orc.fira_step(W_ref[i], G_host[src(i)].astype(np.float64), P_cur[i], states[i], hp,
-                                scaling=scaling, store_bf16=bf)
+                                scaling=scaling, store_bf16=bf, variant=variant)
             W_ref[i] = out["W"]
             c_min = min(c_min, out["c"])
             if stages:

@@ -176,6 +176,25 @@ def test_matrix_level_factor_variant(m, n, r, dtype, norm_mode):
         assert res.worst[k] <= v, f"stage {k}: {msg}"
 
 
+@pytest.mark.parametrize("scaling", ["column", "matrix"])
+@pytest.mark.parametrize("dtype", [fira.FIRA_BF16, fira.FIRA_F32], ids=["bf16", "f32"])
+@pytest.mark.parametrize("m,n,r", [(130, 277, 24), (277, 130, 24)], ids=["130x277r24", "277x130r24"])
+def test_only_scaling_variant(m, n, r, dtype, scaling):
+    """Appendix variant "Fira-only-scaling": W <- W - lr alpha c (G diag(k)), no back-projection; the
+    limiter acts on ||G diag(k)||.  A uniform spike of G is absorbed by the factors, so the spike here
+    is in the subspace-orthogonal part, which changes ||G_i|| but not R."""
+    W0, Gs, P = random_case(500 + m, m, n, r, dtype, 5, spike_at=3)
+    res = H.run_case([(m, n)], r, dtype, 5, lambda i: W0, lambda i, s: Gs[s],
+                     lambda i, s: P if s == 0 else None, orc.OracleHparams(alpha=0.5), scaling=scaling,
+                     variant="only_scaling")
+    assert res.c_min < 1.0
+    msg = H.fmt(res)
+    print(msg, flush=True)
+    assert max(res.w_err) <= TOL_W[dtype], msg
+    for k, v in TOL_STAGE[dtype].items():
+        assert res.worst[k] <= v, f"stage {k}: {msg}"
+
+
 def test_limiter_off_and_degenerate_columns():
     """gamma = inf disables the limiter; an all-zero column gives k = 0 and no NaN."""
     m, n, r = 64, 96, 16

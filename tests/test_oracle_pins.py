@@ -466,6 +466,36 @@ def pin_bf16_rounding(o):
     assert np.max(np.abs(out["W"] - out["W_unrounded"])) <= 2.0 ** -8 * np.max(np.abs(out["W"]))
 
 
+def pin_only_scaling_variant(o):
+    """Appendix variant "Fira-only-scaling": W_{t+1} = W_t - eta phi_t(R_t) G_t.  With the limiter off
+    and alpha = 1 the weight delta of one step is exactly -lr * G * k (k from the same R, N as the
+    full method), column by column; the Adam state advances as in the full method; and the variant
+    differs from the full method by lr * (P N - k (P R)) when P is orthonormal."""
+    rng = np.random.default_rng(41)
+    m, n, r = 5, 8, 2
+    P = _orth(rng, m, r)
+    hp = _hp(o, gamma=float("inf"), alpha=1.0)
+    W0 = rng.standard_normal((m, n))
+    st_a, st_b = o.OracleState.zeros(m, n, r), o.OracleState.zeros(m, n, r)
+    for t in range(3):
+        G = rng.standard_normal((m, n))
+        full = o.fira_step(W0, G, P, st_a, hp)
+        only = o.fira_step(W0, G, P, st_b, hp, variant="only_scaling")
+        np.testing.assert_allclose(only["k"], full["k"], rtol=1e-13)
+        np.testing.assert_allclose(W0 - only["W"], hp.lr * G * full["k"][None, :], rtol=1e-9, atol=1e-15)
+        np.testing.assert_allclose(only["W"] - full["W"],
+                                   hp.lr * (P @ full["N"] - (P @ full["R"]) * full["k"][None, :]), rtol=1e-9, atol=1e-15)
+        np.testing.assert_allclose(st_a.M, st_b.M, rtol=0, atol=0)
+    # transposed problem and the limiter: the norm that is limited is ||k G||
+    hp2 = _hp(o, alpha=1.0)
+    Gt = rng.standard_normal((n, m))
+    st_c = o.OracleState.zeros(n, m, r)
+    o1 = o.fira_step(np.zeros((n, m)), Gt, P, st_c, hp2, variant="only_scaling")
+    np.testing.assert_allclose(o1["s_pre"], np.linalg.norm(Gt * o1["k"][:, None]), rtol=1e-13)
+    o2 = o.fira_step(np.zeros((n, m)), 7.0 * Gt + rng.standard_normal((n, m)), P, st_c, hp2, variant="only_scaling")
+    assert o2["c"] <= 1.0 and o2["s_post"] <= hp2.gamma * (o1["s_post"] + hp2.eps) * (1 + 1e-12)
+
+
 def pin_projector_refresh_helpers(o):
     """Eq. 7 and the subspace measures used to judge a refreshed projector.
     * a matrix of exact rank r: the projector spans its column (row) space and keeps all its energy;
@@ -509,7 +539,8 @@ PINS = [pin_hand_case, pin_brute_force, pin_full_rank_identity_is_adam, pin_full
         pin_orthonormal_split, pin_limiter_bound, pin_first_step_and_constant_gradient,
         pin_scale_invariance, pin_permutation_equivariance, pin_norm_identity, pin_transpose,
         pin_gradient_in_subspace_and_switches, pin_degenerate_columns,
-        pin_projector_switch_keeps_state, pin_bf16_rounding, pin_projector_refresh_helpers]
+        pin_projector_switch_keeps_state, pin_bf16_rounding, pin_projector_refresh_helpers,
+        pin_only_scaling_variant]
 
 
 @pytest.mark.parametrize("pin", PINS, ids=lambda p: p.__name__)
@@ -551,6 +582,8 @@ MUTANTS = [
     ("m > n handled as m <= n", "    if m <= n:\n        out = _step_short_rows", "    if True:\n        out = _step_short_rows"),
     ("bf16 rounding truncates", "np.rint(mant * 256.0)", "np.trunc(mant * 256.0)"),
     ("bf16 keeps 9 bits", "np.rint(mant * 256.0) / 256.0", "np.rint(mant * 512.0) / 512.0"),
+    ("only-scaling keeps the residual", "        S = G * k[None, :]                       # W_{t+1}", "        S = E * k[None, :]                       # W_{t+1}"),
+    ("only-scaling keeps the Adam term", "        G_tilde = hp.alpha * S                   # no Adam term", "        G_tilde = hp.alpha * (P @ N + S)         # no Adam term"),
     ("refresh takes the trailing vectors", "return U[:, :r] if G.shape[0] <= G.shape[1] else Vt[:r, :].T",
      "return U[:, -r:] if G.shape[0] <= G.shape[1] else Vt[-r:, :].T"),
     ("refresh takes the wrong side", "return U[:, :r] if G.shape[0] <= G.shape[1] else Vt[:r, :].T",
