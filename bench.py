@@ -41,6 +41,10 @@ def kernel_models(shapes, r, norm_mode):
     return {
         # R = P^T G: read G and P once, write R (fp32); dense contraction -> MFMA roofline
         "project": dict(flops=gemm, bytes=2 * mn + 2 * Sr + 4 * Lr + (4 * L if gram else 0), bound="mfma"),
+        # fused form of the two kernels around it (R stays in registers): read G and P, read and write M
+        # and V (fp32), write Z (bf16) and the factors.  2 mn r flops against 2 mn + 18 Lr bytes: at
+        # r = 512 the HBM time is twice the MFMA time
+        "project_adam": dict(flops=gemm, bytes=2 * mn + 2 * Sr + (8 + 8 + 2) * Lr + 12 * L, bound="hbm"),
         # read R, M, V (fp32); write M, V (fp32), the bf16 operand Z (for an inactive limiter), the
         # factors; R as a second bf16 operand only when the residual contraction follows
         "adam_norms": dict(flops=0.0, bytes=(4 + 8 + 8 + 2 + (0 if gram else 2)) * Lr + (12 if gram else 4) * L,
@@ -118,6 +122,8 @@ def main():
     ap.add_argument("--refresh-iters", type=int, default=0,
                     help="also time fira_refresh_projectors over all matrices with this many rounds of subspace "
                          "iteration (after the timed steps; reported under \"refresh\", not part of value)")
+    ap.add_argument("--no-fusion", action="store_true",
+                    help="run the projection and Adam as two kernels with R in memory")
     ap.add_argument("--norm-mode", choices=["gram", "residual"], default="gram",
                     help="how the limiter norm ||S|| is obtained (both are parity-tested)")
     args = ap.parse_args()
@@ -139,6 +145,8 @@ def main():
     lds = [((n + args.pad_ld - 1) // args.pad_ld) * args.pad_ld if args.pad_ld else n for (m, n) in shapes]
     ctx = fira.FiraContext(shapes, wl.rank, dt_f, fira.make_hparams(), device=dev, lds=lds)
     ctx.fira_set_options(norm_mode=fira.FIRA_NORM_GRAM if args.norm_mode == "gram" else fira.FIRA_NORM_RESIDUAL)
+    if args.no_fusion:
+        ctx.fira_set_fusion(False)
     # projectors: one seeded orthonormal basis per distinct short side, installed into every matrix
     cache = {}
     for i, (m, n) in enumerate(shapes):
@@ -175,6 +183,10 @@ def main():
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_sum, rec = ctx.fira_profile_end()
+    fused = ctx.fira_last_step_fused()
+    if fused:   # one kernel did the work of the first two slots
+        ms_sum = dict([("project_adam", ms_sum["project"] + ms_sum["adam_norms"])] +
+                      [(k, v) for k, v in ms_sum.items() if k not in ("project", "adam_norms")])
     finite = all(bool(torch.isfinite(w).all()) for w in W[:7])
     limited = sum(1 for i in range(len(shapes)) if ctx.fira_get_diag(i)[2] < 1.0)   # limiter active in the last step
 
@@ -203,7 +215,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": name, "matrices": len(shapes), "rank": wl.rank,
                    "params": sum(m * n for m, n in shapes), "state_bytes": ctx.state_bytes,
-                   "gradient_sets": n_sets, "norm_mode": args.norm_mode, "ld": "n" if not args.pad_ld else f"n rounded up to {args.pad_ld}", "finite": finite,
+                   "gradient_sets": n_sets, "norm_mode": args.norm_mode, "fused_projection_adam": fused, "ld": "n" if not args.pad_ld else f"n rounded up to {args.pad_ld}", "finite": finite,
                    "matrices_limited_last_step": limited},
         "roofline": roof, "kernels": kernels,
     }

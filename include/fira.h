@@ -128,6 +128,17 @@ FIRA_API fira_status fira_set_options(fira_ctx* ctx, fira_scaling scaling, fira_
 typedef enum { FIRA_VARIANT_FULL = 0, FIRA_VARIANT_ONLY_SCALING = 1 } fira_variant;
 FIRA_API fira_status fira_set_variant(fira_ctx* ctx, fira_variant variant);
 
+/* Kernel fusion (on by default).  A step in which every listed matrix is bf16 with r % 4 == 0 and
+ * r <= 512, with column factors (Eq. 10), Algorithm 1 proper and the Gram route to ||S_t|| in force for
+ * all of them, runs the projection R = P^T G and Adam (Eqs. 2-4) in one kernel that keeps R in
+ * registers; any other step, and every step with enable == 0, runs them as two kernels with R in
+ * memory.  Both compute the same quantities; sums are taken in a different order, so results agree to
+ * rounding, not bit for bit.  fira_last_step_fused: 1 if the last fira_step on ctx took the fused
+ * kernel, 0 if not (or ctx is NULL).  After a fused step fira_get_lowrank has R only for the matrices
+ * whose limiter factor was below 1. */
+FIRA_API fira_status fira_set_fusion(fira_ctx* ctx, int enable);
+FIRA_API int fira_last_step_fused(const fira_ctx* ctx);
+
 /* Copy the state of matrix idx to host memory.  Synchronises the stream.
  * host_M, host_V: fp32, in the paper's orientation (r x n row-major for m <= n, m x r for m > n);
  * either may be NULL.  *s_prev = ||S_{t-1}|| or -1 when no step has run yet.  *t = steps taken. */

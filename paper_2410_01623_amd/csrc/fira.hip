@@ -16,6 +16,7 @@
 #include "fira_elementwise.h"
 #include "fira_refresh.h"
 #include "fira_gemm.h"
+#include "fira_fused.h"
 
 namespace {
 
@@ -43,19 +44,21 @@ struct HostMat {
   int ta_project = 0, tb_project = 0, ta_back = 0, tb_back = 0;
   int rowblocks = 0;
   int g2blocks = 0;           // blocks of the ||G_i||^2 kernel
+  int fuse_list = -1;         // tile list of the fused projection/Adam kernel, or -1 if the matrix cannot take it
 };
 
-enum { kTilesProjectLeft = 0, kTilesProjectRight = 1, kTilesBackBf16 = 2, kTilesBackF32 = 3, kNumTileLists = 4 };
+// kTilesFuse + (r > 256 ? 2 : 0) + (left ? 0 : 1): tiles of the fused projection/Adam kernel (one per 128 factors)
+enum { kTilesProjectLeft = 0, kTilesProjectRight = 1, kTilesBackBf16 = 2, kTilesBackF32 = 3, kTilesFuse = 4, kNumTileLists = 8 };
 
 struct ListSlot {
   std::vector<int> idx;
   std::vector<void*> W;
   std::vector<const void*> G;
-  int ntiles[kNumTileLists] = {0, 0, 0, 0};
+  int ntiles[kNumTileLists] = {};
   int rowblocks = 0, g2blocks = 0;
   // device views (inside the slab)
   FiraEnt* d_ents = nullptr;
-  FiraTile* d_tiles[kNumTileLists] = {nullptr, nullptr, nullptr, nullptr};
+  FiraTile* d_tiles[kNumTileLists] = {};
   // pinned host staging, one contiguous block mirrored to the device block
   char* h_stage = nullptr;
   char* d_block = nullptr;
@@ -68,9 +71,9 @@ struct ListSlot {
 struct Plan {
   size_t total = 0;
   size_t off_mats = 0, off_scal = 0, off_partial = 0, off_ortho = 0, ortho_z = 0;
-  size_t off_slots = 0, slot_bytes = 0, slot_off_tiles[kNumTileLists] = {0, 0, 0, 0};
+  size_t off_slots = 0, slot_bytes = 0, slot_off_tiles[kNumTileLists] = {};
   std::vector<HostMat> mats;
-  int max_tiles[kNumTileLists] = {0, 0, 0, 0};
+  int max_tiles[kNumTileLists] = {};
   int adam_lds = 0;          // dynamic LDS of the Adam kernel: 16 rows of the widest register-resident matrix
 };
 
@@ -88,7 +91,7 @@ bool make_plan(const fira_matrix_desc* d, int count, Plan* plan, fira_status* st
   size_t off = 0;
   plan->off_mats = off; off = align_up(off + sizeof(FiraMat) * count);
   plan->off_scal = off; off = align_up(off + sizeof(FiraScal) * count);
-  long long total_tiles[kNumTileLists] = {0, 0, 0, 0};
+  long long total_tiles[kNumTileLists] = {};
   for (int i = 0; i < count; ++i) {
     HostMat& h = plan->mats[i];
     h.d = d[i];
@@ -130,6 +133,10 @@ bool make_plan(const fira_matrix_desc* d, int count, Plan* plan, fira_status* st
     h.g2blocks = m.left ? (m.n + 255) / 256 : (m.m + FIRA_G2_ROWS_PER_WG - 1) / FIRA_G2_ROWS_PER_WG;
     total_tiles[m.left ? kTilesProjectLeft : kTilesProjectRight] += h.tiles_project;
     total_tiles[m.dtype == FIRA_BF16 ? kTilesBackBf16 : kTilesBackF32] += h.tiles_back;
+    if (m.zready && m.r <= FIRA_FUSE_MAX_R) {
+      h.fuse_list = kTilesFuse + 2 * (m.r > 256 ? 1 : 0) + (m.left ? 0 : 1);
+      total_tiles[h.fuse_list] += h.ta_project;
+    }
   }
   for (int l = 0; l < kNumTileLists; ++l) {
     if (total_tiles[l] > (1 << 28)) { *st = FIRA_ERR_SHAPE; *why = "too many tiles"; return false; }
@@ -166,6 +173,8 @@ struct fira_ctx {
   int scaling = FIRA_SCALE_COLUMN;
   int norm_mode = FIRA_NORM_RESIDUAL;
   int variant = FIRA_VARIANT_FULL;
+  bool fusion = true;          // fira_set_fusion
+  bool last_step_fused = false;
   FiraMat* d_mats = nullptr;
   FiraScal* d_scal = nullptr;
   float* d_partial = nullptr;
@@ -240,7 +249,7 @@ ListSlot* acquire_list(fira_ctx* ctx, int count, const int* idx, void* const* W,
   const Plan& p = ctx->plan;
   FiraEnt* ents = reinterpret_cast<FiraEnt*>(s->h_stage);
   FiraTile* tl[kNumTileLists];
-  int nt[kNumTileLists] = {0, 0, 0, 0};
+  int nt[kNumTileLists] = {};
   for (int l = 0; l < kNumTileLists; ++l) tl[l] = reinterpret_cast<FiraTile*>(s->h_stage + p.slot_off_tiles[l]);
   int nparts = 0, rowblocks = 0, g2blocks = 0;
   for (int e = 0; e < count; ++e) {
@@ -254,6 +263,8 @@ ListSlot* acquire_list(fira_ctx* ctx, int count, const int* idx, void* const* W,
     const int lp = h.dev.left ? kTilesProjectLeft : kTilesProjectRight;
     for (int ta = 0; ta < h.ta_project; ++ta)
       for (int tbb = 0; tbb < h.tb_project; ++tbb) tl[lp][nt[lp]++] = FiraTile{e, ta, tbb, 0};
+    if (h.fuse_list >= 0)
+      for (int ta = 0; ta < h.ta_project; ++ta) tl[h.fuse_list][nt[h.fuse_list]++] = FiraTile{e, ta, 0, 0};
     // back-projection: groups of 8 column tiles x all row tiles keep both operand panels in L2
     const int lb = h.dev.dtype == FIRA_BF16 ? kTilesBackBf16 : kTilesBackF32;
     const int grp = 8;
@@ -341,6 +352,8 @@ fira_status fira_init_state(fira_ctx** out, const fira_matrix_desc* d, int count
   FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_backproject_kernel<1, bf16_raw>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_BACK_LDS));
   FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_backproject_kernel<0, float>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_BACK_LDS));
   FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_backproject_kernel<1, float>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_BACK_LDS));
+  FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_project_adam_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_FUSE_LDS(1)));
+  FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_project_adam_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_FUSE_LDS(2)));
   FIRA_INIT_HIP(hipHostMalloc((void**)&ctx->h_stage_all, p.slot_bytes * kSlots, hipHostMallocDefault));
   FIRA_INIT_HIP(hipHostMalloc((void**)&ctx->h_ortho, sizeof(float) * count, hipHostMallocDefault));
   for (int i = 0; i < count; ++i) ctx->h_ortho[i] = INFINITY;
@@ -388,6 +401,14 @@ fira_status fira_set_variant(fira_ctx* ctx, fira_variant variant) {
   ctx->variant = variant;
   return FIRA_OK;
 }
+
+fira_status fira_set_fusion(fira_ctx* ctx, int enable) {
+  if (!ctx) return fail(nullptr, FIRA_ERR_INVALID_ARG, "ctx is null");
+  ctx->fusion = enable != 0;
+  return FIRA_OK;
+}
+
+int fira_last_step_fused(const fira_ctx* ctx) { return ctx && ctx->last_step_fused ? 1 : 0; }
 
 fira_status fira_set_projector(fira_ctx* ctx, int idx, const void* dev_P, fira_dtype p_dtype) {
   if (!ctx) return fail(nullptr, FIRA_ERR_INVALID_ARG, "ctx is null");
@@ -459,20 +480,8 @@ fira_status fira_step(fira_ctx* ctx, int count, const int* idx, void* const* dev
   if (want_g2 && s->ntiles[kTilesBackF32] > 0)
     hipLaunchKernelGGL(fira_gradnorm_kernel, dim3(s->g2blocks), dim3(256), 0, q, ctx->d_mats, ctx->d_scal, s->d_ents, count,
                        s->g2blocks, hp);
-  // 1. R = P^T G (long-side major), one launch per orientation
-  if (s->ntiles[kTilesProjectLeft])
-    hipLaunchKernelGGL(fira_project_kernel<true>, grid8(s->ntiles[kTilesProjectLeft]), blk, FIRA_PROJ_LDS, q,
-                       ctx->d_mats, s->d_ents, s->d_tiles[kTilesProjectLeft], s->ntiles[kTilesProjectLeft], want_g2);
-  if (s->ntiles[kTilesProjectRight])
-    hipLaunchKernelGGL(fira_project_kernel<false>, grid8(s->ntiles[kTilesProjectRight]), blk, FIRA_PROJ_LDS, q,
-                       ctx->d_mats, s->d_ents, s->d_tiles[kTilesProjectRight], s->ntiles[kTilesProjectRight], want_g2);
-  mark(1);
-  // 2. Adam on R, factor norms
-  hipLaunchKernelGGL(fira_adam_kernel, dim3(s->rowblocks), dim3(256), ctx->plan.adam_lds, q, ctx->d_mats, ctx->d_scal, s->d_ents, count,
-                     s->rowblocks, hp);
-  mark(2);
-  // 3. ||k (G - P R)||^2 per tile, unless every listed matrix takes the Gram route (the kernels apply
-  //    the same test per matrix: FiraScal::ortho_err <= FiraHp::ortho_tol)
+  // Whether ||S|| needs the residual contraction: not if every listed matrix takes the Gram route (the
+  // kernels apply the same test per matrix: FiraScal::ortho_err <= FiraHp::ortho_tol).
   bool need_residual = !only_scaling;
   if (need_residual && ctx->norm_mode == FIRA_NORM_GRAM) {
     if (ctx->ortho_pending) {   // a projector was installed since the last step: wait for its gate value
@@ -482,6 +491,41 @@ fira_status fira_step(fira_ctx* ctx, int count, const int* idx, void* const* dev
     need_residual = false;
     for (int e = 0; e < count; ++e) need_residual = need_residual || !(ctx->h_ortho[idx[e]] <= hp.ortho_tol);
   }
+  // The fused projection/Adam kernel serves a step in which every listed matrix can take it.
+  bool fused = ctx->fusion && !only_scaling && ctx->scaling == FIRA_SCALE_COLUMN && ctx->norm_mode == FIRA_NORM_GRAM && !need_residual;
+  for (int e = 0; e < count && fused; ++e) fused = ctx->plan.mats[idx[e]].fuse_list >= 0;
+  ctx->last_step_fused = fused;
+  if (fused) {
+    // 1+2. R = P^T G, Adam on it, factor norms, Z for c = 1
+    for (int rt = 1; rt <= 2; ++rt) {
+      const int ll = kTilesFuse + 2 * (rt - 1), lr = ll + 1;
+      const int nl = s->ntiles[ll], nr = s->ntiles[lr];
+      if (nl + nr == 0) continue;
+      const int bl = (nl + 7) / 8 * 8, br = (nr + 7) / 8 * 8;
+      if (rt == 1)
+        hipLaunchKernelGGL(fira_project_adam_kernel<1>, dim3(bl + br), dim3(256), FIRA_FUSE_LDS(1), q, ctx->d_mats, ctx->d_scal, s->d_ents,
+                           s->d_tiles[ll], nl, bl, s->d_tiles[lr], nr, hp);
+      else
+        hipLaunchKernelGGL(fira_project_adam_kernel<2>, dim3(bl + br), dim3(512), FIRA_FUSE_LDS(2), q, ctx->d_mats, ctx->d_scal, s->d_ents,
+                           s->d_tiles[ll], nl, bl, s->d_tiles[lr], nr, hp);
+    }
+    mark(1);
+    mark(2);
+  } else {
+    // 1. R = P^T G (long-side major), one launch per orientation
+    if (s->ntiles[kTilesProjectLeft])
+      hipLaunchKernelGGL(fira_project_kernel<true>, grid8(s->ntiles[kTilesProjectLeft]), blk, FIRA_PROJ_LDS, q,
+                         ctx->d_mats, s->d_ents, s->d_tiles[kTilesProjectLeft], s->ntiles[kTilesProjectLeft], want_g2, (const FiraScal*)nullptr);
+    if (s->ntiles[kTilesProjectRight])
+      hipLaunchKernelGGL(fira_project_kernel<false>, grid8(s->ntiles[kTilesProjectRight]), blk, FIRA_PROJ_LDS, q,
+                         ctx->d_mats, s->d_ents, s->d_tiles[kTilesProjectRight], s->ntiles[kTilesProjectRight], want_g2, (const FiraScal*)nullptr);
+    mark(1);
+    // 2. Adam on R, factor norms
+    hipLaunchKernelGGL(fira_adam_kernel, dim3(s->rowblocks), dim3(256), ctx->plan.adam_lds, q, ctx->d_mats, ctx->d_scal, s->d_ents, count,
+                       s->rowblocks, hp);
+    mark(2);
+  }
+  // 3. ||k (G - P R)||^2 per tile where the Gram route does not apply
   if (need_residual && s->ntiles[kTilesBackBf16])
     hipLaunchKernelGGL((fira_backproject_kernel<0, bf16_raw>), grid8(s->ntiles[kTilesBackBf16]), dim3(FIRA_BACK_THREADS), FIRA_BACK_LDS, q,
                        ctx->d_mats, ctx->d_scal, s->d_ents, s->d_tiles[kTilesBackBf16], s->ntiles[kTilesBackBf16],
@@ -494,7 +538,16 @@ fira_status fira_step(fira_ctx* ctx, int count, const int* idx, void* const* dev
   // 4. limiter factor, state advance
   hipLaunchKernelGGL(fira_limiter_kernel, dim3(count), dim3(FIRA_LIMITER_THREADS), 0, q, ctx->d_mats, ctx->d_scal, s->d_ents, ctx->d_partial, hp);
   mark(4);
-  // 5. Z = N - c k R
+  // 5. Z = N - c k R.  After the fused kernel R exists only for c = 1 (inside Z); the matrices with c < 1
+  //    get it recomputed first (every other tile of these launches exits at once).
+  if (fused) {
+    if (s->ntiles[kTilesProjectLeft])
+      hipLaunchKernelGGL(fira_project_kernel<true>, grid8(s->ntiles[kTilesProjectLeft]), blk, FIRA_PROJ_LDS, q,
+                         ctx->d_mats, s->d_ents, s->d_tiles[kTilesProjectLeft], s->ntiles[kTilesProjectLeft], 0, (const FiraScal*)ctx->d_scal);
+    if (s->ntiles[kTilesProjectRight])
+      hipLaunchKernelGGL(fira_project_kernel<false>, grid8(s->ntiles[kTilesProjectRight]), blk, FIRA_PROJ_LDS, q,
+                         ctx->d_mats, s->d_ents, s->d_tiles[kTilesProjectRight], s->ntiles[kTilesProjectRight], 0, (const FiraScal*)ctx->d_scal);
+  }
   if (!only_scaling)
     hipLaunchKernelGGL(fira_makez_kernel, dim3(count * FIRA_MAKEZ_PARTS), dim3(256), 0, q, ctx->d_mats, ctx->d_scal, s->d_ents, hp);
   mark(5);
@@ -842,19 +895,19 @@ fira_status fira_refresh_projectors(fira_ctx* ctx, int count, const int* idx, co
     // T = G^T Q (or G Q): the projection kernel, norm route off
     if (s->ntiles[kTilesProjectLeft])
       hipLaunchKernelGGL(fira_project_kernel<true>, grid8(s->ntiles[kTilesProjectLeft]), dim3(FIRA_PROJ_THREADS), FIRA_PROJ_LDS, q,
-                         ctx->d_mats, s->d_ents, s->d_tiles[kTilesProjectLeft], s->ntiles[kTilesProjectLeft], 0);
+                         ctx->d_mats, s->d_ents, s->d_tiles[kTilesProjectLeft], s->ntiles[kTilesProjectLeft], 0, (const FiraScal*)nullptr);
     if (s->ntiles[kTilesProjectRight])
       hipLaunchKernelGGL(fira_project_kernel<false>, grid8(s->ntiles[kTilesProjectRight]), dim3(FIRA_PROJ_THREADS), FIRA_PROJ_LDS, q,
-                         ctx->d_mats, s->d_ents, s->d_tiles[kTilesProjectRight], s->ntiles[kTilesProjectRight], 0);
+                         ctx->d_mats, s->d_ents, s->d_tiles[kTilesProjectRight], s->ntiles[kTilesProjectRight], 0, (const FiraScal*)nullptr);
     // pack T as the K-blocked operand of the way back
     hipLaunchKernelGGL(fira_refresh_pack_kernel, dim3((max_Lp / 32) * nt64, count), dim3(256), 0, q, d_ents);
     // Y = G T (or G^T T): the projection kernel on the other orientation
     if (rp.ntiles[0])
       hipLaunchKernelGGL(fira_project_kernel<false>, grid8(rp.ntiles[0]), dim3(FIRA_PROJ_THREADS), FIRA_PROJ_LDS, q,
-                         d_vmats, d_vents, (const FiraTile*)(ws + rp.off_vtiles[0]), rp.ntiles[0], 0);
+                         d_vmats, d_vents, (const FiraTile*)(ws + rp.off_vtiles[0]), rp.ntiles[0], 0, (const FiraScal*)nullptr);
     if (rp.ntiles[1])
       hipLaunchKernelGGL(fira_project_kernel<true>, grid8(rp.ntiles[1]), dim3(FIRA_PROJ_THREADS), FIRA_PROJ_LDS, q,
-                         d_vmats, d_vents, (const FiraTile*)(ws + rp.off_vtiles[1]), rp.ntiles[1], 0);
+                         d_vmats, d_vents, (const FiraTile*)(ws + rp.off_vtiles[1]), rp.ntiles[1], 0, (const FiraScal*)nullptr);
     // Q = orth(Y): CholeskyQR in fp64
     orthonormalise(d_ents);
   }

@@ -360,9 +360,15 @@ __device__ __forceinline__ void proj_compute(f32x16_t (&acc)[4][2], const char* 
   }
 }
 
-template <bool LEFT, bool FAST, bool SUMSQ>
+// RT = rank tiles of 256 that one workgroup covers (256*RT threads, wave w owns rank rows 64 w ..).
+// With RT = 2 both tiles share the A tile, which only the first four wavefronts load and store; the
+// other four have no A requests in their queue, so their O-half wait is vmcnt(4) where a loading
+// wavefront's is vmcnt(8).
+template <bool LEFT, bool FAST, bool SUMSQ, int RT = 1>
 __device__ __forceinline__ void proj_pipeline(f32x16_t (&acc)[4][2], char* lds, const GemmOperands& g, float (&sq)[4]) {
+  constexpr int STAGE = RT * FIRA_PROJ_RING_STAGE;
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const bool loader = RT == 1 || wave < 4;
   char* la = lds;
   char* ring = lds + FIRA_PROJ_LDS_A;
   const unsigned ring0 = (unsigned)(size_t)(lds_ptr)ring;
@@ -372,14 +378,14 @@ __device__ __forceinline__ void proj_pipeline(f32x16_t (&acc)[4][2], char* lds, 
   const unsigned offb = (unsigned)(lrow * 64 + chunk * 16);
   const char* pb = reinterpret_cast<const char*>((const bf16_raw*)g.B) + ((long long)g.b_row0 + 64 * wave) * 64;
   auto request_b = [&](int s) {
-    const unsigned dst = ring0 + (unsigned)((s % FIRA_RING_STAGES) * FIRA_PROJ_RING_STAGE);
+    const unsigned dst = ring0 + (unsigned)((s % FIRA_RING_STAGES) * STAGE);
     const char* kb = pb + (long long)s * g.ldb * 64;
 #pragma unroll
     for (int q = 0; q < 4; ++q) lds_dma16(kb + q * 1024, offb, dst + (unsigned)((4 * wave + q) * 1024));
   };
   ProjALoader<LEFT, FAST> al(g);
   u32x4 ra[4];
-  al.load(ra);                                 // A(0)
+  if (loader) al.load(ra);                     // A(0)
   request_b(0);
   request_b(1);
   // LAST: the final K stage requests nothing more.  It is written out separately rather than
@@ -387,23 +393,24 @@ __device__ __forceinline__ void proj_pipeline(f32x16_t (&acc)[4][2], char* lds, 
   auto stage = [&](auto last, int S) {
     constexpr bool LAST = decltype(last)::value;
     // E half
-    wait_loads<4>(ra);                         // A(S) and D(2S) have landed; D(2S+1) may be in flight
+    if (loader) wait_loads<4>(ra);             // A(S) and D(2S) have landed; D(2S+1) may be in flight
+    else asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
     asm volatile("s_barrier" ::: "memory");    // everybody is done with the previous stage's A tile and ring slot
-    proj_store_a<LEFT>(la, ra);
+    if (loader) proj_store_a<LEFT>(la, ra);
     if (!LAST) {
       request_b(2 * S + 2);
-      al.load(ra);                             // A(S+1)
+      if (loader) al.load(ra);                 // A(S+1)
     }
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    proj_compute<SUMSQ>(acc, la, ring + ((2 * S) % FIRA_RING_STAGES) * FIRA_PROJ_RING_STAGE, 0, sq);
+    proj_compute<SUMSQ>(acc, la, ring + ((2 * S) % FIRA_RING_STAGES) * STAGE, 0, sq);
     // O half
     // D(2S+1) has landed.  Guarded A loads are the compiler's and may be fewer than 4 instructions,
     // so the edge path only lets D(2S+2)'s four stay in flight.
     if (LAST) asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
-    else if (FAST) asm volatile("s_waitcnt vmcnt(8)\n\ts_barrier" ::: "memory");
+    else if (FAST && loader) asm volatile("s_waitcnt vmcnt(8)\n\ts_barrier" ::: "memory");
     else asm volatile("s_waitcnt vmcnt(4)\n\ts_barrier" ::: "memory");
     if (!LAST) request_b(2 * S + 3);
-    proj_compute<SUMSQ>(acc, la, ring + ((2 * S + 1) % FIRA_RING_STAGES) * FIRA_PROJ_RING_STAGE, 2, sq);
+    proj_compute<SUMSQ>(acc, la, ring + ((2 * S + 1) % FIRA_RING_STAGES) * STAGE, 2, sq);
   };
   for (int S = 0; S + 1 < SS; ++S) stage(std::false_type{}, S);
   stage(std::true_type{}, SS - 1);
@@ -413,12 +420,16 @@ template <bool LEFT>
 __global__ __launch_bounds__(FIRA_PROJ_THREADS, 2) void fira_project_kernel(const FiraMat* __restrict__ mats,
                                                                             const FiraEnt* __restrict__ ents,
                                                                             const FiraTile* __restrict__ tiles,
-                                                                            int ntiles, int norm_mode) {
+                                                                            int ntiles, int norm_mode,
+                                                                            const FiraScal* __restrict__ limited_only) {
   extern __shared__ __attribute__((aligned(16))) char lds[];   // FIRA_PROJ_LDS bytes
   const int ti = xcd_chunked_index(blockIdx.x, ntiles);
   if (ti < 0) return;
   const FiraTile tile = tiles[ti];
   const FiraEnt ent = ents[tile.ent];
+  // Second use, after a step whose first kernel kept R in registers only: recompute R for the matrices
+  // whose limiter factor came out below 1 (the correction of Z needs it); every other tile exits here.
+  if (limited_only && limited_only[ent.mat].c == 1.0f) return;
   const FiraMat mt = mats[ent.mat];
 
   GemmOperands g;

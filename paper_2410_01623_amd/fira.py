@@ -31,7 +31,8 @@ FIRA_NUM_KERNELS = 6
 
 EXPORTS = (
     "fira_method_state_numel", "fira_state_bytes", "fira_init_state", "fira_set_projector", "fira_step",
-    "fira_set_hparams", "fira_set_options", "fira_set_variant", "fira_get_state", "fira_set_state", "fira_get_diag",
+    "fira_set_hparams", "fira_set_options", "fira_set_variant", "fira_set_fusion", "fira_last_step_fused",
+    "fira_get_state", "fira_set_state", "fira_get_diag",
     "fira_get_factors", "fira_get_lowrank", "fira_get_projector", "fira_refresh_workspace_bytes",
     "fira_refresh_projectors", "fira_profile_begin", "fira_profile_end", "fira_kernel_name",
     "fira_last_error", "fira_destroy",
@@ -86,6 +87,10 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.fira_set_options.argtypes = [vp, ci, ci]
     lib.fira_set_variant.restype = ci
     lib.fira_set_variant.argtypes = [vp, ci]
+    lib.fira_set_fusion.restype = ci
+    lib.fira_set_fusion.argtypes = [vp, ci]
+    lib.fira_last_step_fused.restype = ci
+    lib.fira_last_step_fused.argtypes = [vp]
     lib.fira_get_state.restype = ci
     lib.fira_get_state.argtypes = [vp, ci, vp, vp, ctypes.POINTER(cd), ctypes.POINTER(ctypes.c_int64)]
     lib.fira_set_state.restype = ci
@@ -216,6 +221,12 @@ class FiraContext:
 
     def fira_set_variant(self, variant: int):
         _check(self.lib, self.ctx, self.lib.fira_set_variant(self.ctx, variant))
+
+    def fira_set_fusion(self, enable: bool):
+        _check(self.lib, self.ctx, self.lib.fira_set_fusion(self.ctx, 1 if enable else 0))
+
+    def fira_last_step_fused(self) -> bool:
+        return bool(self.lib.fira_last_step_fused(self.ctx))
 
     def fira_get_state(self, idx: int):
         m, n = self.shapes[idx]

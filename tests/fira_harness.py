@@ -51,6 +51,7 @@ class CaseResult:
     states: Dict[int, orc.OracleState]
     diag: List[Tuple]
     w_err_by_step: Dict[int, float] = dataclasses.field(default_factory=dict)   # worst W error after step s+1
+    fused_steps: int = 0          # steps that took the fused projection/Adam kernel
 
 
 def run_case(shapes: Sequence[Tuple[int, int]], rank, dtype: int, steps: int,
@@ -59,12 +60,15 @@ def run_case(shapes: Sequence[Tuple[int, int]], rank, dtype: int, steps: int,
              check: Optional[Sequence[int]] = None, lds: Optional[Sequence[int]] = None,
              stages: bool = True, scaling: str = "column", step_lists: Optional[List[List[int]]] = None,
              alias: Optional[Dict[int, int]] = None, norm_mode: int = fira.FIRA_NORM_RESIDUAL,
-             variant: str = "full") -> CaseResult:
+             variant: str = "full", fusion: bool = True) -> CaseResult:
     """gen_P(mat, step) returns a projector (float64/float32 values already representable in the
     storage type) when the projector of `mat` is (re)installed before `step`, else None.
     `check`: matrices compared against the oracle (default all).  `alias[i] = j`: matrix i is fed
     the same inputs as matrix j (its own device buffers), for bitwise-equality checks.
-    `step_lists[s]`: matrices stepped at step s (default all)."""
+    `step_lists[s]`: matrices stepped at step s (default all).
+    `fusion`: False switches the fused projection/Adam kernel off.  After a fused step the library
+    holds no copy of R (it stays in registers), so R is then checked only through what follows from
+    it: M, V, k, ||S|| and W."""
     nmat = len(shapes)
     check = list(range(nmat)) if check is None else list(check)
     alias = alias or {}
@@ -76,6 +80,9 @@ def run_case(shapes: Sequence[Tuple[int, int]], rank, dtype: int, steps: int,
         ctx.fira_set_options(scaling={"none": fira.FIRA_SCALE_NONE, "column": fira.FIRA_SCALE_COLUMN,
                                       "matrix": fira.FIRA_SCALE_MATRIX}[scaling],
                              norm_mode=norm_mode)
+    if not fusion:
+        ctx.fira_set_fusion(False)
+    fused_steps = 0
     if variant != "full":
         ctx.fira_set_variant({"only_scaling": fira.FIRA_VARIANT_ONLY_SCALING}[variant])
     bf = dtype == fira.FIRA_BF16
@@ -100,6 +107,8 @@ def run_case(shapes: Sequence[Tuple[int, int]], rank, dtype: int, steps: int,
                 P_cur[i] = np.asarray(P, dtype=np.float64)
                 ctx.fira_set_projector(i, to_device(np.asarray(P, dtype=np.float32), dtype))
         ctx.fira_step(listed, [W_dev[i] for i in listed], G_dev)
+        fused = ctx.fira_last_step_fused()
+        fused_steps += int(fused)
         for i in listed:
             if i not in check:
                 continue
@@ -108,7 +117,7 @@ def run_case(shapes: Sequence[Tuple[int, int]], rank, dtype: int, steps: int,
             W_ref[i] = out["W"]
             c_min = min(c_min, out["c"])
             if stages:
-                R = ctx.fira_get_lowrank(i).numpy().astype(np.float64)
+                R = out["R"] if fused else ctx.fira_get_lowrank(i).numpy().astype(np.float64)
                 k = ctx.fira_get_factors(i).numpy().astype(np.float64)
                 s_pre, s_post, c = ctx.fira_get_diag(i)
                 e = dict(R=rel_max(R, out["R"]), k=rel_max(k, out["k"]),
@@ -131,7 +140,7 @@ def run_case(shapes: Sequence[Tuple[int, int]], rank, dtype: int, steps: int,
     for (s, i, e, d) in diag:
         by_step[s + 1] = max(by_step.get(s + 1, 0.0), e["W"])
     by_step[steps] = max([by_step.get(steps, 0.0)] + w_err)
-    return CaseResult(w_err, worst, c_min, ctx, W_dev, W_ref, states, diag, by_step)
+    return CaseResult(w_err, worst, c_min, ctx, W_dev, W_ref, states, diag, by_step, fused_steps)
 
 
 def workload_generators(wl: synth.Workload, proj: str = "svd"):
