@@ -346,8 +346,7 @@ fira_status fira_init_state(fira_ctx** out, const fira_matrix_desc* d, int count
     }                                                                                                \
   } while (0)
   // the contraction kernels use more dynamic LDS than the 64 KB default (gfx950 has 160 KB per CU)
-  FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_project_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_PROJ_LDS));
-  FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_project_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_PROJ_LDS));
+  FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_project_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_PROJ_LDS));
   FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_backproject_kernel<0, bf16_raw>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_BACK_LDS));
   FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_backproject_kernel<1, bf16_raw>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_BACK_LDS));
   FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_backproject_kernel<0, float>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_BACK_LDS));
@@ -474,6 +473,14 @@ fira_status fira_step(fira_ctx* ctx, int count, const int* idx, void* const* dev
   }
   auto grid8 = [](int n) { return dim3((unsigned)(((n + 7) / 8) * 8)); };
   const dim3 blk(FIRA_PROJ_THREADS);
+  // R = P^T G (long-side major) for both orientations in one launch
+  auto launch_project = [&](int norm_arg, const FiraScal* limited_only) {
+    const int nl = s->ntiles[kTilesProjectLeft], nr = s->ntiles[kTilesProjectRight];
+    const int bl = (nl + 7) / 8 * 8, br = (nr + 7) / 8 * 8;
+    if (nl + nr)
+      hipLaunchKernelGGL(fira_project_kernel, dim3(bl + br), blk, FIRA_PROJ_LDS, q, ctx->d_mats, s->d_ents,
+                         s->d_tiles[kTilesProjectLeft], nl, bl, s->d_tiles[kTilesProjectRight], nr, norm_arg, limited_only);
+  };
   // 0. Gram route, fp32 matrices only: ||G_i||^2 for every factor (bf16 matrices get it from step 1)
   const bool only_scaling = ctx->variant == FIRA_VARIANT_ONLY_SCALING;
   const int want_g2 = (ctx->norm_mode == FIRA_NORM_GRAM || only_scaling) ? 1 : 0;   // ||G_i||^2 per factor
@@ -512,13 +519,8 @@ fira_status fira_step(fira_ctx* ctx, int count, const int* idx, void* const* dev
     mark(1);
     mark(2);
   } else {
-    // 1. R = P^T G (long-side major), one launch per orientation
-    if (s->ntiles[kTilesProjectLeft])
-      hipLaunchKernelGGL(fira_project_kernel<true>, grid8(s->ntiles[kTilesProjectLeft]), blk, FIRA_PROJ_LDS, q,
-                         ctx->d_mats, s->d_ents, s->d_tiles[kTilesProjectLeft], s->ntiles[kTilesProjectLeft], want_g2, (const FiraScal*)nullptr);
-    if (s->ntiles[kTilesProjectRight])
-      hipLaunchKernelGGL(fira_project_kernel<false>, grid8(s->ntiles[kTilesProjectRight]), blk, FIRA_PROJ_LDS, q,
-                         ctx->d_mats, s->d_ents, s->d_tiles[kTilesProjectRight], s->ntiles[kTilesProjectRight], want_g2, (const FiraScal*)nullptr);
+    // 1. R = P^T G
+    launch_project(want_g2, (const FiraScal*)nullptr);
     mark(1);
     // 2. Adam on R, factor norms
     hipLaunchKernelGGL(fira_adam_kernel, dim3(s->rowblocks), dim3(256), ctx->plan.adam_lds, q, ctx->d_mats, ctx->d_scal, s->d_ents, count,
@@ -540,14 +542,7 @@ fira_status fira_step(fira_ctx* ctx, int count, const int* idx, void* const* dev
   mark(4);
   // 5. Z = N - c k R.  After the fused kernel R exists only for c = 1 (inside Z); the matrices with c < 1
   //    get it recomputed first (every other tile of these launches exits at once).
-  if (fused) {
-    if (s->ntiles[kTilesProjectLeft])
-      hipLaunchKernelGGL(fira_project_kernel<true>, grid8(s->ntiles[kTilesProjectLeft]), blk, FIRA_PROJ_LDS, q,
-                         ctx->d_mats, s->d_ents, s->d_tiles[kTilesProjectLeft], s->ntiles[kTilesProjectLeft], 0, (const FiraScal*)ctx->d_scal);
-    if (s->ntiles[kTilesProjectRight])
-      hipLaunchKernelGGL(fira_project_kernel<false>, grid8(s->ntiles[kTilesProjectRight]), blk, FIRA_PROJ_LDS, q,
-                         ctx->d_mats, s->d_ents, s->d_tiles[kTilesProjectRight], s->ntiles[kTilesProjectRight], 0, (const FiraScal*)ctx->d_scal);
-  }
+  if (fused) launch_project(0, (const FiraScal*)ctx->d_scal);
   if (!only_scaling)
     hipLaunchKernelGGL(fira_makez_kernel, dim3(count * FIRA_MAKEZ_PARTS), dim3(256), 0, q, ctx->d_mats, ctx->d_scal, s->d_ents, hp);
   mark(5);
@@ -884,6 +879,12 @@ fira_status fira_refresh_projectors(fira_ctx* ctx, int count, const int* idx, co
     hipLaunchKernelGGL(fira_refresh_chol_kernel, dim3(count), dim3(FIRA_CHOL_THREADS), 0, q, de);
     hipLaunchKernelGGL(fira_refresh_solve_kernel, dim3((max_S + 63) / 64, count), dim3(256), 0, q, de);
   };
+  auto launch_project = [&](const FiraMat* mats, const FiraEnt* ents_d, const FiraTile* tl, int nl, const FiraTile* tr, int nr) {
+    const int bl = (nl + 7) / 8 * 8, br = (nr + 7) / 8 * 8;
+    if (nl + nr)
+      hipLaunchKernelGGL(fira_project_kernel, dim3(bl + br), dim3(FIRA_PROJ_THREADS), FIRA_PROJ_LDS, q, mats, ents_d, tl, nl, bl, tr, nr, 0,
+                         (const FiraScal*)nullptr);
+  };
   for (int it = 0; it < iters; ++it) {
     // operands of Q (the fp32 Q becomes the matrix's projector copies; no gate estimate needed here)
     for (int e = 0; e < count; ++e) {
@@ -893,21 +894,13 @@ fira_status fira_refresh_projectors(fira_ctx* ctx, int count, const int* idx, co
       hipLaunchKernelGGL(fira_prep_projector_kernel<float>, dim3(grid), dim3(256), 0, q, h.dev, (const float*)ents[e].Q);
     }
     // T = G^T Q (or G Q): the projection kernel, norm route off
-    if (s->ntiles[kTilesProjectLeft])
-      hipLaunchKernelGGL(fira_project_kernel<true>, grid8(s->ntiles[kTilesProjectLeft]), dim3(FIRA_PROJ_THREADS), FIRA_PROJ_LDS, q,
-                         ctx->d_mats, s->d_ents, s->d_tiles[kTilesProjectLeft], s->ntiles[kTilesProjectLeft], 0, (const FiraScal*)nullptr);
-    if (s->ntiles[kTilesProjectRight])
-      hipLaunchKernelGGL(fira_project_kernel<false>, grid8(s->ntiles[kTilesProjectRight]), dim3(FIRA_PROJ_THREADS), FIRA_PROJ_LDS, q,
-                         ctx->d_mats, s->d_ents, s->d_tiles[kTilesProjectRight], s->ntiles[kTilesProjectRight], 0, (const FiraScal*)nullptr);
+    launch_project(ctx->d_mats, s->d_ents, s->d_tiles[kTilesProjectLeft], s->ntiles[kTilesProjectLeft],
+                   s->d_tiles[kTilesProjectRight], s->ntiles[kTilesProjectRight]);
     // pack T as the K-blocked operand of the way back
     hipLaunchKernelGGL(fira_refresh_pack_kernel, dim3((max_Lp / 32) * nt64, count), dim3(256), 0, q, d_ents);
-    // Y = G T (or G^T T): the projection kernel on the other orientation
-    if (rp.ntiles[0])
-      hipLaunchKernelGGL(fira_project_kernel<false>, grid8(rp.ntiles[0]), dim3(FIRA_PROJ_THREADS), FIRA_PROJ_LDS, q,
-                         d_vmats, d_vents, (const FiraTile*)(ws + rp.off_vtiles[0]), rp.ntiles[0], 0, (const FiraScal*)nullptr);
-    if (rp.ntiles[1])
-      hipLaunchKernelGGL(fira_project_kernel<true>, grid8(rp.ntiles[1]), dim3(FIRA_PROJ_THREADS), FIRA_PROJ_LDS, q,
-                         d_vmats, d_vents, (const FiraTile*)(ws + rp.off_vtiles[1]), rp.ntiles[1], 0, (const FiraScal*)nullptr);
+    // Y = G T (or G^T T): the projection kernel on the other orientation (list [1] is the K-slow one)
+    launch_project(d_vmats, d_vents, (const FiraTile*)(ws + rp.off_vtiles[1]), rp.ntiles[1],
+                   (const FiraTile*)(ws + rp.off_vtiles[0]), rp.ntiles[0]);
     // Q = orth(Y): CholeskyQR in fp64
     orthonormalise(d_ents);
   }

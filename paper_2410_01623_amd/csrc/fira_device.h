@@ -116,15 +116,13 @@ __device__ __forceinline__ bool use_gram(const FiraHp& hp, const FiraScal& sc) {
 
 
 // ---- bf16 helpers ---------------------------------------------------------------------------
-__device__ __forceinline__ bf16_raw f32_to_bf16(float x) {
-  unsigned u = __float_as_uint(x);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_raw)((u >> 16) | 0x40u);  // quiet NaN
-  u += 0x7fffu + ((u >> 16) & 1u);                                            // nearest even
-  return (bf16_raw)(u >> 16);
-}
+// fp32 -> bf16, nearest even (v_cvt_pk_bf16_f32: one instruction for two values; NaN stays NaN)
+__device__ __forceinline__ bf16_raw f32_to_bf16(float x) { return __builtin_bit_cast(bf16_raw, (__bf16)x); }
 __device__ __forceinline__ float bf16_to_f32(bf16_raw b) { return __uint_as_float(((unsigned)b) << 16); }
 __device__ __forceinline__ unsigned pack_bf16x2(float lo, float hi) {
-  return (unsigned)f32_to_bf16(lo) | ((unsigned)f32_to_bf16(hi) << 16);
+  typedef __bf16 bf16x2_v __attribute__((ext_vector_type(2)));
+  typedef float f32x2_v __attribute__((ext_vector_type(2)));
+  return __builtin_bit_cast(unsigned, __builtin_convertvector(f32x2_v{lo, hi}, bf16x2_v));
 }
 __device__ __forceinline__ void split3(float x, bf16_raw& h, bf16_raw& m, bf16_raw& l) {
   h = f32_to_bf16(x);

@@ -25,13 +25,13 @@ __device__ __forceinline__ float residual_sq(const FiraHp& hp, float g2, float r
 // Adam's direction for one element (Eqs. 2-4), N = bias * m / (sqrt(v) + eps), bias = sqrt(1 - beta2^t) /
 // (1 - beta1^t), from the hardware's square root and reciprocal (1 ulp each) rather than the correctly
 // rounded library forms, which cost about five times the instructions: in the fused kernel that
-// arithmetic is not hidden behind memory traffic.  v below 2^-64 is scaled into the instruction's
-// normal range first.  The result is within a few ulp of the exact quotient; they part only when
-// sqrt(v) + eps is itself subnormal (v = 0 and a subnormal eps).
+// arithmetic is not hidden behind memory traffic.  The square-root instruction takes no subnormal
+// input, so v is raised to the smallest normal number first: sqrt(v) then reads 1.1e-19 where it is
+// smaller, which only an eps of that order could tell apart.  Otherwise the result is within a few
+// ulp of the exact quotient.
 __device__ __forceinline__ float adam_direction(float m1, float v1, float bias, float eps) {
-  const bool tiny = v1 < 0x1p-64f;
-  const float s = __builtin_amdgcn_sqrtf(tiny ? v1 * 0x1p64f : v1);
-  return bias * m1 * __builtin_amdgcn_rcpf((tiny ? s * 0x1p-32f : s) + eps);
+  const float s = __builtin_amdgcn_sqrtf(fmaxf(v1, 0x1p-126f));
+  return bias * m1 * __builtin_amdgcn_rcpf(s + eps);
 }
 
 __device__ __forceinline__ float wave_sum(float x) {

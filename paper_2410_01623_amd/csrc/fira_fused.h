@@ -265,10 +265,12 @@ __device__ __forceinline__ void project_adam_tile(char* lds, const FiraMat* __re
   const bool interior = g.a_row0 + FIRA_PA <= g.a_rows && g.KA == g.KB;
   if (interior) {
     if (wave == 0) proj_pipeline<LEFT, true, true, RT>(acc, lds, g, sq);
-    else proj_pipeline<LEFT, true, false, RT>(acc, lds, g, sq);
+    else if (RT == 1 || wave < 4) proj_pipeline<LEFT, true, false, RT>(acc, lds, g, sq);
+    else proj_pipeline<LEFT, true, false, 2, false>(acc, lds, g, sq);
   } else {
     if (wave == 0) proj_pipeline<LEFT, false, true, RT>(acc, lds, g, sq);
-    else proj_pipeline<LEFT, false, false, RT>(acc, lds, g, sq);
+    else if (RT == 1 || wave < 4) proj_pipeline<LEFT, false, false, RT>(acc, lds, g, sq);
+    else proj_pipeline<LEFT, false, false, 2, false>(acc, lds, g, sq);
   }
   if (g.a_row0 + FIRA_PA <= mt.L && mt.r == 256 * RT) project_adam_epilogue<RT, true>(acc, lds, mt, hp, bias, g.a_row0, sq);
   else project_adam_epilogue<RT, false>(acc, lds, mt, hp, bias, g.a_row0, sq);

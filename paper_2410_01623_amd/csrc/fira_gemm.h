@@ -361,14 +361,17 @@ __device__ __forceinline__ void proj_compute(f32x16_t (&acc)[4][2], const char* 
 }
 
 // RT = rank tiles of 256 that one workgroup covers (256*RT threads, wave w owns rank rows 64 w ..).
-// With RT = 2 both tiles share the A tile, which only the first four wavefronts load and store; the
-// other four have no A requests in their queue, so their O-half wait is vmcnt(4) where a loading
-// wavefront's is vmcnt(8).
-template <bool LEFT, bool FAST, bool SUMSQ, int RT = 1>
+// With RT = 2 both tiles share the A tile, which only the first four wavefronts load and store
+// (LOADER); the other four have no A requests in their queue, so their O-half wait is vmcnt(4) where a
+// loading wavefront's is vmcnt(8).
+// (LOADER is a template parameter rather than a test inside, so that each kind of wavefront runs
+// straight-line code in which every request is followed by its own wait.)
+template <bool LEFT, bool FAST, bool SUMSQ, int RT = 1, bool LOADER = true>
 __device__ __forceinline__ void proj_pipeline(f32x16_t (&acc)[4][2], char* lds, const GemmOperands& g, float (&sq)[4]) {
+  static_assert(LOADER || RT == 2, "only the second rank tile's wavefronts go without the gradient");
   constexpr int STAGE = RT * FIRA_PROJ_RING_STAGE;
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const bool loader = RT == 1 || wave < 4;
+  constexpr bool loader = LOADER;
   char* la = lds;
   char* ring = lds + FIRA_PROJ_LDS_A;
   const unsigned ring0 = (unsigned)(size_t)(lds_ptr)ring;
@@ -417,15 +420,8 @@ __device__ __forceinline__ void proj_pipeline(f32x16_t (&acc)[4][2], char* lds, 
 }
 
 template <bool LEFT>
-__global__ __launch_bounds__(FIRA_PROJ_THREADS, 2) void fira_project_kernel(const FiraMat* __restrict__ mats,
-                                                                            const FiraEnt* __restrict__ ents,
-                                                                            const FiraTile* __restrict__ tiles,
-                                                                            int ntiles, int norm_mode,
-                                                                            const FiraScal* __restrict__ limited_only) {
-  extern __shared__ __attribute__((aligned(16))) char lds[];   // FIRA_PROJ_LDS bytes
-  const int ti = xcd_chunked_index(blockIdx.x, ntiles);
-  if (ti < 0) return;
-  const FiraTile tile = tiles[ti];
+__device__ __forceinline__ void project_tile(char* lds, const FiraMat* __restrict__ mats, const FiraEnt* __restrict__ ents,
+                                             const FiraTile& tile, int norm_mode, const FiraScal* __restrict__ limited_only) {
   const FiraEnt ent = ents[tile.ent];
   // Second use, after a step whose first kernel kept R in registers only: recompute R for the matrices
   // whose limiter factor came out below 1 (the correction of Z needs it); every other tile exits here.
@@ -494,6 +490,29 @@ __global__ __launch_bounds__(FIRA_PROJ_THREADS, 2) void fira_project_kernel(cons
         if (row < mt.L && col < mt.r) Rt[(long long)row * mt.r + col] = acc[tm][tn][v];
       }
     }
+}
+
+// One grid for both orientations: workgroups [0, blocks_left) take the tiles of the matrices with
+// m <= n (gradient K-slow), the rest those with m > n, so that only one partly filled round of
+// workgroups ends the launch.  blocks_left is a multiple of 8, which keeps the XCD-aware mapping of
+// each part.
+__global__ __launch_bounds__(FIRA_PROJ_THREADS, 2) void fira_project_kernel(const FiraMat* __restrict__ mats,
+                                                                            const FiraEnt* __restrict__ ents,
+                                                                            const FiraTile* __restrict__ tiles_left, int ntiles_left,
+                                                                            int blocks_left,
+                                                                            const FiraTile* __restrict__ tiles_right, int ntiles_right,
+                                                                            int norm_mode,
+                                                                            const FiraScal* __restrict__ limited_only) {
+  extern __shared__ __attribute__((aligned(16))) char lds[];   // FIRA_PROJ_LDS bytes
+  if ((int)blockIdx.x < blocks_left) {
+    const int ti = xcd_chunked_index(blockIdx.x, ntiles_left);
+    if (ti < 0) return;
+    project_tile<true>(lds, mats, ents, tiles_left[ti], norm_mode, limited_only);
+  } else {
+    const int ti = xcd_chunked_index((int)blockIdx.x - blocks_left, ntiles_right);
+    if (ti < 0) return;
+    project_tile<false>(lds, mats, ents, tiles_right[ti], norm_mode, limited_only);
+  }
 }
 
 // ------------------------------------------------------------------------------------------------

@@ -459,6 +459,28 @@ def test_list_order_and_subsets():
     ctx.fira_step([], [], [])   # empty list: nothing to do
 
 
+def test_device_bf16_rounding_is_nearest_even():
+    """Everything the library stores in bf16 goes through one conversion; an fp32 projector comes back
+    from fira_get_projector as the values it was rounded to.  They must equal round-to-nearest-even bit
+    for bit, including exact ties, values next to ties, subnormal results, and the overflow to infinity."""
+    m, n, r = 64, 96, 16
+    rng = np.random.default_rng(3)
+    P = (rng.standard_normal((m, r)) * np.exp(rng.uniform(-30, 30, (m, r)))).astype(np.float32)
+    bits = P.view(np.uint32).copy()
+    bits[0, :] = (bits[0, :] & 0xFFFF0000) | 0x8000            # exact ties, even and odd kept mantissas
+    bits[1, :] = (bits[1, :] & 0xFFFF0000) | 0x7FFF            # just below a tie
+    bits[2, :] = (bits[2, :] & 0xFFFF0000) | 0x8001            # just above a tie
+    bits[3, :] = (bits[3, :] & 0x80000000) | 0x7F7FFFFF        # largest finite fp32: rounds to infinity
+    bits[4, :] = (bits[4, :] & 0x80000000) | (np.arange(r, dtype=np.uint32) * 0x4321 + 1)   # fp32 subnormals
+    bits[5, :] = 0x7F7F8000 - np.arange(r, dtype=np.uint32)    # around the largest finite bf16's tie
+    P = bits.view(np.float32)
+    ctx = fira.FiraContext([(m, n)], r, fira.FIRA_BF16, fira.make_hparams())
+    ctx.fira_set_projector(0, torch.from_numpy(P).to(H.DEV))
+    got = ctx.fira_get_projector(0).numpy()
+    want = synth.as_bf16_values(P)
+    assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
+
+
 def test_projector_switch_keeps_state_and_errors_are_reported():
     shapes, W0, Gs, Ps = _three_matrices()
     ctx = fira.FiraContext(shapes, 16, fira.FIRA_BF16, fira.make_hparams())

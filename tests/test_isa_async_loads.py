@@ -1,5 +1,5 @@
-"""The projection kernel requests its gradient tiles with inline-assembly loads and waits for them
-with explicit queue depths.  This compiles the device code to assembly (no GPU needed) and checks that
+"""The projection kernels (plain, and fused with Adam) request their gradient tiles with inline-assembly
+loads and wait for them with explicit queue depths.  This compiles the device code to assembly (no GPU needed) and checks that
 the compiler never touches a register between such a load and the wait that covers it."""
 import os
 import shutil
@@ -20,8 +20,8 @@ def test_registers_of_asynchronous_loads_are_untouched_until_their_wait(tmp_path
     cmd = [hipcc, *flags, "--cuda-device-only", "-S", os.path.join(build.CSRC, "fira.hip"), "-o", str(out)]
     res = subprocess.run(cmd, capture_output=True, text=True)
     assert res.returncode == 0, res.stderr[-2000:]
-    ks = {k: v for k, v in isa_async_check.kernels(out.read_text()).items() if "fira_project_kernel" in k}
-    assert len(ks) == 2, list(ks)
+    ks = {k: v for k, v in isa_async_check.kernels(out.read_text()).items() if "fira_project" in k}
+    assert len(ks) == 3, list(ks)   # fira_project_kernel, fira_project_adam_kernel<1>, <2>
     for name, body in ks.items():
         n, loads, viol = isa_async_check.check_kernel(body)
         assert loads >= 8, f"{name}: expected the pipelined loads, found {loads}"
