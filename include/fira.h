@@ -129,7 +129,7 @@ typedef enum { FIRA_VARIANT_FULL = 0, FIRA_VARIANT_ONLY_SCALING = 1 } fira_varia
 FIRA_API fira_status fira_set_variant(fira_ctx* ctx, fira_variant variant);
 
 /* Kernel fusion (on by default).  A step in which every listed matrix is bf16 with r % 4 == 0 and
- * r <= 512, with column factors (Eq. 10), Algorithm 1 proper and the Gram route to ||S_t|| in force for
+ * 128 <= r <= 512, with column factors (Eq. 10), Algorithm 1 proper and the Gram route to ||S_t|| in force for
  * all of them, runs the projection R = P^T G and Adam (Eqs. 2-4) in one kernel that keeps R in
  * registers; any other step, and every step with enable == 0, runs them as two kernels with R in
  * memory.  Both compute the same quantities; sums are taken in a different order, so results agree to

@@ -133,7 +133,7 @@ bool make_plan(const fira_matrix_desc* d, int count, Plan* plan, fira_status* st
     h.g2blocks = m.left ? (m.n + 255) / 256 : (m.m + FIRA_G2_ROWS_PER_WG - 1) / FIRA_G2_ROWS_PER_WG;
     total_tiles[m.left ? kTilesProjectLeft : kTilesProjectRight] += h.tiles_project;
     total_tiles[m.dtype == FIRA_BF16 ? kTilesBackBf16 : kTilesBackF32] += h.tiles_back;
-    if (m.zready && m.r <= FIRA_FUSE_MAX_R) {
+    if (m.zready && m.r >= FIRA_FUSE_MIN_R && m.r <= FIRA_FUSE_MAX_R) {
       h.fuse_list = kTilesFuse + 2 * (m.r > 256 ? 1 : 0) + (m.left ? 0 : 1);
       total_tiles[h.fuse_list] += h.ta_project;
     }

@@ -25,7 +25,7 @@
 // 10" at the end of a chunk means the next chunk has landed while this chunk's stores may still be in
 // flight.  Edge tiles skip rows and columns and wait for everything instead.
 //
-// A step takes this kernel only if every listed matrix is bf16 with r % 4 == 0, r <= 512, column
+// A step takes this kernel only if every listed matrix is bf16 with r % 4 == 0, 128 <= r <= 512, column
 // factors, Algorithm 1 proper, and the Gram route to ||S|| (no operand copy of R is made here).
 // The limiter runs after it; for a matrix whose factor c came out below 1, R is recomputed by
 // fira_project_kernel (limited_only) and Z corrected by fira_makez_kernel.
@@ -35,6 +35,7 @@
 #include "fira_gemm.h"
 
 #define FIRA_FUSE_MAX_R 512
+#define FIRA_FUSE_MIN_R 128   // below half a rank tile the epilogue works mostly on padding; the two-kernel path is faster
 #define FIRA_FUSE_F 16   // factors per chunk of the epilogue
 #define FIRA_FUSE_LDS_MAIN(RT) (FIRA_PROJ_LDS_A + FIRA_RING_STAGES * (RT) * FIRA_PROJ_RING_STAGE)
 // two landing buffers (M and V of a chunk, fp32), the Z image (bf16), per-wave sums, ||G_i||^2 of the tile, k_i
