@@ -134,8 +134,8 @@ FIRA_API fira_status fira_set_variant(fira_ctx* ctx, fira_variant variant);
  * registers; any other step, and every step with enable == 0, runs them as two kernels with R in
  * memory.  Both compute the same quantities; sums are taken in a different order, so results agree to
  * rounding, not bit for bit.  fira_last_step_fused: 1 if the last fira_step on ctx took the fused
- * kernel, 0 if not (or ctx is NULL).  After a fused step fira_get_lowrank has R only for the matrices
- * whose limiter factor was below 1. */
+ * kernel, 0 if not (or ctx is NULL).  A fused step keeps no copy of R: fira_get_lowrank then returns
+ * what an earlier two-kernel step left (zeros if there was none). */
 FIRA_API fira_status fira_set_fusion(fira_ctx* ctx, int enable);
 FIRA_API int fira_last_step_fused(const fira_ctx* ctx);
 

@@ -216,6 +216,7 @@ FiraHp make_hp(const fira_ctx* ctx) {
   h.scaling = ctx->scaling;
   h.norm_mode = ctx->norm_mode;
   h.variant = ctx->variant;
+  h.fused = 0;
   h.ortho_tol = 0.02f;   // bf16-rounded orthonormal projectors measure ~1e-3; 0.02 bounds the error of ||S|| by ~1 %
   return h;
 }
@@ -455,7 +456,7 @@ fira_status fira_step(fira_ctx* ctx, int count, const int* idx, void* const* dev
   fira_status st;
   ListSlot* s = acquire_list(ctx, count, idx, dev_W, dev_G, &st);
   if (!s) return fail(ctx, st, "building the work list failed");
-  const FiraHp hp = make_hp(ctx);
+  FiraHp hp = make_hp(ctx);
   hipStream_t q = ctx->stream;
   hipEvent_t* pe = nullptr;
   if (ctx->prof_steps < ctx->prof_max_steps) pe = &ctx->prof_events[(size_t)ctx->prof_steps++ * (FIRA_NUM_KERNELS + 1)];
@@ -474,12 +475,12 @@ fira_status fira_step(fira_ctx* ctx, int count, const int* idx, void* const* dev
   auto grid8 = [](int n) { return dim3((unsigned)(((n + 7) / 8) * 8)); };
   const dim3 blk(FIRA_PROJ_THREADS);
   // R = P^T G (long-side major) for both orientations in one launch
-  auto launch_project = [&](int norm_arg, const FiraScal* limited_only) {
+  auto launch_project = [&](int norm_arg) {
     const int nl = s->ntiles[kTilesProjectLeft], nr = s->ntiles[kTilesProjectRight];
     const int bl = (nl + 7) / 8 * 8, br = (nr + 7) / 8 * 8;
     if (nl + nr)
       hipLaunchKernelGGL(fira_project_kernel, dim3(bl + br), blk, FIRA_PROJ_LDS, q, ctx->d_mats, s->d_ents,
-                         s->d_tiles[kTilesProjectLeft], nl, bl, s->d_tiles[kTilesProjectRight], nr, norm_arg, limited_only);
+                         s->d_tiles[kTilesProjectLeft], nl, bl, s->d_tiles[kTilesProjectRight], nr, norm_arg);
   };
   // 0. Gram route, fp32 matrices only: ||G_i||^2 for every factor (bf16 matrices get it from step 1)
   const bool only_scaling = ctx->variant == FIRA_VARIANT_ONLY_SCALING;
@@ -502,6 +503,7 @@ fira_status fira_step(fira_ctx* ctx, int count, const int* idx, void* const* dev
   bool fused = ctx->fusion && !only_scaling && ctx->scaling == FIRA_SCALE_COLUMN && ctx->norm_mode == FIRA_NORM_GRAM && !need_residual;
   for (int e = 0; e < count && fused; ++e) fused = ctx->plan.mats[idx[e]].fuse_list >= 0;
   ctx->last_step_fused = fused;
+  hp.fused = fused ? 1 : 0;
   if (fused) {
     // 1+2. R = P^T G, Adam on it, factor norms, Z for c = 1
     for (int rt = 1; rt <= 2; ++rt) {
@@ -520,7 +522,7 @@ fira_status fira_step(fira_ctx* ctx, int count, const int* idx, void* const* dev
     mark(2);
   } else {
     // 1. R = P^T G
-    launch_project(want_g2, (const FiraScal*)nullptr);
+    launch_project(want_g2);
     mark(1);
     // 2. Adam on R, factor norms
     hipLaunchKernelGGL(fira_adam_kernel, dim3(s->rowblocks), dim3(256), ctx->plan.adam_lds, q, ctx->d_mats, ctx->d_scal, s->d_ents, count,
@@ -540,9 +542,7 @@ fira_status fira_step(fira_ctx* ctx, int count, const int* idx, void* const* dev
   // 4. limiter factor, state advance
   hipLaunchKernelGGL(fira_limiter_kernel, dim3(count), dim3(FIRA_LIMITER_THREADS), 0, q, ctx->d_mats, ctx->d_scal, s->d_ents, ctx->d_partial, hp);
   mark(4);
-  // 5. Z = N - c k R.  After the fused kernel R exists only for c = 1 (inside Z); the matrices with c < 1
-  //    get it recomputed first (every other tile of these launches exits at once).
-  if (fused) launch_project(0, (const FiraScal*)ctx->d_scal);
+  // 5. Z = N - c k R (after the fused kernel, which keeps no R: Z = c Z_1 + (1 - c) N for the matrices with c < 1)
   if (!only_scaling)
     hipLaunchKernelGGL(fira_makez_kernel, dim3(count * FIRA_MAKEZ_PARTS), dim3(256), 0, q, ctx->d_mats, ctx->d_scal, s->d_ents, hp);
   mark(5);
@@ -882,8 +882,7 @@ fira_status fira_refresh_projectors(fira_ctx* ctx, int count, const int* idx, co
   auto launch_project = [&](const FiraMat* mats, const FiraEnt* ents_d, const FiraTile* tl, int nl, const FiraTile* tr, int nr) {
     const int bl = (nl + 7) / 8 * 8, br = (nr + 7) / 8 * 8;
     if (nl + nr)
-      hipLaunchKernelGGL(fira_project_kernel, dim3(bl + br), dim3(FIRA_PROJ_THREADS), FIRA_PROJ_LDS, q, mats, ents_d, tl, nl, bl, tr, nr, 0,
-                         (const FiraScal*)nullptr);
+      hipLaunchKernelGGL(fira_project_kernel, dim3(bl + br), dim3(FIRA_PROJ_THREADS), FIRA_PROJ_LDS, q, mats, ents_d, tl, nl, bl, tr, nr, 0);
   };
   for (int it = 0; it < iters; ++it) {
     // operands of Q (the fp32 Q becomes the matrix's projector copies; no gate estimate needed here)

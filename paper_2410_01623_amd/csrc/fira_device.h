@@ -105,6 +105,7 @@ struct FiraHp {     // hyper-parameters as the kernels take them
   int norm_mode;    // 0: ||S|| from the residual tiles; 1: from ||G_i||^2 - ||R_i||^2 where P passes the gate
   float ortho_tol;  // gate of the Gram mode on FiraScal::ortho_err
   int variant;      // 0: Algorithm 1; 1: factors on the full gradient, no Adam term ("Fira-only-scaling")
+  int fused;        // 1: this step's projection and Adam ran as one kernel (no copy of R exists)
 };
 
 // Whether matrix `sc` takes the Gram route to ||S||^2 in this step.

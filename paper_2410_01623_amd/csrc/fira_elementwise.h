@@ -418,6 +418,28 @@ __device__ __forceinline__ void fixz_row(const FiraMat& mt, float f, long long r
   }
 }
 
+// The same correction without R (after the fused kernel): Z = N - c k R = c (N - k R) + (1 - c) N, with N
+// formed again from the updated M and V.  c Z_1 carries Z_1's bf16 rounding, so Z is rounded twice
+// here; that happens only on the steps on which the limiter is active.
+__device__ __forceinline__ void fixz_row_from_moments(const FiraMat& mt, const FiraHp& hp, float c, float bias, long long row) {
+  const int lane = threadIdx.x & 63;
+  gptr<bf16_raw> Nb = as_global(mt.Nb);
+  gptr<const float> M = as_global<const float>(mt.M) + row * mt.r;
+  gptr<const float> V = as_global<const float>(mt.V) + row * mt.r;
+  for (int a = lane * 4; a < mt.r; a += 256) {
+    const long long o = kblk_index(mt.Lq, row, a);
+    const u32x2 zv = *reinterpret_cast<gptr<const u32x2>>(Nb + o);
+    const f32x4 mv = *reinterpret_cast<gptr<const f32x4>>(M + a);
+    const f32x4 vv = *reinterpret_cast<gptr<const f32x4>>(V + a);
+    const float z1[4] = {__uint_as_float(zv.x << 16), __uint_as_float(zv.x & 0xffff0000u), __uint_as_float(zv.y << 16),
+                         __uint_as_float(zv.y & 0xffff0000u)};
+    float z[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) z[e] = c * z1[e] + (1.0f - c) * adam_direction(mv[e], vv[e], bias, hp.epsf);
+    *reinterpret_cast<gptr<u32x2>>(Nb + o) = u32x2{pack_bf16x2(z[0], z[1]), pack_bf16x2(z[2], z[3])};
+  }
+}
+
 #define FIRA_MAKEZ_PARTS 32   // workgroups per listed matrix
 // One workgroup per (listed matrix, part): it reads the matrix's c once and, in the common case, exits;
 // otherwise it takes every FIRA_MAKEZ_PARTS-th block of 16 rows.
@@ -432,13 +454,17 @@ __global__ __launch_bounds__(256) void fira_makez_kernel(const FiraMat* __restri
   if (zready && c == 1.0f) return;             // the Adam kernel already wrote Z for c = 1
   const int wave = threadIdx.x >> 6;
   const int rowblocks = (mt.L + FIRA_ROWS_PER_WG - 1) / FIRA_ROWS_PER_WG;
+  // the limiter has already advanced t: the bias correction of this step uses the count as it stands now
+  const int t = scal[ent.mat].t;
+  const float bias = hp.fused ? (float)(sqrt(1.0 - pow(hp.beta2, (double)t)) / (1.0 - pow(hp.beta1, (double)t))) : 0.0f;
   for (int rb = part; rb < rowblocks; rb += FIRA_MAKEZ_PARTS) {
     const long long row_base = (long long)rb * FIRA_ROWS_PER_WG + wave * 4;
     for (int i = 0; i < 4; ++i) {
       const long long row = row_base + i;
       if (row >= mt.L) break;
       const float k = as_global<const float>(mt.phi)[row];
-      if (zready) fixz_row(mt, (1.0f - c) * k, row);
+      if (zready && hp.fused) fixz_row_from_moments(mt, hp, c, bias, row);
+      else if (zready) fixz_row(mt, (1.0f - c) * k, row);
       else if (mt.kx == 1) makez_row<1>(mt, c * k, row);
       else makez_row<FIRA_KX_SPLIT>(mt, c * k, row);
     }

@@ -27,8 +27,8 @@
 //
 // A step takes this kernel only if every listed matrix is bf16 with r % 4 == 0, 128 <= r <= 512, column
 // factors, Algorithm 1 proper, and the Gram route to ||S|| (no operand copy of R is made here).
-// The limiter runs after it; for a matrix whose factor c came out below 1, R is recomputed by
-// fira_project_kernel (limited_only) and Z corrected by fira_makez_kernel.
+// The limiter runs after it; for a matrix whose factor c came out below 1, fira_makez_kernel turns the Z
+// written here (for c = 1) into c Z + (1 - c) N, with N formed again from the updated M and V.
 #pragma once
 #include "fira_device.h"
 #include "fira_elementwise.h"

@@ -421,11 +421,8 @@ __device__ __forceinline__ void proj_pipeline(f32x16_t (&acc)[4][2], char* lds, 
 
 template <bool LEFT>
 __device__ __forceinline__ void project_tile(char* lds, const FiraMat* __restrict__ mats, const FiraEnt* __restrict__ ents,
-                                             const FiraTile& tile, int norm_mode, const FiraScal* __restrict__ limited_only) {
+                                             const FiraTile& tile, int norm_mode) {
   const FiraEnt ent = ents[tile.ent];
-  // Second use, after a step whose first kernel kept R in registers only: recompute R for the matrices
-  // whose limiter factor came out below 1 (the correction of Z needs it); every other tile exits here.
-  if (limited_only && limited_only[ent.mat].c == 1.0f) return;
   const FiraMat mt = mats[ent.mat];
 
   GemmOperands g;
@@ -501,17 +498,16 @@ __global__ __launch_bounds__(FIRA_PROJ_THREADS, 2) void fira_project_kernel(cons
                                                                             const FiraTile* __restrict__ tiles_left, int ntiles_left,
                                                                             int blocks_left,
                                                                             const FiraTile* __restrict__ tiles_right, int ntiles_right,
-                                                                            int norm_mode,
-                                                                            const FiraScal* __restrict__ limited_only) {
+                                                                            int norm_mode) {
   extern __shared__ __attribute__((aligned(16))) char lds[];   // FIRA_PROJ_LDS bytes
   if ((int)blockIdx.x < blocks_left) {
     const int ti = xcd_chunked_index(blockIdx.x, ntiles_left);
     if (ti < 0) return;
-    project_tile<true>(lds, mats, ents, tiles_left[ti], norm_mode, limited_only);
+    project_tile<true>(lds, mats, ents, tiles_left[ti], norm_mode);
   } else {
     const int ti = xcd_chunked_index((int)blockIdx.x - blocks_left, ntiles_right);
     if (ti < 0) return;
-    project_tile<false>(lds, mats, ents, tiles_right[ti], norm_mode, limited_only);
+    project_tile<false>(lds, mats, ents, tiles_right[ti], norm_mode);
   }
 }
 

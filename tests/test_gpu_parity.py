@@ -225,15 +225,19 @@ def test_config2_llama60m_shapes_with_projector_refresh():
         assert torch.equal(res.W_dev[i], res.W_dev[i % 7]), f"matrix {i} differs from its twin"
 
 
-def test_config3_llama350m_shapes_spike():
+@pytest.mark.parametrize("norm_mode", [fira.FIRA_NORM_RESIDUAL, fira.FIRA_NORM_GRAM], ids=["residual", "gram_fused"])
+def test_config3_llama350m_shapes_spike(norm_mode):
     """168 matrices, r = 256, bf16, Student-t gradients, 20x spike at step 40.  Blocks 1..23 are fed
-    block 0's inputs (and must agree with it bit for bit); the oracle follows block 0."""
+    block 0's inputs (and must agree with it bit for bit); the oracle follows block 0.  On the Gram
+    route the step takes the fused projection/Adam kernel (one rank tile per workgroup), and the spike
+    sends every matrix through the recomputation of R for c < 1."""
     wl = synth.WORKLOADS["llama350m_r256_bf16"]
     gw, gg, gp = H.workload_generators(wl, "random")
     steps = 44
     alias = {i: i % 7 for i in range(7, wl.n_matrices)}
     res = H.run_case(wl.shapes, wl.rank, fira.FIRA_BF16, steps, gw, gg, gp, orc.OracleHparams(),
-                     check=list(range(7)), alias=alias)
+                     check=list(range(7)), alias=alias, norm_mode=norm_mode)
+    assert res.fused_steps == (steps if norm_mode == fira.FIRA_NORM_GRAM else 0)
     check(res, fira.FIRA_BF16)
     fired = [d["c"][1] for s, i, e, d in res.diag if s == 40]
     assert len(fired) == 7 and max(fired) < 0.9, "the spike must be limited on every matrix"
