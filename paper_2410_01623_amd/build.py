@@ -33,5 +33,23 @@ def build_library(verbose: bool = True, extra_flags=()) -> str:
     return LIB_PATH
 
 
+MICROBENCH_PATH = os.path.join(PKG_DIR, "fira_microbench")
+
+
+def build_microbench(verbose: bool = True) -> str:
+    """The machine-calibration program (HBM streams, MFMA rate, LDS read rate); not part of the library."""
+    hipcc = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
+    flags = [f for f in HIPCC_FLAGS if f not in ("-shared", "-fPIC", "-fvisibility=hidden")]
+    cmd = [hipcc, *flags, os.path.join(CSRC, "fira_microbench.hip"), "-o", MICROBENCH_PATH]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    err = "\n".join(l for l in res.stderr.splitlines() if "packed-fp32-ops" not in l)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + err)
+    return MICROBENCH_PATH
+
+
 if __name__ == "__main__":
     print(build_library())
+    print(build_microbench())

@@ -1,0 +1,150 @@
+// Machine calibration for the roofline figures: what one MI355X actually sustains for the three resources
+// the Fira step leans on, measured with the simplest kernels that use nothing else.
+//   read / write / copy : HBM streams over buffers far larger than the caches (16 bytes per lane,
+//                         workgroups striding through the buffer, non-temporal accesses)
+//   mfma                : v_mfma_f32_32x32x16_bf16 on register operands, 8 independent accumulator blocks
+//                         per wavefront (the shape of the step's contractions), 1 or 2 wavefronts per SIMD
+//   lds                 : ds_read_b128 fragment reads, all wavefronts of a CU at once
+// Prints one line per measurement.  Everything is in bounds and every loop has a fixed trip count.
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <cstdlib>
+#include <vector>
+
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
+
+#define CHECK(call)                                                                         \
+  do {                                                                                      \
+    hipError_t e_ = (call);                                                                 \
+    if (e_ != hipSuccess) {                                                                 \
+      std::fprintf(stderr, "%s: %s\n", #call, hipGetErrorString(e_));                       \
+      std::exit(1);                                                                         \
+    }                                                                                       \
+  } while (0)
+
+// MODE 0: read, 1: write, 2: copy.  n16 = number of 16-byte pieces; the grid strides through them.
+template <int MODE>
+__global__ __launch_bounds__(256) void stream_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst, size_t n16,
+                                                     unsigned* __restrict__ sink) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  u32x4 acc = u32x4{0u, 0u, 0u, 0u};
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) {
+    if (MODE == 0) acc ^= __builtin_nontemporal_load(src + i);
+    if (MODE == 1) __builtin_nontemporal_store(u32x4{(unsigned)i, 1u, 2u, 3u}, dst + i);
+    if (MODE == 2) __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
+  }
+  if (MODE == 0 && (acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9e3779b9u) sink[0] = 1u;   // keeps the loads alive
+}
+
+__global__ __launch_bounds__(256) void mfma_kernel(int iters, float* __restrict__ sink) {
+  f32x16_t acc[4][2];
+#pragma unroll
+  for (int a = 0; a < 4; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.0f;
+  bf16x8_t fa[4], fb[2];
+#pragma unroll
+  for (int a = 0; a < 4; ++a)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) fa[a][e] = (__bf16)(float)((threadIdx.x + a + e) & 7);
+#pragma unroll
+  for (int b = 0; b < 2; ++b)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) fb[b][e] = (__bf16)(float)((threadIdx.x + 3 * b + e) & 3);
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+      for (int b = 0; b < 2; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
+  }
+  float s = 0.0f;
+#pragma unroll
+  for (int a = 0; a < 4; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b) s += acc[a][b][0];
+  if (s == 12345.678f) sink[0] = s;
+}
+
+// every lane reads 16 bytes per instruction from a 64 KB LDS array, consecutive lanes consecutive pieces
+__global__ __launch_bounds__(256) void lds_kernel(int iters, unsigned* __restrict__ sink) {
+  __shared__ u32x4 buf[4096];
+  for (int i = threadIdx.x; i < 4096; i += 256) buf[i] = u32x4{(unsigned)i, 0u, 0u, 0u};
+  __syncthreads();
+  u32x4 acc = u32x4{0u, 0u, 0u, 0u};
+  int p = threadIdx.x;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc ^= buf[(p + 256 * u) & 4095];
+    p = (p + 64) & 4095;
+  }
+  if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9e3779b9u) sink[0] = 1u;
+}
+
+template <typename F>
+static double time_ms(F launch, int reps) {
+  hipEvent_t e0, e1;
+  CHECK(hipEventCreate(&e0));
+  CHECK(hipEventCreate(&e1));
+  launch();
+  CHECK(hipDeviceSynchronize());
+  CHECK(hipEventRecord(e0, 0));
+  for (int r = 0; r < reps; ++r) launch();
+  CHECK(hipEventRecord(e1, 0));
+  CHECK(hipEventSynchronize(e1));
+  float ms = 0.0f;
+  CHECK(hipEventElapsedTime(&ms, e0, e1));
+  CHECK(hipGetLastError());
+  CHECK(hipEventDestroy(e0));
+  CHECK(hipEventDestroy(e1));
+  return ms / reps;
+}
+
+int main() {
+  hipDeviceProp_t prop;
+  CHECK(hipGetDeviceProperties(&prop, 0));
+  const int cus = prop.multiProcessorCount;
+  std::printf("device: %s, %d CUs, %.0f MHz, %.1f GiB, %zu KiB LDS per workgroup\n", prop.name, cus, prop.clockRate / 1e3,
+              prop.totalGlobalMem / 1073741824.0, prop.sharedMemPerBlock / 1024);
+  const size_t bytes = (size_t)4 << 30, n16 = bytes / 16;
+  u32x4 *a = nullptr, *b = nullptr;
+  unsigned* sink = nullptr;
+  CHECK(hipMalloc(&a, bytes));
+  CHECK(hipMalloc(&b, bytes));
+  CHECK(hipMalloc(&sink, 256));
+  CHECK(hipMemset(a, 1, bytes));
+  CHECK(hipMemset(b, 2, bytes));
+  for (int wg_per_cu : {4, 8, 16}) {
+    const dim3 grid(cus * wg_per_cu), blk(256);
+    const double tr = time_ms([&] { hipLaunchKernelGGL(stream_kernel<0>, grid, blk, 0, 0, a, b, n16, sink); }, 5);
+    const double tw = time_ms([&] { hipLaunchKernelGGL(stream_kernel<1>, grid, blk, 0, 0, a, b, n16, sink); }, 5);
+    const double tc = time_ms([&] { hipLaunchKernelGGL(stream_kernel<2>, grid, blk, 0, 0, a, b, n16, sink); }, 5);
+    std::printf("hbm, 4 GiB, %2d workgroups per CU: read %.0f GB/s, write %.0f GB/s, copy %.0f GB/s (read + write bytes)\n", wg_per_cu,
+                bytes / tr / 1e6, bytes / tw / 1e6, 2.0 * bytes / tc / 1e6);
+  }
+  const double tm = time_ms([&] { CHECK(hipMemcpyAsync(b, a, bytes, hipMemcpyDeviceToDevice, 0)); }, 5);
+  std::printf("hbm, hipMemcpyAsync device to device, 4 GiB: %.0f GB/s (read + write bytes)\n", 2.0 * bytes / tm / 1e6);
+  for (int waves_per_simd : {1, 2}) {
+    const int iters = 4000;
+    const dim3 grid(cus * waves_per_simd), blk(256);   // one workgroup = four wavefronts = one per SIMD
+    const double t = time_ms([&] { hipLaunchKernelGGL(mfma_kernel, grid, blk, 0, 0, iters, (float*)sink); }, 5);
+    const double flop = (double)grid.x * 4 * iters * 8 * (2.0 * 32 * 32 * 16);
+    std::printf("mfma 32x32x16 bf16, %d wavefront(s) per SIMD: %.0f TFLOP/s\n", waves_per_simd, flop / t / 1e9);
+  }
+  {
+    const int iters = 4000;
+    const dim3 grid(cus * 2), blk(256);
+    const double t = time_ms([&] { hipLaunchKernelGGL(lds_kernel, grid, blk, 0, 0, iters, sink); }, 5);
+    const double by = (double)grid.x * 256 * iters * 8 * 16;
+    std::printf("lds ds_read_b128, 8 wavefronts per CU: %.1f TB/s (%.0f bytes per clock per CU at %.0f MHz)\n", by / t / 1e9,
+                by / t / 1e3 / cus / (prop.clockRate / 1e3) * 1e3 / 1e3, prop.clockRate / 1e3);
+  }
+  CHECK(hipFree(a));
+  CHECK(hipFree(b));
+  CHECK(hipFree(sink));
+  return 0;
+}
