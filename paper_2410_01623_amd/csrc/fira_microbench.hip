@@ -39,6 +39,35 @@ __global__ __launch_bounds__(256) void stream_kernel(const u32x4* __restrict__ s
   if (MODE == 0 && (acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9e3779b9u) sink[0] = 1u;   // keeps the loads alive
 }
 
+// Tile-shaped streams, the access pattern of the update's epilogue: the matrix has `rows` rows of
+// row_bytes bytes; a workgroup takes a tile of 64 KB, tile_bytes bytes wide, and walks down its rows,
+// a wavefront instruction covering 1 KB = 1024 / tile_bytes rows (or a quarter of a 4 KB row piece).
+// Tiles are numbered down the rows first, and consecutive workgroup ids go round the 8 XCDs.
+// MODE 0: read, 1: write, 2: read-modify-write (W), 3: read two, write one (G and W -> W)
+template <int MODE>
+__global__ __launch_bounds__(256) void tile_kernel(const char* __restrict__ src, const char* __restrict__ src2, char* __restrict__ dst,
+                                                   long long rows, long long row_bytes, int tile_bytes, unsigned* __restrict__ sink) {
+  const int tile_rows = 65536 / tile_bytes;
+  const long long tiles_down = rows / tile_rows, ntiles = tiles_down * (row_bytes / tile_bytes);
+  const int per = (int)((ntiles + 7) / 8);
+  const long long t = (long long)(blockIdx.x & 7) * per + (blockIdx.x >> 3);
+  if ((blockIdx.x >> 3) >= per || t >= ntiles) return;
+  const long long r0 = (t % tiles_down) * tile_rows, c0 = (t / tiles_down) * tile_bytes;
+  const int pieces = tile_bytes / 16;              // 16-byte pieces per tile row
+  u32x4 acc = u32x4{0u, 0u, 0u, 0u};
+  for (int i = threadIdx.x; i < 4096; i += 256) {  // 4096 pieces per tile
+    const long long off = (r0 + i / pieces) * row_bytes + c0 + (long long)(i % pieces) * 16;
+    if (MODE == 0) acc ^= __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + off));
+    if (MODE == 1) __builtin_nontemporal_store(u32x4{(unsigned)i, 1u, 2u, 3u}, reinterpret_cast<u32x4*>(dst + off));
+    if (MODE == 2) __builtin_nontemporal_store(__builtin_nontemporal_load(reinterpret_cast<const u32x4*>(dst + off)) + 1u, reinterpret_cast<u32x4*>(dst + off));
+    if (MODE == 3)
+      __builtin_nontemporal_store(__builtin_nontemporal_load(reinterpret_cast<const u32x4*>(dst + off)) +
+                                      __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + off)),
+                                  reinterpret_cast<u32x4*>(dst + off));
+  }
+  if (MODE == 0 && (acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9e3779b9u) sink[0] = 1u;
+}
+
 __global__ __launch_bounds__(256) void mfma_kernel(int iters, float* __restrict__ sink) {
   f32x16_t acc[4][2];
 #pragma unroll
@@ -128,6 +157,21 @@ int main() {
   }
   const double tm = time_ms([&] { CHECK(hipMemcpyAsync(b, a, bytes, hipMemcpyDeviceToDevice, 0)); }, 5);
   std::printf("hbm, hipMemcpyAsync device to device, 4 GiB: %.0f GB/s (read + write bytes)\n", 2.0 * bytes / tm / 1e6);
+  {
+    // 2 GiB matrices of 131072 rows x 16 KiB; tiles of 64 KiB in four shapes
+    const long long rows = 131072, row_bytes = 16384;
+    for (int tile_bytes : {256, 512, 1024, 4096, 16384}) {
+      const long long ntiles = rows * row_bytes / 65536;
+      const dim3 grid((unsigned)((ntiles + 7) / 8 * 8)), blk(256);
+      const double mb = (double)rows * row_bytes;
+      const double t0 = time_ms([&] { hipLaunchKernelGGL(tile_kernel<0>, grid, blk, 0, 0, (const char*)a, (const char*)a, (char*)b, rows, row_bytes, tile_bytes, sink); }, 3);
+      const double t1 = time_ms([&] { hipLaunchKernelGGL(tile_kernel<1>, grid, blk, 0, 0, (const char*)a, (const char*)a, (char*)b, rows, row_bytes, tile_bytes, sink); }, 3);
+      const double t2 = time_ms([&] { hipLaunchKernelGGL(tile_kernel<2>, grid, blk, 0, 0, (const char*)a, (const char*)a, (char*)b, rows, row_bytes, tile_bytes, sink); }, 3);
+      const double t3 = time_ms([&] { hipLaunchKernelGGL(tile_kernel<3>, grid, blk, 0, 0, (const char*)a, (const char*)a, (char*)b, rows, row_bytes, tile_bytes, sink); }, 3);
+      std::printf("hbm, 64 KiB tiles of %5d-byte row pieces: read %.0f, write %.0f, read-modify-write %.0f, two reads + one write %.0f GB/s\n",
+                  tile_bytes, mb / t0 / 1e6, mb / t1 / 1e6, 2 * mb / t2 / 1e6, 3 * mb / t3 / 1e6);
+    }
+  }
   for (int waves_per_simd : {1, 2}) {
     const int iters = 4000;
     const dim3 grid(cus * waves_per_simd), blk(256);   // one workgroup = four wavefronts = one per SIMD
