@@ -38,9 +38,13 @@ def kernel_models(shapes, r, norm_mode):
     L = sum(max(m, n) for m, n in shapes)
     gemm = 2.0 * mn * r
     gram = norm_mode == "gram"
+    proj_bytes = 2 * mn + 2 * Sr + 4 * Lr + (4 * L if gram else 0)
+    # the projection is a dense contraction (MFMA roofline) unless the rank is so small that reading G
+    # takes longer at the HBM peak than the multiplies at the MFMA peak (r = 32: ten times longer)
+    proj_bound = "mfma" if gemm / (PEAK_MFMA_BF16_TFLOPS * 1e12) >= 0.95 * proj_bytes / (PEAK_HBM_GBS * 1e9) else "hbm"
     return {
-        # R = P^T G: read G and P once, write R (fp32); dense contraction -> MFMA roofline
-        "project": dict(flops=gemm, bytes=2 * mn + 2 * Sr + 4 * Lr + (4 * L if gram else 0), bound="mfma"),
+        # R = P^T G: read G and P once, write R (fp32)
+        "project": dict(flops=gemm, bytes=proj_bytes, bound=proj_bound),
         # fused form of the two kernels around it (R stays in registers): read G and P, read and write M
         # and V (fp32), write Z (bf16) and the factors.  2 mn r flops against 2 mn + 18 Lr bytes: at
         # r = 512 the HBM time is twice the MFMA time

@@ -45,10 +45,14 @@ struct HostMat {
   int rowblocks = 0;
   int g2blocks = 0;           // blocks of the ||G_i||^2 kernel
   int fuse_list = -1;         // tile list of the fused projection/Adam kernel, or -1 if the matrix cannot take it
+  bool small_proj = false;    // bf16 with r <= 64: projected by the small-rank kernel
 };
 
 // kTilesFuse + (r > 256 ? 2 : 0) + (left ? 0 : 1): tiles of the fused projection/Adam kernel (one per 128 factors)
-enum { kTilesProjectLeft = 0, kTilesProjectRight = 1, kTilesBackBf16 = 2, kTilesBackF32 = 3, kTilesFuse = 4, kNumTileLists = 8 };
+// kTilesProject*: every matrix (the projector refresh runs the general kernel on all of them); a step uses
+// kTilesProjBig* (general kernel) and kTilesProjSmall* (bf16 matrices with r <= 64), which split them.
+enum { kTilesProjectLeft = 0, kTilesProjectRight = 1, kTilesBackBf16 = 2, kTilesBackF32 = 3, kTilesFuse = 4,
+       kTilesProjBigLeft = 8, kTilesProjBigRight = 9, kTilesProjSmallLeft = 10, kTilesProjSmallRight = 11, kNumTileLists = 12 };
 
 struct ListSlot {
   std::vector<int> idx;
@@ -132,6 +136,8 @@ bool make_plan(const fira_matrix_desc* d, int count, Plan* plan, fira_status* st
     h.rowblocks = (m.L + FIRA_ROWS_PER_WG - 1) / FIRA_ROWS_PER_WG;
     h.g2blocks = m.left ? (m.n + 255) / 256 : (m.m + FIRA_G2_ROWS_PER_WG - 1) / FIRA_G2_ROWS_PER_WG;
     total_tiles[m.left ? kTilesProjectLeft : kTilesProjectRight] += h.tiles_project;
+    h.small_proj = m.kx == 1 && m.r <= FIRA_PS;
+    total_tiles[(h.small_proj ? kTilesProjSmallLeft : kTilesProjBigLeft) + (m.left ? 0 : 1)] += h.tiles_project;
     total_tiles[m.dtype == FIRA_BF16 ? kTilesBackBf16 : kTilesBackF32] += h.tiles_back;
     if (m.zready && m.r >= FIRA_FUSE_MIN_R && m.r <= FIRA_FUSE_MAX_R) {
       h.fuse_list = kTilesFuse + 2 * (m.r > 256 ? 1 : 0) + (m.left ? 0 : 1);
@@ -264,6 +270,9 @@ ListSlot* acquire_list(fira_ctx* ctx, int count, const int* idx, void* const* W,
     const int lp = h.dev.left ? kTilesProjectLeft : kTilesProjectRight;
     for (int ta = 0; ta < h.ta_project; ++ta)
       for (int tbb = 0; tbb < h.tb_project; ++tbb) tl[lp][nt[lp]++] = FiraTile{e, ta, tbb, 0};
+    const int ls = (h.small_proj ? kTilesProjSmallLeft : kTilesProjBigLeft) + (h.dev.left ? 0 : 1);
+    for (int ta = 0; ta < h.ta_project; ++ta)
+      for (int tbb = 0; tbb < h.tb_project; ++tbb) tl[ls][nt[ls]++] = FiraTile{e, ta, tbb, 0};
     if (h.fuse_list >= 0)
       for (int ta = 0; ta < h.ta_project; ++ta) tl[h.fuse_list][nt[h.fuse_list]++] = FiraTile{e, ta, 0, 0};
     // back-projection: groups of 8 column tiles x all row tiles keep both operand panels in L2
@@ -476,11 +485,16 @@ fira_status fira_step(fira_ctx* ctx, int count, const int* idx, void* const* dev
   const dim3 blk(FIRA_PROJ_THREADS);
   // R = P^T G (long-side major) for both orientations in one launch
   auto launch_project = [&](int norm_arg) {
-    const int nl = s->ntiles[kTilesProjectLeft], nr = s->ntiles[kTilesProjectRight];
-    const int bl = (nl + 7) / 8 * 8, br = (nr + 7) / 8 * 8;
+    int nl = s->ntiles[kTilesProjBigLeft], nr = s->ntiles[kTilesProjBigRight];
+    int bl = (nl + 7) / 8 * 8, br = (nr + 7) / 8 * 8;
     if (nl + nr)
       hipLaunchKernelGGL(fira_project_kernel, dim3(bl + br), blk, FIRA_PROJ_LDS, q, ctx->d_mats, s->d_ents,
-                         s->d_tiles[kTilesProjectLeft], nl, bl, s->d_tiles[kTilesProjectRight], nr, norm_arg);
+                         s->d_tiles[kTilesProjBigLeft], nl, bl, s->d_tiles[kTilesProjBigRight], nr, norm_arg);
+    nl = s->ntiles[kTilesProjSmallLeft]; nr = s->ntiles[kTilesProjSmallRight];
+    bl = (nl + 7) / 8 * 8; br = (nr + 7) / 8 * 8;
+    if (nl + nr)
+      hipLaunchKernelGGL(fira_project_small_kernel, dim3(bl + br), blk, FIRA_PROJ_SMALL_LDS, q, ctx->d_mats, s->d_ents,
+                         s->d_tiles[kTilesProjSmallLeft], nl, bl, s->d_tiles[kTilesProjSmallRight], nr, norm_arg);
   };
   // 0. Gram route, fp32 matrices only: ||G_i||^2 for every factor (bf16 matrices get it from step 1)
   const bool only_scaling = ctx->variant == FIRA_VARIANT_ONLY_SCALING;

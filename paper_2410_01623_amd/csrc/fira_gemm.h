@@ -240,8 +240,9 @@ __device__ __forceinline__ void gload16_async(u32x4& dst, const void* base, unsi
 }
 template <int N>
 __device__ __forceinline__ void wait_loads(u32x4 (&r)[4]) {
-  static_assert(N == 4 || N == 0, "queue depths used by the projection pipeline");
+  static_assert(N == 4 || N == 1 || N == 0, "queue depths used by the projection pipelines");
   if (N == 4) asm volatile("s_waitcnt vmcnt(4) ; %0 %1 %2 %3" : "+v"(r[0]), "+v"(r[1]), "+v"(r[2]), "+v"(r[3]) :: "memory");
+  else if (N == 1) asm volatile("s_waitcnt vmcnt(1) ; %0 %1 %2 %3" : "+v"(r[0]), "+v"(r[1]), "+v"(r[2]), "+v"(r[3]) :: "memory");
   else asm volatile("s_waitcnt vmcnt(0) ; %0 %1 %2 %3" : "+v"(r[0]), "+v"(r[1]), "+v"(r[2]), "+v"(r[3]) :: "memory");
 }
 
@@ -508,6 +509,156 @@ __global__ __launch_bounds__(FIRA_PROJ_THREADS, 2) void fira_project_kernel(cons
     const int ti = xcd_chunked_index((int)blockIdx.x - blocks_left, ntiles_right);
     if (ti < 0) return;
     project_tile<false>(lds, mats, ents, tiles_right[ti], norm_mode);
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Kernel 1 for small ranks (r <= 64, the fine-tuning setting's r = 32): with a 256-wide rank tile three
+// quarters or more of the multiplies would work on padding.  Here the tile is 128 (gradient side) x 64
+// (rank); wave w owns gradient rows 32 w .. 32 w + 31 and all 64 rank columns (two accumulator
+// blocks), so the kernel needs few registers and 28 KB of LDS, several workgroups share a CU, and the
+// gradient stream is what bounds it.  Same pipeline as above (single gradient tile, E and O halves);
+// a ring stage is 64 rows x 32 k = 4 KB, one request instruction per wavefront, so the E-half wait is
+// vmcnt(1) and the O-half wait vmcnt(5) (one ring request and the four of A(S+1) are younger).
+// ------------------------------------------------------------------------------------------------
+#define FIRA_PS 64                                   // rank columns of the small tile
+#define FIRA_PROJ_SMALL_STAGE (FIRA_PS * 64)
+#define FIRA_PROJ_SMALL_LDS (FIRA_PROJ_LDS_A + FIRA_RING_STAGES * FIRA_PROJ_SMALL_STAGE)
+
+template <bool SUMSQ>
+__device__ __forceinline__ void proj_compute_small(f32x16_t (&acc)[2], const char* la, const char* lb, int kk4, float& sq) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  bf16x8_t fa[2], fb[2][2];
+#pragma unroll
+  for (int kk = 0; kk < 2; ++kk) {
+    fa[kk] = *reinterpret_cast<const bf16x8_t*>(la + lds_tile_off(32 * wave + (lane & 31), 2 * (kk4 + kk) + (lane >> 5)));
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+      fb[kk][t] = *reinterpret_cast<const bf16x8_t*>(lb + ring_tile_off(32 * t + (lane & 31), 2 * kk + (lane >> 5)));
+  }
+#pragma unroll
+  for (int kk = 0; kk < 2; ++kk) {
+#pragma unroll
+    for (int t = 0; t < 2; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[kk], fb[kk][t], acc[t], 0, 0, 0);
+    if (SUMSQ) {
+      const u32x4 w = __builtin_bit_cast(u32x4, fa[kk]);
+      const unsigned d[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const bf16x2_t v = __builtin_bit_cast(bf16x2_t, d[e]);
+        sq = __builtin_amdgcn_fdot2_f32_bf16(v, v, sq, false);
+      }
+    }
+  }
+}
+
+template <bool LEFT, bool FAST, bool SUMSQ>
+__device__ __forceinline__ void proj_pipeline_small(f32x16_t (&acc)[2], char* lds, const GemmOperands& g, float& sq) {
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  char* la = lds;
+  char* ring = lds + FIRA_PROJ_LDS_A;
+  const unsigned ring0 = (unsigned)(size_t)(lds_ptr)ring;
+  const int SS = g.KB / 64;
+  const int lrow = lane >> 2;
+  const int chunk = (lane & 3) ^ ring_swz(lrow);
+  const unsigned offb = (unsigned)(lrow * 64 + chunk * 16);
+  const char* pb = reinterpret_cast<const char*>((const bf16_raw*)g.B) + ((long long)g.b_row0 + 16 * wave) * 64;
+  auto request_b = [&](int s) {   // this wave's 16 of the stage's 64 rows
+    lds_dma16(pb + (long long)s * g.ldb * 64, offb, ring0 + (unsigned)((s % FIRA_RING_STAGES) * FIRA_PROJ_SMALL_STAGE + wave * 1024));
+  };
+  ProjALoader<LEFT, FAST> al(g);
+  u32x4 ra[4];
+  al.load(ra);                                 // A(0)
+  request_b(0);
+  request_b(1);
+  auto stage = [&](auto last, int S) {
+    constexpr bool LAST = decltype(last)::value;
+    wait_loads<1>(ra);                         // A(S) and D(2S) have landed; D(2S+1) may be in flight
+    asm volatile("s_barrier" ::: "memory");
+    proj_store_a<LEFT>(la, ra);
+    if (!LAST) {
+      request_b(2 * S + 2);
+      al.load(ra);                             // A(S+1)
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    proj_compute_small<SUMSQ>(acc, la, ring + ((2 * S) % FIRA_RING_STAGES) * FIRA_PROJ_SMALL_STAGE, 0, sq);
+    // D(2S+1) has landed (guarded A loads may be fewer than 4 instructions: the edge path lets one stay)
+    if (LAST) asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+    else if (FAST) asm volatile("s_waitcnt vmcnt(5)\n\ts_barrier" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(1)\n\ts_barrier" ::: "memory");
+    if (!LAST) request_b(2 * S + 3);
+    proj_compute_small<SUMSQ>(acc, la, ring + ((2 * S + 1) % FIRA_RING_STAGES) * FIRA_PROJ_SMALL_STAGE, 2, sq);
+  };
+  for (int S = 0; S + 1 < SS; ++S) stage(std::false_type{}, S);
+  stage(std::true_type{}, SS - 1);
+}
+
+template <bool LEFT>
+__device__ __forceinline__ void project_small_tile(char* lds, const FiraMat* __restrict__ mats, const FiraEnt* __restrict__ ents,
+                                                   const FiraTile& tile, int norm_mode) {
+  const FiraEnt ent = ents[tile.ent];
+  const FiraMat mt = mats[ent.mat];
+  GemmOperands g;
+  g.a_row0 = tile.ta * FIRA_PA;
+  g.a_rows = mt.L;
+  g.b_row0 = 0;
+  g.b_rows = mt.r;
+  g.B = as_global<const bf16_raw>(mt.PT);
+  g.ldb = mt.rq;
+  g.KB = mt.Sp;
+  g.A = as_global(reinterpret_cast<const bf16_raw*>(ent.G));
+  g.lda = mt.ld;
+  g.KA = mt.S;
+  f32x16_t acc[2];
+  float sq = 0.0f;
+#pragma unroll
+  for (int tn = 0; tn < 2; ++tn)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[tn][v] = 0.0f;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const bool sumsq = norm_mode == 1;           // every wave owns its own 32 factors
+  const bool interior = g.a_row0 + FIRA_PA <= g.a_rows && g.KA == g.KB;
+  if (interior) {
+    if (sumsq) proj_pipeline_small<LEFT, true, true>(acc, lds, g, sq);
+    else proj_pipeline_small<LEFT, true, false>(acc, lds, g, sq);
+  } else {
+    if (sumsq) proj_pipeline_small<LEFT, false, true>(acc, lds, g, sq);
+    else proj_pipeline_small<LEFT, false, false>(acc, lds, g, sq);
+  }
+  if (sumsq) {
+    const float tot = sq + __shfl_xor(sq, 32, 64);
+    const int row = g.a_row0 + 32 * wave + (lane & 31);
+    if (lane < 32 && row < mt.L) as_global(mt.g2)[row] = tot;
+  }
+  gptr<float> Rt = as_global(mt.Rt);
+#pragma unroll
+  for (int tn = 0; tn < 2; ++tn) {
+    const int col = 32 * tn + (lane & 31);
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int row = g.a_row0 + 32 * wave + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+      if (row < mt.L && col < mt.r) Rt[(long long)row * mt.r + col] = acc[tn][v];
+    }
+  }
+}
+
+// bf16 matrices with r <= 64 only (the host keeps their tiles in lists of their own); both orientations
+// in one grid, as in fira_project_kernel.
+__global__ __launch_bounds__(FIRA_PROJ_THREADS, 4) void fira_project_small_kernel(const FiraMat* __restrict__ mats,
+                                                                                  const FiraEnt* __restrict__ ents,
+                                                                                  const FiraTile* __restrict__ tiles_left, int ntiles_left,
+                                                                                  int blocks_left,
+                                                                                  const FiraTile* __restrict__ tiles_right, int ntiles_right,
+                                                                                  int norm_mode) {
+  extern __shared__ __attribute__((aligned(16))) char lds[];   // FIRA_PROJ_SMALL_LDS bytes
+  if ((int)blockIdx.x < blocks_left) {
+    const int ti = xcd_chunked_index(blockIdx.x, ntiles_left);
+    if (ti < 0) return;
+    project_small_tile<true>(lds, mats, ents, tiles_left[ti], norm_mode);
+  } else {
+    const int ti = xcd_chunked_index((int)blockIdx.x - blocks_left, ntiles_right);
+    if (ti < 0) return;
+    project_small_tile<false>(lds, mats, ents, tiles_right[ti], norm_mode);
   }
 }
 

@@ -21,7 +21,7 @@ def test_registers_of_asynchronous_loads_are_untouched_until_their_wait(tmp_path
     res = subprocess.run(cmd, capture_output=True, text=True)
     assert res.returncode == 0, res.stderr[-2000:]
     ks = {k: v for k, v in isa_async_check.kernels(out.read_text()).items() if "fira_project" in k}
-    assert len(ks) == 3, list(ks)   # fira_project_kernel, fira_project_adam_kernel<1>, <2>
+    assert len(ks) == 4, list(ks)   # fira_project_kernel, fira_project_small_kernel, fira_project_adam_kernel<1>, <2>
     for name, body in ks.items():
         n, loads, viol = isa_async_check.check_kernel(body)
         assert loads >= 8, f"{name}: expected the pipelined loads, found {loads}"
