@@ -873,7 +873,6 @@ fira_status fira_refresh_projectors(fira_ctx* ctx, int count, const int* idx, co
   const FiraRefreshEnt* d_ents2 = (const FiraRefreshEnt*)(ws + rp.off_ents2);
   const FiraMat* d_vmats = (const FiraMat*)(ws + rp.off_vmats);
   const FiraEnt* d_vents = (const FiraEnt*)(ws + rp.off_vents);
-  auto grid8 = [](int n) { return dim3((unsigned)(((n + 7) / 8) * 8)); };
 
   // the forward product uses the step's own work-list machinery (W is not touched by the projection)
   std::vector<void*> fakeW(count);
