@@ -279,6 +279,9 @@ struct ProjALoader {
       step = 64 * 2;
     }
   }
+  // FAST only: request j of the four of a stage (the caller issues all four, in order, then advance())
+  __device__ __forceinline__ void load_one(u32x4 (&ra)[4], int j) { gload16_async(ra[j], base, off[j]); }
+  __device__ __forceinline__ void advance() { base += step; }
   __device__ __forceinline__ void load(u32x4 (&ra)[4]) {
     if (FAST) {
 #pragma unroll
@@ -340,25 +343,41 @@ __device__ __forceinline__ void proj_store_a(char* la, const u32x4 (&ra)[4]) {
 
 // 32 k of the wave's 128 x 64 sub-tile: A fragments from the 128-B-per-row tile (k-slices kk4, kk4+1
 // of its 4), B fragments from a ring stage.
-template <bool SUMSQ>
+// A wavefront issues in order, and a multiply holds the matrix pipe for 32 cycles: sixteen multiplies
+// in a row leave the wavefront unable to issue anything else for as long as they queue, and whatever
+// else the half stage has to do (the second slice's fragment reads, the requests of the next ring stage
+// and gradient tile) then runs with the matrix pipe idle.  So that work is dealt out between the
+// multiplies of the first slice: `piece(j)`, j = 0..7, is called after the j-th of them, and scheduling
+// barriers keep the compiler from gathering the multiplies again.
+template <bool SUMSQ, typename Piece>
 __device__ __forceinline__ void proj_compute(f32x16_t (&acc)[4][2], const char* la, const char* lb, int kk4,
-                                             float (&sq)[4]) {
+                                             float (&sq)[4], Piece piece) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   Frags f[2];
+  auto read_a = [&](int kk, int t) {
+    f[kk].a[t] = *reinterpret_cast<const bf16x8_t*>(la + lds_tile_off(32 * t + (lane & 31), 2 * (kk4 + kk) + (lane >> 5)));
+  };
+  auto read_b = [&](int kk, int t) {
+    f[kk].b[t] = *reinterpret_cast<const bf16x8_t*>(lb + ring_tile_off(wave * 64 + 32 * t + (lane & 31), 2 * kk + (lane >> 5)));
+  };
 #pragma unroll
-  for (int kk = 0; kk < 2; ++kk) {
+  for (int t = 0; t < 4; ++t) read_a(0, t);
 #pragma unroll
-    for (int t = 0; t < 4; ++t)
-      f[kk].a[t] = *reinterpret_cast<const bf16x8_t*>(la + lds_tile_off(32 * t + (lane & 31), 2 * (kk4 + kk) + (lane >> 5)));
+  for (int t = 0; t < 2; ++t) read_b(0, t);
+  __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int t = 0; t < 2; ++t)
-      f[kk].b[t] = *reinterpret_cast<const bf16x8_t*>(lb + ring_tile_off(wave * 64 + 32 * t + (lane & 31), 2 * kk + (lane >> 5)));
+  for (int j = 0; j < 8; ++j) {
+    const int tm = j >> 1, tn = j & 1;
+    acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[0].a[tm], f[0].b[tn], acc[tm][tn], 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    if (j < 4) read_a(1, j);
+    else if (j < 6) read_b(1, j - 4);
+    piece(j);
+    __builtin_amdgcn_sched_barrier(0);
   }
-#pragma unroll
-  for (int kk = 0; kk < 2; ++kk) {
-    gemm_mfma_slice(acc, f[kk]);
-    if (SUMSQ) gemm_sumsq_slice(sq, f[kk]);
-  }
+  if (SUMSQ) gemm_sumsq_slice(sq, f[0]);
+  gemm_mfma_slice(acc, f[1]);
+  if (SUMSQ) gemm_sumsq_slice(sq, f[1]);
 }
 
 // RT = rank tiles of 256 that one workgroup covers (256*RT threads, wave w owns rank rows 64 w ..).
@@ -387,6 +406,12 @@ __device__ __forceinline__ void proj_pipeline(f32x16_t (&acc)[4][2], char* lds, 
 #pragma unroll
     for (int q = 0; q < 4; ++q) lds_dma16(kb + q * 1024, offb, dst + (unsigned)((4 * wave + q) * 1024));
   };
+  // request q (of 4) of ring stage s
+  auto request_b1 = [&](int s, int q) {
+    const unsigned dst = ring0 + (unsigned)((s % FIRA_RING_STAGES) * STAGE);
+    const char* kb = pb + (long long)s * g.ldb * 64;
+    lds_dma16(kb + q * 1024, offb, dst + (unsigned)((4 * wave + q) * 1024));
+  };
   ProjALoader<LEFT, FAST> al(g);
   u32x4 ra[4];
   if (loader) al.load(ra);                     // A(0)
@@ -401,20 +426,30 @@ __device__ __forceinline__ void proj_pipeline(f32x16_t (&acc)[4][2], char* lds, 
     else asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
     asm volatile("s_barrier" ::: "memory");    // everybody is done with the previous stage's A tile and ring slot
     if (loader) proj_store_a<LEFT>(la, ra);
-    if (!LAST) {
-      request_b(2 * S + 2);
-      if (loader) al.load(ra);                 // A(S+1)
-    }
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    proj_compute<SUMSQ>(acc, la, ring + ((2 * S) % FIRA_RING_STAGES) * STAGE, 0, sq);
+    // the requests of D(2S+2) (into the slot of D(2S-1), free since the first barrier) and of A(S+1)
+    // (whose registers proj_store_a has just released) go out between the multiplies
+    proj_compute<SUMSQ>(acc, la, ring + ((2 * S) % FIRA_RING_STAGES) * STAGE, 0, sq, [&](int j) {
+      if (LAST) return;
+      if (j < 4) request_b1(2 * S + 2, j);
+      else if (loader) {
+        if (FAST) {
+          al.load_one(ra, j - 4);
+          if (j == 7) al.advance();
+        } else if (j == 4) {
+          al.load(ra);
+        }
+      }
+    });
     // O half
     // D(2S+1) has landed.  Guarded A loads are the compiler's and may be fewer than 4 instructions,
     // so the edge path only lets D(2S+2)'s four stay in flight.
     if (LAST) asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
     else if (FAST && loader) asm volatile("s_waitcnt vmcnt(8)\n\ts_barrier" ::: "memory");
     else asm volatile("s_waitcnt vmcnt(4)\n\ts_barrier" ::: "memory");
-    if (!LAST) request_b(2 * S + 3);
-    proj_compute<SUMSQ>(acc, la, ring + ((2 * S + 1) % FIRA_RING_STAGES) * STAGE, 2, sq);
+    proj_compute<SUMSQ>(acc, la, ring + ((2 * S + 1) % FIRA_RING_STAGES) * STAGE, 2, sq, [&](int j) {
+      if (!LAST && j < 4) request_b1(2 * S + 3, j);
+    });
   };
   for (int S = 0; S + 1 < SS; ++S) stage(std::false_type{}, S);
   stage(std::true_type{}, SS - 1);
