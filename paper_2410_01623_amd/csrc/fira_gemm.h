@@ -314,31 +314,38 @@ struct ProjALoader {
   }
 };
 
+// Registers -> LDS tile of one K stage (128 rows x 64 k, lds_tile_off layout), written as eight parts.  t = the thread's place among the 256 loaders.
+//   K-slow (LEFT): ra[j] holds row k = 4*kq + j of a 4(k) x 8(a) block, dword d of it the elements
+//   a = 2d, 2d+1.  Part p emits output row a = p: its four k values, two byte permutes and one 8-byte
+//   write.  The row's chunk position is (chunk ^ row ^ row>>3 ^ row>>6) & 7 with row = 8*ib + p, i.e.
+//   a per-thread constant XOR p.
+//   K-contiguous: part p is half p & 1 of the 16-byte piece q = p >> 1 (row rr + 32 q); the chunk
+//   position is a per-thread constant XOR a constant of q.
 template <bool LEFT>
-__device__ __forceinline__ void proj_store_a(char* la, const u32x4 (&ra)[4]) {
-  const int t = threadIdx.x;
+__device__ __forceinline__ void proj_store_a_part(char* la, const u32x4 (&ra)[4], int p, int t) {
   if (LEFT) {
-    // ra[j] holds row k = 4*kq + j of a 4(k) x 8(a) block; emit, for each a, its 4 k values (8 B).
     const int ib = proj_kslow_ib(t), kq = proj_kslow_kq(t);
+    const int bx = ((kq >> 1) ^ ib ^ (ib >> 3)) & 7;
+    char* row0 = la + ib * 1024 + 8 * (kq & 1);
     const unsigned in[16] = {ra[0].x, ra[0].y, ra[0].z, ra[0].w, ra[1].x, ra[1].y, ra[1].z, ra[1].w,
-                             ra[2].x, ra[2].y, ra[2].z, ra[2].w, ra[3].x, ra[3].y, ra[3].z, ra[3].w};  // in[4*j + d]: a = 2d, 2d+1
-#pragma unroll
-    for (int ii = 0; ii < 8; ++ii) {
-      unsigned w[2];
-#pragma unroll
-      for (int d = 0; d < 2; ++d) {
-        const unsigned x = in[4 * (2 * d) + (ii >> 1)];      // k = 2d
-        const unsigned y = in[4 * (2 * d + 1) + (ii >> 1)];  // k = 2d + 1
-        w[d] = (ii & 1) ? ((x >> 16) | (y & 0xffff0000u)) : ((x & 0xffffu) | (y << 16));
-      }
-      const int row = 8 * ib + ii;
-      *reinterpret_cast<u32x2*>(la + lds_tile_off(row, kq >> 1) + 8 * (kq & 1)) = u32x2{w[0], w[1]};
-    }
+                             ra[2].x, ra[2].y, ra[2].z, ra[2].w, ra[3].x, ra[3].y, ra[3].z, ra[3].w};  // in[4*j + d]
+    const unsigned sel = (p & 1) ? 0x07060302u : 0x05040100u;   // the high or the low halves of (x, y)
+    const unsigned w0 = __builtin_amdgcn_perm(in[4 + (p >> 1)], in[0 + (p >> 1)], sel);    // k = 0, 1
+    const unsigned w1 = __builtin_amdgcn_perm(in[12 + (p >> 1)], in[8 + (p >> 1)], sel);   // k = 2, 3
+    *reinterpret_cast<u32x2*>(row0 + p * 128 + ((bx ^ p) << 4)) = u32x2{w0, w1};
   } else {
-    const int cc = t & 7, rr = t >> 3;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) *reinterpret_cast<u32x4*>(la + lds_tile_off(rr + 32 * q, cc)) = ra[q];
+    const int cc = t & 7, rr = t >> 3, q = p >> 1;
+    const int bx = (cc ^ rr ^ (rr >> 3)) & 7;
+    const int cq = (4 * (q & 1)) ^ (q >> 1);
+    const u32x2 half = (p & 1) ? u32x2{ra[q].z, ra[q].w} : u32x2{ra[q].x, ra[q].y};
+    *reinterpret_cast<u32x2*>(la + rr * 128 + q * 4096 + ((bx ^ cq) << 4) + 8 * (p & 1)) = half;
   }
+}
+
+template <bool LEFT>
+__device__ __forceinline__ void proj_store_a(char* la, const u32x4 (&ra)[4], int t = threadIdx.x) {
+#pragma unroll
+  for (int p = 0; p < 8; ++p) proj_store_a_part<LEFT>(la, ra, p, t);
 }
 
 // 32 k of the wave's 128 x 64 sub-tile: A fragments from the 128-B-per-row tile (k-slices kk4, kk4+1
