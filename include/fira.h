@@ -78,9 +78,11 @@ typedef struct {
 typedef enum { FIRA_SCALE_COLUMN = 0, FIRA_SCALE_MATRIX = 1, FIRA_SCALE_NONE = 2 } fira_scaling;
 
 /* How ||S_t|| (Eq. 12) is obtained.  FIRA_NORM_RESIDUAL forms G - P R tile by tile with an extra
- * rank-r contraction (exact for any P).  FIRA_NORM_GRAM uses
- * ||G_i - P R_i||^2 = ||G_i||^2 - 2||R_i||^2 + R_i^T (P^T P) R_i, which holds for any P because
- * G_i^T P = R_i^T, and saves one contraction and one pass over G; it loses accuracy by
+ * rank-r contraction and a second pass over G (exact for any P).  FIRA_NORM_GRAM, the default, uses
+ * ||G_i - P R_i||^2 = ||G_i||^2 - ||R_i||^2, which holds when P^T P = I (G_i^T P = R_i^T always) and
+ * needs neither: fira_set_projector estimates ||P^T P - I||, and a matrix whose estimate exceeds 0.02
+ * takes the residual route regardless of this setting.  With a bf16-rounded orthonormal P the identity
+ * holds to about 1e-3 of ||R_i||^2, so ||S_t|| carries a relative error of a few 1e-4, growing by
  * cancellation when the residual is tiny compared with G (r close to min(m,n)). */
 typedef enum { FIRA_NORM_RESIDUAL = 0, FIRA_NORM_GRAM = 1 } fira_norm_mode;
 
@@ -118,7 +120,8 @@ FIRA_API fira_status fira_step(fira_ctx* ctx, int count, const int* idx, void* c
  * next fira_step. */
 FIRA_API fira_status fira_set_hparams(fira_ctx* ctx, const fira_hparams* hp);
 
-/* Variant switches (Sec. 5.3 ablations) and the way ||S_t|| is computed; both default to 0. */
+/* Variant switches (Sec. 5.3 ablations) and the way ||S_t|| is computed.  Defaults: FIRA_SCALE_COLUMN,
+ * FIRA_NORM_GRAM. */
 FIRA_API fira_status fira_set_options(fira_ctx* ctx, fira_scaling scaling, fira_norm_mode norm_mode);
 
 /* FIRA_VARIANT_FULL is Algorithm 1.  FIRA_VARIANT_ONLY_SCALING is the appendix's "Fira-only-scaling"

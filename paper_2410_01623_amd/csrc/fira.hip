@@ -177,7 +177,7 @@ struct fira_ctx {
   hipStream_t stream = nullptr;
   fira_hparams hp{};
   int scaling = FIRA_SCALE_COLUMN;
-  int norm_mode = FIRA_NORM_RESIDUAL;
+  int norm_mode = FIRA_NORM_GRAM;
   int variant = FIRA_VARIANT_FULL;
   bool fusion = true;          // fira_set_fusion
   bool last_step_fused = false;

@@ -216,7 +216,7 @@ class FiraContext:
         self.hp = hp
         _check(self.lib, self.ctx, self.lib.fira_set_hparams(self.ctx, ctypes.byref(hp)))
 
-    def fira_set_options(self, scaling=FIRA_SCALE_COLUMN, norm_mode=FIRA_NORM_RESIDUAL):
+    def fira_set_options(self, scaling=FIRA_SCALE_COLUMN, norm_mode=FIRA_NORM_GRAM):
         _check(self.lib, self.ctx, self.lib.fira_set_options(self.ctx, scaling, norm_mode))
 
     def fira_set_variant(self, variant: int):

@@ -76,10 +76,10 @@ def run_case(shapes: Sequence[Tuple[int, int]], rank, dtype: int, steps: int,
     ranks = rank if isinstance(rank, (list, tuple)) else [rank] * nmat
     chp = fira.make_hparams(hp.lr, hp.beta1, hp.beta2, hp.eps, hp.alpha, hp.gamma)
     ctx = fira.FiraContext(shapes, rank, dtype, chp, device=DEV, lds=lds)
-    if scaling != "column" or norm_mode != fira.FIRA_NORM_RESIDUAL:
-        ctx.fira_set_options(scaling={"none": fira.FIRA_SCALE_NONE, "column": fira.FIRA_SCALE_COLUMN,
-                                      "matrix": fira.FIRA_SCALE_MATRIX}[scaling],
-                             norm_mode=norm_mode)
+    # always explicit: the cases do not depend on the library's defaults
+    ctx.fira_set_options(scaling={"none": fira.FIRA_SCALE_NONE, "column": fira.FIRA_SCALE_COLUMN,
+                                  "matrix": fira.FIRA_SCALE_MATRIX}[scaling],
+                         norm_mode=norm_mode)
     if not fusion:
         ctx.fira_set_fusion(False)
     fused_steps = 0
