@@ -790,7 +790,8 @@ struct Elem8<float> {
 // instruction drops four-fold.  The G (and W) values of the second slab are requested while the
 // first one is consumed.
 #define FIRA_EPI_STRIDE 260   // floats per staged row: 256 + 4 (keeps 16-byte alignment, shifts banks)
-#define FIRA_EPI_LDS (2 * 32 * FIRA_EPI_STRIDE * 4)
+#define FIRA_EPI_SLAB (2 * 32 * FIRA_EPI_STRIDE * 4)
+#define FIRA_EPI_LDS (FIRA_EPI_SLAB + FIRA_BB * 4)   // the slabs, then one factor per tile row (matrices with m > n)
 #define FIRA_BACK_LDS (FIRA_EPI_LDS > FIRA_RING_LDS ? FIRA_EPI_LDS : FIRA_RING_LDS)
 template <int MODE, typename T, bool INTERIOR>
 __device__ __forceinline__ float backproject_epilogue(f32x16_t (&acc)[4][2], char* lds, const FiraMat& mt,
@@ -800,6 +801,7 @@ __device__ __forceinline__ float backproject_epilogue(f32x16_t (&acc)[4][2], cha
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wm = wave & 1, wn = wave >> 1;
   float* buf = reinterpret_cast<float*>(lds) + wn * (32 * FIRA_EPI_STRIDE);
+  float* rowphi = reinterpret_cast<float*>(lds + FIRA_EPI_SLAB);
   gptr<const T> G = as_global(reinterpret_cast<const T*>(ent.G));
   gptr<T> W = as_global(reinterpret_cast<T*>(ent.W));
   gptr<const float> phi = as_global<const float>(mt.phi);
@@ -837,6 +839,13 @@ __device__ __forceinline__ float backproject_epilogue(f32x16_t (&acc)[4][2], cha
 #pragma unroll
   for (int tn = 0; tn < 2; ++tn) {
     __syncthreads();  // previous slab fully consumed (first time: the main loop's LDS reads are done)
+    // One factor per row (m > n): the tile's 128 go through LDS.  Loaded from global memory inside a pass
+    // they would have to be waited for there, and the memory counter being in order, that wait would
+    // cover every request in flight for the later passes.
+    if (tn == 0 && !mt.left && threadIdx.x < FIRA_BB) {
+      const long long i = (long long)i0 + threadIdx.x;
+      rowphi[threadIdx.x] = (INTERIOR || i < mt.m) ? (unitk ? c : c * phi[i]) : 0.0f;
+    }
 #pragma unroll
     for (int tm = 0; tm < 4; ++tm)
 #pragma unroll
@@ -860,7 +869,7 @@ __device__ __forceinline__ float backproject_epilogue(f32x16_t (&acc)[4][2], cha
         float g[8];
         Elem8<T>::unpack(gr, g);
         if (!mt.left) {
-          const float f = unitk ? c : c * phi[i];
+          const float f = rowphi[wn * 64 + 32 * tn + il];
 #pragma unroll
           for (int e = 0; e < 8; ++e) cphi[e] = f;
         }
