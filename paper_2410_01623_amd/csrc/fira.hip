@@ -361,6 +361,8 @@ fira_status fira_init_state(fira_ctx** out, const fira_matrix_desc* d, int count
   FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_backproject_kernel<1, bf16_raw>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_BACK_LDS));
   FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_backproject_kernel<0, float>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_BACK_LDS));
   FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_backproject_kernel<1, float>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_BACK_LDS));
+  FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_refresh_solve_kernel<32>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_SOLVE_LDS(32, 1152)));
+  FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_refresh_solve_kernel<16>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_SOLVE_LDS(16, FIRA_REFRESH_MAX_R)));
   FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_project_adam_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_FUSE_LDS(1)));
   FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_project_adam_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_FUSE_LDS(2)));
   FIRA_INIT_HIP(hipHostMalloc((void**)&ctx->h_stage_all, p.slot_bytes * kSlots, hipHostMallocDefault));
@@ -785,7 +787,7 @@ bool make_refresh_plan(const fira_ctx* ctx, int count, const int* idx, RefreshPl
     rp->off_y[e] = take((size_t)m.S * m.r * 4);
     rp->off_q[e] = take((size_t)m.S * m.r * 4);
     rp->off_c[e] = take((size_t)m.r * m.r * 8);
-    rp->off_linv[e] = take((size_t)m.r * m.r * 8);
+    rp->off_linv[e] = take((size_t)m.S * 16 + (size_t)FIRA_ORTHO_SPLITS * m.r * 16);   // scratch of the gate estimate
   }
   rp->total = off;
   return true;
@@ -814,6 +816,7 @@ fira_status fira_refresh_projectors(fira_ctx* ctx, int count, const int* idx, co
       seen[idx[e]] = 1;
       if (!dev_G[e]) return fail(ctx, FIRA_ERR_INVALID_ARG, "null G pointer");
       if (ctx->plan.mats[idx[e]].dev.kx != 1) return fail(ctx, FIRA_ERR_DTYPE, "the device refresh handles bf16 matrices only");
+      if (ctx->plan.mats[idx[e]].dev.r > FIRA_REFRESH_MAX_R) return fail(ctx, FIRA_ERR_SHAPE, "the device refresh handles ranks up to 1792");
     }
   }
   RefreshPlan rp;
@@ -839,7 +842,7 @@ fira_status fira_refresh_projectors(fira_ctx* ctx, int count, const int* idx, co
     re.Y = (float*)(ws + rp.off_y[e]);
     re.Q = (float*)(ws + rp.off_q[e]);
     re.C = (double*)(ws + rp.off_c[e]);
-    re.Linv = (double*)(ws + rp.off_linv[e]);
+    re.inst = (float*)(ws + rp.off_linv[e]);
     ents2[e] = re;                       // second orthonormalisation pass of the last round: Q -> Y
     std::swap(ents2[e].Y, ents2[e].Q);
     max_S = std::max(max_S, m.S); max_r = std::max(max_r, m.r); max_Lp = std::max(max_Lp, re.Lp);
@@ -887,10 +890,14 @@ fira_status fira_refresh_projectors(fira_ctx* ctx, int count, const int* idx, co
                        d_ents, (unsigned long long)seed);
   }
   const int nt64 = (max_r + 63) / 64;
+  const int prep_blocks = (int)std::min<long long>(((long long)max_S * max_r + 255) / 256, 4096);
   auto orthonormalise = [&](const FiraRefreshEnt* de) {
     hipLaunchKernelGGL(fira_refresh_gram_kernel, dim3(nt64 * (nt64 + 1) / 2, count), dim3(256), 0, q, de);
     hipLaunchKernelGGL(fira_refresh_chol_kernel, dim3(count), dim3(FIRA_CHOL_THREADS), 0, q, de);
-    hipLaunchKernelGGL(fira_refresh_solve_kernel, dim3((max_S + 63) / 64, count), dim3(256), 0, q, de);
+    if (max_r <= 1152)
+      hipLaunchKernelGGL(fira_refresh_solve_kernel<32>, dim3((max_S + 31) / 32, count), dim3(256), FIRA_SOLVE_LDS(32, max_r), q, de);
+    else
+      hipLaunchKernelGGL(fira_refresh_solve_kernel<16>, dim3((max_S + 15) / 16, count), dim3(256), FIRA_SOLVE_LDS(16, max_r), q, de);
   };
   auto launch_project = [&](const FiraMat* mats, const FiraEnt* ents_d, const FiraTile* tl, int nl, const FiraTile* tr, int nr) {
     const int bl = (nl + 7) / 8 * 8, br = (nr + 7) / 8 * 8;
@@ -899,12 +906,7 @@ fira_status fira_refresh_projectors(fira_ctx* ctx, int count, const int* idx, co
   };
   for (int it = 0; it < iters; ++it) {
     // operands of Q (the fp32 Q becomes the matrix's projector copies; no gate estimate needed here)
-    for (int e = 0; e < count; ++e) {
-      const HostMat& h = ctx->plan.mats[idx[e]];
-      const long long total = (long long)h.dev.S * h.dev.r;
-      const int grid = (int)std::min<long long>((total + 255) / 256, 65535);
-      hipLaunchKernelGGL(fira_prep_projector_kernel<float>, dim3(grid), dim3(256), 0, q, h.dev, (const float*)ents[e].Q);
-    }
+    hipLaunchKernelGGL(fira_refresh_prep_kernel, dim3(prep_blocks, count), dim3(256), 0, q, ctx->d_mats, d_ents);
     // T = G^T Q (or G Q): the projection kernel, norm route off
     launch_project(ctx->d_mats, s->d_ents, s->d_tiles[kTilesProjectLeft], s->ntiles[kTilesProjectLeft],
                    s->d_tiles[kTilesProjectRight], s->ntiles[kTilesProjectRight]);
@@ -920,10 +922,21 @@ fira_status fira_refresh_projectors(fira_ctx* ctx, int count, const int* idx, co
   // when Y was ill conditioned; its result lands in the Y buffers.
   orthonormalise(d_ents2);
   FIRA_HIP(ctx, hipGetLastError());
+  // install the result (what fira_set_projector does per matrix, here one launch per phase for the whole list)
+  hipLaunchKernelGGL(fira_refresh_prep_kernel, dim3(prep_blocks, count), dim3(256), 0, q, ctx->d_mats, d_ents2);
+  hipLaunchKernelGGL(fira_refresh_ortho_y_kernel, dim3((max_S + 3) / 4, count), dim3(256), 0, q, ctx->d_mats, d_ents2);
+  hipLaunchKernelGGL(fira_refresh_ortho_z_kernel, dim3(FIRA_ORTHO_SPLITS, count), dim3(256), 0, q, ctx->d_mats, d_ents2);
+  hipLaunchKernelGGL(fira_refresh_ortho_final_kernel, dim3(count), dim3(256), 0, q, ctx->d_mats, d_ents2, ctx->d_scal);
+  FIRA_HIP(ctx, hipGetLastError());
   for (int e = 0; e < count; ++e) {
-    const fira_status ps = fira_set_projector(ctx, idx[e], ents2[e].Q, FIRA_F32);
-    if (ps != FIRA_OK) return ps;
+    ctx->h_ortho[idx[e]] = INFINITY;
+    ctx->plan.mats[idx[e]].has_projector = true;
   }
+  // every matrix's gate value in one strided copy (those not listed are copied unchanged)
+  FIRA_HIP(ctx, hipMemcpy2DAsync(ctx->h_ortho, sizeof(float), reinterpret_cast<char*>(ctx->d_scal) + offsetof(FiraScal, ortho_err),
+                                 sizeof(FiraScal), sizeof(float), (size_t)nmat, hipMemcpyDeviceToHost, q));
+  FIRA_HIP(ctx, hipEventRecord(ctx->ortho_event, q));
+  ctx->ortho_pending = true;
   return FIRA_OK;
 }
 

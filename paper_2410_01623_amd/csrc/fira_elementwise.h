@@ -541,7 +541,7 @@ __global__ __launch_bounds__(256) void fira_scale_update_kernel(const FiraMat* _
 
 // Projector P[S][r] (fp32 or bf16) -> Pn[S][kx*rp] and PT[r][kx*Sp]; split planes follow sequence B.
 template <typename TP>
-__global__ void fira_prep_projector_kernel(FiraMat mt, const TP* __restrict__ P) {
+__device__ __forceinline__ void prep_projector_body(const FiraMat& mt, const TP* __restrict__ P) {
   const long long total = (long long)mt.S * mt.r;
   for (long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
        idx += (long long)gridDim.x * blockDim.x) {
@@ -568,6 +568,8 @@ __global__ void fira_prep_projector_kernel(FiraMat mt, const TP* __restrict__ P)
     }
   }
 }
+template <typename TP>
+__global__ void fira_prep_projector_kernel(FiraMat mt, const TP* __restrict__ P) { prep_projector_body<TP>(mt, P); }
 
 // fp32 gradient -> split bf16 planes (sequence A), stacked along the contraction axis.
 __global__ void fira_split_gradient_kernel(FiraMat mt, const float* __restrict__ G) {
@@ -701,7 +703,7 @@ __device__ __forceinline__ float ortho_sign(int a, int trial) {
   return ((h >> 15) & 1u) ? 1.0f : -1.0f;
 }
 
-__global__ __launch_bounds__(256) void fira_ortho_y_kernel(FiraMat mt, float* __restrict__ y /* [S][4] */) {
+__device__ __forceinline__ void ortho_y_body(const FiraMat& mt, float* __restrict__ y /* [S][4] */) {
   gptr<const bf16_raw> Pn = as_global<const bf16_raw>(mt.Pn);
   const int lane = threadIdx.x & 63;
   const int s = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -720,10 +722,12 @@ __global__ __launch_bounds__(256) void fira_ortho_y_kernel(FiraMat mt, float* __
   }
 }
 
+__global__ __launch_bounds__(256) void fira_ortho_y_kernel(FiraMat mt, float* __restrict__ y) { ortho_y_body(mt, y); }
+
 // z-partials: workgroup b sums rows [b*chunk, (b+1)*chunk) of P^T y for all four trials.
 #define FIRA_ORTHO_SPLITS 64
-__global__ __launch_bounds__(256) void fira_ortho_z_kernel(FiraMat mt, const float* __restrict__ y,
-                                                           float* __restrict__ zpart /* [splits][r][4] */) {
+__device__ __forceinline__ void ortho_z_body(const FiraMat& mt, const float* __restrict__ y,
+                                             float* __restrict__ zpart /* [splits][r][4] */) {
   gptr<const bf16_raw> Pn = as_global<const bf16_raw>(mt.Pn);
   gptr<const float> yy = as_global(y);
   const int chunk = (mt.S + FIRA_ORTHO_SPLITS - 1) / FIRA_ORTHO_SPLITS;
@@ -740,9 +744,12 @@ __global__ __launch_bounds__(256) void fira_ortho_z_kernel(FiraMat mt, const flo
   }
 }
 
-__global__ __launch_bounds__(256) void fira_ortho_final_kernel(FiraMat mt, const float* __restrict__ zpart,
-                                                               FiraScal* __restrict__ scal, int mat) {
-  __shared__ float red[4][4];
+__global__ __launch_bounds__(256) void fira_ortho_z_kernel(FiraMat mt, const float* __restrict__ y, float* __restrict__ zpart) {
+  ortho_z_body(mt, y, zpart);
+}
+
+__device__ __forceinline__ void ortho_final_body(const FiraMat& mt, const float* __restrict__ zpart,
+                                                 FiraScal* __restrict__ scal, int mat, float (&red)[4][4]) {
   gptr<const float> zp = as_global(zpart);
   const int t = threadIdx.x;
   float zz[4] = {0.f, 0.f, 0.f, 0.f};
@@ -768,4 +775,9 @@ __global__ __launch_bounds__(256) void fira_ortho_final_kernel(FiraMat mt, const
       worst = fmaxf(worst, sqrtf(((red[0][k] + red[1][k]) + (red[2][k] + red[3][k])) / (float)mt.r));
     as_global(scal)[mat].ortho_err = worst;
   }
+}
+__global__ __launch_bounds__(256) void fira_ortho_final_kernel(FiraMat mt, const float* __restrict__ zpart,
+                                                               FiraScal* __restrict__ scal, int mat) {
+  __shared__ float red[4][4];
+  ortho_final_body(mt, zpart, scal, mat, red);
 }

@@ -25,7 +25,7 @@ struct FiraRefreshEnt {
   float* Y;            // [S][r]
   float* Q;            // [S][r]
   double* C;           // [r][r]            Gram matrix, then its Cholesky factor (lower triangle)
-  double* Linv;        // (unused; kept so that the layout of the workspace does not depend on the solver)
+  float* inst;         // scratch of the orthonormality estimate: [S][4], then [FIRA_ORTHO_SPLITS][r][4]
 };
 
 // splitmix64 finaliser: one independent 64-bit value per counter
@@ -230,72 +230,124 @@ __global__ __launch_bounds__(FIRA_CHOL_THREADS) void fira_refresh_chol_kernel(co
 
 // Q = Y L^-T, i.e. every row solves  q L^T = y  by forward substitution:
 //     q_a = (y_a - sum_{b < a} q_b L[a][b]) / L[a][a].
-// Rows are independent, so one workgroup takes 64 rows and walks over the columns in blocks of 16:
-// the contribution of the columns already solved is a 64 x 16 x (16 jb) product accumulated in fp64
-// (4 outputs per thread, operands staged through LDS), then 64 threads finish their row's 16 values
-// against the diagonal block.  Solved values are written as fp32 and read back from there.
+// Rows are independent.  A workgroup keeps ROWS of them in LDS for the whole solve (a row starts as y
+// and is overwritten by q column block by column block; fp32, as the result is stored).  Columns go in
+// blocks of 16, four per wavefront.  In the product with the columns already solved, ROWS x 16 x jb in
+// fp64, a lane owns one row and every 64/ROWS-th pair of k, so its q values come from LDS without bank
+// conflicts, and the L values, the same for all lanes of a row group, are read straight from memory (one
+// cache line per request, shared by every workgroup of the matrix in L2): four fp64 multiply-adds per
+// q value and L request.  Then ROWS threads finish their row's 16 values against the diagonal block with
+// the reciprocals of its diagonal.  Three barriers per column block.  The loop is bound by the latency
+// of the L requests; 32 rows per workgroup leave room for two workgroups per CU up to r = 560.
+// (A version that re-read Q from memory 16 columns at a time, two barriers and a global round trip per
+// 16 x 16 piece, took 20 % longer; one that staged L through LDS was bound by LDS reads and slower.)
+// ROWS = 32 up to r = 1152, 16 up to FIRA_REFRESH_MAX_R: the rows must fit the CU's LDS.
 #define FIRA_SOLVE_NB 16
+#define FIRA_REFRESH_MAX_R 1792
+#define FIRA_SOLVE_LDS(ROWS, r) ((ROWS) * ((((r) + 15) / 16 * 16) + 1) * 4 + (ROWS) * (FIRA_SOLVE_NB + 1) * 8 + \
+                                 FIRA_SOLVE_NB * (FIRA_SOLVE_NB + 1) * 8 + FIRA_SOLVE_NB * 8 + 16)
+template <int ROWS>
 __global__ __launch_bounds__(256) void fira_refresh_solve_kernel(const FiraRefreshEnt* __restrict__ ents) {
-  __shared__ float sq[64][FIRA_SOLVE_NB + 1];                   // Q[s][b0 .. b0+16)
-  __shared__ double slt[FIRA_SOLVE_NB][FIRA_SOLVE_NB + 1];      // L[jb + j][b0 + c]
-  __shared__ double sacc[64][FIRA_SOLVE_NB + 1];
+  constexpr int NB = FIRA_SOLVE_NB;
+  constexpr int KS = 64 / ROWS;                              // lanes that share a row, each taking every KS-th pair of k
+  extern __shared__ __attribute__((aligned(16))) char solve_lds[];
   const FiraRefreshEnt e = ents[blockIdx.y];
-  const int s0 = blockIdx.x * 64;
+  const int s0 = blockIdx.x * ROWS;
   if (s0 >= e.S) return;
-  const int r = e.r;
+  const int r = e.r, rp = (r + NB - 1) / NB * NB, QP = rp + 1;   // odd row pitch: the rows of a column fall in distinct banks
+  float* qs = reinterpret_cast<float*>(solve_lds);                 // [ROWS][QP]
+  double* sacc = reinterpret_cast<double*>(solve_lds + ((ROWS * QP * 4 + 15) & ~15));   // [ROWS][NB + 1]
+  double* ld = sacc + ROWS * (NB + 1);                             // [NB][NB + 1]: diagonal block
+  double* rinv = ld + NB * (NB + 1);                               // [NB]
   gptr<const float> Y = as_global<const float>(e.Y);
   gptr<const double> Lm = as_global<const double>(e.C);
   gptr<float> Q = as_global(e.Q);
-  const int t = threadIdx.x;
-  const int row = t >> 2, c4 = (t & 3) * 4;                     // this thread's 4 outputs of the 64 x 16 tile
-  for (int jb = 0; jb < r; jb += FIRA_SOLVE_NB) {
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int row = lane % ROWS, ks = lane / ROWS, cw = 4 * wave;
+  // the rows of Y (zeros beyond S and r)
+  for (int x = t; x < ROWS * rp; x += 256) {
+    const int rr = x / rp, a = x % rp;
+    qs[rr * QP + a] = (s0 + rr < e.S && a < r) ? Y[(long long)(s0 + rr) * r + a] : 0.0f;
+  }
+  __syncthreads();
+  for (int jb = 0; jb < rp; jb += NB) {
     double acc[4] = {0.0, 0.0, 0.0, 0.0};
-    for (int b0 = 0; b0 < jb; b0 += FIRA_SOLVE_NB) {
-      // stage Q[s0 .. s0+64)[b0 .. b0+16) and L[jb .. jb+16)[b0 .. b0+16)
+    // rows jb + cw + c of L, clamped into the matrix (columns beyond r have no weight: their q is zero)
+    gptr<const double> lrow[4];
 #pragma unroll
-      for (int p = 0; p < 4; ++p) {
-        const int x = t + 256 * p, rr = x >> 4, cc = x & 15;
-        sq[rr][cc] = (s0 + rr < e.S) ? Q[(long long)(s0 + rr) * r + b0 + cc] : 0.0f;
-      }
-      {
-        const int j = t >> 4, cc = t & 15;
-        slt[j][cc] = (jb + j < r) ? Lm[(long long)(jb + j) * r + b0 + cc] : 0.0;
-      }
-      __syncthreads();
+    for (int c = 0; c < 4; ++c) lrow[c] = Lm + (long long)(jb + cw + c < r ? jb + cw + c : r - 1) * r;
+    const float* qrow = qs + row * QP;
+#pragma unroll 8
+    for (int k = 2 * ks; k < jb; k += 2 * KS) {     // jb is a multiple of 16: pairs never straddle it
+      const float q0 = qrow[k], q1 = qrow[k + 1];
 #pragma unroll
-      for (int cc = 0; cc < FIRA_SOLVE_NB; ++cc) {
-        const double qv = (double)sq[row][cc];
-#pragma unroll
-        for (int k = 0; k < 4; ++k) acc[k] += qv * slt[c4 + k][cc];
+      for (int c = 0; c < 4; ++c) {
+        const double l0 = lrow[c][k], l1 = lrow[c][k + 1];
+        acc[c] += (double)q0 * l0 + (double)q1 * l1;
       }
-      __syncthreads();
     }
-    // right-hand side minus the solved part, and the diagonal block of L
+    if (KS > 1) {
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      const int a = jb + c4 + k;
-      const double y = (s0 + row < e.S && a < r) ? (double)Y[(long long)(s0 + row) * r + a] : 0.0;
-      sacc[row][c4 + k] = y - acc[k];
+      for (int c = 0; c < 4; ++c)
+#pragma unroll
+        for (int o = ROWS; o < 64; o <<= 1) acc[c] += __shfl_xor(acc[c], o, 64);
+    }
+    // right-hand side minus the solved part; the diagonal block of L and the reciprocals of its diagonal
+    if (ks == 0) {
+#pragma unroll
+      for (int c = 0; c < 4; ++c) sacc[row * (NB + 1) + cw + c] = (jb + cw + c < r) ? (double)qs[row * QP + jb + cw + c] - acc[c] : 0.0;
     }
     {
       const int j = t >> 4, cc = t & 15;
-      slt[j][cc] = (jb + j < r && jb + cc < r && cc <= j) ? Lm[(long long)(jb + j) * r + jb + cc] : (cc == j ? 1.0 : 0.0);
+      const bool in = jb + j < r && jb + cc < r;
+      const double v = (in && cc <= j) ? Lm[(long long)(jb + j) * r + jb + cc] : (cc == j ? 1.0 : 0.0);
+      ld[j * (NB + 1) + cc] = v;
+      if (cc == j) rinv[j] = 1.0 / v;
     }
     __syncthreads();
-    if (t < 64 && s0 + t < e.S) {
-      double q[FIRA_SOLVE_NB];
+    if (t < ROWS) {
+      double q[NB];
 #pragma unroll
-      for (int k = 0; k < FIRA_SOLVE_NB; ++k) {
-        double v = sacc[t][k];
+      for (int k = 0; k < NB; ++k) {
+        double v = sacc[t * (NB + 1) + k];
 #pragma unroll
-        for (int p = 0; p < FIRA_SOLVE_NB; ++p)
-          if (p < k) v -= q[p] * slt[k][p];
-        q[k] = v / slt[k][k];
+        for (int p2 = 0; p2 < NB; ++p2)
+          if (p2 < k) v -= q[p2] * ld[k * (NB + 1) + p2];
+        q[k] = v * rinv[k];
       }
 #pragma unroll
-      for (int k = 0; k < FIRA_SOLVE_NB; ++k)
-        if (jb + k < r) Q[(long long)(s0 + t) * r + jb + k] = (float)q[k];
+      for (int k = 0; k < NB; ++k) qs[t * QP + jb + k] = (float)q[k];
     }
-    __syncthreads();   // the block's Q values are in memory before the next block reads them
+    __syncthreads();
   }
+  for (int x = t; x < ROWS * r; x += 256) {
+    const int rr = x / r, a = x % r;
+    if (s0 + rr < e.S) Q[(long long)(s0 + rr) * r + a] = qs[rr * QP + a];
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Installation of the listed matrices' projectors from their Q buffers, one launch per phase for all
+// of them (blockIdx.y = list entry) instead of four launches per matrix: the operand copies Pn / PT
+// (fira_prep_projector_kernel) and the estimate of ||P^T P - I|| behind the Gram gate (the three
+// fira_ortho_* kernels), each with its own scratch.
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void fira_refresh_prep_kernel(const FiraMat* __restrict__ mats, const FiraRefreshEnt* __restrict__ ents) {
+  const FiraRefreshEnt e = ents[blockIdx.y];
+  prep_projector_body<float>(mats[e.mat], e.Q);
+}
+__global__ __launch_bounds__(256) void fira_refresh_ortho_y_kernel(const FiraMat* __restrict__ mats, const FiraRefreshEnt* __restrict__ ents) {
+  const FiraRefreshEnt e = ents[blockIdx.y];
+  if ((int)blockIdx.x * 4 >= e.S) return;
+  ortho_y_body(mats[e.mat], e.inst);
+}
+__global__ __launch_bounds__(256) void fira_refresh_ortho_z_kernel(const FiraMat* __restrict__ mats, const FiraRefreshEnt* __restrict__ ents) {
+  const FiraRefreshEnt e = ents[blockIdx.y];
+  ortho_z_body(mats[e.mat], e.inst, e.inst + (size_t)e.S * 4);
+}
+__global__ __launch_bounds__(256) void fira_refresh_ortho_final_kernel(const FiraMat* __restrict__ mats, const FiraRefreshEnt* __restrict__ ents,
+                                                                       FiraScal* __restrict__ scal) {
+  __shared__ float red[4][4];
+  const FiraRefreshEnt e = ents[blockIdx.x];
+  ortho_final_body(mats[e.mat], e.inst + (size_t)e.S * 4, scal, e.mat, red);
 }
