@@ -361,6 +361,7 @@ fira_status fira_init_state(fira_ctx** out, const fira_matrix_desc* d, int count
   FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_backproject_kernel<1, bf16_raw>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_BACK_LDS));
   FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_backproject_kernel<0, float>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_BACK_LDS));
   FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_backproject_kernel<1, float>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_BACK_LDS));
+  FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_refresh_solve_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_SOLVE_LDS(64, 576)));
   FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_refresh_solve_kernel<32>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_SOLVE_LDS(32, 1152)));
   FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_refresh_solve_kernel<16>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_SOLVE_LDS(16, FIRA_REFRESH_MAX_R)));
   FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_project_adam_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_FUSE_LDS(1)));
@@ -894,7 +895,9 @@ fira_status fira_refresh_projectors(fira_ctx* ctx, int count, const int* idx, co
   auto orthonormalise = [&](const FiraRefreshEnt* de) {
     hipLaunchKernelGGL(fira_refresh_gram_kernel, dim3(nt64 * (nt64 + 1) / 2, count), dim3(256), 0, q, de);
     hipLaunchKernelGGL(fira_refresh_chol_kernel, dim3(count), dim3(FIRA_CHOL_THREADS), 0, q, de);
-    if (max_r <= 1152)
+    if (max_r <= 576)
+      hipLaunchKernelGGL(fira_refresh_solve_kernel<64>, dim3((max_S + 63) / 64, count), dim3(256), FIRA_SOLVE_LDS(64, max_r), q, de);
+    else if (max_r <= 1152)
       hipLaunchKernelGGL(fira_refresh_solve_kernel<32>, dim3((max_S + 31) / 32, count), dim3(256), FIRA_SOLVE_LDS(32, max_r), q, de);
     else
       hipLaunchKernelGGL(fira_refresh_solve_kernel<16>, dim3((max_S + 15) / 16, count), dim3(256), FIRA_SOLVE_LDS(16, max_r), q, de);

@@ -233,15 +233,16 @@ __global__ __launch_bounds__(FIRA_CHOL_THREADS) void fira_refresh_chol_kernel(co
 // Rows are independent.  A workgroup keeps ROWS of them in LDS for the whole solve (a row starts as y
 // and is overwritten by q column block by column block; fp32, as the result is stored).  Columns go in
 // blocks of 16, four per wavefront.  In the product with the columns already solved, ROWS x 16 x jb in
-// fp64, a lane owns one row and every 64/ROWS-th pair of k, so its q values come from LDS without bank
-// conflicts, and the L values, the same for all lanes of a row group, are read straight from memory (one
-// cache line per request, shared by every workgroup of the matrix in L2): four fp64 multiply-adds per
-// q value and L request.  Then ROWS threads finish their row's 16 values against the diagonal block with
-// the reciprocals of its diagonal.  Three barriers per column block.  The loop is bound by the latency
-// of the L requests; 32 rows per workgroup leave room for two workgroups per CU up to r = 560.
-// (A version that re-read Q from memory 16 columns at a time, two barriers and a global round trip per
-// 16 x 16 piece, took 20 % longer; one that staged L through LDS was bound by LDS reads and slower.)
-// ROWS = 32 up to r = 1152, 16 up to FIRA_REFRESH_MAX_R: the rows must fit the CU's LDS.
+// fp64, a lane owns one row (ROWS = 64) or one row and every 64/ROWS-th pair of k, so its q values come
+// from LDS without bank conflicts.  The L values are the same for all lanes of a row group and are read
+// straight from memory: with one row per lane through the scalar cache (64 bytes per request), otherwise
+// one cache line per vector request; every workgroup of a matrix shares them in L2.  Four fp64
+// multiply-adds per q value and L value.  Then ROWS threads finish their row's 16 values against the
+// diagonal block with the reciprocals of its diagonal.  Three barriers per column block.  What bounds the
+// loop is the latency of the L requests (about a tenth of the fp64 rate is reached); staging L in LDS
+// instead was slower (broadcast reads cost full LDS bandwidth), and so was re-reading Q from memory
+// 16 columns at a time with two barriers per 16 x 16 piece, the first form of this kernel.
+// ROWS = 64 up to r = 576, 32 up to 1152, 16 up to FIRA_REFRESH_MAX_R: the rows must fit the CU's LDS.
 #define FIRA_SOLVE_NB 16
 #define FIRA_REFRESH_MAX_R 1792
 #define FIRA_SOLVE_LDS(ROWS, r) ((ROWS) * ((((r) + 15) / 16 * 16) + 1) * 4 + (ROWS) * (FIRA_SOLVE_NB + 1) * 8 + \
@@ -262,8 +263,8 @@ __global__ __launch_bounds__(256) void fira_refresh_solve_kernel(const FiraRefre
   gptr<const float> Y = as_global<const float>(e.Y);
   gptr<const double> Lm = as_global<const double>(e.C);
   gptr<float> Q = as_global(e.Q);
-  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-  const int row = lane % ROWS, ks = lane / ROWS, cw = 4 * wave;
+  const int t = threadIdx.x, lane = t & 63, wave = __builtin_amdgcn_readfirstlane(t >> 6);
+  const int row = lane % ROWS, ks = KS == 1 ? 0 : lane / ROWS, cw = 4 * wave;
   // the rows of Y (zeros beyond S and r)
   for (int x = t; x < ROWS * rp; x += 256) {
     const int rr = x / rp, a = x % rp;
@@ -273,9 +274,14 @@ __global__ __launch_bounds__(256) void fira_refresh_solve_kernel(const FiraRefre
   for (int jb = 0; jb < rp; jb += NB) {
     double acc[4] = {0.0, 0.0, 0.0, 0.0};
     // rows jb + cw + c of L, clamped into the matrix (columns beyond r have no weight: their q is zero)
-    gptr<const double> lrow[4];
+    // (with one row per lane the addresses are the same for the whole wavefront: the constant address
+    // space lets the compiler fetch them through the scalar cache, leaving LDS and the vector memory
+    // path to the q values; L is not written in this kernel)
+    typedef const __attribute__((address_space(4))) double* lptr_t;
+    lptr_t lrow[4];
 #pragma unroll
-    for (int c = 0; c < 4; ++c) lrow[c] = Lm + (long long)(jb + cw + c < r ? jb + cw + c : r - 1) * r;
+    for (int c = 0; c < 4; ++c)
+      lrow[c] = (lptr_t)(const double*)Lm + (long long)(jb + cw + c < r ? jb + cw + c : r - 1) * r;
     const float* qrow = qs + row * QP;
 #pragma unroll 8
     for (int k = 2 * ks; k < jb; k += 2 * KS) {     // jb is a multiple of 16: pairs never straddle it
