@@ -361,6 +361,7 @@ fira_status fira_init_state(fira_ctx** out, const fira_matrix_desc* d, int count
   FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_backproject_kernel<1, bf16_raw>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_BACK_LDS));
   FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_backproject_kernel<0, float>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_BACK_LDS));
   FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_backproject_kernel<1, float>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_BACK_LDS));
+  FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_refresh_chol_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_CHOL_PAN_ROWS * (FIRA_CHOL_NB + 1) * 8));
   FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_refresh_solve_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_SOLVE_LDS(64, 576)));
   FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_refresh_solve_kernel<32>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_SOLVE_LDS(32, 1152)));
   FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_refresh_solve_kernel<16>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_SOLVE_LDS(16, FIRA_REFRESH_MAX_R)));
@@ -894,7 +895,10 @@ fira_status fira_refresh_projectors(fira_ctx* ctx, int count, const int* idx, co
   const int prep_blocks = (int)std::min<long long>(((long long)max_S * max_r + 255) / 256, 4096);
   auto orthonormalise = [&](const FiraRefreshEnt* de) {
     hipLaunchKernelGGL(fira_refresh_gram_kernel, dim3(nt64 * (nt64 + 1) / 2, count), dim3(256), 0, q, de);
-    hipLaunchKernelGGL(fira_refresh_chol_kernel, dim3(count), dim3(FIRA_CHOL_THREADS), 0, q, de);
+    {
+      const int pan_rows = std::min(FIRA_CHOL_PAN_ROWS, std::max(max_r - FIRA_CHOL_NB, 0));
+      hipLaunchKernelGGL(fira_refresh_chol_kernel, dim3(count), dim3(FIRA_CHOL_THREADS), (size_t)pan_rows * (FIRA_CHOL_NB + 1) * 8, q, de, pan_rows);
+    }
     if (max_r <= 576)
       hipLaunchKernelGGL(fira_refresh_solve_kernel<64>, dim3((max_S + 63) / 64, count), dim3(256), FIRA_SOLVE_LDS(64, max_r), q, de);
     else if (max_r <= 1152)

@@ -136,9 +136,15 @@ __global__ __launch_bounds__(256) void fira_refresh_gram_kernel(const FiraRefres
 // keeps the factor finite; the directions it affects carry no energy of G.
 #define FIRA_CHOL_THREADS 512
 #define FIRA_CHOL_NB 32
-__global__ __launch_bounds__(FIRA_CHOL_THREADS) void fira_refresh_chol_kernel(const FiraRefreshEnt* __restrict__ ents) {
+#define FIRA_CHOL_PAN_ROWS 544   // panel rows kept in LDS: 544 x 33 doubles = 140 KB (every panel of a matrix with r <= 576)
+__global__ __launch_bounds__(FIRA_CHOL_THREADS) void fira_refresh_chol_kernel(const FiraRefreshEnt* __restrict__ ents, int pan_rows) {
   __shared__ double D[FIRA_CHOL_NB][FIRA_CHOL_NB + 1];
+  __shared__ double rinv_s[FIRA_CHOL_NB];
   __shared__ double dmax_s;
+  // the panel below the diagonal block, [rows][FIRA_CHOL_NB + 1], while it fits (pan_rows rows of dynamic LDS):
+  // the panel solve and the trailing update then read it from LDS instead of walking through memory
+  extern __shared__ __attribute__((aligned(16))) double chol_pan[];
+  constexpr int PP = FIRA_CHOL_NB + 1;
   const FiraRefreshEnt e = ents[blockIdx.x];
   const int r = e.r, t = threadIdx.x;
   gptr<double> C = as_global(e.C);
@@ -183,8 +189,30 @@ __global__ __launch_bounds__(FIRA_CHOL_THREADS) void fira_refresh_chol_kernel(co
       const int i = x / nb, k = x % nb;
       if (k <= i) C[(long long)(jb + i) * r + jb + k] = D[i][k];
     }
+    if (t < nb) rinv_s[t] = 1.0 / D[t][t];
     // (2) panel: rows below the block, X D^T = C_panel  (forward substitution along the block's columns)
     const int below = r - (jb + nb);
+    const bool in_lds = below <= pan_rows;
+    if (in_lds) {
+      for (int x = t; x < below * nb; x += FIRA_CHOL_THREADS) {
+        const int i = x / nb, k = x % nb;
+        chol_pan[i * PP + k] = C[(long long)(jb + nb + i) * r + jb + k];
+      }
+      __syncthreads();
+      for (int i = t; i < below; i += FIRA_CHOL_THREADS) {
+        double* row = chol_pan + i * PP;
+        for (int k = 0; k < nb; ++k) {
+          double sacc = row[k];
+          for (int p = 0; p < k; ++p) sacc -= row[p] * D[k][p];
+          row[k] = sacc * rinv_s[k];
+        }
+      }
+      __syncthreads();
+      for (int x = t; x < below * nb; x += FIRA_CHOL_THREADS) {
+        const int i = x / nb, k = x % nb;
+        C[(long long)(jb + nb + i) * r + jb + k] = chol_pan[i * PP + k];
+      }
+    } else
     for (int i = t; i < below; i += FIRA_CHOL_THREADS) {
       gptr<double> row = C + (long long)(jb + nb + i) * r + jb;
       // the row's own earlier results are read back from memory (a thread sees its own stores)
@@ -210,8 +238,13 @@ __global__ __launch_bounds__(FIRA_CHOL_THREADS) void fira_refresh_chol_kernel(co
         double a[4], b[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          a[i] = (i0 + i < r) ? C[(long long)(i0 + i) * r + jb + p] : 0.0;
-          b[i] = (k0 + i < r) ? C[(long long)(k0 + i) * r + jb + p] : 0.0;
+          if (in_lds) {
+            a[i] = (i0 + i < r) ? chol_pan[(4 * bi + i) * PP + p] : 0.0;
+            b[i] = (k0 + i < r) ? chol_pan[(4 * bk + i) * PP + p] : 0.0;
+          } else {
+            a[i] = (i0 + i < r) ? C[(long long)(i0 + i) * r + jb + p] : 0.0;
+            b[i] = (k0 + i < r) ? C[(long long)(k0 + i) * r + jb + p] : 0.0;
+          }
         }
 #pragma unroll
         for (int i = 0; i < 4; ++i)
