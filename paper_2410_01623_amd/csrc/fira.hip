@@ -362,9 +362,7 @@ fira_status fira_init_state(fira_ctx** out, const fira_matrix_desc* d, int count
   FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_backproject_kernel<0, float>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_BACK_LDS));
   FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_backproject_kernel<1, float>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_BACK_LDS));
   FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_refresh_chol_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_CHOL_PAN_ROWS * (FIRA_CHOL_NB + 1) * 8));
-  FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_refresh_solve_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_SOLVE_LDS(64, 576)));
-  FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_refresh_solve_kernel<32>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_SOLVE_LDS(32, 1152)));
-  FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_refresh_solve_kernel<16>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_SOLVE_LDS(16, FIRA_REFRESH_MAX_R)));
+  FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_refresh_solve_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_SOLVE_LDS));
   FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_project_adam_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_FUSE_LDS(1)));
   FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_project_adam_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_FUSE_LDS(2)));
   FIRA_INIT_HIP(hipHostMalloc((void**)&ctx->h_stage_all, p.slot_bytes * kSlots, hipHostMallocDefault));
@@ -789,7 +787,9 @@ bool make_refresh_plan(const fira_ctx* ctx, int count, const int* idx, RefreshPl
     rp->off_y[e] = take((size_t)m.S * m.r * 4);
     rp->off_q[e] = take((size_t)m.S * m.r * 4);
     rp->off_c[e] = take((size_t)m.r * m.r * 8);
-    rp->off_linv[e] = take((size_t)m.S * 16 + (size_t)FIRA_ORTHO_SPLITS * m.r * 16);   // scratch of the gate estimate
+    // scratch of the gate estimate, which before that holds the inverses of the solve's diagonal blocks
+    rp->off_linv[e] = take(std::max((size_t)m.S * 16 + (size_t)FIRA_ORTHO_SPLITS * m.r * 16,
+                                    (size_t)((m.r + FIRA_SOLVE_JB - 1) / FIRA_SOLVE_JB) * FIRA_SOLVE_JB * FIRA_SOLVE_JB * 8));
   }
   rp->total = off;
   return true;
@@ -818,7 +818,6 @@ fira_status fira_refresh_projectors(fira_ctx* ctx, int count, const int* idx, co
       seen[idx[e]] = 1;
       if (!dev_G[e]) return fail(ctx, FIRA_ERR_INVALID_ARG, "null G pointer");
       if (ctx->plan.mats[idx[e]].dev.kx != 1) return fail(ctx, FIRA_ERR_DTYPE, "the device refresh handles bf16 matrices only");
-      if (ctx->plan.mats[idx[e]].dev.r > FIRA_REFRESH_MAX_R) return fail(ctx, FIRA_ERR_SHAPE, "the device refresh handles ranks up to 1792");
     }
   }
   RefreshPlan rp;
@@ -899,12 +898,10 @@ fira_status fira_refresh_projectors(fira_ctx* ctx, int count, const int* idx, co
       const int pan_rows = std::min(FIRA_CHOL_PAN_ROWS, std::max(max_r - FIRA_CHOL_NB, 0));
       hipLaunchKernelGGL(fira_refresh_chol_kernel, dim3(count), dim3(FIRA_CHOL_THREADS), (size_t)pan_rows * (FIRA_CHOL_NB + 1) * 8, q, de, pan_rows);
     }
-    if (max_r <= 576)
-      hipLaunchKernelGGL(fira_refresh_solve_kernel<64>, dim3((max_S + 63) / 64, count), dim3(256), FIRA_SOLVE_LDS(64, max_r), q, de);
-    else if (max_r <= 1152)
-      hipLaunchKernelGGL(fira_refresh_solve_kernel<32>, dim3((max_S + 31) / 32, count), dim3(256), FIRA_SOLVE_LDS(32, max_r), q, de);
-    else
-      hipLaunchKernelGGL(fira_refresh_solve_kernel<16>, dim3((max_S + 15) / 16, count), dim3(256), FIRA_SOLVE_LDS(16, max_r), q, de);
+    const int nj = (max_r + FIRA_SOLVE_JB - 1) / FIRA_SOLVE_JB;
+    hipLaunchKernelGGL(fira_refresh_diaginv_kernel, dim3(nj, count), dim3(64), 0, q, de);
+    for (int J = 0; J < nj; ++J)
+      hipLaunchKernelGGL(fira_refresh_solve_kernel, dim3((max_S + 63) / 64, count), dim3(256), FIRA_SOLVE_LDS, q, de, J);
   };
   auto launch_project = [&](const FiraMat* mats, const FiraEnt* ents_d, const FiraTile* tl, int nl, const FiraTile* tr, int nr) {
     const int bl = (nl + 7) / 8 * 8, br = (nr + 7) / 8 * 8;

@@ -25,7 +25,8 @@ struct FiraRefreshEnt {
   float* Y;            // [S][r]
   float* Q;            // [S][r]
   double* C;           // [r][r]            Gram matrix, then its Cholesky factor (lower triangle)
-  float* inst;         // scratch of the orthonormality estimate: [S][4], then [FIRA_ORTHO_SPLITS][r][4]
+  float* inst;         // scratch: inverses of the solve's diagonal blocks ([r/64][64][64] fp64), later the
+                       // orthonormality estimate's [S][4] and [FIRA_ORTHO_SPLITS][r][4]
 };
 
 // splitmix64 finaliser: one independent 64-bit value per counter
@@ -261,108 +262,123 @@ __global__ __launch_bounds__(FIRA_CHOL_THREADS) void fira_refresh_chol_kernel(co
   }
 }
 
-// Q = Y L^-T, i.e. every row solves  q L^T = y  by forward substitution:
-//     q_a = (y_a - sum_{b < a} q_b L[a][b]) / L[a][a].
-// Rows are independent.  A workgroup keeps ROWS of them in LDS for the whole solve (a row starts as y
-// and is overwritten by q column block by column block; fp32, as the result is stored).  Columns go in
-// blocks of 16, four per wavefront.  In the product with the columns already solved, ROWS x 16 x jb in
-// fp64, a lane owns one row (ROWS = 64) or one row and every 64/ROWS-th pair of k, so its q values come
-// from LDS without bank conflicts.  The L values are the same for all lanes of a row group and are read
-// straight from memory: with one row per lane through the scalar cache (64 bytes per request), otherwise
-// one cache line per vector request; every workgroup of a matrix shares them in L2.  Four fp64
-// multiply-adds per q value and L value.  Then ROWS threads finish their row's 16 values against the
-// diagonal block with the reciprocals of its diagonal.  Three barriers per column block.  What bounds the
-// loop is the latency of the L requests (about a tenth of the fp64 rate is reached); staging L in LDS
-// instead was slower (broadcast reads cost full LDS bandwidth), and so was re-reading Q from memory
-// 16 columns at a time with two barriers per 16 x 16 piece, the first form of this kernel.
-// ROWS = 64 up to r = 576, 32 up to 1152, 16 up to FIRA_REFRESH_MAX_R: the rows must fit the CU's LDS.
-#define FIRA_SOLVE_NB 16
-#define FIRA_REFRESH_MAX_R 1792
-#define FIRA_SOLVE_LDS(ROWS, r) ((ROWS) * ((((r) + 15) / 16 * 16) + 1) * 4 + (ROWS) * (FIRA_SOLVE_NB + 1) * 8 + \
-                                 FIRA_SOLVE_NB * (FIRA_SOLVE_NB + 1) * 8 + FIRA_SOLVE_NB * 8 + 16)
-template <int ROWS>
-__global__ __launch_bounds__(256) void fira_refresh_solve_kernel(const FiraRefreshEnt* __restrict__ ents) {
-  constexpr int NB = FIRA_SOLVE_NB;
-  constexpr int KS = 64 / ROWS;                              // lanes that share a row, each taking every KS-th pair of k
-  extern __shared__ __attribute__((aligned(16))) char solve_lds[];
+// Q = Y L^-T, i.e. every row solves  q L^T = y  by forward substitution, done in column blocks of 64:
+//     Q_J = (Y_J - Q_{<J} L_{J,<J}^T) inv(L_JJ)^T.
+// Everything but the 64 x 64 inverses of the diagonal blocks is a dense product, so the work is tiled like
+// the Gram kernel (64 x 64 output tile, fp64 accumulation, 4 x 4 outputs per thread, operands staged through
+// LDS): one launch per column block J, in order, each reading the blocks of Q written by the launches
+// before it (fp32, as the result is stored).  The inverses of the diagonal blocks come from a small
+// kernel of their own (one thread per column of an inverse) and live in the scratch of the installation,
+// which is idle until the solves are done.  (Forms that kept a workgroup's rows in LDS and walked along
+// the columns, one row per lane with L read from memory or staged in LDS, ran at a tenth of the fp64
+// rate: bound by the latency, or the LDS bandwidth, of the operand every lane shares.)
+#define FIRA_SOLVE_JB 64
+#define FIRA_SOLVE_LDS (16 * 64 * 4 + 16 * 64 * 8 + 64 * 65 * 8 + 64 * 64 * 8)
+
+// inv(L_JJ) for every diagonal block J of a matrix: inv[J][k][c], k >= c (zero above the diagonal).
+// Rows and columns beyond r act as an identity.
+__global__ __launch_bounds__(64) void fira_refresh_diaginv_kernel(const FiraRefreshEnt* __restrict__ ents) {
+  __shared__ double Ld[64][65];
   const FiraRefreshEnt e = ents[blockIdx.y];
-  const int s0 = blockIdx.x * ROWS;
-  if (s0 >= e.S) return;
-  const int r = e.r, rp = (r + NB - 1) / NB * NB, QP = rp + 1;   // odd row pitch: the rows of a column fall in distinct banks
-  float* qs = reinterpret_cast<float*>(solve_lds);                 // [ROWS][QP]
-  double* sacc = reinterpret_cast<double*>(solve_lds + ((ROWS * QP * 4 + 15) & ~15));   // [ROWS][NB + 1]
-  double* ld = sacc + ROWS * (NB + 1);                             // [NB][NB + 1]: diagonal block
-  double* rinv = ld + NB * (NB + 1);                               // [NB]
+  const int r = e.r, j0 = blockIdx.x * FIRA_SOLVE_JB, c = threadIdx.x;
+  if (j0 >= r) return;
+  gptr<const double> Lm = as_global<const double>(e.C);
+  for (int x = c; x < 64 * 64; x += 64) {
+    const int i = x >> 6, k = x & 63;
+    const bool in = j0 + i < r && j0 + k < r;
+    Ld[i][k] = (in && k <= i) ? Lm[(long long)(j0 + i) * r + j0 + k] : (i == k ? 1.0 : 0.0);
+  }
+  __syncthreads();
+  // column c of the inverse: L x = e_c
+  double x[64];
+#pragma unroll
+  for (int i = 0; i < 64; ++i) {
+    double v = (i == c) ? 1.0 : 0.0;
+#pragma unroll
+    for (int p = 0; p < 64; ++p)
+      if (p < i) v -= Ld[i][p] * x[p];
+    x[i] = (i < c) ? 0.0 : v / Ld[i][i];
+  }
+  gptr<double> inv = reinterpret_cast<gptr<double>>(as_global(e.inst)) + (size_t)blockIdx.x * 64 * 64;
+#pragma unroll
+  for (int i = 0; i < 64; ++i) inv[i * 64 + c] = x[i];
+}
+
+// Column block J of Q for 64 rows.
+__global__ __launch_bounds__(256) void fira_refresh_solve_kernel(const FiraRefreshEnt* __restrict__ ents, int J) {
+  extern __shared__ __attribute__((aligned(16))) char solve_lds[];
+  float (*sa)[64] = reinterpret_cast<float (*)[64]>(solve_lds);                       // [16][64]  Q[s0 + i][k0 + kk]
+  double (*sb)[64] = reinterpret_cast<double (*)[64]>(solve_lds + 16 * 64 * 4);        // [16][64]  L[j0 + j][k0 + kk]
+  double (*st)[65] = reinterpret_cast<double (*)[65]>(solve_lds + 16 * 64 * 4 + 16 * 64 * 8);   // [64][65] Y_J - update
+  double (*invT)[64] = reinterpret_cast<double (*)[64]>(solve_lds + 16 * 64 * 4 + 16 * 64 * 8 + 64 * 65 * 8);   // [c][k]
+  const FiraRefreshEnt e = ents[blockIdx.y];
+  const int r = e.r, s0 = blockIdx.x * 64, j0 = J * FIRA_SOLVE_JB;
+  if (s0 >= e.S || j0 >= r) return;
   gptr<const float> Y = as_global<const float>(e.Y);
   gptr<const double> Lm = as_global<const double>(e.C);
   gptr<float> Q = as_global(e.Q);
-  const int t = threadIdx.x, lane = t & 63, wave = __builtin_amdgcn_readfirstlane(t >> 6);
-  const int row = lane % ROWS, ks = KS == 1 ? 0 : lane / ROWS, cw = 4 * wave;
-  // the rows of Y (zeros beyond S and r)
-  for (int x = t; x < ROWS * rp; x += 256) {
-    const int rr = x / rp, a = x % rp;
-    qs[rr * QP + a] = (s0 + rr < e.S && a < r) ? Y[(long long)(s0 + rr) * r + a] : 0.0f;
+  gptr<const double> inv = reinterpret_cast<gptr<const double>>(as_global(e.inst)) + (size_t)J * 64 * 64;
+  const int t = threadIdx.x, tx = t & 15, ty = t >> 4;
+  RefreshAcc acc;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc.v[i][j] = 0.0;
+  const int lr = t >> 2, lk = (t & 3) * 4;      // staging: row (or column of the block) lr, four k from lk
+  for (int k0 = 0; k0 < j0; k0 += 16) {         // j0 is a multiple of 64: whole tiles, all inside the matrix
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      sa[lk + q][lr] = (s0 + lr < e.S) ? Q[(long long)(s0 + lr) * r + k0 + lk + q] : 0.0f;
+      sb[lk + q][lr] = (j0 + lr < r) ? Lm[(long long)(j0 + lr) * r + k0 + lk + q] : 0.0;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < 16; ++kk) {
+      double a[4], b[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { a[i] = (double)sa[kk][4 * ty + i]; b[i] = sb[kk][4 * tx + i]; }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc.v[i][j] += a[i] * b[j];
+    }
+    __syncthreads();
+  }
+  // T = Y_J - update, and the inverse of the diagonal block (transposed: invT[c][k] = inv[k][c])
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int row = 4 * ty + i, col = 4 * tx + j;
+      const double y = (s0 + row < e.S && j0 + col < r) ? (double)Y[(long long)(s0 + row) * r + j0 + col] : 0.0;
+      st[row][col] = y - acc.v[i][j];
+    }
+  for (int x = t; x < 64 * 64; x += 256) {
+    const int k = x >> 6, c = x & 63;
+    invT[c][k] = inv[x];
   }
   __syncthreads();
-  for (int jb = 0; jb < rp; jb += NB) {
-    double acc[4] = {0.0, 0.0, 0.0, 0.0};
-    // rows jb + cw + c of L, clamped into the matrix (columns beyond r have no weight: their q is zero)
-    // (with one row per lane the addresses are the same for the whole wavefront: the constant address
-    // space lets the compiler fetch them through the scalar cache, leaving LDS and the vector memory
-    // path to the q values; L is not written in this kernel)
-    typedef const __attribute__((address_space(4))) double* lptr_t;
-    lptr_t lrow[4];
+  // Q_J = T inv^T:  q[row][k] = sum_{c <= k} T[row][c] inv[k][c]
 #pragma unroll
-    for (int c = 0; c < 4; ++c)
-      lrow[c] = (lptr_t)(const double*)Lm + (long long)(jb + cw + c < r ? jb + cw + c : r - 1) * r;
-    const float* qrow = qs + row * QP;
-#pragma unroll 8
-    for (int k = 2 * ks; k < jb; k += 2 * KS) {     // jb is a multiple of 16: pairs never straddle it
-      const float q0 = qrow[k], q1 = qrow[k + 1];
+  for (int i = 0; i < 4; ++i)
 #pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        const double l0 = lrow[c][k], l1 = lrow[c][k + 1];
-        acc[c] += (double)q0 * l0 + (double)q1 * l1;
-      }
-    }
-    if (KS > 1) {
+    for (int j = 0; j < 4; ++j) acc.v[i][j] = 0.0;
+  for (int c = 0; c < 64; ++c) {
+    double a[4], b[4];
 #pragma unroll
-      for (int c = 0; c < 4; ++c)
+    for (int i = 0; i < 4; ++i) { a[i] = st[4 * ty + i][c]; b[i] = invT[c][4 * tx + i]; }
 #pragma unroll
-        for (int o = ROWS; o < 64; o <<= 1) acc[c] += __shfl_xor(acc[c], o, 64);
-    }
-    // right-hand side minus the solved part; the diagonal block of L and the reciprocals of its diagonal
-    if (ks == 0) {
+    for (int i = 0; i < 4; ++i)
 #pragma unroll
-      for (int c = 0; c < 4; ++c) sacc[row * (NB + 1) + cw + c] = (jb + cw + c < r) ? (double)qs[row * QP + jb + cw + c] - acc[c] : 0.0;
-    }
-    {
-      const int j = t >> 4, cc = t & 15;
-      const bool in = jb + j < r && jb + cc < r;
-      const double v = (in && cc <= j) ? Lm[(long long)(jb + j) * r + jb + cc] : (cc == j ? 1.0 : 0.0);
-      ld[j * (NB + 1) + cc] = v;
-      if (cc == j) rinv[j] = 1.0 / v;
-    }
-    __syncthreads();
-    if (t < ROWS) {
-      double q[NB];
-#pragma unroll
-      for (int k = 0; k < NB; ++k) {
-        double v = sacc[t * (NB + 1) + k];
-#pragma unroll
-        for (int p2 = 0; p2 < NB; ++p2)
-          if (p2 < k) v -= q[p2] * ld[k * (NB + 1) + p2];
-        q[k] = v * rinv[k];
-      }
-#pragma unroll
-      for (int k = 0; k < NB; ++k) qs[t * QP + jb + k] = (float)q[k];
-    }
-    __syncthreads();
+      for (int j = 0; j < 4; ++j) acc.v[i][j] += a[i] * b[j];
   }
-  for (int x = t; x < ROWS * r; x += 256) {
-    const int rr = x / r, a = x % r;
-    if (s0 + rr < e.S) Q[(long long)(s0 + rr) * r + a] = qs[rr * QP + a];
-  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int row = 4 * ty + i, k = 4 * tx + j;
+      if (s0 + row < e.S && j0 + k < r) Q[(long long)(s0 + row) * r + j0 + k] = (float)acc.v[i][j];
+    }
 }
 
 // ------------------------------------------------------------------------------------------------
