@@ -41,3 +41,58 @@ def test_twin_matrices_stay_bit_identical(norm_mode):
         bad = [i for i in range(nb, n) if not torch.equal(W[i], W[i % nb])]
         assert not bad, f"step {s}: matrices {bad[:8]} differ from their twins"
     assert all(bool(torch.isfinite(W[j]).all()) for j in range(nb))
+
+
+def test_step_replays_from_a_hip_graph():
+    """fira_step only enqueues kernels once its work list is cached and the projectors' gate values are in,
+    so a training loop can capture it in a HIP graph.  Three replays with fresh gradients (copied into the
+    captured buffers, with eager work and synchronisations in between) must give, bit for bit, what eager
+    steps give on a twin context."""
+    dev = "cuda:0"
+    shapes = [(256, 640), (640, 256), (384, 384)]
+    r = 128
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(7)
+    side = torch.cuda.Stream(device=dev)
+    ctx_e = fira.FiraContext(shapes, r, fira.FIRA_BF16, device=dev)                  # eager twin
+    ctx_g = fira.FiraContext(shapes, r, fira.FIRA_BF16, device=dev, stream=side)     # captured
+    W_e = [(0.02 * torch.randn(s, device=dev, generator=gen)).to(torch.bfloat16) for s in shapes]
+    W_g = [w.clone() for w in W_e]
+    G_e = [torch.zeros(s, device=dev, dtype=torch.bfloat16) for s in shapes]
+    G_g = [torch.zeros(s, device=dev, dtype=torch.bfloat16) for s in shapes]
+    for i, (m, n) in enumerate(shapes):
+        q, _ = torch.linalg.qr(torch.randn((min(m, n), r), device=dev, generator=gen))
+        P = q.to(torch.bfloat16).contiguous()
+        torch.cuda.synchronize()
+        ctx_e.fira_set_projector(i, P)
+        ctx_g.fira_set_projector(i, P)
+    idx = list(range(len(shapes)))
+    prep_e, prep_g = ctx_e.prepare(idx, W_e, G_e), ctx_g.prepare(idx, W_g, G_g)
+
+    def load_new_gradients():
+        for ge, gg, s in zip(G_e, G_g, shapes):
+            g = (1e-2 * torch.randn(s, device=dev, generator=gen)).to(torch.bfloat16)
+            ge.copy_(g)
+            gg.copy_(g)
+        torch.cuda.synchronize()
+
+    # one eager step on both: caches the work lists and collects the gate values
+    load_new_gradients()
+    ctx_e.fira_step(prepared=prep_e)
+    ctx_g.fira_step(prepared=prep_g)
+    torch.cuda.synchronize()
+    assert ctx_g.fira_last_step_fused()
+    for a, b in zip(W_e, W_g):
+        assert torch.equal(a, b)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        ctx_g.fira_step(prepared=prep_g)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        load_new_gradients()
+        graph.replay()
+        ctx_e.fira_step(prepared=prep_e)
+        torch.cuda.synchronize()
+        _ = sum(float(w.float().abs().sum()) for w in W_g)      # eager work between the replays
+        for i in range(len(shapes)):
+            assert torch.equal(W_g[i], W_e[i]), f"replay {rep}, matrix {i}"
