@@ -797,7 +797,8 @@ template <int MODE, typename T, bool INTERIOR>
 __device__ __forceinline__ float backproject_epilogue(f32x16_t (&acc)[4][2], char* lds, const FiraMat& mt,
                                                       const FiraEnt& ent, int i0, int j0, float c, float lr_alpha, bool unitk) {
   typedef typename Elem8<T>::Raw Raw;
-  constexpr bool PIPE = sizeof(T) == 2;       // fp32 tiles would need 128 more registers: no prefetch
+  // fp32 tiles would need 128 more registers: no prefetch; neither in the norm pass, which spills with it
+  constexpr bool PIPE = sizeof(T) == 2 && MODE == 1;
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wm = wave & 1, wn = wave >> 1;
   float* buf = reinterpret_cast<float*>(lds) + wn * (32 * FIRA_EPI_STRIDE);
