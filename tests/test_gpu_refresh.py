@@ -24,8 +24,9 @@ def _gapped_gradient(rng, m, n, r, tail=0.05):
     return synth.as_bf16_values(1e-2 * (U * s) @ V.T)
 
 
-@pytest.mark.parametrize("m,n,r", [(300, 517, 40), (517, 300, 40), (256, 256, 64), (1024, 2736, 128), (2736, 1024, 128)],
-                         ids=["300x517r40", "517x300r40", "256x256r64", "1024x2736r128", "2736x1024r128"])
+@pytest.mark.parametrize("m,n,r", [(300, 517, 40), (517, 300, 40), (256, 256, 64), (1024, 2736, 128), (2736, 1024, 128),
+                                   (330, 650, 200)],
+                         ids=["300x517r40", "517x300r40", "256x256r64", "1024x2736r128", "2736x1024r128", "330x650r200"])
 def test_refreshed_projector_spans_the_leading_singular_subspace(m, n, r):
     rng = np.random.default_rng(1000 + m + n)
     G = _gapped_gradient(rng, m, n, r)
@@ -51,6 +52,24 @@ def test_refreshed_projector_spans_the_leading_singular_subspace(m, n, r):
     st = orc.OracleState.zeros(m, n, r)
     out = orc.fira_step(W0.astype(np.float64), G.astype(np.float64), P, st, orc.OracleHparams(), store_bf16=True)
     assert H.rel_max(H.to_host(Wd), out["W"]) <= 2e-2
+    del ws
+
+
+def test_refresh_of_a_list_with_different_ranks():
+    """One call over matrices of different ranks and orientations (the orthonormalisation runs as many column
+    blocks as the largest rank needs; a matrix of smaller rank leaves the later launches at once)."""
+    shapes, ranks = [(300, 517), (517, 300), (200, 260)], [40, 136, 24]
+    rng = np.random.default_rng(77)
+    Gs = [_gapped_gradient(rng, m, n, r) for (m, n), r in zip(shapes, ranks)]
+    ctx = fira.FiraContext(shapes, ranks, fira.FIRA_BF16, device=H.DEV)
+    ws = ctx.fira_refresh_projectors([0, 1, 2], [H.to_device(G, fira.FIRA_BF16) for G in Gs], iters=3, seed=3)
+    torch.cuda.synchronize()
+    for i, (G, r) in enumerate(zip(Gs, ranks)):
+        P = ctx.fira_get_projector(i).numpy().astype(np.float64)
+        assert np.all(np.isfinite(P)) and np.max(np.abs(P.T @ P - np.eye(r))) < 2e-2
+        Pref = orc.top_r_projector(G, r)
+        assert orc.subspace_sines(Pref, P).max() < 1e-2
+        assert orc.captured_energy(G, P) > orc.captured_energy(G, Pref) - 1e-4
     del ws
 
 
