@@ -434,6 +434,43 @@ def test_checkpoint_resume_is_bitwise_identical():
         assert torch.equal(A[0], B[0]) and torch.equal(A[1], B[1]) and A[2] == B[2] and A[3] == B[3] == 10
 
 
+def test_checkpoint_resume_through_the_fused_kernel():
+    """The same round trip at a rank the fused projection/Adam kernel takes: M and V written by its epilogue
+    come back through fira_get_state / fira_set_state and the run continues bit for bit."""
+    shapes, r = [(200, 330), (330, 200)], 128
+    rng = np.random.default_rng(31)
+    W0 = [synth.as_bf16_values(0.02 * rng.standard_normal(s)) for s in shapes]
+    Gs = [[synth.as_bf16_values(1e-2 * rng.standard_normal(s)) for s in shapes] for _ in range(6)]
+    Ps = [synth.store_projector(synth.projector_from_gradient(Gs[0][i], r), "bf16") for i in range(2)]
+
+    def fresh():
+        ctx = fira.FiraContext(shapes, r, fira.FIRA_BF16, fira.make_hparams())
+        for i, P in enumerate(Ps):
+            ctx.fira_set_projector(i, H.to_device(P, fira.FIRA_BF16))
+        return ctx, [H.to_device(w, fira.FIRA_BF16) for w in W0]
+
+    def run(ctx, W, steps):
+        for s in steps:
+            ctx.fira_step([0, 1], W, [H.to_device(g, fira.FIRA_BF16) for g in Gs[s]])
+            assert ctx.fira_last_step_fused()
+
+    ctx, W = fresh()
+    run(ctx, W, range(6))
+    ctx2, W2 = fresh()
+    run(ctx2, W2, range(3))
+    saved = [ctx2.fira_get_state(i) for i in range(2)]
+    assert saved[0][0].shape == (r, 330) and saved[1][0].shape == (330, r) and saved[0][3] == 3
+    ctx3, _ = fresh()
+    for i, (M, V, sp, t) in enumerate(saved):
+        ctx3.fira_set_state(i, M, V, sp, t)
+    run(ctx3, W2, range(3, 6))
+    for a, b in zip(W, W2):
+        assert torch.equal(a, b)
+    for i in range(2):
+        A, B = ctx.fira_get_state(i), ctx3.fira_get_state(i)
+        assert torch.equal(A[0], B[0]) and torch.equal(A[1], B[1]) and A[2] == B[2] and A[3] == B[3] == 6
+
+
 def test_list_order_and_subsets():
     """Shuffling the list, or stepping the matrices in separate calls, gives identical bits; t is
     per matrix; repeated runs are bitwise reproducible (no float atomics anywhere)."""
