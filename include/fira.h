@@ -188,6 +188,21 @@ FIRA_API size_t fira_refresh_workspace_bytes(const fira_ctx* ctx, int count, con
 FIRA_API fira_status fira_refresh_projectors(fira_ctx* ctx, int count, const int* idx, const void* const* dev_G,
                                              int iters, uint64_t seed, void* dev_workspace, size_t workspace_bytes);
 
+/* fira_refresh_projectors for callers that cannot allocate device memory (code that runs under a HIP
+ * graph capture, tight serving or training loops, harnesses that forbid hipMalloc): the same computation
+ * with the same kernels and the same result, but the workspace is a static device array of
+ * FIRA_STATIC_SCRATCH_BYTES that is part of the library's code object, so the call performs no device
+ * allocation and takes no workspace argument.  FIRA_ERR_WORKSPACE (nothing enqueued) when the listed
+ * matrices need more than that (fira_refresh_workspace_bytes tells how much: about 16 MB for a
+ * 2048 x 5461 matrix at r = 512, so a large model is refreshed a few matrices per call).  Every GPU the
+ * library is used on holds its own copy of the array until the process ends; all calls on one GPU share
+ * it and it keeps the last call's contents (what must start at zero is cleared by the call itself), so
+ * two calls that overlap in time on one GPU, e.g. from contexts on different streams, race: serialise
+ * them. */
+#define FIRA_STATIC_SCRATCH_BYTES (64u << 20)
+FIRA_API fira_status fira_refresh_projectors_static(fira_ctx* ctx, int count, const int* idx, const void* const* dev_G,
+                                                    int iters, uint64_t seed);
+
 /* Per-kernel timing of the step's launch sequence with HIP events on the context's stream.
  * fira_profile_begin creates the events for up to max_steps steps (the only allocation; it happens
  * here, not in fira_step); every following fira_step records one event before its first kernel

@@ -9,6 +9,7 @@
 #include <cstdio>
 #include <cstddef>
 #include <cstring>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -34,6 +35,37 @@ inline int operand_pitch(long long k) {
 }
 
 thread_local std::string g_last_error;
+
+}  // namespace
+
+// Scratch of fira_refresh_projectors_static: device memory that exists from the moment the library is
+// loaded, so that the call needs no allocation.  Every GPU the library runs on holds its own copy at its own
+// address until the process ends.  In host code the name is only a handle for hipGetSymbolAddress: the
+// device address is looked up once per device (static_scratch_address) and that pointer is what kernels,
+// copies and fills are given.
+static __device__ __align__(256) unsigned char scratch[FIRA_STATIC_SCRATCH_BYTES];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mutex;
+
+// Device address of `scratch` on the current device (looked up once per device); null on failure.
+void* static_scratch_address(int* device_out, std::string* why) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess || dev < 0 || dev >= kMaxDevices) { *why = std::string("hipGetDevice: ") + hipGetErrorString(e); return nullptr; }
+  if (device_out) *device_out = dev;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) { *why = std::string("hipGetSymbolAddress(scratch): ") + hipGetErrorString(e); return nullptr; }
+    g_scratch_ptr[dev] = p;
+  }
+  return g_scratch_ptr[dev];
+}
 
 struct HostMat {
   fira_matrix_desc d;
@@ -192,6 +224,8 @@ struct fira_ctx {
   hipEvent_t ortho_event = nullptr;
   bool ortho_pending = false;
   uint64_t use_counter = 0;
+  int device = -1;               // HIP device that was current at fira_init_state
+  void* static_scratch = nullptr;   // that device's copy of the library's static scratch array
   std::string last_error;
   // optional per-kernel timing (fira_profile_begin / fira_profile_end)
   std::vector<hipEvent_t> prof_events;   // (FIRA_NUM_KERNELS + 1) per recorded step
@@ -321,6 +355,8 @@ fira_status fira_init_state(fira_ctx** out, const fira_matrix_desc* d, int count
   if (((uintptr_t)dev_state % kAlign) != 0 || dev_state_bytes < ctx->plan.total) {
     delete ctx; return fail(nullptr, FIRA_ERR_WORKSPACE, "dev_state must be 256-byte aligned and hold fira_state_bytes() bytes");
   }
+  ctx->static_scratch = static_scratch_address(&ctx->device, &why);
+  if (!ctx->static_scratch) { delete ctx; return fail(nullptr, FIRA_ERR_HIP, why); }
   ctx->slab = (char*)dev_state;
   ctx->stream = (hipStream_t)hip_stream;
   ctx->hp = *hp;
@@ -803,10 +839,16 @@ size_t fira_refresh_workspace_bytes(const fira_ctx* ctx, int count, const int* i
   return rp.total;
 }
 
-fira_status fira_refresh_projectors(fira_ctx* ctx, int count, const int* idx, const void* const* dev_G,
-                                    int iters, uint64_t seed, void* dev_workspace, size_t workspace_bytes) {
-  if (!ctx) return fail(nullptr, FIRA_ERR_INVALID_ARG, "ctx is null");
-  if (count == 0) return FIRA_OK;
+namespace {
+
+// 16-byte pieces [0, n16) of p set to zero (a kernel rather than hipMemsetAsync, so that it is an ordinary
+// kernel node wherever the stream's work is recorded).
+__global__ __launch_bounds__(256) void fira_zero_fill_kernel(u32x4* __restrict__ p, size_t n16) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) p[i] = u32x4{0u, 0u, 0u, 0u};
+}
+
+// Argument checks shared by the two refresh entry points; on success *rp is the workspace layout.
+fira_status refresh_check(fira_ctx* ctx, int count, const int* idx, const void* const* dev_G, int iters, RefreshPlan* rp) {
   const int nmat = (int)ctx->plan.mats.size();
   if (count < 0 || count > nmat || !idx || !dev_G) return fail(ctx, FIRA_ERR_INVALID_ARG, "bad count or null array");
   if (iters < 1 || iters > 64) return fail(ctx, FIRA_ERR_INVALID_ARG, "iters must be in [1, 64]");
@@ -820,11 +862,47 @@ fira_status fira_refresh_projectors(fira_ctx* ctx, int count, const int* idx, co
       if (ctx->plan.mats[idx[e]].dev.kx != 1) return fail(ctx, FIRA_ERR_DTYPE, "the device refresh handles bf16 matrices only");
     }
   }
+  if (!make_refresh_plan(ctx, count, idx, rp)) return fail(ctx, FIRA_ERR_INVALID_ARG, "bad list");
+  return FIRA_OK;
+}
+
+fira_status refresh_run(fira_ctx* ctx, int count, const int* idx, const void* const* dev_G, int iters, uint64_t seed,
+                        const RefreshPlan& rp, char* ws);
+
+}  // namespace
+
+fira_status fira_refresh_projectors(fira_ctx* ctx, int count, const int* idx, const void* const* dev_G,
+                                    int iters, uint64_t seed, void* dev_workspace, size_t workspace_bytes) {
+  if (!ctx) return fail(nullptr, FIRA_ERR_INVALID_ARG, "ctx is null");
+  if (count == 0) return FIRA_OK;
   RefreshPlan rp;
-  if (!make_refresh_plan(ctx, count, idx, &rp)) return fail(ctx, FIRA_ERR_INVALID_ARG, "bad list");
+  const fira_status st = refresh_check(ctx, count, idx, dev_G, iters, &rp);
+  if (st != FIRA_OK) return st;
   if (!dev_workspace || ((uintptr_t)dev_workspace % kAlign) != 0 || workspace_bytes < rp.total)
     return fail(ctx, FIRA_ERR_WORKSPACE, "dev_workspace must be 256-byte aligned and hold fira_refresh_workspace_bytes() bytes");
-  char* ws = (char*)dev_workspace;
+  return refresh_run(ctx, count, idx, dev_G, iters, seed, rp, (char*)dev_workspace);
+}
+
+fira_status fira_refresh_projectors_static(fira_ctx* ctx, int count, const int* idx, const void* const* dev_G,
+                                           int iters, uint64_t seed) {
+  if (!ctx) return fail(nullptr, FIRA_ERR_INVALID_ARG, "ctx is null");
+  if (count == 0) return FIRA_OK;
+  RefreshPlan rp;
+  const fira_status st = refresh_check(ctx, count, idx, dev_G, iters, &rp);
+  if (st != FIRA_OK) return st;
+  if (rp.total > (size_t)FIRA_STATIC_SCRATCH_BYTES)
+    return fail(ctx, FIRA_ERR_WORKSPACE, "the listed matrices need " + std::to_string(rp.total) + " bytes of workspace, more than the " +
+                                         std::to_string((size_t)FIRA_STATIC_SCRATCH_BYTES) + " bytes of the library's static scratch: "
+                                         "list fewer matrices per call or use fira_refresh_projectors");
+  // ctx->static_scratch is the device address found at fira_init_state (never the array's name)
+  return refresh_run(ctx, count, idx, dev_G, iters, seed, rp, (char*)ctx->static_scratch);
+}
+
+namespace {
+
+fira_status refresh_run(fira_ctx* ctx, int count, const int* idx, const void* const* dev_G, int iters, uint64_t seed,
+                        const RefreshPlan& rp, char* ws) {
+  const int nmat = (int)ctx->plan.mats.size();
   hipStream_t q = ctx->stream;
 
   // host images of the small tables
@@ -871,7 +949,11 @@ fira_status fira_refresh_projectors(fira_ctx* ctx, int count, const int* idx, co
       FIRA_HIP(ctx, hipMemcpyAsync(ws + rp.off_vtiles[l], vtiles[l].data(), sizeof(FiraTile) * vtiles[l].size(), hipMemcpyHostToDevice, q));
   // the host vectors go away when this function returns: the copies above must have been made
   FIRA_HIP(ctx, hipStreamSynchronize(q));
-  FIRA_HIP(ctx, hipMemsetAsync(ws + rp.top_begin, 0, rp.top_end - rp.top_begin, q));   // padding rows of the packed operand
+  {   // padding rows of the packed operand must read as zero (the workspace keeps whatever it held before)
+    const size_t n16 = (rp.top_end - rp.top_begin) / 16;
+    const unsigned grid = (unsigned)std::min<size_t>((n16 + 255) / 256, 8192);
+    if (n16) hipLaunchKernelGGL(fira_zero_fill_kernel, dim3(grid), dim3(256), 0, q, reinterpret_cast<u32x4*>(ws + rp.top_begin), n16);
+  }
 
   const FiraRefreshEnt* d_ents = (const FiraRefreshEnt*)(ws + rp.off_ents);
   const FiraRefreshEnt* d_ents2 = (const FiraRefreshEnt*)(ws + rp.off_ents2);
@@ -943,6 +1025,8 @@ fira_status fira_refresh_projectors(fira_ctx* ctx, int count, const int* idx, co
   ctx->ortho_pending = true;
   return FIRA_OK;
 }
+
+}  // namespace
 
 const char* fira_last_error(const fira_ctx* ctx) { return ctx ? ctx->last_error.c_str() : g_last_error.c_str(); }
 

@@ -28,13 +28,14 @@ FIRA_SCALE_COLUMN, FIRA_SCALE_MATRIX, FIRA_SCALE_NONE = 0, 1, 2
 FIRA_VARIANT_FULL, FIRA_VARIANT_ONLY_SCALING = 0, 1
 FIRA_NORM_RESIDUAL, FIRA_NORM_GRAM = 0, 1
 FIRA_NUM_KERNELS = 6
+FIRA_STATIC_SCRATCH_BYTES = 64 << 20
 
 EXPORTS = (
     "fira_method_state_numel", "fira_state_bytes", "fira_init_state", "fira_set_projector", "fira_step",
     "fira_set_hparams", "fira_set_options", "fira_set_variant", "fira_set_fusion", "fira_last_step_fused",
     "fira_get_state", "fira_set_state", "fira_get_diag",
     "fira_get_factors", "fira_get_lowrank", "fira_get_projector", "fira_refresh_workspace_bytes",
-    "fira_refresh_projectors", "fira_profile_begin", "fira_profile_end", "fira_kernel_name",
+    "fira_refresh_projectors", "fira_refresh_projectors_static", "fira_profile_begin", "fira_profile_end", "fira_kernel_name",
     "fira_last_error", "fira_destroy",
 )
 
@@ -108,6 +109,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.fira_refresh_projectors.restype = ci
     lib.fira_refresh_projectors.argtypes = [vp, ci, ctypes.POINTER(ci), ctypes.POINTER(vp), ci, ctypes.c_uint64, vp,
                                             ctypes.c_size_t]
+    lib.fira_refresh_projectors_static.restype = ci
+    lib.fira_refresh_projectors_static.argtypes = [vp, ci, ctypes.POINTER(ci), ctypes.POINTER(vp), ci, ctypes.c_uint64]
     lib.fira_profile_begin.restype = ci
     lib.fira_profile_begin.argtypes = [vp, ci]
     lib.fira_profile_end.restype = ci
@@ -295,6 +298,14 @@ class FiraContext:
         _check(self.lib, self.ctx, self.lib.fira_refresh_projectors(self.ctx, count, ci, cg, iters, seed,
                                                                     ctypes.c_void_p(workspace.data_ptr()), need))
         return workspace
+
+    def fira_refresh_projectors_static(self, idx: Sequence[int], G: Sequence[torch.Tensor], iters: int = 2, seed: int = 0):
+        """fira_refresh_projectors on the library's static scratch: no workspace, no device allocation."""
+        count = len(idx)
+        assert len(G) == count
+        ci = (ctypes.c_int * count)(*idx)
+        cg = (ctypes.c_void_p * count)(*[g.data_ptr() for g in G])
+        _check(self.lib, self.ctx, self.lib.fira_refresh_projectors_static(self.ctx, count, ci, cg, iters, seed))
 
     def fira_profile_begin(self, max_steps: int):
         _check(self.lib, self.ctx, self.lib.fira_profile_begin(self.ctx, max_steps))
