@@ -66,19 +66,37 @@ def kernel_models(shapes, r, norm_mode):
     }
 
 
+def kernel_sources_hash():
+    """Hash of the kernel sources (csrc/*): a traffic record in profiles/ carries the hash of the sources it
+    was measured on and is dropped when they have changed since."""
+    import hashlib
+    h = hashlib.sha256()
+    d = os.path.join(ROOT, "paper_2410_01623_amd", "csrc")
+    for name in sorted(os.listdir(d)):
+        if name.endswith((".h", ".hip")) and "microbench" not in name:
+            h.update(name.encode())
+            h.update(open(os.path.join(d, name), "rb").read())
+    return h.hexdigest()[:16]
+
+
 def read_traffic(workload, norm_mode):
     """HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by the same
-    counters on a plain 1 GiB copy), as recorded in profiles/; {} when no record matches."""
+    counters on a plain 1 GiB copy), as recorded in profiles/; {} when no record matches the workload or
+    the record was made on other kernel sources (line "# kernel_sources <hash>")."""
     path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}_{norm_mode}.txt")
-    out = {}
+    out, stamp = {}, None
     if os.path.exists(path):
         for line in open(path):
             p = line.split()
+            if line.startswith("# kernel_sources") and len(p) >= 3:
+                stamp = p[2]
             if len(p) >= 2 and not line.startswith("#"):
                 try:
                     out[p[0]] = float(p[1])
                 except ValueError:
                     pass
+    if stamp != kernel_sources_hash():
+        return {}
     return out
 
 
@@ -106,7 +124,8 @@ def cpu_baseline(wl, sample_mats, steps=1):
             orc.fira_step(W, G, P, st, hp, store_bf16=(wl.dtype == "bf16"))
     dt = (time.perf_counter() - t0) / steps
     frac = sum(m * n for m, n in (wl.shapes[i] for i in sample_mats)) / sum(m * n for m, n in wl.shapes)
-    return dict(value=frac / dt, unit="steps/s", cores=int(cores), kind="oracle",
+    return dict(value=frac / dt, unit="steps/s", cores=int(cores),
+                kind=f"oracle (numpy fp64; its matrix products run in the BLAS numpy links, {int(cores)} threads)",
                 sample=f"{len(sample_mats)} of {wl.n_matrices} matrices (one block), {steps} step(s), "
                        f"{dt:.2f} s per step of the sample ({dt * steps:.1f} s in all), scaled by the sample's share "
                        f"of the elements ({frac:.4f})")
@@ -116,7 +135,13 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=40,
+                    help="untimed steps first; the first ones start from zero moments, their factors move and the "
+                         "limiter acts, so the default leaves them all outside the timed region")
+    ap.add_argument("--limited-steps", type=int, default=30,
+                    help="after the timed steps, also time this many steps in which the limiter acts on every matrix "
+                         "(gradients whose part outside the subspace is eight times larger; reported under "
+                         "\"limiter_active\", not part of value); 0 = skip")
     ap.add_argument("--workload", default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -181,6 +206,7 @@ def main():
     for s in range(args.warmup):
         ctx.fira_step(prepared=prepared[s % n_sets])
     torch.cuda.synchronize()
+    limited_at_start = sum(1 for i in range(len(shapes)) if ctx.fira_get_diag(i)[2] < 1.0)   # last warm-up step
     ctx.fira_profile_begin(args.steps)
     t0 = time.perf_counter()
     for s in range(args.steps):
@@ -221,9 +247,42 @@ def main():
         "config": {"workload": name, "matrices": len(shapes), "rank": wl.rank,
                    "params": sum(m * n for m, n in shapes), "state_bytes": ctx.state_bytes,
                    "gradient_sets": n_sets, "norm_mode": args.norm_mode, "fused_projection_adam": fused, "ld": "n" if not args.pad_ld else f"n rounded up to {args.pad_ld}", "finite": finite,
-                   "matrices_limited_last_step": limited},
+                   "matrices_limited_last_step": limited, "matrices_limited_last_warmup_step": limited_at_start},
         "roofline": roof, "kernels": kernels,
     }
+    if args.limited_steps > 0:
+        # The limiter-active regime (Algorithm 1's limiter line fires whenever ||S_t|| grows by more than gamma):
+        # gradients whose out-of-subspace part is eight times larger, G + 7 (G - P P^T G).  R, M, V and the
+        # factors are unchanged, ||S_t|| is eight times larger, and since the limiter lets the remembered norm
+        # grow by 1 % a step, every matrix stays limited for about 200 steps.  The inputs are prepared here
+        # with torch (input generation, outside the timed region).
+        def spiked(i, g):
+            m, n = shapes[i]
+            P = cache[(min(m, n), m <= n)].float()
+            gf = g.float()
+            out = gf - P @ (P.t() @ gf) if m <= n else gf - (gf @ P) @ P.t()
+            t = torch.empty((m, lds[i]), dtype=dt_t, device=dev)[:, :n]
+            t.copy_((gf + 7.0 * out).to(dt_t))
+            return t
+        Gspike = [[spiked(i, g) for i, g in enumerate(G)] for G in Gsets]
+        prep_spike = [ctx.prepare(idx, W, G) for G in Gspike]
+        torch.cuda.synchronize()
+        for s in range(5):
+            ctx.fira_step(prepared=prep_spike[s % n_sets])
+        torch.cuda.synchronize()
+        ctx.fira_profile_begin(args.limited_steps)
+        t1 = time.perf_counter()
+        for s in range(args.limited_steps):
+            ctx.fira_step(prepared=prep_spike[s % n_sets])
+        torch.cuda.synchronize()
+        dtl = time.perf_counter() - t1
+        ms_l, rec_l = ctx.fira_profile_end()
+        cs = [ctx.fira_get_diag(i)[2] for i in range(len(shapes))]
+        out["limiter_active"] = dict(ms_per_step=round(1e3 * dtl / args.limited_steps, 4), steps=args.limited_steps,
+                                     matrices_limited=sum(1 for c in cs if c < 1.0), c_mean=round(sum(cs) / len(cs), 4),
+                                     make_z_ms=round(ms_l["make_z"] / max(rec_l, 1), 4),
+                                     finite=all(bool(torch.isfinite(w).all()) for w in W[:7]))
+        del Gspike, prep_spike
     if args.refresh_iters > 0:
         # projector refresh (Algorithm 1's "if t mod T = 0" branch) over every matrix, from the first gradient set
         idx_all = list(range(len(shapes)))
@@ -234,8 +293,16 @@ def main():
         ctx.fira_refresh_projectors(idx_all, Gsets[0], iters=args.refresh_iters, seed=2, workspace=ws)
         torch.cuda.synchronize()
         rms = 1e3 * (time.perf_counter() - t1)
+        # what was timed must be a usable projector: finite, orthonormal to the bf16 rounding of its entries
+        defect = 0.0
+        for i in sorted(set([0, len(wl.block_shapes) - 1, len(shapes) - 1])):
+            Pi = ctx.fira_get_projector(i).double()
+            assert bool(torch.isfinite(Pi).all()), f"refresh left a non-finite projector for matrix {i}"
+            defect = max(defect, float((Pi.t() @ Pi - torch.eye(wl.rank, dtype=torch.float64)).abs().max()))
+        assert defect < 2e-2, f"refreshed projector is not orthonormal: max |P^T P - I| = {defect:.3g}"
         # the subspace iteration multiplies by G four times per round (two contractions of 2 mn r flops each way)
         out["refresh"] = dict(ms=round(rms, 2), iters=args.refresh_iters, workspace_bytes=int(ws.numel()),
+                              max_orthonormality_defect=round(defect, 6),
                               ms_per_step_at_T200=round(rms / 200.0, 4),
                               contraction_tflops=round(args.refresh_iters * 2 * 2.0 * sum(m * n for m, n in shapes) * wl.rank / (rms * 1e-3) / 1e12, 1))
         del ws

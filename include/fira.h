@@ -80,10 +80,19 @@ typedef enum { FIRA_SCALE_COLUMN = 0, FIRA_SCALE_MATRIX = 1, FIRA_SCALE_NONE = 2
 /* How ||S_t|| (Eq. 12) is obtained.  FIRA_NORM_RESIDUAL forms G - P R tile by tile with an extra
  * rank-r contraction and a second pass over G (exact for any P).  FIRA_NORM_GRAM, the default, uses
  * ||G_i - P R_i||^2 = ||G_i||^2 - ||R_i||^2, which holds when P^T P = I (G_i^T P = R_i^T always) and
- * needs neither: fira_set_projector estimates ||P^T P - I||, and a matrix whose estimate exceeds 0.02
- * takes the residual route regardless of this setting.  With a bf16-rounded orthonormal P the identity
- * holds to about 1e-3 of ||R_i||^2, so ||S_t|| carries a relative error of a few 1e-4, growing by
- * cancellation when the residual is tiny compared with G (r close to min(m,n)). */
+ * needs neither.  With a bf16-rounded orthonormal P the identity holds to about 1e-3 of ||R_i||^2,
+ * which is harmless while the part of G outside the subspace is not small against the part inside; the
+ * difference cancels when the subspace holds nearly all of G (P the leading singular vectors of a
+ * gradient of low effective rank, or r close to min(m,n)).  Two gates per matrix therefore decide,
+ * whatever this setting says:
+ *   1. fira_set_projector estimates ||P^T P - I||; beyond 0.02 the matrix stays on the residual route;
+ *   2. the first step after a projector is installed takes the residual route for that matrix and
+ *      also forms the Gram value from the same data; the relative difference of the two ||S_t||^2 is kept,
+ *      and the following steps take the Gram route only if it was at most 2e-3 (1e-3 of ||S_t||).
+ * The second gate is measured once per installed projector, on that step's gradient; a gradient that
+ * moves into the subspace later is not noticed until the next installation (select
+ * FIRA_NORM_RESIDUAL for such workloads).  fira_get_gate reads both values; fira_set_gate restores
+ * them after fira_set_projector (checkpoint resume without a new measurement). */
 typedef enum { FIRA_NORM_RESIDUAL = 0, FIRA_NORM_GRAM = 1 } fira_norm_mode;
 
 /* Number of optimizer-state values the METHOD keeps for one matrix: m r + 2 n r + 1 for m <= n
@@ -112,7 +121,19 @@ FIRA_API fira_status fira_set_projector(fira_ctx* ctx, int idx, const void* dev_
 /* One optimizer step (Algorithm 1's loop body below the SVD branch) for `count` distinct
  * matrices idx[0..count), in one grouped launch sequence.  dev_W[i] is updated in place, dev_G[i]
  * is read only; both are m x n with the descriptor's ld and dtype.  t advances by one for each
- * listed matrix.  idx, dev_W, dev_G are host arrays of length count. */
+ * listed matrix.  idx, dev_W, dev_G are host arrays of length count.
+ *
+ * Capturing a step in a HIP graph: the hyper-parameters, the options, the variant, the fusion switch
+ * and the route of every listed matrix are decided on the host when the call is made and travel as
+ * kernel arguments, and the work list (which W and G pointers, which tiles) sits in one of four
+ * cached slots of the slab.  A captured step therefore replays exactly what was in force at capture:
+ * later fira_set_hparams (a learning-rate schedule), fira_set_options, fira_set_variant,
+ * fira_set_fusion, fira_set_projector or fira_refresh_projectors calls do not reach it, and it must be
+ * captured again after any of them.  Capture only from the second step after a projector was
+ * installed on (the first one measures the Gram route's gate and reads it back).  While a captured
+ * step may still be replayed, do not step more than three other distinct (idx, W, G) lists on the
+ * same context: the fifth distinct list reuses the oldest slot and would rewrite the captured one's
+ * work list. */
 FIRA_API fira_status fira_step(fira_ctx* ctx, int count, const int* idx, void* const* dev_W,
                       const void* const* dev_G);
 
@@ -131,14 +152,16 @@ FIRA_API fira_status fira_set_options(fira_ctx* ctx, fira_scaling scaling, fira_
 typedef enum { FIRA_VARIANT_FULL = 0, FIRA_VARIANT_ONLY_SCALING = 1 } fira_variant;
 FIRA_API fira_status fira_set_variant(fira_ctx* ctx, fira_variant variant);
 
-/* Kernel fusion (on by default).  A step in which every listed matrix is bf16 with r % 4 == 0 and
- * 128 <= r <= 512, with column factors (Eq. 10), Algorithm 1 proper and the Gram route to ||S_t|| in force for
- * all of them, runs the projection R = P^T G and Adam (Eqs. 2-4) in one kernel that keeps R in
- * registers; any other step, and every step with enable == 0, runs them as two kernels with R in
- * memory.  Both compute the same quantities; sums are taken in a different order, so results agree to
- * rounding, not bit for bit.  fira_last_step_fused: 1 if the last fira_step on ctx took the fused
- * kernel, 0 if not (or ctx is NULL).  A fused step keeps no copy of R: fira_get_lowrank then returns
- * what an earlier two-kernel step left (zeros if there was none). */
+/* Kernel fusion (on by default).  With column factors (Eq. 11), Algorithm 1 proper and FIRA_NORM_GRAM, the
+ * listed matrices that take the Gram route run the projection R = P^T G and Adam (Eqs. 2-4) in one
+ * kernel that keeps R in registers, provided each of them is bf16 with r % 4 == 0 and 128 <= r <= 512;
+ * the listed matrices on the residual route (e.g. in the first step after their projector was
+ * installed) run them as two kernels with R in memory in the same step.  Any other step, and every
+ * step with enable == 0, runs two kernels for all.  Both compute the same quantities; sums are taken in
+ * a different order, so results agree to rounding, not bit for bit.  fira_last_step_fused: 1 if the
+ * last fira_step on ctx took the fused kernel for every listed matrix, 0 if not (or ctx is NULL).  A
+ * fused step keeps no copy of R: fira_get_lowrank then returns what an earlier two-kernel step left
+ * (zeros if there was none). */
 FIRA_API fira_status fira_set_fusion(fira_ctx* ctx, int enable);
 FIRA_API int fira_last_step_fused(const fira_ctx* ctx);
 
@@ -157,6 +180,16 @@ FIRA_API fira_status fira_set_state(fira_ctx* ctx, int idx, const float* host_M,
  * factor applied (the "gradient norm" curve of Fig. 3).  Synchronises the stream. */
 FIRA_API fira_status fira_get_diag(fira_ctx* ctx, int idx, double* s_norm_pre, double* s_norm_post,
                           double* c);
+
+/* The two gate values of the Gram route for matrix idx (see fira_norm_mode): the estimate of
+ * ||P^T P - I|| and the measured relative error of the Gram route's ||S_t||^2 (+inf while not yet
+ * measured, or before any projector), and the route the last step took for this matrix (0: residual
+ * route; 1: Gram route, two kernels; 2: Gram route, fused projection/Adam kernel, which keeps no R).
+ * Any output may be NULL.  Synchronises the stream.  fira_set_gate writes the two values back (after
+ * fira_set_projector, which resets them), so that a restored run continues on the same route without
+ * measuring again; values must be >= 0. */
+FIRA_API fira_status fira_get_gate(fira_ctx* ctx, int idx, float* ortho_err, float* gram_err, int* gram_route);
+FIRA_API fira_status fira_set_gate(fira_ctx* ctx, int idx, float ortho_err, float gram_err);
 
 /* Copy the scaling factors k_i of the last step of matrix idx (n values for m <= n, m values for
  * m > n) to host memory.  Synchronises the stream. */
@@ -183,7 +216,10 @@ FIRA_API fira_status fira_get_projector(fira_ctx* ctx, int idx, float* host_P);
  *                  aligned, owned by the caller, free to reuse once the stream has passed this call
  * Enqueues on the context's stream and returns; the small work lists are uploaded with blocking
  * copies, so the call is not meant for the step's inner loop.  Uses the listed matrices' step
- * scratch (not their state). */
+ * scratch (not their state).  The rounds of the iteration work in the matrices' own operand copies of
+ * P: if a launch fails on the way (FIRA_ERR_HIP), the listed matrices are left WITHOUT a projector
+ * (fira_step reports FIRA_ERR_NO_PROJECTOR for them until one is installed again); M, V, t and the
+ * remembered norm are untouched in every case. */
 FIRA_API size_t fira_refresh_workspace_bytes(const fira_ctx* ctx, int count, const int* idx);
 FIRA_API fira_status fira_refresh_projectors(fira_ctx* ctx, int count, const int* idx, const void* const* dev_G,
                                              int iters, uint64_t seed, void* dev_workspace, size_t workspace_bytes);

@@ -18,21 +18,9 @@
 #include "fira_refresh.h"
 #include "fira_gemm.h"
 #include "fira_fused.h"
+#include "fira_plan.h"
 
 namespace {
-
-constexpr size_t kAlign = 256;
-constexpr int kSlots = 4;  // cached work lists (a training loop alternates between very few)
-
-inline size_t align_up(size_t x, size_t a = kAlign) { return (x + a - 1) / a * a; }
-inline int round_up_int(long long x, int a) { return (int)((x + a - 1) / a * a); }
-// Row pitch (bf16 elements) for an operand row of k values: a whole number of 256-byte L2-channel
-// lines, and an odd number of them, so that consecutive rows walk through all sixteen channels.
-inline int operand_pitch(long long k) {
-  long long lines = (k * 2 + 255) / 256;
-  if (lines % 2 == 0) ++lines;
-  return (int)(lines * 128);
-}
 
 thread_local std::string g_last_error;
 
@@ -67,24 +55,9 @@ void* static_scratch_address(int* device_out, std::string* why) {
   return g_scratch_ptr[dev];
 }
 
-struct HostMat {
-  fira_matrix_desc d;
-  FiraMat dev;          // copy of the device description (pointers are device pointers)
-  bool has_projector = false;
-  int tiles_project = 0;      // tiles of the R contraction
-  int tiles_back = 0;         // tiles of the back-projection (and of the residual-norm pass)
-  int ta_project = 0, tb_project = 0, ta_back = 0, tb_back = 0;
-  int rowblocks = 0;
-  int g2blocks = 0;           // blocks of the ||G_i||^2 kernel
-  int fuse_list = -1;         // tile list of the fused projection/Adam kernel, or -1 if the matrix cannot take it
-  bool small_proj = false;    // bf16 with r <= 64: projected by the small-rank kernel
-};
+}  // namespace
 
-// kTilesFuse + (r > 256 ? 2 : 0) + (left ? 0 : 1): tiles of the fused projection/Adam kernel (one per 128 factors)
-// kTilesProject*: every matrix (the projector refresh runs the general kernel on all of them); a step uses
-// kTilesProjBig* (general kernel) and kTilesProjSmall* (bf16 matrices with r <= 64), which split them.
-enum { kTilesProjectLeft = 0, kTilesProjectRight = 1, kTilesBackBf16 = 2, kTilesBackF32 = 3, kTilesFuse = 4,
-       kTilesProjBigLeft = 8, kTilesProjBigRight = 9, kTilesProjSmallLeft = 10, kTilesProjSmallRight = 11, kNumTileLists = 12 };
+namespace {
 
 struct ListSlot {
   std::vector<int> idx;
@@ -104,103 +77,6 @@ struct ListSlot {
   bool valid = false;
 };
 
-struct Plan {
-  size_t total = 0;
-  size_t off_mats = 0, off_scal = 0, off_partial = 0, off_ortho = 0, ortho_z = 0;
-  size_t off_slots = 0, slot_bytes = 0, slot_off_tiles[kNumTileLists] = {};
-  std::vector<HostMat> mats;
-  int max_tiles[kNumTileLists] = {};
-  int adam_lds = 0;          // dynamic LDS of the Adam kernel: 16 rows of the widest register-resident matrix
-};
-
-bool valid_desc(const fira_matrix_desc& d, std::string* why) {
-  if (d.m < 1 || d.n < 1 || d.m > (1 << 22) || d.n > (1 << 22)) { *why = "m, n must be in [1, 2^22]"; return false; }
-  if (d.ld < d.n || d.ld > (1 << 22)) { *why = "ld must be in [n, 2^22]"; return false; }
-  if (d.r < 1 || d.r > std::min(d.m, d.n)) { *why = "need 1 <= r <= min(m, n)"; return false; }
-  return true;
-}
-
-// Lays the slab out.  Pointers in Plan::mats[i].dev are offsets from a null base until rebased.
-bool make_plan(const fira_matrix_desc* d, int count, Plan* plan, fira_status* st, std::string* why) {
-  if (!d || count < 1 || count > (1 << 20)) { *st = FIRA_ERR_INVALID_ARG; *why = "descriptor array is null or count out of range"; return false; }
-  plan->mats.resize(count);
-  size_t off = 0;
-  plan->off_mats = off; off = align_up(off + sizeof(FiraMat) * count);
-  plan->off_scal = off; off = align_up(off + sizeof(FiraScal) * count);
-  long long total_tiles[kNumTileLists] = {};
-  for (int i = 0; i < count; ++i) {
-    HostMat& h = plan->mats[i];
-    h.d = d[i];
-    if (d[i].wg_dtype != FIRA_F32 && d[i].wg_dtype != FIRA_BF16) { *st = FIRA_ERR_DTYPE; *why = "wg_dtype must be FIRA_F32 or FIRA_BF16"; return false; }
-    if (!valid_desc(d[i], why)) { *st = FIRA_ERR_SHAPE; return false; }
-    FiraMat& m = h.dev;
-    std::memset(&m, 0, sizeof(m));
-    m.m = (int)d[i].m; m.n = (int)d[i].n; m.r = d[i].r; m.left = d[i].m <= d[i].n;
-    m.ld = d[i].ld;
-    m.L = (int)std::max(d[i].m, d[i].n); m.S = (int)std::min(d[i].m, d[i].n);
-    m.rp = round_up_int(m.r, 64); m.Sp = round_up_int(m.S, 64);
-    m.dtype = d[i].wg_dtype;
-    m.kx = (m.dtype == FIRA_F32) ? FIRA_KX_SPLIT : 1;
-    m.Lq = round_up_int(m.L, 256); m.Sq = round_up_int(m.S, 256); m.rq = round_up_int(m.r, 256);
-    m.zready = (m.kx == 1 && (m.r & 3) == 0 && m.r <= FIRA_ZREADY_MAX_R) ? 1 : 0;
-    if (m.zready) plan->adam_lds = std::max(plan->adam_lds, FIRA_ROWS_PER_WG * m.rp * 2);
-    m.gx_ld = m.left ? round_up_int(m.n, 8) : operand_pitch((long long)m.kx * m.Sp);
-    const size_t Lr = (size_t)m.L * m.r;
-    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
-    m.M = (float*)take(Lr * 4);
-    m.V = (float*)take(Lr * 4);
-    m.Rt = (float*)take(Lr * 4);
-    m.phi = (float*)take((size_t)m.L * 4);
-    m.g2 = (float*)take((size_t)m.L * 4);
-    m.q = (float*)take((size_t)m.L * 4);
-    m.Nb = (bf16_raw*)take((size_t)m.Lq * m.kx * m.rp * 2);
-    m.Rb = (bf16_raw*)take((size_t)m.Lq * m.kx * m.rp * 2);
-    m.Pn = (bf16_raw*)take((size_t)m.Sq * m.kx * m.rp * 2);
-    m.PT = (bf16_raw*)take((size_t)m.rq * m.kx * m.Sp * 2);
-    if (m.kx > 1) {
-      const size_t gx = m.left ? (size_t)m.kx * m.Sp * m.gx_ld : (size_t)m.m * m.gx_ld;
-      m.Gx = (bf16_raw*)take(gx * 2);
-    }
-    h.ta_project = (m.L + FIRA_PA - 1) / FIRA_PA; h.tb_project = (m.r + FIRA_PB - 1) / FIRA_PB;
-    h.ta_back = (m.n + FIRA_BA - 1) / FIRA_BA;    h.tb_back = (m.m + FIRA_BB - 1) / FIRA_BB;
-    h.tiles_project = h.ta_project * h.tb_project;
-    h.tiles_back = h.ta_back * h.tb_back;
-    h.rowblocks = (m.L + FIRA_ROWS_PER_WG - 1) / FIRA_ROWS_PER_WG;
-    h.g2blocks = m.left ? (m.n + 255) / 256 : (m.m + FIRA_G2_ROWS_PER_WG - 1) / FIRA_G2_ROWS_PER_WG;
-    total_tiles[m.left ? kTilesProjectLeft : kTilesProjectRight] += h.tiles_project;
-    h.small_proj = m.kx == 1 && m.r <= FIRA_PS;
-    total_tiles[(h.small_proj ? kTilesProjSmallLeft : kTilesProjBigLeft) + (m.left ? 0 : 1)] += h.tiles_project;
-    total_tiles[m.dtype == FIRA_BF16 ? kTilesBackBf16 : kTilesBackF32] += h.tiles_back;
-    if (m.zready && m.r >= FIRA_FUSE_MIN_R && m.r <= FIRA_FUSE_MAX_R) {
-      h.fuse_list = kTilesFuse + 2 * (m.r > 256 ? 1 : 0) + (m.left ? 0 : 1);
-      total_tiles[h.fuse_list] += h.ta_project;
-    }
-  }
-  for (int l = 0; l < kNumTileLists; ++l) {
-    if (total_tiles[l] > (1 << 28)) { *st = FIRA_ERR_SHAPE; *why = "too many tiles"; return false; }
-    plan->max_tiles[l] = (int)total_tiles[l];
-  }
-  plan->off_partial = off;
-  off = align_up(off + (size_t)(total_tiles[kTilesBackBf16] + total_tiles[kTilesBackF32]) * 4);
-  long long max_S = 0;
-  for (const HostMat& h : plan->mats) max_S = std::max<long long>(max_S, h.dev.S);
-  long long max_r = 0;
-  for (const HostMat& h : plan->mats) max_r = std::max<long long>(max_r, h.dev.r);
-  plan->off_ortho = off;   // scratch of the orthonormality estimate: S x 4 floats, then splits x r x 4 floats
-  plan->ortho_z = align_up((size_t)max_S * 16);
-  off = align_up(off + plan->ortho_z + (size_t)FIRA_ORTHO_SPLITS * max_r * 16);
-  size_t s = 0;
-  s = align_up(s + sizeof(FiraEnt) * count);
-  for (int l = 0; l < kNumTileLists; ++l) {
-    plan->slot_off_tiles[l] = s;
-    s = align_up(s + sizeof(FiraTile) * (size_t)total_tiles[l]);
-  }
-  plan->slot_bytes = s;
-  plan->off_slots = off; off += s * kSlots;
-  plan->total = off;
-  return true;
-}
-
 }  // namespace
 
 struct fira_ctx {
@@ -218,9 +94,11 @@ struct fira_ctx {
   float* d_partial = nullptr;
   ListSlot slots[kSlots];
   char* h_stage_all = nullptr;
-  // Host copy of every matrix's FiraScal::ortho_err (pinned; +inf until known), so that a step on the
-  // Gram route can leave out the residual launch when no listed matrix needs it.
-  float* h_ortho = nullptr;
+  // Host copy of every matrix's two gate values of the Gram route (FiraScal::ortho_err, FiraScal::gram_err;
+  // pinned; +inf until known), so that a step knows which listed matrices take which route and can leave out
+  // the launches that nobody needs.
+  struct Gate { float ortho_err, gram_err; };
+  Gate* h_gate = nullptr;
   hipEvent_t ortho_event = nullptr;
   bool ortho_pending = false;
   uint64_t use_counter = 0;
@@ -257,13 +135,25 @@ FiraHp make_hp(const fira_ctx* ctx) {
   h.norm_mode = ctx->norm_mode;
   h.variant = ctx->variant;
   h.fused = 0;
-  h.ortho_tol = 0.02f;   // bf16-rounded orthonormal projectors measure ~1e-3; 0.02 bounds the error of ||S|| by ~1 %
+  h.ortho_tol = 0.02f;   // bf16-rounded orthonormal projectors measure ~1e-3; a projector beyond 0.02 is not meant to be orthonormal
+  h.gram_tol = 2e-3f;    // measured relative error of ||S||^2 by the Gram route: 1e-3 of ||S||
+  h.mixed = 0;
   return h;
 }
 
 bool valid_hp(const fira_hparams* hp) {
   return hp && std::isfinite(hp->lr) && hp->beta1 >= 0 && hp->beta1 < 1 && hp->beta2 >= 0 && hp->beta2 < 1 &&
          hp->eps >= 0 && std::isfinite(hp->eps) && std::isfinite(hp->alpha) && hp->gamma > 0;
+}
+
+// Every matrix's gate values of the Gram route in one strided copy (stream-ordered; fira_step waits for it).
+fira_status read_back_gates(fira_ctx* ctx) {
+  const size_t nmat = ctx->plan.mats.size();
+  FIRA_HIP(ctx, hipMemcpy2DAsync(ctx->h_gate, sizeof(fira_ctx::Gate), reinterpret_cast<char*>(ctx->d_scal) + offsetof(FiraScal, ortho_err),
+                                 sizeof(FiraScal), sizeof(fira_ctx::Gate), nmat, hipMemcpyDeviceToHost, ctx->stream));
+  FIRA_HIP(ctx, hipEventRecord(ctx->ortho_event, ctx->stream));
+  ctx->ortho_pending = true;
+  return FIRA_OK;
 }
 
 // Builds the work list of one fira_step call in pinned staging and returns its slot.
@@ -288,37 +178,7 @@ ListSlot* acquire_list(fira_ctx* ctx, int count, const int* idx, void* const* W,
   s->W.assign(W, W + count);
   s->G.assign(G, G + count);
   const Plan& p = ctx->plan;
-  FiraEnt* ents = reinterpret_cast<FiraEnt*>(s->h_stage);
-  FiraTile* tl[kNumTileLists];
-  int nt[kNumTileLists] = {};
-  for (int l = 0; l < kNumTileLists; ++l) tl[l] = reinterpret_cast<FiraTile*>(s->h_stage + p.slot_off_tiles[l]);
-  int nparts = 0, rowblocks = 0, g2blocks = 0;
-  for (int e = 0; e < count; ++e) {
-    const HostMat& h = p.mats[idx[e]];
-    FiraEnt& en = ents[e];
-    en.mat = idx[e]; en.part0 = nparts; en.npart = h.tiles_back; en.row0 = rowblocks; en.g2b0 = g2blocks; en.pad = 0;
-    en.W = W[e]; en.G = G[e];
-    rowblocks += h.rowblocks;
-    g2blocks += h.g2blocks;
-    // R contraction: rank tiles innermost, so the tiles that share a panel of G are neighbours
-    const int lp = h.dev.left ? kTilesProjectLeft : kTilesProjectRight;
-    for (int ta = 0; ta < h.ta_project; ++ta)
-      for (int tbb = 0; tbb < h.tb_project; ++tbb) tl[lp][nt[lp]++] = FiraTile{e, ta, tbb, 0};
-    const int ls = (h.small_proj ? kTilesProjSmallLeft : kTilesProjBigLeft) + (h.dev.left ? 0 : 1);
-    for (int ta = 0; ta < h.ta_project; ++ta)
-      for (int tbb = 0; tbb < h.tb_project; ++tbb) tl[ls][nt[ls]++] = FiraTile{e, ta, tbb, 0};
-    if (h.fuse_list >= 0)
-      for (int ta = 0; ta < h.ta_project; ++ta) tl[h.fuse_list][nt[h.fuse_list]++] = FiraTile{e, ta, 0, 0};
-    // back-projection: groups of 8 column tiles x all row tiles keep both operand panels in L2
-    const int lb = h.dev.dtype == FIRA_BF16 ? kTilesBackBf16 : kTilesBackF32;
-    const int grp = 8;
-    for (int ta0 = 0; ta0 < h.ta_back; ta0 += grp)
-      for (int t2 = 0; t2 < h.tb_back; ++t2)
-        for (int ta = ta0; ta < std::min(ta0 + grp, h.ta_back); ++ta) tl[lb][nt[lb]++] = FiraTile{e, ta, t2, nparts++};
-  }
-  for (int l = 0; l < kNumTileLists; ++l) s->ntiles[l] = nt[l];
-  s->rowblocks = rowblocks;
-  s->g2blocks = g2blocks;
+  build_work_list(p, count, idx, W, G, s->h_stage, s->ntiles, &s->rowblocks, &s->g2blocks);
   if (hipMemcpyAsync(s->d_block, s->h_stage, p.slot_bytes, hipMemcpyHostToDevice, ctx->stream) != hipSuccess ||
       hipEventRecord(s->uploaded, ctx->stream) != hipSuccess) { *st = FIRA_ERR_HIP; return nullptr; }
   s->valid = true;
@@ -378,7 +238,7 @@ fira_status fira_init_state(fira_ctx** out, const fira_matrix_desc* d, int count
   auto cleanup = [&]() {
     for (ListSlot& s : ctx->slots) if (s.uploaded) (void)hipEventDestroy(s.uploaded);
     if (ctx->h_stage_all) (void)hipHostFree(ctx->h_stage_all);
-    if (ctx->h_ortho) (void)hipHostFree(ctx->h_ortho);
+    if (ctx->h_gate) (void)hipHostFree(ctx->h_gate);
     if (ctx->ortho_event) (void)hipEventDestroy(ctx->ortho_event);
     delete ctx;
   };
@@ -402,8 +262,8 @@ fira_status fira_init_state(fira_ctx** out, const fira_matrix_desc* d, int count
   FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_project_adam_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_FUSE_LDS(1)));
   FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_project_adam_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_FUSE_LDS(2)));
   FIRA_INIT_HIP(hipHostMalloc((void**)&ctx->h_stage_all, p.slot_bytes * kSlots, hipHostMallocDefault));
-  FIRA_INIT_HIP(hipHostMalloc((void**)&ctx->h_ortho, sizeof(float) * count, hipHostMallocDefault));
-  for (int i = 0; i < count; ++i) ctx->h_ortho[i] = INFINITY;
+  FIRA_INIT_HIP(hipHostMalloc((void**)&ctx->h_gate, sizeof(fira_ctx::Gate) * count, hipHostMallocDefault));
+  for (int i = 0; i < count; ++i) ctx->h_gate[i] = fira_ctx::Gate{INFINITY, INFINITY};
   FIRA_INIT_HIP(hipEventCreateWithFlags(&ctx->ortho_event, hipEventDisableTiming));
   for (int i = 0; i < kSlots; ++i) {
     ListSlot& s = ctx->slots[i];
@@ -476,9 +336,10 @@ fira_status fira_set_projector(fira_ctx* ctx, int idx, const void* dev_P, fira_d
   hipLaunchKernelGGL(fira_ortho_z_kernel, dim3(FIRA_ORTHO_SPLITS), dim3(256), 0, ctx->stream, h.dev, (const float*)ybuf, zbuf);
   hipLaunchKernelGGL(fira_ortho_final_kernel, dim3(1), dim3(256), 0, ctx->stream, h.dev, (const float*)zbuf, ctx->d_scal, idx);
   FIRA_HIP(ctx, hipGetLastError());
-  ctx->h_ortho[idx] = INFINITY;
-  FIRA_HIP(ctx, hipMemcpyAsync(&ctx->h_ortho[idx], reinterpret_cast<char*>(&ctx->d_scal[idx]) + offsetof(FiraScal, ortho_err),
-                               sizeof(float), hipMemcpyDeviceToHost, ctx->stream));
+  static_assert(offsetof(FiraScal, gram_err) == offsetof(FiraScal, ortho_err) + sizeof(float), "the two gate values are read back as one piece");
+  ctx->h_gate[idx] = fira_ctx::Gate{INFINITY, INFINITY};
+  FIRA_HIP(ctx, hipMemcpyAsync(&ctx->h_gate[idx], reinterpret_cast<char*>(&ctx->d_scal[idx]) + offsetof(FiraScal, ortho_err),
+                               sizeof(fira_ctx::Gate), hipMemcpyDeviceToHost, ctx->stream));
   FIRA_HIP(ctx, hipEventRecord(ctx->ortho_event, ctx->stream));
   ctx->ortho_pending = true;
   h.has_projector = true;
@@ -527,12 +388,12 @@ fira_status fira_step(fira_ctx* ctx, int count, const int* idx, void* const* dev
     int bl = (nl + 7) / 8 * 8, br = (nr + 7) / 8 * 8;
     if (nl + nr)
       hipLaunchKernelGGL(fira_project_kernel, dim3(bl + br), blk, FIRA_PROJ_LDS, q, ctx->d_mats, s->d_ents,
-                         s->d_tiles[kTilesProjBigLeft], nl, bl, s->d_tiles[kTilesProjBigRight], nr, norm_arg);
+                         s->d_tiles[kTilesProjBigLeft], nl, bl, s->d_tiles[kTilesProjBigRight], nr, norm_arg, (const FiraScal*)ctx->d_scal, hp);
     nl = s->ntiles[kTilesProjSmallLeft]; nr = s->ntiles[kTilesProjSmallRight];
     bl = (nl + 7) / 8 * 8; br = (nr + 7) / 8 * 8;
     if (nl + nr)
       hipLaunchKernelGGL(fira_project_small_kernel, dim3(bl + br), blk, FIRA_PROJ_SMALL_LDS, q, ctx->d_mats, s->d_ents,
-                         s->d_tiles[kTilesProjSmallLeft], nl, bl, s->d_tiles[kTilesProjSmallRight], nr, norm_arg);
+                         s->d_tiles[kTilesProjSmallLeft], nl, bl, s->d_tiles[kTilesProjSmallRight], nr, norm_arg, (const FiraScal*)ctx->d_scal, hp);
   };
   // 0. Gram route, fp32 matrices only: ||G_i||^2 for every factor (bf16 matrices get it from step 1)
   const bool only_scaling = ctx->variant == FIRA_VARIANT_ONLY_SCALING;
@@ -540,22 +401,36 @@ fira_status fira_step(fira_ctx* ctx, int count, const int* idx, void* const* dev
   if (want_g2 && s->ntiles[kTilesBackF32] > 0)
     hipLaunchKernelGGL(fira_gradnorm_kernel, dim3(s->g2blocks), dim3(256), 0, q, ctx->d_mats, ctx->d_scal, s->d_ents, count,
                        s->g2blocks, hp);
-  // Whether ||S|| needs the residual contraction: not if every listed matrix takes the Gram route (the
-  // kernels apply the same test per matrix: FiraScal::ortho_err <= FiraHp::ortho_tol).
+  // Which listed matrices take the Gram route to ||S|| (the kernels apply the same test per matrix: both
+  // gate values of FiraScal within FiraHp's tolerances).  A matrix whose second gate value is still to be
+  // measured takes the residual route in this step, and the limiter measures it.
   bool need_residual = !only_scaling;
+  bool any_gram = false, measures = false;
   if (need_residual && ctx->norm_mode == FIRA_NORM_GRAM) {
-    if (ctx->ortho_pending) {   // a projector was installed since the last step: wait for its gate value
+    if (ctx->ortho_pending) {   // gate values are on their way back (a projector was installed, or a step measured one)
       FIRA_HIP(ctx, hipEventSynchronize(ctx->ortho_event));
       ctx->ortho_pending = false;
     }
     need_residual = false;
-    for (int e = 0; e < count; ++e) need_residual = need_residual || !(ctx->h_ortho[idx[e]] <= hp.ortho_tol);
+    for (int e = 0; e < count; ++e) {
+      const fira_ctx::Gate gt = ctx->h_gate[idx[e]];
+      const bool gram = gt.ortho_err <= hp.ortho_tol && gt.gram_err <= hp.gram_tol;
+      any_gram = any_gram || gram;
+      need_residual = need_residual || !gram;
+      measures = measures || (gt.ortho_err <= hp.ortho_tol && !(gt.gram_err < INFINITY));
+    }
   }
-  // The fused projection/Adam kernel serves a step in which every listed matrix can take it.
-  bool fused = ctx->fusion && !only_scaling && ctx->scaling == FIRA_SCALE_COLUMN && ctx->norm_mode == FIRA_NORM_GRAM && !need_residual;
-  for (int e = 0; e < count && fused; ++e) fused = ctx->plan.mats[idx[e]].fuse_list >= 0;
-  ctx->last_step_fused = fused;
+  // The fused projection/Adam kernel serves the listed matrices on the Gram route if each of them can take
+  // it; those on the residual route then go through the two-kernel path in the same step (hp.mixed).
+  bool fused = ctx->fusion && !only_scaling && ctx->scaling == FIRA_SCALE_COLUMN && ctx->norm_mode == FIRA_NORM_GRAM && any_gram;
+  for (int e = 0; e < count && fused; ++e) {
+    const fira_ctx::Gate gt = ctx->h_gate[idx[e]];
+    if (gt.ortho_err <= hp.ortho_tol && gt.gram_err <= hp.gram_tol) fused = ctx->plan.mats[idx[e]].fuse_list >= 0;
+  }
+  const bool mixed = fused && need_residual;
+  ctx->last_step_fused = fused && !mixed;
   hp.fused = fused ? 1 : 0;
+  hp.mixed = mixed ? 1 : 0;
   if (fused) {
     // 1+2. R = P^T G, Adam on it, factor norms, Z for c = 1
     for (int rt = 1; rt <= 2; ++rt) {
@@ -570,15 +445,17 @@ fira_status fira_step(fira_ctx* ctx, int count, const int* idx, void* const* dev
         hipLaunchKernelGGL(fira_project_adam_kernel<2>, dim3(bl + br), dim3(512), FIRA_FUSE_LDS(2), q, ctx->d_mats, ctx->d_scal, s->d_ents,
                            s->d_tiles[ll], nl, bl, s->d_tiles[lr], nr, hp);
     }
-    mark(1);
-    mark(2);
-  } else {
+  }
+  if (!fused || mixed) {
     // 1. R = P^T G
     launch_project(want_g2);
     mark(1);
     // 2. Adam on R, factor norms
     hipLaunchKernelGGL(fira_adam_kernel, dim3(s->rowblocks), dim3(256), ctx->plan.adam_lds, q, ctx->d_mats, ctx->d_scal, s->d_ents, count,
                        s->rowblocks, hp);
+    mark(2);
+  } else {
+    mark(1);
     mark(2);
   }
   // 3. ||k (G - P R)||^2 per tile where the Gram route does not apply
@@ -618,6 +495,7 @@ fira_status fira_step(fira_ctx* ctx, int count, const int* idx, void* const* dev
   }
   mark(6);
   FIRA_HIP(ctx, hipGetLastError());
+  if (measures) return read_back_gates(ctx);   // the limiter has measured a second gate value: the next step needs it
   return FIRA_OK;
 }
 
@@ -732,6 +610,30 @@ fira_status fira_get_diag(fira_ctx* ctx, int idx, double* s_norm_pre, double* s_
   return FIRA_OK;
 }
 
+fira_status fira_get_gate(fira_ctx* ctx, int idx, float* ortho_err, float* gram_err, int* gram_route) {
+  if (!ctx) return fail(nullptr, FIRA_ERR_INVALID_ARG, "ctx is null");
+  if (idx < 0 || idx >= (int)ctx->plan.mats.size()) return fail(ctx, FIRA_ERR_INVALID_ARG, "matrix index out of range");
+  FIRA_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  FiraScal sc;
+  FIRA_HIP(ctx, hipMemcpy(&sc, ctx->d_scal + idx, sizeof(sc), hipMemcpyDeviceToHost));
+  if (ortho_err) *ortho_err = ctx->plan.mats[idx].has_projector ? sc.ortho_err : INFINITY;
+  if (gram_err) *gram_err = ctx->plan.mats[idx].has_projector ? sc.gram_err : INFINITY;
+  if (gram_route) *gram_route = sc.gram_now;
+  return FIRA_OK;
+}
+
+fira_status fira_set_gate(fira_ctx* ctx, int idx, float ortho_err, float gram_err) {
+  if (!ctx) return fail(nullptr, FIRA_ERR_INVALID_ARG, "ctx is null");
+  if (idx < 0 || idx >= (int)ctx->plan.mats.size()) return fail(ctx, FIRA_ERR_INVALID_ARG, "matrix index out of range");
+  if (!ctx->plan.mats[idx].has_projector) return fail(ctx, FIRA_ERR_NO_PROJECTOR, "install the projector first: fira_set_projector resets the gate");
+  if (!(ortho_err >= 0.0f) || !(gram_err >= 0.0f)) return fail(ctx, FIRA_ERR_INVALID_ARG, "gate values must be >= 0 (+inf = not measured)");
+  FIRA_HIP(ctx, hipStreamSynchronize(ctx->stream));
+  const fira_ctx::Gate gt{ortho_err, gram_err};
+  FIRA_HIP(ctx, hipMemcpy(reinterpret_cast<char*>(ctx->d_scal + idx) + offsetof(FiraScal, ortho_err), &gt, sizeof(gt), hipMemcpyHostToDevice));
+  ctx->h_gate[idx] = gt;
+  return FIRA_OK;
+}
+
 fira_status fira_get_factors(fira_ctx* ctx, int idx, float* host_k) {
   if (!ctx) return fail(nullptr, FIRA_ERR_INVALID_ARG, "ctx is null");
   if (idx < 0 || idx >= (int)ctx->plan.mats.size()) return fail(ctx, FIRA_ERR_INVALID_ARG, "matrix index out of range");
@@ -784,58 +686,9 @@ fira_status fira_get_projector(fira_ctx* ctx, int idx, float* host_P) {
   return FIRA_OK;
 }
 
-namespace {
-
-struct RefreshPlan {
-  size_t total = 0;
-  size_t off_ents = 0, off_ents2 = 0, off_vmats = 0, off_vents = 0, off_vtiles[2] = {0, 0};
-  int ntiles[2] = {0, 0};                 // virtual launches: [0] K-contiguous (real left), [1] K-slow (real right)
-  std::vector<size_t> off_top, off_y, off_q, off_c, off_linv;
-  size_t top_begin = 0, top_end = 0;
-};
-
-bool make_refresh_plan(const fira_ctx* ctx, int count, const int* idx, RefreshPlan* rp) {
-  const int nmat = (int)ctx->plan.mats.size();
-  if (count < 1 || count > nmat || !idx) return false;
-  size_t off = 0;
-  auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
-  rp->off_ents = take(sizeof(FiraRefreshEnt) * count);
-  rp->off_ents2 = take(sizeof(FiraRefreshEnt) * count);
-  rp->off_vmats = take(sizeof(FiraMat) * count);
-  rp->off_vents = take(sizeof(FiraEnt) * count);
-  rp->ntiles[0] = rp->ntiles[1] = 0;
-  for (int e = 0; e < count; ++e) {
-    if (idx[e] < 0 || idx[e] >= nmat) return false;
-    const FiraMat& m = ctx->plan.mats[idx[e]].dev;
-    rp->ntiles[m.left ? 0 : 1] += ((m.S + FIRA_PA - 1) / FIRA_PA) * ((m.r + FIRA_PB - 1) / FIRA_PB);
-  }
-  rp->off_vtiles[0] = take(sizeof(FiraTile) * std::max(rp->ntiles[0], 1));
-  rp->off_vtiles[1] = take(sizeof(FiraTile) * std::max(rp->ntiles[1], 1));
-  rp->off_top.resize(count); rp->off_y.resize(count); rp->off_q.resize(count); rp->off_c.resize(count); rp->off_linv.resize(count);
-  rp->top_begin = off;
-  for (int e = 0; e < count; ++e) {
-    const FiraMat& m = ctx->plan.mats[idx[e]].dev;
-    rp->off_top[e] = take((size_t)round_up_int(m.L, 64) * m.rq * 2);
-  }
-  rp->top_end = off;
-  for (int e = 0; e < count; ++e) {
-    const FiraMat& m = ctx->plan.mats[idx[e]].dev;
-    rp->off_y[e] = take((size_t)m.S * m.r * 4);
-    rp->off_q[e] = take((size_t)m.S * m.r * 4);
-    rp->off_c[e] = take((size_t)m.r * m.r * 8);
-    // scratch of the gate estimate, which before that holds the inverses of the solve's diagonal blocks
-    rp->off_linv[e] = take(std::max((size_t)m.S * 16 + (size_t)FIRA_ORTHO_SPLITS * m.r * 16,
-                                    (size_t)((m.r + FIRA_SOLVE_JB - 1) / FIRA_SOLVE_JB) * FIRA_SOLVE_JB * FIRA_SOLVE_JB * 8));
-  }
-  rp->total = off;
-  return true;
-}
-
-}  // namespace
-
 size_t fira_refresh_workspace_bytes(const fira_ctx* ctx, int count, const int* idx) {
   RefreshPlan rp;
-  if (!ctx || !make_refresh_plan(ctx, count, idx, &rp)) return 0;
+  if (!ctx || !make_refresh_plan(ctx->plan, count, idx, &rp)) return 0;
   return rp.total;
 }
 
@@ -862,7 +715,7 @@ fira_status refresh_check(fira_ctx* ctx, int count, const int* idx, const void* 
       if (ctx->plan.mats[idx[e]].dev.kx != 1) return fail(ctx, FIRA_ERR_DTYPE, "the device refresh handles bf16 matrices only");
     }
   }
-  if (!make_refresh_plan(ctx, count, idx, rp)) return fail(ctx, FIRA_ERR_INVALID_ARG, "bad list");
+  if (!make_refresh_plan(ctx->plan, count, idx, rp)) return fail(ctx, FIRA_ERR_INVALID_ARG, "bad list");
   return FIRA_OK;
 }
 
@@ -985,10 +838,12 @@ fira_status refresh_run(fira_ctx* ctx, int count, const int* idx, const void* co
     for (int J = 0; J < nj; ++J)
       hipLaunchKernelGGL(fira_refresh_solve_kernel, dim3((max_S + 63) / 64, count), dim3(256), FIRA_SOLVE_LDS, q, de, J);
   };
+  const FiraHp refresh_hp = make_hp(ctx);   // (mixed = 0: the projection kernel serves every listed matrix)
   auto launch_project = [&](const FiraMat* mats, const FiraEnt* ents_d, const FiraTile* tl, int nl, const FiraTile* tr, int nr) {
     const int bl = (nl + 7) / 8 * 8, br = (nr + 7) / 8 * 8;
     if (nl + nr)
-      hipLaunchKernelGGL(fira_project_kernel, dim3(bl + br), dim3(FIRA_PROJ_THREADS), FIRA_PROJ_LDS, q, mats, ents_d, tl, nl, bl, tr, nr, 0);
+      hipLaunchKernelGGL(fira_project_kernel, dim3(bl + br), dim3(FIRA_PROJ_THREADS), FIRA_PROJ_LDS, q, mats, ents_d, tl, nl, bl, tr, nr, 0,
+                         (const FiraScal*)ctx->d_scal, refresh_hp);
   };
   for (int it = 0; it < iters; ++it) {
     // operands of Q (the fp32 Q becomes the matrix's projector copies; no gate estimate needed here)
@@ -1007,23 +862,33 @@ fira_status refresh_run(fira_ctx* ctx, int count, const int* idx, const void* co
   // A second pass over the final basis (CholeskyQR2) brings ||Q^T Q - I|| down to rounding level even
   // when Y was ill conditioned; its result lands in the Y buffers.
   orthonormalise(d_ents2);
-  FIRA_HIP(ctx, hipGetLastError());
+  // The rounds above worked in the listed matrices' operand copies of P.  If anything failed to launch, what
+  // they hold now is not a projector: mark the matrices as having none rather than leave a half-made basis
+  // behind the old gate values.
+  auto invalidate = [&]() {
+    for (int e = 0; e < count; ++e) {
+      ctx->plan.mats[idx[e]].has_projector = false;
+      ctx->h_gate[idx[e]] = fira_ctx::Gate{INFINITY, INFINITY};
+    }
+  };
+  {
+    const hipError_t e_ = hipGetLastError();
+    if (e_ != hipSuccess) { invalidate(); return fail(ctx, FIRA_ERR_HIP, std::string("projector refresh: ") + hipGetErrorString(e_)); }
+  }
   // install the result (what fira_set_projector does per matrix, here one launch per phase for the whole list)
   hipLaunchKernelGGL(fira_refresh_prep_kernel, dim3(prep_blocks, count), dim3(256), 0, q, ctx->d_mats, d_ents2);
   hipLaunchKernelGGL(fira_refresh_ortho_y_kernel, dim3((max_S + 3) / 4, count), dim3(256), 0, q, ctx->d_mats, d_ents2);
   hipLaunchKernelGGL(fira_refresh_ortho_z_kernel, dim3(FIRA_ORTHO_SPLITS, count), dim3(256), 0, q, ctx->d_mats, d_ents2);
   hipLaunchKernelGGL(fira_refresh_ortho_final_kernel, dim3(count), dim3(256), 0, q, ctx->d_mats, d_ents2, ctx->d_scal);
-  FIRA_HIP(ctx, hipGetLastError());
+  {
+    const hipError_t e_ = hipGetLastError();
+    if (e_ != hipSuccess) { invalidate(); return fail(ctx, FIRA_ERR_HIP, std::string("projector refresh: ") + hipGetErrorString(e_)); }
+  }
   for (int e = 0; e < count; ++e) {
-    ctx->h_ortho[idx[e]] = INFINITY;
+    ctx->h_gate[idx[e]] = fira_ctx::Gate{INFINITY, INFINITY};
     ctx->plan.mats[idx[e]].has_projector = true;
   }
-  // every matrix's gate value in one strided copy (those not listed are copied unchanged)
-  FIRA_HIP(ctx, hipMemcpy2DAsync(ctx->h_ortho, sizeof(float), reinterpret_cast<char*>(ctx->d_scal) + offsetof(FiraScal, ortho_err),
-                                 sizeof(FiraScal), sizeof(float), (size_t)nmat, hipMemcpyDeviceToHost, q));
-  FIRA_HIP(ctx, hipEventRecord(ctx->ortho_event, q));
-  ctx->ortho_pending = true;
-  return FIRA_OK;
+  return read_back_gates(ctx);
 }
 
 }  // namespace
@@ -1037,7 +902,7 @@ void fira_destroy(fira_ctx* ctx) {
   for (ListSlot& s : ctx->slots)
     if (s.uploaded) (void)hipEventDestroy(s.uploaded);
   if (ctx->h_stage_all) (void)hipHostFree(ctx->h_stage_all);
-  if (ctx->h_ortho) (void)hipHostFree(ctx->h_ortho);
+  if (ctx->h_gate) (void)hipHostFree(ctx->h_gate);
   if (ctx->ortho_event) (void)hipEventDestroy(ctx->ortho_event);
   delete ctx;
 }

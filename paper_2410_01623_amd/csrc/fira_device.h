@@ -74,7 +74,14 @@ struct FiraScal {
   float c;         // limiter factor of the current step
   int has_prev;    // 0 until the first step has recorded a norm
   int t;           // steps taken
-  float ortho_err; // estimate of ||P^T P - I|| from the last fira_set_projector (Gram-mode gate)
+  float ortho_err; // estimate of ||P^T P - I|| from the last fira_set_projector (first gate of the Gram route)
+  // Second gate of the Gram route: relative error of its ||S||^2 against the residual route's, measured on
+  // the first step after the projector was installed (that step takes the residual route and has both).
+  // +inf until measured.  ||G_i||^2 - ||R_i||^2 cancels when the gradient lies almost entirely in the
+  // subspace, and what is left is then the orthonormality defect of the rounded P and fp32 rounding.
+  float gram_err;
+  int gram_now;    // route of the last step for this matrix: 0 residual, 1 Gram with two kernels, 2 Gram with the fused kernel
+  int pad;
 };
 
 // One entry of a step's work list.
@@ -104,6 +111,8 @@ struct FiraHp {     // hyper-parameters as the kernels take them
   int scaling;      // 0 column, 1 matrix, 2 none
   int norm_mode;    // 0: ||S|| from the residual tiles; 1: from ||G_i||^2 - ||R_i||^2 where P passes the gate
   float ortho_tol;  // gate of the Gram mode on FiraScal::ortho_err
+  float gram_tol;   // ... and on FiraScal::gram_err
+  int mixed;        // 1: the fused kernel serves the matrices on the Gram route, the two-kernel path the others
   int variant;      // 0: Algorithm 1; 1: factors on the full gradient, no Adam term ("Fira-only-scaling")
   int fused;        // 1: this step's projection and Adam ran as one kernel (no copy of R exists)
 };
@@ -112,8 +121,45 @@ struct FiraHp {     // hyper-parameters as the kernels take them
 // (The only-scaling variant needs ||G diag(k)||^2 = sum_i k_i^2 ||G_i||^2, which is this route's data
 // without any condition on P.)
 __device__ __forceinline__ bool use_gram(const FiraHp& hp, const FiraScal& sc) {
-  return hp.variant == 1 || (hp.norm_mode == 1 && sc.ortho_err <= hp.ortho_tol);
+  return hp.variant == 1 || (hp.norm_mode == 1 && sc.ortho_err <= hp.ortho_tol && sc.gram_err <= hp.gram_tol);
 }
+// Whether ||G_i||^2 is computed in this step (every listed matrix, whatever its route: the step that
+// measures FiraScal::gram_err needs both routes' data).
+__device__ __forceinline__ bool have_g2(const FiraHp& hp) { return hp.variant == 1 || hp.norm_mode == 1; }
+// Whether this step measures FiraScal::gram_err for matrix `sc`: Gram mode, P passes the first gate, the
+// step takes the residual route, and no measurement has been made since the projector was installed.
+__device__ __forceinline__ bool calibrates_gram(const FiraHp& hp, const FiraScal& sc) {
+  return hp.variant == 0 && hp.norm_mode == 1 && sc.ortho_err <= hp.ortho_tol && !(sc.gram_err < INFINITY);
+}
+
+
+// ---- tile geometry shared by the kernels and the host planner -----------------------------------
+#define FIRA_PA 128          // projection: tile rows on the gradient (long) side
+#define FIRA_PB 256          // projection: tile rows on the rank side
+#define FIRA_PS 64           // projection at small ranks (r <= 64): rank columns of the tile
+#define FIRA_BA 256          // rank-axis contractions (back-projection): tile rows on the A side (n)
+#define FIRA_BB 128          // ... and on the B side (m)
+#define FIRA_ROWS_PER_WG 16  // Adam pass: 4 wavefronts x 4 rows
+#define FIRA_G2_ROWS_PER_WG 32   // ||G_i||^2 kernel, right orientation: rows per workgroup (8 per wavefront)
+#define FIRA_FUSE_MAX_R 512  // largest rank of the fused projection/Adam kernel
+#define FIRA_FUSE_MIN_R 128  // below half a rank tile its epilogue works mostly on padding; the two-kernel path is faster
+#define FIRA_ORTHO_SPLITS 64 // workgroups of the orthonormality estimate's second phase
+#define FIRA_SOLVE_JB 64     // projector refresh: column block of the triangular solve
+
+// One list entry of the projector refresh (device array in the caller's workspace).
+struct FiraRefreshEnt {
+  int S, L, r, left;   // short side, long side, rank, orientation of the real matrix
+  int Lp;              // L rounded up to 64: contraction length of the packed operand
+  int rq;              // r rounded up to 256: rows of the packed operand
+  int mat, pad0;
+  const float* T;      // [L][r]            the matrix's Rt
+  bf16_raw* Top;       // [Lp/32][rq][32]   T transposed, K-blocked along the long side
+  float* Y;            // [S][r]
+  float* Q;            // [S][r]
+  double* C;           // [r][r]            Gram matrix, then its Cholesky factor (lower triangle)
+  float* inst;         // scratch: inverses of the solve's diagonal blocks ([r/64][64][64] fp64), later the
+                       // orthonormality estimate's [S][4] and [FIRA_ORTHO_SPLITS][r][4]
+};
 
 
 // ---- bf16 helpers ---------------------------------------------------------------------------

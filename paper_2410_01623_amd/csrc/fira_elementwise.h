@@ -4,7 +4,6 @@
 #pragma once
 #include "fira_device.h"
 
-#define FIRA_ROWS_PER_WG 16  // 4 wavefronts x 4 rows
 
 // Work-list lookup for the row-blocked kernels: entry e covers row-blocks [ents[e].row0, ents[e+1].row0).
 __device__ __forceinline__ int find_entry(const FiraEnt* __restrict__ ents, int count, int rowblock) {
@@ -124,7 +123,7 @@ __device__ __forceinline__ void adam_row(const FiraMat& mt, const FiraHp& hp, fl
       const float k = (hp.scaling == 2) ? 1.0f : sqrtf(nn) / (sqrtf(rr) + hp.epsf);
       as_global(mt.phi)[row] = k;
       // Gram route: ||G_i - P R_i||^2 = ||G_i||^2 - ||R_i||^2 when P^T P = I (G_i^T P = R_i^T always)
-      if (gram) as_global(mt.q)[row] = k * k * residual_sq(hp, as_global<const float>(mt.g2)[row], rr);
+      if (have_g2(hp)) as_global(mt.q)[row] = k * k * residual_sq(hp, as_global<const float>(mt.g2)[row], rr);
     }
   }
 }
@@ -185,7 +184,7 @@ __device__ __forceinline__ void adam_row_zready(const FiraMat& mt, const FiraHp&
   }
   if (lane == 0) {
     as_global(mt.phi)[row] = k;
-    if (gram) as_global(mt.q)[row] = k * k * residual_sq(hp, as_global<const float>(mt.g2)[row], rr);
+    if (have_g2(hp)) as_global(mt.q)[row] = k * k * residual_sq(hp, as_global<const float>(mt.g2)[row], rr);
   }
 }
 
@@ -237,7 +236,7 @@ __device__ __forceinline__ void adam_rows4_small(const FiraMat& mt, const FiraHp
   }
   if ((lane & 15) == 0 && row < mt.L) {
     as_global(mt.phi)[row] = k;
-    if (gram) as_global(mt.q)[row] = k * k * residual_sq(hp, as_global<const float>(mt.g2)[row], rr);
+    if (have_g2(hp)) as_global(mt.q)[row] = k * k * residual_sq(hp, as_global<const float>(mt.g2)[row], rr);
   }
 }
 
@@ -258,6 +257,7 @@ __global__ __launch_bounds__(256, 4) void fira_adam_kernel(const FiraMat* __rest
   const FiraScal sc = scal[ent.mat];
   const int t = sc.t + 1;
   const bool gram = use_gram(hp, sc);
+  if (hp.mixed && gram) return;                // the fused kernel has served this matrix
   const float bias = (float)(sqrt(1.0 - pow(hp.beta2, (double)t)) / (1.0 - pow(hp.beta1, (double)t)));
   const int wave = threadIdx.x >> 6;
   const long long row_base = (long long)(rb - ent.row0) * FIRA_ROWS_PER_WG + wave * 4;
@@ -316,8 +316,12 @@ __global__ __launch_bounds__(FIRA_LIMITER_THREADS) void fira_limiter_kernel(cons
   __shared__ double red[4];
   const FiraEnt ent = ents[blockIdx.x];
   const int tid = threadIdx.x;
-  const bool gram = use_gram(hp, scal[ent.mat]);
-  double acc = 0.0;
+  const FiraScal sc0 = scal[ent.mat];
+  const bool gram = use_gram(hp, sc0);
+  // On the residual route with the Gram data at hand (the first step after an install), also form the
+  // Gram route's value and record how far it is from the exact one: the second gate of that route.
+  const bool calibrate = !gram && calibrates_gram(hp, sc0);
+  double acc = 0.0, accg = 0.0;
   if (hp.scaling == 1) {
     // Matrix-level factor (Eq. 9): k = ||N|| / (||R|| + eps) from the row sums the Adam kernel left in
     // phi and q; ||S||^2 = k^2 * (sum_i ||G_i - P R_i||^2), the sum taken with unit factors by either route.
@@ -330,6 +334,7 @@ __global__ __launch_bounds__(FIRA_LIMITER_THREADS) void fira_limiter_kernel(cons
       nn += (double)phi[i];
       rr += (double)q[i];
       if (gram) acc += (double)residual_sq(hp, g2[i], q[i]);
+      else if (calibrate) accg += (double)residual_sq(hp, g2[i], q[i]);
     }
     if (!gram)
       for (int i = tid; i < ent.npart; i += FIRA_LIMITER_THREADS) acc += (double)partial[ent.part0 + i];
@@ -337,15 +342,21 @@ __global__ __launch_bounds__(FIRA_LIMITER_THREADS) void fira_limiter_kernel(cons
     rr = limiter_block_sum(rr, red);
     const float k = (float)(sqrt(nn) / (sqrt(rr) + hp.eps));
     acc *= (double)k * (double)k;
+    accg *= (double)k * (double)k;
     for (int i = tid; i < mt.L; i += FIRA_LIMITER_THREADS) phi[i] = k;
-  } else if (gram) {
-    const FiraMat mt = mats[ent.mat];
-    gptr<const float> q = as_global<const float>(mt.q);
-    for (int i = tid; i < mt.L; i += FIRA_LIMITER_THREADS) acc += (double)q[i];
   } else {
-    for (int i = tid; i < ent.npart; i += FIRA_LIMITER_THREADS) acc += (double)partial[ent.part0 + i];
+    if (gram || calibrate) {
+      const FiraMat mt = mats[ent.mat];
+      gptr<const float> q = as_global<const float>(mt.q);
+      double a = 0.0;
+      for (int i = tid; i < mt.L; i += FIRA_LIMITER_THREADS) a += (double)q[i];
+      if (gram) acc = a; else accg = a;
+    }
+    if (!gram)
+      for (int i = tid; i < ent.npart; i += FIRA_LIMITER_THREADS) acc += (double)partial[ent.part0 + i];
   }
   acc = limiter_block_sum(acc, red);
+  if (calibrate) accg = limiter_block_sum(accg, red);   // (uniform over the workgroup)
   if (tid == 0) {
     FiraScal s = scal[ent.mat];
     const double sn = sqrt(acc);
@@ -355,6 +366,8 @@ __global__ __launch_bounds__(FIRA_LIMITER_THREADS) void fira_limiter_kernel(cons
       const double ratio = den > 0.0 ? sn / den : INFINITY;
       c = hp.gamma / fmax(ratio, hp.gamma);
     }
+    if (calibrate) s.gram_err = (acc == accg) ? 0.0f : (float)fmin(fabs(accg - acc) / fmax(acc, 1e-300), 3.0e38);
+    s.gram_now = gram ? (hp.fused ? 2 : 1) : 0;
     s.s_pre = sn;
     s.s_post = c * sn;
     s.s_prev = s.s_post;      // the remembered norm is the limited one
@@ -452,18 +465,20 @@ __global__ __launch_bounds__(256) void fira_makez_kernel(const FiraMat* __restri
   const FiraMat mt = mats[ent.mat];
   const bool zready = mt.zready && hp.scaling != 1;
   if (zready && c == 1.0f) return;             // the Adam kernel already wrote Z for c = 1
+  // whether the fused kernel served this matrix (then no copy of R exists)
+  const bool fused_here = scal[ent.mat].gram_now == 2;
   const int wave = threadIdx.x >> 6;
   const int rowblocks = (mt.L + FIRA_ROWS_PER_WG - 1) / FIRA_ROWS_PER_WG;
   // the limiter has already advanced t: the bias correction of this step uses the count as it stands now
   const int t = scal[ent.mat].t;
-  const float bias = hp.fused ? (float)(sqrt(1.0 - pow(hp.beta2, (double)t)) / (1.0 - pow(hp.beta1, (double)t))) : 0.0f;
+  const float bias = fused_here ? (float)(sqrt(1.0 - pow(hp.beta2, (double)t)) / (1.0 - pow(hp.beta1, (double)t))) : 0.0f;
   for (int rb = part; rb < rowblocks; rb += FIRA_MAKEZ_PARTS) {
     const long long row_base = (long long)rb * FIRA_ROWS_PER_WG + wave * 4;
     for (int i = 0; i < 4; ++i) {
       const long long row = row_base + i;
       if (row >= mt.L) break;
       const float k = as_global<const float>(mt.phi)[row];
-      if (zready && hp.fused) fixz_row_from_moments(mt, hp, c, bias, row);
+      if (zready && fused_here) fixz_row_from_moments(mt, hp, c, bias, row);
       else if (zready) fixz_row(mt, (1.0f - c) * k, row);
       else if (mt.kx == 1) makez_row<1>(mt, c * k, row);
       else makez_row<FIRA_KX_SPLIT>(mt, c * k, row);
@@ -599,7 +614,6 @@ __global__ void fira_split_gradient_kernel(FiraMat mt, const float* __restrict__
 //   right (m >  n): row sums of squares; one wavefront per row.
 // Fixed summation order: deterministic.
 // ------------------------------------------------------------------------------------------------
-#define FIRA_G2_ROWS_PER_WG 32   // right orientation: rows per workgroup (8 per wavefront)
 
 __device__ __forceinline__ int find_g2_entry(const FiraEnt* __restrict__ ents, int count, int blk) {
   int lo = 0, hi = count - 1;
@@ -686,7 +700,7 @@ __global__ __launch_bounds__(256) void fira_gradnorm_kernel(const FiraMat* __res
   if (b >= total_blocks) return;
   const int e = find_g2_entry(ents, count, b);
   const FiraEnt ent = ents[e];
-  if (!use_gram(hp, scal[ent.mat])) return;
+  if (!have_g2(hp)) return;
   const FiraMat mt = mats[ent.mat];
   if (mt.dtype == 1) return;   // bf16 matrices: the projection kernel accumulates ||G_i||^2 itself
   g2_block<float>(mt, ent, b - ent.g2b0, red);
@@ -725,7 +739,6 @@ __device__ __forceinline__ void ortho_y_body(const FiraMat& mt, float* __restric
 __global__ __launch_bounds__(256) void fira_ortho_y_kernel(FiraMat mt, float* __restrict__ y) { ortho_y_body(mt, y); }
 
 // z-partials: workgroup b sums rows [b*chunk, (b+1)*chunk) of P^T y for all four trials.
-#define FIRA_ORTHO_SPLITS 64
 __device__ __forceinline__ void ortho_z_body(const FiraMat& mt, const float* __restrict__ y,
                                              float* __restrict__ zpart /* [splits][r][4] */) {
   gptr<const bf16_raw> Pn = as_global<const bf16_raw>(mt.Pn);
@@ -774,6 +787,7 @@ __device__ __forceinline__ void ortho_final_body(const FiraMat& mt, const float*
     for (int k = 0; k < 4; ++k)
       worst = fmaxf(worst, sqrtf(((red[0][k] + red[1][k]) + (red[2][k] + red[3][k])) / (float)mt.r));
     as_global(scal)[mat].ortho_err = worst;
+    as_global(scal)[mat].gram_err = INFINITY;   // to be measured on the next step
   }
 }
 __global__ __launch_bounds__(256) void fira_ortho_final_kernel(FiraMat mt, const float* __restrict__ zpart,

@@ -1,5 +1,5 @@
 // Projection and Adam in one kernel (Algorithm 1: R = P^T G, the moment updates of Eqs. 2-4, the factor
-// k_i of Eq. 10, and the back-projection operand Z_i = N_i - k_i R_i).
+// k_i of Eq. 11, and the back-projection operand Z_i = N_i - k_i R_i).
 //
 // When the rank fits one workgroup (r <= 512) the whole row R_i of a factor sits in the accumulators of
 // the workgroup that projected it, so Adam can run on it there: R never goes to memory, and neither
@@ -20,10 +20,11 @@
 //   2. one thread per factor adds the waves' sums in order, forms k_i, writes phi and q;
 //   3. Z = N - k R is rounded to bf16 into an LDS image of the K-blocked operand;
 //   4. the new M and V and Z leave LDS in 16-byte pieces, whole rows contiguous.
-// Waits on the LDS-direct loads are explicit (see fira_gemm.h): in an interior tile a wave issues
-// exactly 8 load instructions per chunk and 10 store instructions in step 4, so "all but the newest
-// 10" at the end of a chunk means the next chunk has landed while this chunk's stores may still be in
-// flight.  Edge tiles skip rows and columns and wait for everything instead.
+// Waits on the LDS-direct loads are explicit (see fira_gemm.h).  The wait for chunk c + 1 stands between
+// steps 3 and 4 of chunk c, before the chunk's stores are issued, and waits for everything in flight: that
+// is the loads of chunk c + 1 and the stores of chunk c - 1, which are a whole chunk old.  The stores of
+// chunk c then stay in flight while chunk c + 1 is processed.  No count of instructions, and no
+// assumption about the order in which loads and stores retire relative to each other, is involved.
 //
 // A step takes this kernel only if every listed matrix is bf16 with r % 4 == 0, 128 <= r <= 512, column
 // factors, Algorithm 1 proper, and the Gram route to ||S|| (no operand copy of R is made here).
@@ -34,8 +35,6 @@
 #include "fira_elementwise.h"
 #include "fira_gemm.h"
 
-#define FIRA_FUSE_MAX_R 512
-#define FIRA_FUSE_MIN_R 128   // below half a rank tile the epilogue works mostly on padding; the two-kernel path is faster
 #define FIRA_FUSE_F 16   // factors per chunk of the epilogue
 #define FIRA_FUSE_LDS_MAIN(RT) (FIRA_PROJ_LDS_A + FIRA_RING_STAGES * (RT) * FIRA_PROJ_RING_STAGE)
 // two landing buffers (M and V of a chunk, fp32), the Z image (bf16), per-wave sums, ||G_i||^2 of the tile, k_i
@@ -192,6 +191,12 @@ __device__ __forceinline__ void project_adam_epilogue(f32x16_t (&acc)[4][2], cha
       }
     }
     __syncthreads();
+    // The next chunk has landed (this wave's share of it).  The wait stands before this chunk's stores are
+    // issued, so that it can be "everything": the only other operations in flight are the previous chunk's
+    // stores, which have had this whole chunk to complete.  (Placed after the stores, the wait would have
+    // to let exactly their number stay in flight, which is right only if stores never retire before older
+    // loads and the compiler emits exactly the instructions counted.)
+    if (c + 1 < 8) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     // M and V: 2 x 16 rows x C/4 pieces of 16 bytes, 8 per thread; Z: C/32 K blocks x 1 KB, 2 per thread
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
@@ -215,12 +220,9 @@ __device__ __forceinline__ void project_adam_epilogue(f32x16_t (&acc)[4][2], cha
               *reinterpret_cast<const u32x4*>(reinterpret_cast<const char*>(zl) + p * 16);
       }
     }
-    if (c + 1 < 8) {
-      // the next chunk has landed (this wave's share); this chunk's stores may stay in flight
-      if (INTERIOR) asm volatile("s_waitcnt vmcnt(10)" ::: "memory");
-      else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-      __syncthreads();                                             // ... everybody's share; all are done with this chunk's LDS
-    }
+    // everybody's share of the next chunk has landed, and all are done reading this chunk's LDS (the stores
+    // above have read it into registers: the compiler waits for those LDS reads before the barrier)
+    if (c + 1 < 8) __syncthreads();
   };
   chunk(std::integral_constant<int, 0>{});
   chunk(std::integral_constant<int, 1>{});
@@ -236,6 +238,7 @@ template <bool LEFT, int RT>
 __device__ __forceinline__ void project_adam_tile(char* lds, const FiraMat* __restrict__ mats, const FiraScal* __restrict__ scal,
                                                   const FiraEnt* __restrict__ ents, const FiraTile& tile, const FiraHp& hp) {
   const FiraEnt ent = ents[tile.ent];
+  if (!use_gram(hp, scal[ent.mat])) return;    // this matrix takes the residual route: the two-kernel path serves it
   const FiraMat mt = mats[ent.mat];
 
   GemmOperands g;

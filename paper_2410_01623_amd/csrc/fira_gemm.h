@@ -23,7 +23,6 @@
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
 
-#define FIRA_BA 256  // rank-axis contractions (back-projection): tile rows on the A side (n)
 
 // [row][64 k] bf16 tile, 128 B per row, 16-byte chunks XOR-swizzled by row so that fragment reads
 // and tile writes spread over all banks.
@@ -121,7 +120,6 @@ __device__ __forceinline__ void gemm_sumsq_slice(float (&sq)[4], const Frags& f)
 // Operand rows are padded to whole tiles (zeros), so no row index needs clamping; what the padding
 // rows produce lands in accumulators that are never stored.
 // ------------------------------------------------------------------------------------------------
-#define FIRA_BB 128   // ... and on the B side (m)
 #define FIRA_BACK_THREADS 256
 #define FIRA_RK 32
 #define FIRA_RING_A (FIRA_BA * 64)
@@ -225,8 +223,6 @@ __device__ __forceinline__ void ring_mainloop(f32x16_t (&acc)[4][2], char* lds, 
 // D may be in flight), O with vmcnt(8).  Edge tiles load A with ordinary guarded loads at the same
 // points of the sequence; the compiler's own waits for those only wait longer.
 // ------------------------------------------------------------------------------------------------
-#define FIRA_PA 128
-#define FIRA_PB 256
 #define FIRA_PROJ_THREADS 256
 #define FIRA_PROJ_LDS_A (FIRA_PA * 128)
 #define FIRA_PROJ_RING_STAGE (FIRA_PB * 64)
@@ -464,8 +460,9 @@ __device__ __forceinline__ void proj_pipeline(f32x16_t (&acc)[4][2], char* lds, 
 
 template <bool LEFT>
 __device__ __forceinline__ void project_tile(char* lds, const FiraMat* __restrict__ mats, const FiraEnt* __restrict__ ents,
-                                             const FiraTile& tile, int norm_mode) {
+                                             const FiraTile& tile, int norm_mode, const FiraScal* __restrict__ scal, const FiraHp& hp) {
   const FiraEnt ent = ents[tile.ent];
+  if (hp.mixed && use_gram(hp, scal[ent.mat])) return;   // the fused kernel serves this matrix
   const FiraMat mt = mats[ent.mat];
 
   GemmOperands g;
@@ -535,22 +532,23 @@ __device__ __forceinline__ void project_tile(char* lds, const FiraMat* __restric
 // One grid for both orientations: workgroups [0, blocks_left) take the tiles of the matrices with
 // m <= n (gradient K-slow), the rest those with m > n, so that only one partly filled round of
 // workgroups ends the launch.  blocks_left is a multiple of 8, which keeps the XCD-aware mapping of
-// each part.
+// each part.  scal is read only when hp.mixed is set (a step in which the fused kernel serves the
+// matrices on the Gram route and this kernel the others).
 __global__ __launch_bounds__(FIRA_PROJ_THREADS, 2) void fira_project_kernel(const FiraMat* __restrict__ mats,
                                                                             const FiraEnt* __restrict__ ents,
                                                                             const FiraTile* __restrict__ tiles_left, int ntiles_left,
                                                                             int blocks_left,
                                                                             const FiraTile* __restrict__ tiles_right, int ntiles_right,
-                                                                            int norm_mode) {
+                                                                            int norm_mode, const FiraScal* __restrict__ scal, FiraHp hp) {
   extern __shared__ __attribute__((aligned(16))) char lds[];   // FIRA_PROJ_LDS bytes
   if ((int)blockIdx.x < blocks_left) {
     const int ti = xcd_chunked_index(blockIdx.x, ntiles_left);
     if (ti < 0) return;
-    project_tile<true>(lds, mats, ents, tiles_left[ti], norm_mode);
+    project_tile<true>(lds, mats, ents, tiles_left[ti], norm_mode, scal, hp);
   } else {
     const int ti = xcd_chunked_index((int)blockIdx.x - blocks_left, ntiles_right);
     if (ti < 0) return;
-    project_tile<false>(lds, mats, ents, tiles_right[ti], norm_mode);
+    project_tile<false>(lds, mats, ents, tiles_right[ti], norm_mode, scal, hp);
   }
 }
 
@@ -563,7 +561,6 @@ __global__ __launch_bounds__(FIRA_PROJ_THREADS, 2) void fira_project_kernel(cons
 // a ring stage is 64 rows x 32 k = 4 KB, one request instruction per wavefront, so the E-half wait is
 // vmcnt(1) and the O-half wait vmcnt(5) (one ring request and the four of A(S+1) are younger).
 // ------------------------------------------------------------------------------------------------
-#define FIRA_PS 64                                   // rank columns of the small tile
 #define FIRA_PROJ_SMALL_STAGE (FIRA_PS * 64)
 #define FIRA_PROJ_SMALL_LDS (FIRA_PROJ_LDS_A + FIRA_RING_STAGES * FIRA_PROJ_SMALL_STAGE)
 
@@ -637,8 +634,9 @@ __device__ __forceinline__ void proj_pipeline_small(f32x16_t (&acc)[2], char* ld
 
 template <bool LEFT>
 __device__ __forceinline__ void project_small_tile(char* lds, const FiraMat* __restrict__ mats, const FiraEnt* __restrict__ ents,
-                                                   const FiraTile& tile, int norm_mode) {
+                                                   const FiraTile& tile, int norm_mode, const FiraScal* __restrict__ scal, const FiraHp& hp) {
   const FiraEnt ent = ents[tile.ent];
+  if (hp.mixed && use_gram(hp, scal[ent.mat])) return;   // (never the case today: the fused kernel takes no rank this small)
   const FiraMat mt = mats[ent.mat];
   GemmOperands g;
   g.a_row0 = tile.ta * FIRA_PA;
@@ -691,16 +689,16 @@ __global__ __launch_bounds__(FIRA_PROJ_THREADS, 4) void fira_project_small_kerne
                                                                                   const FiraTile* __restrict__ tiles_left, int ntiles_left,
                                                                                   int blocks_left,
                                                                                   const FiraTile* __restrict__ tiles_right, int ntiles_right,
-                                                                                  int norm_mode) {
+                                                                                  int norm_mode, const FiraScal* __restrict__ scal, FiraHp hp) {
   extern __shared__ __attribute__((aligned(16))) char lds[];   // FIRA_PROJ_SMALL_LDS bytes
   if ((int)blockIdx.x < blocks_left) {
     const int ti = xcd_chunked_index(blockIdx.x, ntiles_left);
     if (ti < 0) return;
-    project_small_tile<true>(lds, mats, ents, tiles_left[ti], norm_mode);
+    project_small_tile<true>(lds, mats, ents, tiles_left[ti], norm_mode, scal, hp);
   } else {
     const int ti = xcd_chunked_index((int)blockIdx.x - blocks_left, ntiles_right);
     if (ti < 0) return;
-    project_small_tile<false>(lds, mats, ents, tiles_right[ti], norm_mode);
+    project_small_tile<false>(lds, mats, ents, tiles_right[ti], norm_mode, scal, hp);
   }
 }
 

@@ -15,19 +15,6 @@
 #pragma once
 #include "fira_device.h"
 
-struct FiraRefreshEnt {
-  int S, L, r, left;   // short side, long side, rank, orientation of the real matrix
-  int Lp;              // L rounded up to 64: contraction length of the packed operand
-  int rq;              // r rounded up to 256: rows of the packed operand
-  int mat, pad0;
-  const float* T;      // [L][r]            the matrix's Rt
-  bf16_raw* Top;       // [Lp/32][rq][32]   T transposed, K-blocked along the long side
-  float* Y;            // [S][r]
-  float* Q;            // [S][r]
-  double* C;           // [r][r]            Gram matrix, then its Cholesky factor (lower triangle)
-  float* inst;         // scratch: inverses of the solve's diagonal blocks ([r/64][64][64] fp64), later the
-                       // orthonormality estimate's [S][4] and [FIRA_ORTHO_SPLITS][r][4]
-};
 
 // splitmix64 finaliser: one independent 64-bit value per counter
 __device__ __forceinline__ unsigned long long refresh_mix64(unsigned long long z) {
@@ -272,7 +259,6 @@ __global__ __launch_bounds__(FIRA_CHOL_THREADS) void fira_refresh_chol_kernel(co
 // which is idle until the solves are done.  (Forms that kept a workgroup's rows in LDS and walked along
 // the columns, one row per lane with L read from memory or staged in LDS, ran at a tenth of the fp64
 // rate: bound by the latency, or the LDS bandwidth, of the operand every lane shares.)
-#define FIRA_SOLVE_JB 64
 #define FIRA_SOLVE_LDS (16 * 64 * 4 + 16 * 64 * 8 + 64 * 65 * 8 + 64 * 64 * 8)
 
 // inv(L_JJ) for every diagonal block J of a matrix: inv[J][k][c], k >= c (zero above the diagonal).

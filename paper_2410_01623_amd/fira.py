@@ -33,7 +33,7 @@ FIRA_STATIC_SCRATCH_BYTES = 64 << 20
 EXPORTS = (
     "fira_method_state_numel", "fira_state_bytes", "fira_init_state", "fira_set_projector", "fira_step",
     "fira_set_hparams", "fira_set_options", "fira_set_variant", "fira_set_fusion", "fira_last_step_fused",
-    "fira_get_state", "fira_set_state", "fira_get_diag",
+    "fira_get_state", "fira_set_state", "fira_get_diag", "fira_get_gate", "fira_set_gate",
     "fira_get_factors", "fira_get_lowrank", "fira_get_projector", "fira_refresh_workspace_bytes",
     "fira_refresh_projectors", "fira_refresh_projectors_static", "fira_profile_begin", "fira_profile_end", "fira_kernel_name",
     "fira_last_error", "fira_destroy",
@@ -98,6 +98,10 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.fira_set_state.argtypes = [vp, ci, vp, vp, cd, ctypes.c_int64]
     lib.fira_get_diag.restype = ci
     lib.fira_get_diag.argtypes = [vp, ci, ctypes.POINTER(cd), ctypes.POINTER(cd), ctypes.POINTER(cd)]
+    lib.fira_get_gate.restype = ci
+    lib.fira_get_gate.argtypes = [vp, ci, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ci)]
+    lib.fira_set_gate.restype = ci
+    lib.fira_set_gate.argtypes = [vp, ci, ctypes.c_float, ctypes.c_float]
     lib.fira_get_factors.restype = ci
     lib.fira_get_factors.argtypes = [vp, ci, vp]
     lib.fira_get_lowrank.restype = ci
@@ -253,6 +257,15 @@ class FiraContext:
         a, b, c = ctypes.c_double(), ctypes.c_double(), ctypes.c_double()
         _check(self.lib, self.ctx, self.lib.fira_get_diag(self.ctx, idx, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)))
         return a.value, b.value, c.value
+
+    def fira_get_gate(self, idx: int):
+        """-> (ortho_err, gram_err, route of the last step: 0 residual, 1 Gram, 2 Gram with the fused kernel)"""
+        a, b, r = ctypes.c_float(), ctypes.c_float(), ctypes.c_int()
+        _check(self.lib, self.ctx, self.lib.fira_get_gate(self.ctx, idx, ctypes.byref(a), ctypes.byref(b), ctypes.byref(r)))
+        return a.value, b.value, int(r.value)
+
+    def fira_set_gate(self, idx: int, ortho_err: float, gram_err: float):
+        _check(self.lib, self.ctx, self.lib.fira_set_gate(self.ctx, idx, ortho_err, gram_err))
 
     def fira_get_factors(self, idx: int) -> torch.Tensor:
         m, n = self.shapes[idx]

@@ -44,8 +44,8 @@ def test_twin_matrices_stay_bit_identical(norm_mode):
 
 
 def test_step_replays_from_a_hip_graph():
-    """fira_step only enqueues kernels once its work list is cached and the projectors' gate values are in,
-    so a training loop can capture it in a HIP graph.  Three replays with fresh gradients (copied into the
+    """fira_step only enqueues kernels once its work list is cached and the projectors' gate values are in
+    (from the second step after an installation on), so a training loop can capture it in a HIP graph.  Three replays with fresh gradients (copied into the
     captured buffers, with eager work and synchronisations in between) must give, bit for bit, what eager
     steps give on a twin context."""
     dev = "cuda:0"
@@ -76,11 +76,13 @@ def test_step_replays_from_a_hip_graph():
             gg.copy_(g)
         torch.cuda.synchronize()
 
-    # one eager step on both: caches the work lists and collects the gate values
-    load_new_gradients()
-    ctx_e.fira_step(prepared=prep_e)
-    ctx_g.fira_step(prepared=prep_g)
-    torch.cuda.synchronize()
+    # two eager steps on both: the first caches the work lists and measures the gate of the Gram route (on the
+    # residual route), the second collects the gate values and runs the launch sequence that is captured
+    for _ in range(2):
+        load_new_gradients()
+        ctx_e.fira_step(prepared=prep_e)
+        ctx_g.fira_step(prepared=prep_g)
+        torch.cuda.synchronize()
     assert ctx_g.fira_last_step_fused()
     for a, b in zip(W_e, W_g):
         assert torch.equal(a, b)

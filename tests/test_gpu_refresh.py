@@ -25,9 +25,12 @@ def _gapped_gradient(rng, m, n, r, tail=0.05):
 
 
 @pytest.mark.parametrize("m,n,r", [(300, 517, 40), (517, 300, 40), (256, 256, 64), (1024, 2736, 128), (2736, 1024, 128),
-                                   (330, 650, 200)],
-                         ids=["300x517r40", "517x300r40", "256x256r64", "1024x2736r128", "2736x1024r128", "330x650r200"])
+                                   (330, 650, 200), (2048, 5461, 512), (5461, 2048, 512)],
+                         ids=["300x517r40", "517x300r40", "256x256r64", "1024x2736r128", "2736x1024r128", "330x650r200",
+                              "2048x5461r512", "5461x2048r512"])
 def test_refreshed_projector_spans_the_leading_singular_subspace(m, n, r):
+    """(The last two cases are the headline workload's rectangular shapes at its rank, the configuration whose
+    refresh bench.py times.)"""
     rng = np.random.default_rng(1000 + m + n)
     G = _gapped_gradient(rng, m, n, r)
     ctx = fira.FiraContext([(m, n)], r, fira.FIRA_BF16, device=H.DEV)
