@@ -165,6 +165,16 @@ FIRA_API fira_status fira_set_variant(fira_ctx* ctx, fira_variant variant);
 FIRA_API fira_status fira_set_fusion(fira_ctx* ctx, int enable);
 FIRA_API int fira_last_step_fused(const fira_ctx* ctx);
 
+/* Precision of the back-projection operand Z = N - c k R of bf16 matrices (Algorithm 1's last two lines are
+ * computed as W -= lr alpha (P Z + c k G)).  planes = 1, the default: Z is rounded to bf16 once, which puts
+ * about 2^-9 relative error on P Z; harmless for one step, but W is stored in bf16, and an element whose
+ * update sits next to half an ulp then moves or stays differently from exact arithmetic, one ulp per step
+ * for as long as that lasts.  planes = 2: Z is kept as two bf16 planes, its rounding and the rounding of the
+ * remainder (16 mantissa bits), the contraction runs over both, and W follows exact arithmetic over long
+ * runs; the back-projection does twice the multiplies and the fused projection/Adam kernel is not used.
+ * Applies to bf16 matrices with r % 4 == 0, r <= 1024 and column or no factors; others keep one plane. */
+FIRA_API fira_status fira_set_z_planes(fira_ctx* ctx, int planes);
+
 /* Copy the state of matrix idx to host memory.  Synchronises the stream.
  * host_M, host_V: fp32, in the paper's orientation (r x n row-major for m <= n, m x r for m > n);
  * either may be NULL.  *s_prev = ||S_{t-1}|| or -1 when no step has run yet.  *t = steps taken. */

@@ -88,6 +88,7 @@ struct fira_ctx {
   int norm_mode = FIRA_NORM_GRAM;
   int variant = FIRA_VARIANT_FULL;
   bool fusion = true;          // fira_set_fusion
+  bool zsplit = false;         // fira_set_z_planes(2)
   bool last_step_fused = false;
   FiraMat* d_mats = nullptr;
   FiraScal* d_scal = nullptr;
@@ -138,6 +139,7 @@ FiraHp make_hp(const fira_ctx* ctx) {
   h.ortho_tol = 0.02f;   // bf16-rounded orthonormal projectors measure ~1e-3; a projector beyond 0.02 is not meant to be orthonormal
   h.gram_tol = 2e-3f;    // measured relative error of ||S||^2 by the Gram route: 1e-3 of ||S||
   h.mixed = 0;
+  h.zsplit = ctx->zsplit ? 1 : 0;
   return h;
 }
 
@@ -259,6 +261,7 @@ fira_status fira_init_state(fira_ctx** out, const fira_matrix_desc* d, int count
   FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_backproject_kernel<1, float>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_BACK_LDS));
   FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_refresh_chol_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_CHOL_PAN_ROWS * (FIRA_CHOL_NB + 1) * 8));
   FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_refresh_solve_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_SOLVE_LDS));
+  FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_adam_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * FIRA_ROWS_PER_WG * FIRA_ZREADY_MAX_R * 2));
   FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_project_adam_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_FUSE_LDS(1)));
   FIRA_INIT_HIP(hipFuncSetAttribute((const void*)fira_project_adam_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize, FIRA_FUSE_LDS(2)));
   FIRA_INIT_HIP(hipHostMalloc((void**)&ctx->h_stage_all, p.slot_bytes * kSlots, hipHostMallocDefault));
@@ -316,6 +319,13 @@ fira_status fira_set_fusion(fira_ctx* ctx, int enable) {
 }
 
 int fira_last_step_fused(const fira_ctx* ctx) { return ctx && ctx->last_step_fused ? 1 : 0; }
+
+fira_status fira_set_z_planes(fira_ctx* ctx, int planes) {
+  if (!ctx) return fail(nullptr, FIRA_ERR_INVALID_ARG, "ctx is null");
+  if (planes != 1 && planes != 2) return fail(ctx, FIRA_ERR_INVALID_ARG, "planes must be 1 or 2");
+  ctx->zsplit = planes == 2;
+  return FIRA_OK;
+}
 
 fira_status fira_set_projector(fira_ctx* ctx, int idx, const void* dev_P, fira_dtype p_dtype) {
   if (!ctx) return fail(nullptr, FIRA_ERR_INVALID_ARG, "ctx is null");
@@ -422,7 +432,7 @@ fira_status fira_step(fira_ctx* ctx, int count, const int* idx, void* const* dev
   }
   // The fused projection/Adam kernel serves the listed matrices on the Gram route if each of them can take
   // it; those on the residual route then go through the two-kernel path in the same step (hp.mixed).
-  bool fused = ctx->fusion && !only_scaling && ctx->scaling == FIRA_SCALE_COLUMN && ctx->norm_mode == FIRA_NORM_GRAM && any_gram;
+  bool fused = ctx->fusion && !ctx->zsplit && !only_scaling && ctx->scaling == FIRA_SCALE_COLUMN && ctx->norm_mode == FIRA_NORM_GRAM && any_gram;
   for (int e = 0; e < count && fused; ++e) {
     const fira_ctx::Gate gt = ctx->h_gate[idx[e]];
     if (gt.ortho_err <= hp.ortho_tol && gt.gram_err <= hp.gram_tol) fused = ctx->plan.mats[idx[e]].fuse_list >= 0;
@@ -451,8 +461,8 @@ fira_status fira_step(fira_ctx* ctx, int count, const int* idx, void* const* dev
     launch_project(want_g2);
     mark(1);
     // 2. Adam on R, factor norms
-    hipLaunchKernelGGL(fira_adam_kernel, dim3(s->rowblocks), dim3(256), ctx->plan.adam_lds, q, ctx->d_mats, ctx->d_scal, s->d_ents, count,
-                       s->rowblocks, hp);
+    hipLaunchKernelGGL(fira_adam_kernel, dim3(s->rowblocks), dim3(256), ctx->plan.adam_lds * (ctx->zsplit ? 2 : 1), q, ctx->d_mats, ctx->d_scal,
+                       s->d_ents, count, s->rowblocks, hp);
     mark(2);
   } else {
     mark(1);

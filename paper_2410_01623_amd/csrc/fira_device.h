@@ -54,7 +54,8 @@ struct FiraMat {
   float* phi;          // [L]      scaling factors k_i of this step
   float* g2;           // [L]      ||G_i||^2 (Gram mode)
   float* q;            // [L]      k_i^2 (||G_i||^2 - ||R_i||^2), the terms of ||S||^2 (Gram mode)
-  bf16_raw* Nb;        // [kx*rp/32][Lq][32] Z = N - c k_i R_i of this step (MFMA operand)
+  bf16_raw* Nb;        // [kx*rp/32][Lq][32] Z = N - c k_i R_i of this step (MFMA operand); bf16 matrices have room for a
+                       // second plane of K blocks, Z's rounding remainder, used when FiraHp::zsplit is set
   bf16_raw* Rb;        // [kx*rp/32][Lq][32] R of this step as MFMA operand (residual route)
   bf16_raw* Pn;        // [kx*rp/32][Sq][32] projector, rank along K (operand of the back-projection)
   bf16_raw* PT;        // [kx*Sp/32][rq][32] projector transposed, short side along K (operand of R)
@@ -113,6 +114,7 @@ struct FiraHp {     // hyper-parameters as the kernels take them
   float ortho_tol;  // gate of the Gram mode on FiraScal::ortho_err
   float gram_tol;   // ... and on FiraScal::gram_err
   int mixed;        // 1: the fused kernel serves the matrices on the Gram route, the two-kernel path the others
+  int zsplit;       // 1: Z of the register-resident Adam rows is stored as two bf16 planes, hi + lo (K = 2 rp)
   int variant;      // 0: Algorithm 1; 1: factors on the full gradient, no Adam term ("Fira-only-scaling")
   int fused;        // 1: this step's projection and Adam ran as one kernel (no copy of R exists)
 };

@@ -128,6 +128,14 @@ __device__ __forceinline__ void adam_row(const FiraMat& mt, const FiraHp& hp, fl
   }
 }
 
+// Second bf16 plane of four values whose first plane (nearest-even bf16) is `hi`: bf16(z - hi), so that
+// hi + lo carries 16 mantissa bits of z.
+__device__ __forceinline__ u32x2 split_remainder(const f32x4& z, const u32x2& hi) {
+  const float h0 = __uint_as_float(hi.x << 16), h1 = __uint_as_float(hi.x & 0xffff0000u);
+  const float h2 = __uint_as_float(hi.y << 16), h3 = __uint_as_float(hi.y & 0xffff0000u);
+  return u32x2{pack_bf16x2(z[0] - h0, z[1] - h1), pack_bf16x2(z[2] - h2, z[3] - h3)};
+}
+
 // Same update for bf16 matrices with r % 4 == 0 and r <= FIRA_ZREADY_MAX_R: the factor's N and R stay
 // in registers until k_i is known, and the row is written once as the back-projection operand for
 // an inactive limiter, Z_i = N_i - k_i R_i, rounded from fp32 a single time.  R is written as an
@@ -167,19 +175,23 @@ __device__ __forceinline__ void adam_row_zready(const FiraMat& mt, const FiraHp&
   nn = wave_sum(nn);
   rr = wave_sum(rr);
   const float k = (hp.scaling == 2) ? 1.0f : sqrtf(nn) / (sqrtf(rr) + hp.epsf);
+  const int lo_off = (mt.rp >> 5) * (FIRA_ROWS_PER_WG * 32);   // second plane of the LDS image (hp.zsplit)
 #pragma unroll
   for (int it = 0; it < NIT; ++it) {
     const int a = lane * 4 + 256 * it;
     if (a < mt.rp) {
-      u32x2 zv = u32x2{0u, 0u};
+      u32x2 zv = u32x2{0u, 0u}, zlo = u32x2{0u, 0u};
       if (a < r) {
         const f32x4 z = nv[it] - k * rv[it];
         zv = u32x2{pack_bf16x2(z[0], z[1]), pack_bf16x2(z[2], z[3])};
+        if (hp.zsplit) zlo = split_remainder(z, zv);
         if (!gram)
           *reinterpret_cast<gptr<u32x2>>(Rb + kblk_index(mt.Lq, row, a)) =
               u32x2{pack_bf16x2(rv[it][0], rv[it][1]), pack_bf16x2(rv[it][2], rv[it][3])};
       }
-      *reinterpret_cast<u32x2*>(zl + (a >> 5) * (FIRA_ROWS_PER_WG * 32) + rowlocal * 32 + (a & 31)) = zv;
+      bf16_raw* dst = zl + (a >> 5) * (FIRA_ROWS_PER_WG * 32) + rowlocal * 32 + (a & 31);
+      *reinterpret_cast<u32x2*>(dst) = zv;
+      if (hp.zsplit) *reinterpret_cast<u32x2*>(dst + lo_off) = zlo;
     }
   }
   if (lane == 0) {
@@ -224,15 +236,18 @@ __device__ __forceinline__ void adam_rows4_small(const FiraMat& mt, const FiraHp
   }
   const float k = (hp.scaling == 2) ? 1.0f : sqrtf(nn) / (sqrtf(rr) + hp.epsf);
   if (a < mt.rp) {
-    u32x2 zv = u32x2{0u, 0u};   // rows beyond L and columns beyond r: the operand's zero padding
+    u32x2 zv = u32x2{0u, 0u}, zlo = u32x2{0u, 0u};   // rows beyond L and columns beyond r: the operand's zero padding
     if (live) {
       const f32x4 z = nv - k * rv;
       zv = u32x2{pack_bf16x2(z[0], z[1]), pack_bf16x2(z[2], z[3])};
+      if (hp.zsplit) zlo = split_remainder(z, zv);
       if (!gram)
         *reinterpret_cast<gptr<u32x2>>(as_global(mt.Rb) + kblk_index(mt.Lq, row, a)) =
             u32x2{pack_bf16x2(rv[0], rv[1]), pack_bf16x2(rv[2], rv[3])};
     }
-    *reinterpret_cast<u32x2*>(zl + (a >> 5) * (FIRA_ROWS_PER_WG * 32) + (wave * 4 + g) * 32 + (a & 31)) = zv;
+    bf16_raw* dst = zl + (a >> 5) * (FIRA_ROWS_PER_WG * 32) + (wave * 4 + g) * 32 + (a & 31);
+    *reinterpret_cast<u32x2*>(dst) = zv;
+    if (hp.zsplit) *reinterpret_cast<u32x2*>(dst + (mt.rp >> 5) * (FIRA_ROWS_PER_WG * 32)) = zlo;
   }
   if ((lane & 15) == 0 && row < mt.L) {
     as_global(mt.phi)[row] = k;
@@ -266,7 +281,7 @@ __global__ __launch_bounds__(256, 4) void fira_adam_kernel(const FiraMat* __rest
     const long long row = row_base + i;
     if (row >= mt.L) {
       if (zready)   // rows of the padding: zeros
-        for (int a = (threadIdx.x & 63) * 4; a < mt.rp; a += 256)
+        for (int a = (threadIdx.x & 63) * 4; a < (hp.zsplit ? 2 : 1) * mt.rp; a += 256)
           *reinterpret_cast<u32x2*>(zl + (a >> 5) * (FIRA_ROWS_PER_WG * 32) + (wave * 4 + i) * 32 + (a & 31)) = u32x2{0u, 0u};
       continue;
     }
@@ -285,7 +300,7 @@ __global__ __launch_bounds__(256, 4) void fira_adam_kernel(const FiraMat* __rest
     // the 16 rows of one K block are 1 KB of contiguous memory
     gptr<char> nb = reinterpret_cast<gptr<char>>(as_global(mt.Nb));
     const long long row0 = (long long)(rb - ent.row0) * FIRA_ROWS_PER_WG;
-    const int nbytes = (mt.rp >> 5) * (FIRA_ROWS_PER_WG * 64);
+    const int nbytes = (hp.zsplit ? 2 : 1) * (mt.rp >> 5) * (FIRA_ROWS_PER_WG * 64);   // K blocks [rp/32, 2 rp/32): the lo plane
     for (int o = threadIdx.x * 16; o < nbytes; o += 256 * 16) {
       const int kb = o / (FIRA_ROWS_PER_WG * 64), w = o % (FIRA_ROWS_PER_WG * 64);
       *reinterpret_cast<gptr<u32x4>>(nb + ((long long)kb * mt.Lq + row0) * 64 + w) =
@@ -415,19 +430,25 @@ __device__ __forceinline__ void makez_row(const FiraMat& mt, float f, long long 
 }
 
 // Rows that already hold Z for c = 1 (N_i - k_i R_i): add back (1 - c) k_i R_i, with R in fp32.
-__device__ __forceinline__ void fixz_row(const FiraMat& mt, float f, long long row) {
+__device__ __forceinline__ void fixz_row(const FiraMat& mt, float f, long long row, bool zsplit) {
   const int lane = threadIdx.x & 63;
   gptr<bf16_raw> Nb = as_global(mt.Nb);
   gptr<const float> R = as_global<const float>(mt.Rt) + row * mt.r;
   for (int a = lane * 4; a < mt.r; a += 256) {
-    const long long o = kblk_index(mt.Lq, row, a);
+    const long long o = kblk_index(mt.Lq, row, a), ol = kblk_index(mt.Lq, row, mt.rp + a);
     const u32x2 zv = *reinterpret_cast<gptr<const u32x2>>(Nb + o);
     const f32x4 rv = *reinterpret_cast<gptr<const f32x4>>(R + a);
-    const float z0 = __uint_as_float(zv.x << 16) + f * rv[0];
-    const float z1 = __uint_as_float(zv.x & 0xffff0000u) + f * rv[1];
-    const float z2 = __uint_as_float(zv.y << 16) + f * rv[2];
-    const float z3 = __uint_as_float(zv.y & 0xffff0000u) + f * rv[3];
-    *reinterpret_cast<gptr<u32x2>>(Nb + o) = u32x2{pack_bf16x2(z0, z1), pack_bf16x2(z2, z3)};
+    f32x4 z = f32x4{__uint_as_float(zv.x << 16), __uint_as_float(zv.x & 0xffff0000u), __uint_as_float(zv.y << 16),
+                    __uint_as_float(zv.y & 0xffff0000u)};
+    if (zsplit) {
+      const u32x2 lv = *reinterpret_cast<gptr<const u32x2>>(Nb + ol);
+      z += f32x4{__uint_as_float(lv.x << 16), __uint_as_float(lv.x & 0xffff0000u), __uint_as_float(lv.y << 16),
+                 __uint_as_float(lv.y & 0xffff0000u)};
+    }
+    z += f * rv;
+    const u32x2 hi = u32x2{pack_bf16x2(z[0], z[1]), pack_bf16x2(z[2], z[3])};
+    *reinterpret_cast<gptr<u32x2>>(Nb + o) = hi;
+    if (zsplit) *reinterpret_cast<gptr<u32x2>>(Nb + ol) = split_remainder(z, hi);
   }
 }
 
@@ -479,7 +500,7 @@ __global__ __launch_bounds__(256) void fira_makez_kernel(const FiraMat* __restri
       if (row >= mt.L) break;
       const float k = as_global<const float>(mt.phi)[row];
       if (zready && fused_here) fixz_row_from_moments(mt, hp, c, bias, row);
-      else if (zready) fixz_row(mt, (1.0f - c) * k, row);
+      else if (zready) fixz_row(mt, (1.0f - c) * k, row, hp.zsplit != 0);
       else if (mt.kx == 1) makez_row<1>(mt, c * k, row);
       else makez_row<FIRA_KX_SPLIT>(mt, c * k, row);
     }

@@ -69,6 +69,7 @@ struct GemmOperands {
   long long ldb;      // padded row count of B
   int b_row0, b_rows;
   int KB;             // stored contraction length of B (>= KA, a multiple of 64)
+  int wrapA = 0, wrapB = 0;   // ring core only: K blocks of 32 after which the operand repeats (Z in two planes meets P twice); 0 = never
 };
 
 // Fragments of one k-slice (16) of a wave's 128 (A) x 64 (B) block and its 8 MFMAs.
@@ -182,8 +183,9 @@ __device__ __forceinline__ void ring_mainloop(f32x16_t (&acc)[4][2], char* lds, 
   const char* pb = reinterpret_cast<const char*>((const bf16_raw*)g.B) + ((long long)g.b_row0 + 32 * wave) * 64;
   auto issue = [&](int s) {
     const unsigned dst = lds0 + (unsigned)((s % FIRA_RING_STAGES) * FIRA_RING_STAGE);
-    const char* ka = pa + (long long)s * g.lda * 64;
-    const char* kb = pb + (long long)s * g.ldb * 64;
+    const int sa = (g.wrapA && s >= g.wrapA) ? s - g.wrapA : s, sb = (g.wrapB && s >= g.wrapB) ? s - g.wrapB : s;
+    const char* ka = pa + (long long)sa * g.lda * 64;
+    const char* kb = pb + (long long)sb * g.ldb * 64;
 #pragma unroll
     for (int q = 0; q < 4; ++q) lds_dma16(ka + q * 1024, off, dst + (unsigned)((4 * wave + q) * 1024));
 #pragma unroll
@@ -919,7 +921,11 @@ __global__ __launch_bounds__(FIRA_BACK_THREADS, 2) void fira_backproject_kernel(
   g.a_rows = mt.n;
   g.b_row0 = tile.tb * FIRA_BB;
   g.b_rows = mt.m;
-  g.KA = g.KB = mt.kx * mt.rp;
+  // Z in two planes (hi + lo): the contraction runs over 2 rp, and the projector's K blocks are used twice
+  const bool split = MODE == 1 && hp.zsplit && mt.zready && hp.scaling != 1;
+  g.KA = g.KB = (split ? 2 : mt.kx) * mt.rp;
+  g.wrapA = (split && !mt.left) ? mt.rp / FIRA_RK : 0;
+  g.wrapB = (split && mt.left) ? mt.rp / FIRA_RK : 0;
   g.A = mt.left ? lowrank : proj;
   g.B = mt.left ? proj : lowrank;
   g.lda = mt.left ? mt.Lq : mt.Sq;

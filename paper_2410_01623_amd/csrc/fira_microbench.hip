@@ -68,6 +68,47 @@ __global__ __launch_bounds__(256) void tile_kernel(const char* __restrict__ src,
   if (MODE == 0 && (acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9e3779b9u) sink[0] = 1u;
 }
 
+// The memory traffic of the fused projection/Adam kernel without its arithmetic, at the shape that
+// dominates the headline workload (2048 x 5461 bf16 gradients, r = 512): one workgroup per tile of 128
+// factors reads the tile's gradient panel (2048 rows, one 256-byte piece per row, rows 10922 bytes apart:
+// no 16-byte access is aligned), then, in 8 chunks of 16 factors, reads and rewrites 32 KB of M and of V
+// (contiguous) and writes the chunk's Z as 16 pieces of 1 KB.  1 MB read and 640 KB written per tile.
+typedef u32x4 __attribute__((aligned(2))) u32x4_a2;
+#define FUSED_TILES_PER_MATRIX 42
+__global__ __launch_bounds__(512) void fused_stream_kernel(const char* __restrict__ G, char* __restrict__ M, char* __restrict__ V,
+                                                           char* __restrict__ Z, int ntiles, unsigned* __restrict__ sink) {
+  const int per = (ntiles + 7) / 8;
+  const int t = (int)(blockIdx.x & 7) * per + (int)(blockIdx.x >> 3);
+  if ((int)(blockIdx.x >> 3) >= per || t >= ntiles) return;
+  const long long mat = t / FUSED_TILES_PER_MATRIX, ta = t % FUSED_TILES_PER_MATRIX;
+  const long long ld = 10922, g_bytes = 2048 * ld, mv_bytes = 5461LL * 2048, z_rows = 5632, z_bytes = 16 * z_rows * 64;
+  const char* g = G + mat * g_bytes + ta * 256;
+  u32x4 acc = u32x4{0u, 0u, 0u, 0u};
+  for (int r0 = 0; r0 < 2048; r0 += 32) {
+    const int row = r0 + (threadIdx.x >> 4), piece = threadIdx.x & 15;
+    acc ^= __builtin_nontemporal_load(reinterpret_cast<const u32x4_a2*>(g + row * ld + piece * 16));
+  }
+  char* m = M + mat * mv_bytes + ta * 128 * 2048;
+  char* v = V + mat * mv_bytes + ta * 128 * 2048;
+  char* z = Z + mat * z_bytes + ta * 128 * 64;
+  for (int c = 0; c < 8; ++c) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const long long off = (long long)c * 32768 + ((long long)threadIdx.x + 512 * i) * 16;
+      u32x4* pm = reinterpret_cast<u32x4*>(m + off);
+      u32x4* pv = reinterpret_cast<u32x4*>(v + off);
+      *pm = *pm + 1u;
+      *pv = *pv + 1u;
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int p = threadIdx.x + 512 * i;            // K block p / 64, 16-byte piece p % 64 of its 1 KB
+      *reinterpret_cast<u32x4*>(z + (long long)(p >> 6) * z_rows * 64 + c * 1024 + (p & 63) * 16) = u32x4{(unsigned)p, 1u, 2u, acc.x};
+    }
+  }
+  if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9e3779b9u) sink[0] = 1u;
+}
+
 __global__ __launch_bounds__(256) void mfma_kernel(int iters, float* __restrict__ sink) {
   f32x16_t acc[4][2];
 #pragma unroll
@@ -171,6 +212,21 @@ int main() {
       std::printf("hbm, 64 KiB tiles of %5d-byte row pieces: read %.0f, write %.0f, read-modify-write %.0f, two reads + one write %.0f GB/s\n",
                   tile_bytes, mb / t0 / 1e6, mb / t1 / 1e6, 2 * mb / t2 / 1e6, 3 * mb / t3 / 1e6);
     }
+  }
+  {
+    // 160 matrices: gradients in a (3.58 GB), M in b's first half and V in its second (1.79 GB each), Z in c
+    const int nmat = 160, ntiles = nmat * FUSED_TILES_PER_MATRIX;
+    char* c = nullptr;
+    const size_t z_total = (size_t)nmat * 16 * 5632 * 64;
+    CHECK(hipMalloc(&c, z_total));
+    CHECK(hipMemset(c, 0, z_total));
+    const dim3 grid((unsigned)((ntiles + 7) / 8 * 8)), blk(512);
+    const double t = time_ms([&] { hipLaunchKernelGGL(fused_stream_kernel, grid, blk, 0, 0, (const char*)a, (char*)b, (char*)b + ((size_t)2 << 30), c, ntiles, sink); }, 3);
+    const double rd = (double)ntiles * (2048.0 * 256 + 2 * 128 * 2048), wr = (double)ntiles * (2 * 128 * 2048 + 128 * 1024);
+    std::printf("hbm, traffic of the fused projection/Adam kernel without arithmetic (%d tiles: gradient panel in 256-byte pieces, M and V read "
+                "and rewritten in 32 KB pieces, Z written in 1 KB pieces): %.0f GB/s (%.2f GB read + %.2f GB written in %.3f ms)\n",
+                ntiles, (rd + wr) / t / 1e6, rd / 1e9, wr / 1e9, t);
+    CHECK(hipFree(c));
   }
   for (int waves_per_simd : {1, 2}) {
     const int iters = 4000;

@@ -87,7 +87,7 @@ bool make_plan(const fira_matrix_desc* d, int count, Plan* plan, fira_status* st
     m.kx = (m.dtype == FIRA_F32) ? FIRA_KX_SPLIT : 1;
     m.Lq = round_up_int(m.L, 256); m.Sq = round_up_int(m.S, 256); m.rq = round_up_int(m.r, 256);
     m.zready = (m.kx == 1 && (m.r & 3) == 0 && m.r <= FIRA_ZREADY_MAX_R) ? 1 : 0;
-    if (m.zready) plan->adam_lds = std::max(plan->adam_lds, FIRA_ROWS_PER_WG * m.rp * 2);
+    if (m.zready) plan->adam_lds = std::max(plan->adam_lds, FIRA_ROWS_PER_WG * m.rp * 2);   // (twice that with Z in two planes)
     m.gx_ld = m.left ? round_up_int(m.n, 8) : operand_pitch((long long)m.kx * m.Sp);
     const size_t Lr = (size_t)m.L * m.r;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
@@ -97,7 +97,7 @@ bool make_plan(const fira_matrix_desc* d, int count, Plan* plan, fira_status* st
     m.phi = (float*)take((size_t)m.L * 4);
     m.g2 = (float*)take((size_t)m.L * 4);
     m.q = (float*)take((size_t)m.L * 4);
-    m.Nb = (bf16_raw*)take((size_t)m.Lq * m.kx * m.rp * 2);
+    m.Nb = (bf16_raw*)take((size_t)m.Lq * (m.kx == 1 ? 2 : m.kx) * m.rp * 2);   // bf16 matrices: room for the hi + lo form of Z
     m.Rb = (bf16_raw*)take((size_t)m.Lq * m.kx * m.rp * 2);
     m.Pn = (bf16_raw*)take((size_t)m.Sq * m.kx * m.rp * 2);
     m.PT = (bf16_raw*)take((size_t)m.rq * m.kx * m.Sp * 2);

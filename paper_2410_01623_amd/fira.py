@@ -32,7 +32,7 @@ FIRA_STATIC_SCRATCH_BYTES = 64 << 20
 
 EXPORTS = (
     "fira_method_state_numel", "fira_state_bytes", "fira_init_state", "fira_set_projector", "fira_step",
-    "fira_set_hparams", "fira_set_options", "fira_set_variant", "fira_set_fusion", "fira_last_step_fused",
+    "fira_set_hparams", "fira_set_options", "fira_set_variant", "fira_set_fusion", "fira_last_step_fused", "fira_set_z_planes",
     "fira_get_state", "fira_set_state", "fira_get_diag", "fira_get_gate", "fira_set_gate",
     "fira_get_factors", "fira_get_lowrank", "fira_get_projector", "fira_refresh_workspace_bytes",
     "fira_refresh_projectors", "fira_refresh_projectors_static", "fira_profile_begin", "fira_profile_end", "fira_kernel_name",
@@ -90,6 +90,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.fira_set_variant.argtypes = [vp, ci]
     lib.fira_set_fusion.restype = ci
     lib.fira_set_fusion.argtypes = [vp, ci]
+    lib.fira_set_z_planes.restype = ci
+    lib.fira_set_z_planes.argtypes = [vp, ci]
     lib.fira_last_step_fused.restype = ci
     lib.fira_last_step_fused.argtypes = [vp]
     lib.fira_get_state.restype = ci
@@ -231,6 +233,9 @@ class FiraContext:
 
     def fira_set_fusion(self, enable: bool):
         _check(self.lib, self.ctx, self.lib.fira_set_fusion(self.ctx, 1 if enable else 0))
+
+    def fira_set_z_planes(self, planes: int):
+        _check(self.lib, self.ctx, self.lib.fira_set_z_planes(self.ctx, planes))
 
     def fira_last_step_fused(self) -> bool:
         return bool(self.lib.fira_last_step_fused(self.ctx))

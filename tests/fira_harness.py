@@ -53,6 +53,9 @@ class CaseResult:
     w_err_by_step: Dict[int, float] = dataclasses.field(default_factory=dict)   # worst W error after step s+1
     fused_steps: int = 0          # steps that took the fused projection/Adam kernel
     routes: List[Tuple[int, int, int]] = dataclasses.field(default_factory=list)   # (step, matrix, route: 0 residual, 1 Gram, 2 Gram fused)
+    # per checked matrix, after the last step: error against an oracle run that never rounds W to the storage
+    # type (its W stays fp64 throughout); only filled with track_unrounded
+    w_err_unrounded: List[float] = dataclasses.field(default_factory=list)
 
 
 def run_case(shapes: Sequence[Tuple[int, int]], rank, dtype: int, steps: int,
@@ -61,7 +64,7 @@ def run_case(shapes: Sequence[Tuple[int, int]], rank, dtype: int, steps: int,
              check: Optional[Sequence[int]] = None, lds: Optional[Sequence[int]] = None,
              stages: bool = True, scaling: str = "column", step_lists: Optional[List[List[int]]] = None,
              alias: Optional[Dict[int, int]] = None, norm_mode: int = fira.FIRA_NORM_RESIDUAL,
-             variant: str = "full", fusion: bool = True) -> CaseResult:
+             variant: str = "full", fusion: bool = True, z_planes: int = 1, track_unrounded: bool = False) -> CaseResult:
     """gen_P(mat, step) returns a projector (float64/float32 values already representable in the
     storage type) when the projector of `mat` is (re)installed before `step`, else None.
     `check`: matrices compared against the oracle (default all).  `alias[i] = j`: matrix i is fed
@@ -84,6 +87,8 @@ def run_case(shapes: Sequence[Tuple[int, int]], rank, dtype: int, steps: int,
                          norm_mode=norm_mode)
     if not fusion:
         ctx.fira_set_fusion(False)
+    if z_planes != 1:
+        ctx.fira_set_z_planes(z_planes)
     fused_steps = 0
     if variant != "full":
         ctx.fira_set_variant({"only_scaling": fira.FIRA_VARIANT_ONLY_SCALING}[variant])
@@ -92,6 +97,9 @@ def run_case(shapes: Sequence[Tuple[int, int]], rank, dtype: int, steps: int,
     W_dev = [to_device(W_host[src(i)], dtype, None if lds is None else lds[i]) for i in range(nmat)]
     W_ref = {i: W_host[src(i)].astype(np.float64) for i in check}
     states = {i: orc.OracleState.zeros(shapes[i][0], shapes[i][1], ranks[i]) for i in check}
+    # second oracle run whose W is never rounded (the bf16 storage of W is a reading of the paper, not part of it)
+    W_unr = {i: W_host[src(i)].astype(np.float64) for i in check} if track_unrounded else {}
+    states_unr = {i: orc.OracleState.zeros(shapes[i][0], shapes[i][1], ranks[i]) for i in check} if track_unrounded else {}
     P_cur: Dict[int, np.ndarray] = {}
     worst = dict(R=0.0, k=0.0, s_pre=0.0, c=0.0, W=0.0, M=0.0, V=0.0)
     c_min = 1.0
@@ -120,6 +128,9 @@ def run_case(shapes: Sequence[Tuple[int, int]], rank, dtype: int, steps: int,
                                 scaling=scaling, store_bf16=bf, variant=variant)
             W_ref[i] = out["W"]
             c_min = min(c_min, out["c"])
+            if track_unrounded:
+                W_unr[i] = orc.fira_step(W_unr[i], G_host[src(i)].astype(np.float64), P_cur[i], states_unr[i], hp,
+                                         scaling=scaling, store_bf16=False, variant=variant)["W"]
             if stages:
                 _, _, route = ctx.fira_get_gate(i)
                 routes.append((s, i, route))
@@ -155,7 +166,8 @@ def run_case(shapes: Sequence[Tuple[int, int]], rank, dtype: int, steps: int,
     for (s, i, e, d) in diag:
         by_step[s + 1] = max(by_step.get(s + 1, 0.0), e["W"])
     by_step[steps] = max([by_step.get(steps, 0.0)] + w_err)
-    return CaseResult(w_err, worst, c_min, ctx, W_dev, W_ref, states, diag, by_step, fused_steps, routes)
+    w_unr = [rel_max(to_host(W_dev[i]), W_unr[i]) for i in check] if track_unrounded else []
+    return CaseResult(w_err, worst, c_min, ctx, W_dev, W_ref, states, diag, by_step, fused_steps, routes, w_unr)
 
 
 def workload_generators(wl: synth.Workload, proj: str = "svd"):
