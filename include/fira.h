@@ -118,6 +118,19 @@ FIRA_API fira_status fira_init_state(fira_ctx** out, const fira_matrix_desc* d, 
  * to bf16 (nearest even).  M, V, t and ||S_prev|| are kept (Sec. 4.2, loss-spike analysis). */
 FIRA_API fira_status fira_set_projector(fira_ctx* ctx, int idx, const void* dev_P, fira_dtype p_dtype);
 
+/* fira_set_projector for `count` distinct matrices idx[0..count) at once (Eq. 7: a training loop
+ * installs every matrix's projector at the same step, every T steps): dev_P[i] is the projector of
+ * matrix idx[i], all of dtype p_dtype; idx and dev_P are host arrays of length count.  The same
+ * copies, the same estimate behind the Gram route's first gate and the same result as `count` single
+ * calls, bit for bit, in one launch per phase for every 16 matrices and one read-back of the gate values
+ * instead of four launches and a copy per matrix.  A call may wait on the host for the previous call's
+ * table of pointers to have reached the device.  Errors found on the host (a bad index, a matrix
+ * listed twice, a null pointer, an unknown dtype) leave every projector as it was; a launch failure
+ * (FIRA_ERR_HIP) leaves the listed matrices without a projector (fira_step then reports
+ * FIRA_ERR_NO_PROJECTOR for them). */
+FIRA_API fira_status fira_set_projectors(fira_ctx* ctx, int count, const int* idx, const void* const* dev_P,
+                                         fira_dtype p_dtype);
+
 /* One optimizer step (Algorithm 1's loop body below the SVD branch) for `count` distinct
  * matrices idx[0..count), in one grouped launch sequence.  dev_W[i] is updated in place, dev_G[i]
  * is read only; both are m x n with the descriptor's ld and dtype.  t advances by one for each

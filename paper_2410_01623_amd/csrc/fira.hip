@@ -102,6 +102,11 @@ struct fira_ctx {
   Gate* h_gate = nullptr;
   hipEvent_t ortho_event = nullptr;
   bool ortho_pending = false;
+  // fira_set_projectors: host image (pinned) of the table of installations of one call, and the event after
+  // its upload (the next call waits for it before it rewrites the image)
+  FiraRefreshEnt* h_install = nullptr;
+  hipEvent_t install_event = nullptr;
+  bool install_pending = false;
   uint64_t use_counter = 0;
   int device = -1;               // HIP device that was current at fira_init_state
   void* static_scratch = nullptr;   // that device's copy of the library's static scratch array
@@ -241,7 +246,9 @@ fira_status fira_init_state(fira_ctx** out, const fira_matrix_desc* d, int count
     for (ListSlot& s : ctx->slots) if (s.uploaded) (void)hipEventDestroy(s.uploaded);
     if (ctx->h_stage_all) (void)hipHostFree(ctx->h_stage_all);
     if (ctx->h_gate) (void)hipHostFree(ctx->h_gate);
+    if (ctx->h_install) (void)hipHostFree(ctx->h_install);
     if (ctx->ortho_event) (void)hipEventDestroy(ctx->ortho_event);
+    if (ctx->install_event) (void)hipEventDestroy(ctx->install_event);
     delete ctx;
   };
 #define FIRA_INIT_HIP(call)                                                                          \
@@ -268,6 +275,8 @@ fira_status fira_init_state(fira_ctx** out, const fira_matrix_desc* d, int count
   FIRA_INIT_HIP(hipHostMalloc((void**)&ctx->h_gate, sizeof(fira_ctx::Gate) * count, hipHostMallocDefault));
   for (int i = 0; i < count; ++i) ctx->h_gate[i] = fira_ctx::Gate{INFINITY, INFINITY};
   FIRA_INIT_HIP(hipEventCreateWithFlags(&ctx->ortho_event, hipEventDisableTiming));
+  FIRA_INIT_HIP(hipHostMalloc((void**)&ctx->h_install, sizeof(FiraRefreshEnt) * count, hipHostMallocDefault));
+  FIRA_INIT_HIP(hipEventCreateWithFlags(&ctx->install_event, hipEventDisableTiming));
   for (int i = 0; i < kSlots; ++i) {
     ListSlot& s = ctx->slots[i];
     s.h_stage = ctx->h_stage_all + p.slot_bytes * i;
@@ -354,6 +363,71 @@ fira_status fira_set_projector(fira_ctx* ctx, int idx, const void* dev_P, fira_d
   ctx->ortho_pending = true;
   h.has_projector = true;
   return FIRA_OK;
+}
+
+fira_status fira_set_projectors(fira_ctx* ctx, int count, const int* idx, const void* const* dev_P, fira_dtype p_dtype) {
+  if (!ctx) return fail(nullptr, FIRA_ERR_INVALID_ARG, "ctx is null");
+  if (count == 0) return FIRA_OK;
+  const int nmat = (int)ctx->plan.mats.size();
+  if (count < 0 || count > nmat || !idx || !dev_P) return fail(ctx, FIRA_ERR_INVALID_ARG, "bad count or null array");
+  if (p_dtype != FIRA_F32 && p_dtype != FIRA_BF16) return fail(ctx, FIRA_ERR_DTYPE, "p_dtype must be FIRA_F32 or FIRA_BF16");
+  {
+    std::vector<char> seen(nmat, 0);
+    for (int e = 0; e < count; ++e) {
+      if (idx[e] < 0 || idx[e] >= nmat) return fail(ctx, FIRA_ERR_INVALID_ARG, "matrix index out of range");
+      if (seen[idx[e]]) return fail(ctx, FIRA_ERR_INVALID_ARG, "a matrix is listed twice");
+      seen[idx[e]] = 1;
+      if (!dev_P[e]) return fail(ctx, FIRA_ERR_INVALID_ARG, "null P pointer");
+    }
+  }
+  hipStream_t q = ctx->stream;
+  if (ctx->install_pending) {   // the previous call's table may still be on its way to the device
+    FIRA_HIP(ctx, hipEventSynchronize(ctx->install_event));
+    ctx->install_pending = false;
+  }
+  char* scratch = ctx->slab + ctx->plan.off_ortho;
+  for (int e = 0; e < count; ++e) {
+    const FiraMat& m = ctx->plan.mats[idx[e]].dev;
+    FiraRefreshEnt& re = ctx->h_install[e];
+    std::memset(&re, 0, sizeof(re));
+    re.S = m.S; re.L = m.L; re.r = m.r; re.left = m.left; re.rq = m.rq; re.mat = idx[e];
+    re.q_dtype = p_dtype == FIRA_BF16 ? 1 : 0;
+    re.Q = reinterpret_cast<float*>(const_cast<void*>(dev_P[e]));   // read only, as q_dtype says
+    re.inst = reinterpret_cast<float*>(scratch + ctx->plan.ortho_slot * (size_t)(e % kInstallBatch));
+  }
+  FiraRefreshEnt* d_table = reinterpret_cast<FiraRefreshEnt*>(ctx->slab + ctx->plan.off_install);
+  FIRA_HIP(ctx, hipMemcpyAsync(d_table, ctx->h_install, sizeof(FiraRefreshEnt) * count, hipMemcpyHostToDevice, q));
+  FIRA_HIP(ctx, hipEventRecord(ctx->install_event, q));
+  ctx->install_pending = true;
+  // one launch per phase for kInstallBatch matrices at a time (they share the scratch pieces, in stream order)
+  for (int e0 = 0; e0 < count; e0 += kInstallBatch) {
+    const int nb = std::min(kInstallBatch, count - e0);
+    int max_S = 0, max_r = 0;
+    for (int e = e0; e < e0 + nb; ++e) {
+      max_S = std::max(max_S, ctx->h_install[e].S);
+      max_r = std::max(max_r, ctx->h_install[e].r);
+    }
+    const int prep_blocks = (int)std::min<long long>(((long long)max_S * max_r + 255) / 256, 4096);
+    hipLaunchKernelGGL(fira_refresh_prep_kernel, dim3(prep_blocks, nb), dim3(256), 0, q, ctx->d_mats, d_table + e0);
+    hipLaunchKernelGGL(fira_refresh_ortho_y_kernel, dim3((max_S + 3) / 4, nb), dim3(256), 0, q, ctx->d_mats, d_table + e0);
+    hipLaunchKernelGGL(fira_refresh_ortho_z_kernel, dim3(FIRA_ORTHO_SPLITS, nb), dim3(256), 0, q, ctx->d_mats, d_table + e0);
+    hipLaunchKernelGGL(fira_refresh_ortho_final_kernel, dim3(nb), dim3(256), 0, q, ctx->d_mats, d_table + e0, ctx->d_scal);
+  }
+  {
+    const hipError_t e_ = hipGetLastError();
+    if (e_ != hipSuccess) {   // some of the listed matrices' operand copies may be half written
+      for (int e = 0; e < count; ++e) {
+        ctx->plan.mats[idx[e]].has_projector = false;
+        ctx->h_gate[idx[e]] = fira_ctx::Gate{INFINITY, INFINITY};
+      }
+      return fail(ctx, FIRA_ERR_HIP, std::string("projector installation: ") + hipGetErrorString(e_));
+    }
+  }
+  for (int e = 0; e < count; ++e) {
+    ctx->h_gate[idx[e]] = fira_ctx::Gate{INFINITY, INFINITY};
+    ctx->plan.mats[idx[e]].has_projector = true;
+  }
+  return read_back_gates(ctx);
 }
 
 fira_status fira_step(fira_ctx* ctx, int count, const int* idx, void* const* dev_W, const void* const* dev_G) {
@@ -913,7 +987,9 @@ void fira_destroy(fira_ctx* ctx) {
     if (s.uploaded) (void)hipEventDestroy(s.uploaded);
   if (ctx->h_stage_all) (void)hipHostFree(ctx->h_stage_all);
   if (ctx->h_gate) (void)hipHostFree(ctx->h_gate);
+  if (ctx->h_install) (void)hipHostFree(ctx->h_install);
   if (ctx->ortho_event) (void)hipEventDestroy(ctx->ortho_event);
+  if (ctx->install_event) (void)hipEventDestroy(ctx->install_event);
   delete ctx;
 }
 

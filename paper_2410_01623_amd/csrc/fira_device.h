@@ -153,7 +153,8 @@ struct FiraRefreshEnt {
   int S, L, r, left;   // short side, long side, rank, orientation of the real matrix
   int Lp;              // L rounded up to 64: contraction length of the packed operand
   int rq;              // r rounded up to 256: rows of the packed operand
-  int mat, pad0;
+  int mat;
+  int q_dtype;         // element type of Q when it is installed as the projector (0 fp32, 1 bf16: a caller's array)
   const float* T;      // [L][r]            the matrix's Rt
   bf16_raw* Top;       // [Lp/32][rq][32]   T transposed, K-blocked along the long side
   float* Y;            // [S][r]

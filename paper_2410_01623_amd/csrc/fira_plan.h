@@ -16,6 +16,7 @@
 namespace {
 
 constexpr size_t kAlign = 256;
+constexpr int kInstallBatch = 16;   // matrices per launch of a batched projector installation
 constexpr int kSlots = 4;  // cached work lists (a training loop alternates between very few)
 
 inline size_t align_up(size_t x, size_t a = kAlign) { return (x + a - 1) / a * a; }
@@ -51,6 +52,7 @@ enum { kTilesProjectLeft = 0, kTilesProjectRight = 1, kTilesBackBf16 = 2, kTiles
 struct Plan {
   size_t total = 0;
   size_t off_mats = 0, off_scal = 0, off_partial = 0, off_ortho = 0, ortho_z = 0;
+  size_t ortho_slot = 0, off_install = 0;   // batched installation: kInstallBatch scratch pieces of ortho_slot bytes, table of FiraRefreshEnt
   size_t off_slots = 0, slot_bytes = 0, slot_off_tiles[kNumTileLists] = {};
   std::vector<HostMat> mats;
   int max_tiles[kNumTileLists] = {};
@@ -132,7 +134,12 @@ bool make_plan(const fira_matrix_desc* d, int count, Plan* plan, fira_status* st
   for (const HostMat& h : plan->mats) max_r = std::max<long long>(max_r, h.dev.r);
   plan->off_ortho = off;   // scratch of the orthonormality estimate: S x 4 floats, then splits x r x 4 floats
   plan->ortho_z = align_up((size_t)max_S * 16);
-  off = align_up(off + plan->ortho_z + (size_t)FIRA_ORTHO_SPLITS * max_r * 16);
+  // fira_set_projectors estimates up to kInstallBatch matrices per launch, each in a piece of its own ([S][4]
+  // directly followed by [splits][r][4]); fira_set_projector uses the first piece
+  plan->ortho_slot = align_up(plan->ortho_z + (size_t)FIRA_ORTHO_SPLITS * max_r * 16);
+  off = align_up(off + plan->ortho_slot * (size_t)std::min(count, kInstallBatch));
+  plan->off_install = off;
+  off = align_up(off + sizeof(FiraRefreshEnt) * (size_t)count);
   size_t s = 0;
   s = align_up(s + sizeof(FiraEnt) * count);
   for (int l = 0; l < kNumTileLists; ++l) {

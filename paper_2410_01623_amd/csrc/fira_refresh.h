@@ -375,7 +375,8 @@ __global__ __launch_bounds__(256) void fira_refresh_solve_kernel(const FiraRefre
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void fira_refresh_prep_kernel(const FiraMat* __restrict__ mats, const FiraRefreshEnt* __restrict__ ents) {
   const FiraRefreshEnt e = ents[blockIdx.y];
-  prep_projector_body<float>(mats[e.mat], e.Q);
+  if (e.q_dtype == 1) prep_projector_body<bf16_raw>(mats[e.mat], reinterpret_cast<const bf16_raw*>(e.Q));
+  else prep_projector_body<float>(mats[e.mat], e.Q);
 }
 __global__ __launch_bounds__(256) void fira_refresh_ortho_y_kernel(const FiraMat* __restrict__ mats, const FiraRefreshEnt* __restrict__ ents) {
   const FiraRefreshEnt e = ents[blockIdx.y];

@@ -31,7 +31,7 @@ FIRA_NUM_KERNELS = 6
 FIRA_STATIC_SCRATCH_BYTES = 64 << 20
 
 EXPORTS = (
-    "fira_method_state_numel", "fira_state_bytes", "fira_init_state", "fira_set_projector", "fira_step",
+    "fira_method_state_numel", "fira_state_bytes", "fira_init_state", "fira_set_projector", "fira_set_projectors", "fira_step",
     "fira_set_hparams", "fira_set_options", "fira_set_variant", "fira_set_fusion", "fira_last_step_fused", "fira_set_z_planes",
     "fira_get_state", "fira_set_state", "fira_get_diag", "fira_get_gate", "fira_set_gate",
     "fira_get_factors", "fira_get_lowrank", "fira_get_projector", "fira_refresh_workspace_bytes",
@@ -80,6 +80,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
                                     ctypes.POINTER(fira_hparams), vp, ctypes.c_size_t, vp]
     lib.fira_set_projector.restype = ci
     lib.fira_set_projector.argtypes = [vp, ci, vp, ci]
+    lib.fira_set_projectors.restype = ci
+    lib.fira_set_projectors.argtypes = [vp, ci, ctypes.POINTER(ci), ctypes.POINTER(vp), ci]
     lib.fira_step.restype = ci
     lib.fira_step.argtypes = [vp, ci, ctypes.POINTER(ci), ctypes.POINTER(vp), ctypes.POINTER(vp)]
     lib.fira_set_hparams.restype = ci
@@ -205,6 +207,22 @@ class FiraContext:
         m, n = self.shapes[idx]
         assert tuple(P.shape) == (min(m, n), self.descs[idx].r), "P must be min(m,n) x r"
         _check(self.lib, self.ctx, self.lib.fira_set_projector(self.ctx, idx, ctypes.c_void_p(P.data_ptr()), dt))
+
+    def fira_set_projectors(self, idx, Ps):
+        """Projectors of several matrices in one call (all of one dtype)."""
+        idx = list(idx)
+        assert len(idx) == len(Ps)
+        dts = {P.dtype for P in Ps}
+        assert len(dts) <= 1, "one dtype per call"
+        dt = {torch.float32: FIRA_F32, torch.bfloat16: FIRA_BF16}[Ps[0].dtype] if Ps else FIRA_F32
+        for i, P in zip(idx, Ps):
+            assert P.is_contiguous() and P.device == self.slab.device
+            if 0 <= i < len(self.descs):   # the library reports bad indices
+                m, n = self.shapes[i]
+                assert tuple(P.shape) == (min(m, n), self.descs[i].r), "P must be min(m,n) x r"
+        c_idx = (ctypes.c_int * len(idx))(*idx)
+        c_P = (ctypes.c_void_p * len(idx))(*[P.data_ptr() for P in Ps])
+        _check(self.lib, self.ctx, self.lib.fira_set_projectors(self.ctx, len(idx), c_idx, c_P, dt))
 
     def prepare(self, idx, Ws, Gs) -> PreparedList:
         for i, w, g in zip(idx, Ws, Gs):

@@ -81,6 +81,7 @@ def test_host_side_argument_errors(lib):
     # null context
     assert lib.fira_step(None, 0, None, None, None) == fira.FIRA_ERR_INVALID_ARG
     assert lib.fira_set_projector(None, 0, None, 0) == fira.FIRA_ERR_INVALID_ARG
+    assert lib.fira_set_projectors(None, 0, None, None, 0) == fira.FIRA_ERR_INVALID_ARG
     assert lib.fira_set_hparams(None, ctypes.byref(hp)) == fira.FIRA_ERR_INVALID_ARG
     assert lib.fira_get_diag(None, 0, None, None, None) == fira.FIRA_ERR_INVALID_ARG
     lib.fira_destroy(None)   # no-op
