@@ -233,7 +233,11 @@ FIRA_API fira_status fira_get_projector(fira_ctx* ctx, int idx, float* host_P);
  * as fira_set_projector would (M, V, t and the remembered norm are kept).  The basis comes from
  * `iters` >= 1 rounds of subspace iteration, Q <- orth(G G^T Q) (or G^T G for m > n), from a random
  * start that is a function of (seed, matrix index) only; it is a rotation of the singular vectors
- * inside that subspace, not the vectors themselves.  bf16 matrices only (FIRA_ERR_DTYPE otherwise).
+ * inside that subspace, not the vectors themselves.  For fp32 matrices the product G^T Q runs on the
+ * split planes of G as in a step, the product back on a bf16 rounding of G (kept in the workspace),
+ * and the orthonormalisation in fp64 as for every matrix: the installed basis is orthonormal to fp32
+ * accuracy, the subspace it spans is found with about 8 bits per product, which a few rounds of
+ * subspace iteration do not resolve anyway.
  *   dev_G[e]       gradient of matrix idx[e], same layout as in fira_step; read only
  *   dev_workspace  device scratch of fira_refresh_workspace_bytes(ctx, count, idx) bytes, 256-byte
  *                  aligned, owned by the caller, free to reuse once the stream has passed this call

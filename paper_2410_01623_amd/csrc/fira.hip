@@ -796,7 +796,6 @@ fira_status refresh_check(fira_ctx* ctx, int count, const int* idx, const void* 
       if (seen[idx[e]]) return fail(ctx, FIRA_ERR_INVALID_ARG, "a matrix is listed twice");
       seen[idx[e]] = 1;
       if (!dev_G[e]) return fail(ctx, FIRA_ERR_INVALID_ARG, "null G pointer");
-      if (ctx->plan.mats[idx[e]].dev.kx != 1) return fail(ctx, FIRA_ERR_DTYPE, "the device refresh handles bf16 matrices only");
     }
   }
   if (!make_refresh_plan(ctx->plan, count, idx, rp)) return fail(ctx, FIRA_ERR_INVALID_ARG, "bad list");
@@ -866,13 +865,16 @@ fira_status refresh_run(fira_ctx* ctx, int count, const int* idx, const void* co
     // of the same gradient: long side L' = S, contraction over S' = L, operand "PT" = Top, output "Rt" = Y.
     FiraMat& v = vmats[e];
     std::memset(&v, 0, sizeof(v));
-    v.m = m.m; v.n = m.n; v.r = m.r; v.left = !m.left; v.ld = m.ld;
-    v.L = m.S; v.S = m.L; v.rp = m.rp; v.Sp = re.Lp; v.kx = 1; v.dtype = m.dtype;
+    // fp32 matrices: the way back reads a bf16 rounding of the gradient made below (the way there runs on the
+    // matrix's own split planes, as in a step)
+    const bool f32 = m.kx != 1;
+    v.m = m.m; v.n = m.n; v.r = m.r; v.left = !m.left; v.ld = f32 ? refresh_gb_ld(m.n) : m.ld;
+    v.L = m.S; v.S = m.L; v.rp = m.rp; v.Sp = re.Lp; v.kx = 1; v.dtype = FIRA_BF16;
     v.Lq = round_up_int(m.S, 256); v.Sq = round_up_int(m.L, 256); v.rq = m.rq;
     v.PT = re.Top; v.Rt = re.Y;
     FiraEnt& ve = vents[e];
     std::memset(&ve, 0, sizeof(ve));
-    ve.mat = e; ve.W = nullptr; ve.G = dev_G[e];
+    ve.mat = e; ve.W = nullptr; ve.G = f32 ? (const void*)(ws + rp.off_gb[e]) : dev_G[e];
     const int ta_n = (m.S + FIRA_PA - 1) / FIRA_PA, tb_n = (m.r + FIRA_PB - 1) / FIRA_PB;
     for (int ta = 0; ta < ta_n; ++ta)
       for (int tb = 0; tb < tb_n; ++tb) vtiles[m.left ? 0 : 1].push_back(FiraTile{e, ta, tb, 0});
@@ -890,6 +892,16 @@ fira_status refresh_run(fira_ctx* ctx, int count, const int* idx, const void* co
     const size_t n16 = (rp.top_end - rp.top_begin) / 16;
     const unsigned grid = (unsigned)std::min<size_t>((n16 + 255) / 256, 8192);
     if (n16) hipLaunchKernelGGL(fira_zero_fill_kernel, dim3(grid), dim3(256), 0, q, reinterpret_cast<u32x4*>(ws + rp.top_begin), n16);
+  }
+
+  for (int e = 0; e < count; ++e) {   // fp32 matrices: split planes for the way there, a bf16 rounding for the way back
+    const FiraMat& m = ctx->plan.mats[idx[e]].dev;
+    if (m.kx == 1) continue;
+    const long long total = (long long)m.m * m.n;
+    const int grid = (int)std::min<long long>((total + 255) / 256, 65535);
+    hipLaunchKernelGGL(fira_split_gradient_kernel, dim3(grid), dim3(256), 0, q, m, (const float*)dev_G[e]);
+    hipLaunchKernelGGL(fira_round_gradient_kernel, dim3(grid), dim3(256), 0, q, (const float*)dev_G[e],
+                       (bf16_raw*)(ws + rp.off_gb[e]), m.m, m.n, (long long)m.ld, (long long)refresh_gb_ld(m.n));
   }
 
   const FiraRefreshEnt* d_ents = (const FiraRefreshEnt*)(ws + rp.off_ents);

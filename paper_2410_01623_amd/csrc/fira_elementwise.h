@@ -628,6 +628,19 @@ __global__ void fira_split_gradient_kernel(FiraMat mt, const float* __restrict__
   }
 }
 
+// fp32 gradient -> its bf16 rounding (nearest even), rows of ldb elements (the projector refresh's way back).
+__global__ void fira_round_gradient_kernel(const float* __restrict__ G, bf16_raw* __restrict__ Gb, int m, int n,
+                                           long long ld, long long ldb) {
+  const long long total = (long long)m * n;
+  gptr<bf16_raw> out = as_global(Gb);
+  for (long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
+       idx += (long long)gridDim.x * blockDim.x) {
+    const long long i = idx / n;
+    const long long j = idx - i * n;
+    out[i * ldb + j] = f32_to_bf16(G[i * ld + j]);
+  }
+}
+
 // ------------------------------------------------------------------------------------------------
 // Gram route to ||S||: g2[i] = sum over the short axis of G(s, i)^2 for every long index i.
 //   left  (m <= n): column sums of squares; one workgroup per 256 columns walks all m rows with

@@ -195,8 +195,12 @@ struct RefreshPlan {
   size_t off_ents = 0, off_ents2 = 0, off_vmats = 0, off_vents = 0, off_vtiles[2] = {0, 0};
   int ntiles[2] = {0, 0};                 // virtual launches: [0] K-contiguous (real left), [1] K-slow (real right)
   std::vector<size_t> off_top, off_y, off_q, off_c, off_linv;
+  std::vector<size_t> off_gb;             // fp32 matrices: bf16 rounding of the gradient, rows of gb_ld elements (else unused)
   size_t top_begin = 0, top_end = 0;
 };
+
+// Row pitch (elements) of the bf16 rounding of an fp32 gradient that the refresh's way back reads.
+inline int refresh_gb_ld(int n) { return round_up_int(n, 8); }
 
 bool make_refresh_plan(const Plan& plan, int count, const int* idx, RefreshPlan* rp) {
   const int nmat = (int)plan.mats.size();
@@ -215,6 +219,7 @@ bool make_refresh_plan(const Plan& plan, int count, const int* idx, RefreshPlan*
   }
   rp->off_vtiles[0] = take(sizeof(FiraTile) * std::max(rp->ntiles[0], 1));
   rp->off_vtiles[1] = take(sizeof(FiraTile) * std::max(rp->ntiles[1], 1));
+  rp->off_gb.assign(count, 0);
   rp->off_top.resize(count); rp->off_y.resize(count); rp->off_q.resize(count); rp->off_c.resize(count); rp->off_linv.resize(count);
   rp->top_begin = off;
   for (int e = 0; e < count; ++e) {
@@ -230,6 +235,7 @@ bool make_refresh_plan(const Plan& plan, int count, const int* idx, RefreshPlan*
     // scratch of the gate estimate, which before that holds the inverses of the solve's diagonal blocks
     rp->off_linv[e] = take(std::max((size_t)m.S * 16 + (size_t)FIRA_ORTHO_SPLITS * m.r * 16,
                                     (size_t)((m.r + FIRA_SOLVE_JB - 1) / FIRA_SOLVE_JB) * FIRA_SOLVE_JB * FIRA_SOLVE_JB * 8));
+    if (m.kx != 1) rp->off_gb[e] = take((size_t)m.m * refresh_gb_ld(m.n) * 2);
   }
   rp->total = off;
   return true;

@@ -137,11 +137,51 @@ def test_refresh_argument_errors():
     with pytest.raises(fira.FiraError) as ei:
         ctx.fira_refresh_projectors([0], [g0], iters=0)
     assert ei.value.status == fira.FIRA_ERR_INVALID_ARG
-    f32 = fira.FiraContext([(64, 96)], 8, fira.FIRA_F32, device=H.DEV)
-    gf = torch.zeros((64, 96), dtype=torch.float32, device=H.DEV)
     with pytest.raises(fira.FiraError) as ei:
-        f32.fira_refresh_projectors([0], [gf], iters=1)
-    assert ei.value.status == fira.FIRA_ERR_DTYPE
+        ctx.fira_refresh_projectors([0, 0], [g0, g0], iters=1)
+    assert ei.value.status == fira.FIRA_ERR_INVALID_ARG
+
+
+@pytest.mark.parametrize("m,n,r", [(256, 688, 64), (688, 256, 64), (100, 333, 24)], ids=["256x688r64", "688x256r64", "100x333r24"])
+def test_refresh_of_fp32_matrices(m, n, r):
+    """fp32 matrices: the way there runs on the split planes of G (as a step does), the way back on a bf16
+    rounding of G, the orthonormalisation in fp64; the installed projector is orthonormal to fp32 accuracy,
+    spans the leading subspace, and is the one the following steps use (10 steps against the oracle, to the
+    fp32 gate).  A list that mixes an fp32 and a bf16 matrix goes through one call."""
+    rng = np.random.default_rng(2000 + m + n)
+    S = min(m, n)
+    U, _ = np.linalg.qr(rng.standard_normal((m, S)))
+    V, _ = np.linalg.qr(rng.standard_normal((n, S)))
+    sv = np.concatenate([np.linspace(2.0, 1.0, r), 0.05 * np.linspace(1.0, 0.2, S - r)])
+    G = (1e-2 * (U * sv) @ V.T).astype(np.float32)
+    Gb = synth.as_bf16_values(G)
+    ctx = fira.FiraContext([(m, n), (m, n)], r, [fira.FIRA_F32, fira.FIRA_BF16], device=H.DEV)
+    Gd, Gbd = H.to_device(G, fira.FIRA_F32), H.to_device(Gb, fira.FIRA_BF16)
+    ws = ctx.fira_refresh_projectors([1, 0], [Gbd, Gd], iters=3, seed=11)
+    torch.cuda.synchronize()
+    P = ctx.fira_get_projector(0).numpy().astype(np.float64)
+    assert P.shape == (S, r) and np.all(np.isfinite(P))
+    assert np.max(np.abs(P.T @ P - np.eye(r))) < 1e-5            # fp32 entries (three bf16 planes)
+    Pref = orc.top_r_projector(G.astype(np.float64), r)
+    sines = orc.subspace_sines(Pref, P)
+    e_ref, e_gpu = orc.captured_energy(G.astype(np.float64), Pref), orc.captured_energy(G.astype(np.float64), P)
+    print(f"fp32: max sine {sines.max():.3e}  energy kept: svd {e_ref:.6f} device {e_gpu:.6f}", flush=True)
+    assert sines.max() < 1e-2 and e_gpu > e_ref - 1e-4
+    # the bf16 twin in the same call got a basis of the same subspace
+    Pb = ctx.fira_get_projector(1).numpy().astype(np.float64)
+    assert orc.subspace_sines(Pref, Pb).max() < 1e-2
+    # ten steps with the installed projector, fresh fp32 gradients, against the oracle fed the same P
+    W = (0.02 * rng.standard_normal((m, n))).astype(np.float32)
+    Wd = H.to_device(W, fira.FIRA_F32)
+    Wref = W.astype(np.float64)
+    st = orc.OracleState.zeros(m, n, r)
+    for t in range(10):
+        Gt = (G + 1e-3 * rng.standard_normal((m, n))).astype(np.float32)
+        ctx.fira_step([0], [Wd], [H.to_device(Gt, fira.FIRA_F32)])
+        out = orc.fira_step(Wref, Gt.astype(np.float64), P, st, orc.OracleHparams(), store_bf16=False)
+        Wref = out["W"]
+    assert H.rel_max(H.to_host(Wd), Wref) <= 1e-4
+    del ws
 
 
 def test_algorithm1_with_the_refresh_branch_on_the_device():
