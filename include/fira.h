@@ -136,12 +136,15 @@ FIRA_API fira_status fira_set_projectors(fira_ctx* ctx, int count, const int* id
  * is read only; both are m x n with the descriptor's ld and dtype.  t advances by one for each
  * listed matrix.  idx, dev_W, dev_G are host arrays of length count.
  *
- * Capturing a step in a HIP graph: the hyper-parameters, the options, the variant, the fusion switch
- * and the route of every listed matrix are decided on the host when the call is made and travel as
- * kernel arguments, and the work list (which W and G pointers, which tiles) sits in one of four
- * cached slots of the slab.  A captured step therefore replays exactly what was in force at capture:
- * later fira_set_hparams (a learning-rate schedule), fira_set_options, fira_set_variant,
- * fira_set_fusion, fira_set_projector or fira_refresh_projectors calls do not reach it, and it must be
+ * Capturing a step in a HIP graph: the step size lr * alpha is read from device memory, which
+ * fira_set_hparams rewrites in stream order, so a learning-rate schedule reaches a captured step:
+ * call fira_set_hparams on the same stream, then replay.  Everything else is decided on the host when
+ * the call is made and travels as kernel arguments: beta1, beta2, eps, gamma, the options, the
+ * variant, the fusion switch and the route of every listed matrix; and the work list (which W and G
+ * pointers, which tiles) sits in one of four cached slots of the slab.  A captured step therefore
+ * replays those as they were in force at capture: later changes of them through fira_set_hparams,
+ * fira_set_options, fira_set_variant, fira_set_fusion, and fira_set_projector(s) or
+ * fira_refresh_projectors calls (which may change a matrix's route) do not reach it, and it must be
  * captured again after any of them.  Capture only from the second step after a projector was
  * installed on (the first one measures the Gram route's gate and reads it back).  While a captured
  * step may still be replayed, do not step more than three other distinct (idx, W, G) lists on the
@@ -151,7 +154,8 @@ FIRA_API fira_status fira_step(fira_ctx* ctx, int count, const int* idx, void* c
                       const void* const* dev_G);
 
 /* Replace the hyper-parameters (e.g. the learning rate under a schedule); takes effect at the
- * next fira_step. */
+ * next fira_step.  Enqueues one small kernel on the context's stream, which stores lr * alpha in the
+ * slab for the update kernel to read (see fira_step on HIP graphs). */
 FIRA_API fira_status fira_set_hparams(fira_ctx* ctx, const fira_hparams* hp);
 
 /* Variant switches (Sec. 5.3 ablations) and the way ||S_t|| is computed.  Defaults: FIRA_SCALE_COLUMN,

@@ -93,6 +93,7 @@ struct fira_ctx {
   FiraMat* d_mats = nullptr;
   FiraScal* d_scal = nullptr;
   float* d_partial = nullptr;
+  float* d_lr_alpha = nullptr;   // lr * alpha as the kernels read it (see store_step_size)
   ListSlot slots[kSlots];
   char* h_stage_all = nullptr;
   // Host copy of every matrix's two gate values of the Gram route (FiraScal::ortho_err, FiraScal::gram_err;
@@ -130,13 +131,20 @@ fira_status fail(fira_ctx* ctx, fira_status st, const std::string& msg) {
       return fail(ctx, FIRA_ERR_HIP, std::string(#call) + ": " + hipGetErrorString(e_));        \
   } while (0)
 
+// lr * alpha lives in device memory and is rewritten in stream order: the value travels as a kernel argument,
+// so no host buffer has to outlive the call.
+hipError_t store_step_size(fira_ctx* ctx) {
+  hipLaunchKernelGGL(fira_store_float_kernel, dim3(1), dim3(64), 0, ctx->stream, ctx->d_lr_alpha, (float)(ctx->hp.lr * ctx->hp.alpha));
+  return hipGetLastError();
+}
+
 FiraHp make_hp(const fira_ctx* ctx) {
   FiraHp h;
   h.beta1 = ctx->hp.beta1; h.beta2 = ctx->hp.beta2; h.eps = ctx->hp.eps; h.gamma = ctx->hp.gamma;
   h.b1 = (float)ctx->hp.beta1; h.b2 = (float)ctx->hp.beta2;
   h.omb1 = (float)(1.0 - ctx->hp.beta1); h.omb2 = (float)(1.0 - ctx->hp.beta2);
   h.epsf = (float)ctx->hp.eps;
-  h.lr_alpha = (float)(ctx->hp.lr * ctx->hp.alpha);
+  h.lr_alpha = ctx->d_lr_alpha;
   h.scaling = ctx->scaling;
   h.norm_mode = ctx->norm_mode;
   h.variant = ctx->variant;
@@ -241,6 +249,7 @@ fira_status fira_init_state(fira_ctx** out, const fira_matrix_desc* d, int count
   ctx->d_mats = (FiraMat*)(ctx->slab + p.off_mats);
   ctx->d_scal = (FiraScal*)(ctx->slab + p.off_scal);
   ctx->d_partial = (float*)(ctx->slab + p.off_partial);
+  ctx->d_lr_alpha = (float*)(ctx->slab + p.off_dyn);
 
   auto cleanup = [&]() {
     for (ListSlot& s : ctx->slots) if (s.uploaded) (void)hipEventDestroy(s.uploaded);
@@ -289,6 +298,7 @@ fira_status fira_init_state(fira_ctx** out, const fira_matrix_desc* d, int count
   }
   // Zero everything: M = V = 0, t = 0, "no previous norm", and the zero padding of every operand.
   FIRA_INIT_HIP(hipMemsetAsync(ctx->slab, 0, p.total, ctx->stream));
+  FIRA_INIT_HIP(store_step_size(ctx));
   std::vector<FiraMat> mats(count);
   for (int i = 0; i < count; ++i) mats[i] = p.mats[i].dev;
   FIRA_INIT_HIP(hipMemcpyAsync(ctx->d_mats, mats.data(), sizeof(FiraMat) * count, hipMemcpyHostToDevice, ctx->stream));
@@ -302,6 +312,7 @@ fira_status fira_set_hparams(fira_ctx* ctx, const fira_hparams* hp) {
   if (!ctx) return fail(nullptr, FIRA_ERR_INVALID_ARG, "ctx is null");
   if (!valid_hp(hp)) return fail(ctx, FIRA_ERR_INVALID_ARG, "hyper-parameters are null or out of range");
   ctx->hp = *hp;
+  FIRA_HIP(ctx, store_step_size(ctx));
   return FIRA_OK;
 }
 

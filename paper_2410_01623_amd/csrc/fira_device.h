@@ -108,7 +108,8 @@ struct FiraTile {
 struct FiraHp {     // hyper-parameters as the kernels take them
   double beta1, beta2, eps, gamma;
   float b1, b2, omb1, omb2, epsf;
-  float lr_alpha;   // lr * alpha
+  const float* lr_alpha;   // device address of lr * alpha (fira_set_hparams rewrites it in stream order, so a
+                           // learning-rate schedule reaches a step that replays from a HIP graph)
   int scaling;      // 0 column, 1 matrix, 2 none
   int norm_mode;    // 0: ||S|| from the residual tiles; 1: from ||G_i||^2 - ||R_i||^2 where P passes the gate
   float ortho_tol;  // gate of the Gram mode on FiraScal::ortho_err

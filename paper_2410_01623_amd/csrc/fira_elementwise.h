@@ -522,7 +522,7 @@ __global__ __launch_bounds__(256) void fira_scale_update_kernel(const FiraMat* _
   const FiraTile tile = tiles[ti];
   const FiraEnt ent = ents[tile.ent];
   const FiraMat mt = mats[ent.mat];
-  const float f = hp.lr_alpha * scal[ent.mat].c;
+  const float f = *hp.lr_alpha * scal[ent.mat].c;
   gptr<const T> G = as_global(reinterpret_cast<const T*>(ent.G));
   gptr<T> W = as_global(reinterpret_cast<T*>(ent.W));
   gptr<const float> phi = as_global<const float>(mt.phi);
@@ -626,6 +626,11 @@ __global__ void fira_split_gradient_kernel(FiraMat mt, const float* __restrict__
       for (int p = 0; p < 6; ++p) Gx[i * mt.gx_ld + (long long)p * mt.Sp + j] = seq[p];
     }
   }
+}
+
+// One float in device memory (the step size lr * alpha), written in stream order.
+__global__ void fira_store_float_kernel(float* __restrict__ dst, float value) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) *as_global(dst) = value;
 }
 
 // fp32 gradient -> its bf16 rounding (nearest even), rows of ldb elements (the projector refresh's way back).

@@ -911,7 +911,7 @@ __global__ __launch_bounds__(FIRA_BACK_THREADS, 2) void fira_backproject_kernel(
   const FiraEnt ent = ents[tile.ent];
   if (MODE == 0 && use_gram(hp, scal[ent.mat])) return;   // this matrix takes the Gram route to ||S||
   const FiraMat mt = mats[ent.mat];
-  const float lr_alpha = hp.lr_alpha;
+  const float lr_alpha = MODE == 1 ? *hp.lr_alpha : 0.0f;
 
   // Y (n side) is the A operand, X (m side) the B operand.
   gptr<const bf16_raw> lowrank = as_global<const bf16_raw>((MODE == 0) ? mt.Rb : mt.Nb);

@@ -52,7 +52,7 @@ enum { kTilesProjectLeft = 0, kTilesProjectRight = 1, kTilesBackBf16 = 2, kTiles
 struct Plan {
   size_t total = 0;
   size_t off_mats = 0, off_scal = 0, off_partial = 0, off_ortho = 0, ortho_z = 0;
-  size_t ortho_slot = 0, off_install = 0;   // batched installation: kInstallBatch scratch pieces of ortho_slot bytes, table of FiraRefreshEnt
+  size_t ortho_slot = 0, off_install = 0, off_dyn = 0;   // batched installation: kInstallBatch scratch pieces of ortho_slot bytes, table of FiraRefreshEnt
   size_t off_slots = 0, slot_bytes = 0, slot_off_tiles[kNumTileLists] = {};
   std::vector<HostMat> mats;
   int max_tiles[kNumTileLists] = {};
@@ -140,6 +140,8 @@ bool make_plan(const fira_matrix_desc* d, int count, Plan* plan, fira_status* st
   off = align_up(off + plan->ortho_slot * (size_t)std::min(count, kInstallBatch));
   plan->off_install = off;
   off = align_up(off + sizeof(FiraRefreshEnt) * (size_t)count);
+  plan->off_dyn = off;     // values that the kernels read at run time: [0] lr * alpha
+  off = align_up(off + 64);
   size_t s = 0;
   s = align_up(s + sizeof(FiraEnt) * count);
   for (int l = 0; l < kNumTileLists; ++l) {

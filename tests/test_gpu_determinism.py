@@ -98,3 +98,16 @@ def test_step_replays_from_a_hip_graph():
         _ = sum(float(w.float().abs().sum()) for w in W_g)      # eager work between the replays
         for i in range(len(shapes)):
             assert torch.equal(W_g[i], W_e[i]), f"replay {rep}, matrix {i}"
+    # A learning-rate schedule reaches the captured step: lr * alpha is read from device memory, which
+    # fira_set_hparams rewrites in stream order.
+    for rep, lr in enumerate([5e-4, 2.5e-4]):
+        for c in (ctx_e, ctx_g):
+            c.fira_set_hparams(fira.make_hparams(lr=lr))
+        load_new_gradients()
+        before = [w.clone() for w in W_g]
+        graph.replay()
+        ctx_e.fira_step(prepared=prep_e)
+        torch.cuda.synchronize()
+        for i in range(len(shapes)):
+            assert torch.equal(W_g[i], W_e[i]), f"replay with lr {lr}, matrix {i}"
+            assert not torch.equal(W_g[i], before[i])
