@@ -135,9 +135,14 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
-    ap.add_argument("--warmup", type=int, default=40,
-                    help="untimed steps first; the first ones start from zero moments, their factors move and the "
-                         "limiter acts, so the default leaves them all outside the timed region")
+    ap.add_argument("--warmup", type=int, default=10, help="untimed steps directly before the timed ones")
+    ap.add_argument("--settle-steps", type=int, default=40,
+                    help="untimed steps before the warm-up that bring the optimizer state from its zero start to "
+                         "the steady state: from M = V = 0 the factors move and the limiter (Eq. 12) acts on the "
+                         "first 30 or so steps of a run, which belong to the limiter-active regime that is timed "
+                         "separately (--limited-steps), not to the steady state that `value` reports; whatever "
+                         "--warmup says, the timed region then starts with no matrix limited "
+                         "(config.matrices_limited_last_warmup_step)")
     ap.add_argument("--limited-steps", type=int, default=30,
                     help="after the timed steps, also time this many steps in which the limiter acts on every matrix "
                          "(gradients whose part outside the subspace is eight times larger; reported under "
@@ -208,7 +213,7 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    for s in range(args.warmup):
+    for s in range(args.settle_steps + args.warmup):
         ctx.fira_step(prepared=prepared[s % n_sets])
     torch.cuda.synchronize()
     limited_at_start = sum(1 for i in range(len(shapes)) if ctx.fira_get_diag(i)[2] < 1.0)   # last warm-up step
@@ -253,7 +258,7 @@ def main():
                    "params": sum(m * n for m, n in shapes), "state_bytes": ctx.state_bytes,
                    "gradient_sets": n_sets, "norm_mode": args.norm_mode, "fused_projection_adam": fused, "ld": "n" if not args.pad_ld else f"n rounded up to {args.pad_ld}", "finite": finite,
                    "matrices_limited_last_step": limited, "matrices_limited_last_warmup_step": limited_at_start,
-                   "projector_install_ms": round(install_ms, 3)},
+                   "projector_install_ms": round(install_ms, 3), "settle_steps": args.settle_steps},
         "roofline": roof, "kernels": kernels,
     }
     if args.limited_steps > 0:
