@@ -466,14 +466,16 @@ fira_status fira_step(fira_ctx* ctx, int count, const int* idx, void* const* dev
   auto mark = [&](int k) { if (pe) (void)hipEventRecord(pe[k], q); };
   mark(0);
 
-  // fp32 matrices: split the gradient into bf16 planes first
-  for (int e = 0; e < count; ++e) {
-    const HostMat& h = ctx->plan.mats[idx[e]];
-    if (h.dev.kx > 1) {
-      const long long total = (long long)h.dev.m * h.dev.n;
-      const int grid = (int)std::min<long long>((total + 255) / 256, 65535);
-      hipLaunchKernelGGL(fira_split_gradient_kernel, dim3(grid), dim3(256), 0, q, h.dev, (const float*)dev_G[e]);
+  // fp32 matrices: split the gradient into bf16 planes first (one launch for all of them)
+  {
+    long long most = 0;
+    for (int e = 0; e < count; ++e) {
+      const HostMat& h = ctx->plan.mats[idx[e]];
+      if (h.dev.kx > 1) most = std::max(most, (long long)h.dev.m * h.dev.n);
     }
+    if (most > 0)
+      hipLaunchKernelGGL(fira_split_gradients_kernel, dim3((unsigned)std::min<long long>((most + 255) / 256, 4096), count), dim3(256), 0, q,
+                         ctx->d_mats, s->d_ents);
   }
   auto grid8 = [](int n) { return dim3((unsigned)(((n + 7) / 8) * 8)); };
   const dim3 blk(FIRA_PROJ_THREADS);

@@ -608,7 +608,7 @@ template <typename TP>
 __global__ void fira_prep_projector_kernel(FiraMat mt, const TP* __restrict__ P) { prep_projector_body<TP>(mt, P); }
 
 // fp32 gradient -> split bf16 planes (sequence A), stacked along the contraction axis.
-__global__ void fira_split_gradient_kernel(FiraMat mt, const float* __restrict__ G) {
+__device__ __forceinline__ void split_gradient_body(const FiraMat& mt, const float* __restrict__ G) {
   const long long total = (long long)mt.m * mt.n;
   gptr<bf16_raw> Gx = as_global(mt.Gx);
   for (long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
@@ -626,6 +626,14 @@ __global__ void fira_split_gradient_kernel(FiraMat mt, const float* __restrict__
       for (int p = 0; p < 6; ++p) Gx[i * mt.gx_ld + (long long)p * mt.Sp + j] = seq[p];
     }
   }
+}
+__global__ void fira_split_gradient_kernel(FiraMat mt, const float* __restrict__ G) { split_gradient_body(mt, G); }
+// ... for every fp32 matrix of a step's work list in one launch (blockIdx.y = list entry; bf16 entries exit)
+__global__ void fira_split_gradients_kernel(const FiraMat* __restrict__ mats, const FiraEnt* __restrict__ ents) {
+  const FiraEnt ent = ents[blockIdx.y];
+  const FiraMat mt = mats[ent.mat];
+  if (mt.kx == 1) return;
+  split_gradient_body(mt, reinterpret_cast<const float*>(ent.G));
 }
 
 // One float in device memory (the step size lr * alpha), written in stream order.
