@@ -79,6 +79,49 @@ def kernel_sources_hash():
     return h.hexdigest()[:16]
 
 
+class PowerSampler:
+    """Socket power from the amdgpu hwmon file (microwatts), sampled by a thread while work runs.  mean() is None
+    when the file is not readable."""
+
+    def __init__(self, period=0.02):
+        import glob
+        import threading
+        files = sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_input"))
+        self.path = files[0] if files else None
+        self.period, self.samples = period, []
+        self._stop, self._thread = threading.Event(), None
+        self._threading = threading
+
+    def cap(self):
+        try:
+            return int(open(self.path.replace("power1_input", "power1_cap")).read()) / 1e6
+        except Exception:
+            return None
+
+    def _run(self):
+        while not self._stop.is_set():
+            try:
+                self.samples.append(int(open(self.path).read()) / 1e6)
+            except Exception:
+                return
+            time.sleep(self.period)
+
+    def __enter__(self):
+        if self.path:
+            self._thread = self._threading.Thread(target=self._run, daemon=True)
+            self._thread.start()
+        return self
+
+    def __exit__(self, *exc):
+        self._stop.set()
+        if self._thread:
+            self._thread.join()
+
+    def mean(self, skip_first_third=False):
+        x = self.samples[len(self.samples) // 3:] if skip_first_third else self.samples
+        return round(sum(x) / len(x), 1) if x else None
+
+
 def read_traffic(workload, norm_mode):
     """HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by the same
     counters on a plain 1 GiB copy), as recorded in profiles/; {} when no record matches the workload or
@@ -157,6 +200,10 @@ def main():
     ap.add_argument("--refresh-iters", type=int, default=0,
                     help="also time fira_refresh_projectors over all matrices with this many rounds of subspace "
                          "iteration (after the timed steps; reported under \"refresh\", not part of value)")
+    ap.add_argument("--power-seconds", type=float, default=0.0,
+                    help="after the timed steps, keep stepping for this many seconds while the socket power is sampled "
+                         "(reported under \"power\", together with a plain copy and a library bf16 matrix product "
+                         "run the same way for comparison; not part of value)")
     ap.add_argument("--no-fusion", action="store_true",
                     help="run the projection and Adam as two kernels with R in memory")
     ap.add_argument("--norm-mode", choices=["gram", "residual"], default="gram",
@@ -218,11 +265,12 @@ def main():
     torch.cuda.synchronize()
     limited_at_start = sum(1 for i in range(len(shapes)) if ctx.fira_get_diag(i)[2] < 1.0)   # last warm-up step
     ctx.fira_profile_begin(args.steps)
-    t0 = time.perf_counter()
-    for s in range(args.steps):
-        ctx.fira_step(prepared=prepared[s % n_sets])
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
+    with PowerSampler() as power:
+        t0 = time.perf_counter()
+        for s in range(args.steps):
+            ctx.fira_step(prepared=prepared[s % n_sets])
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
     ms_sum, rec = ctx.fira_profile_end()
     fused = ctx.fira_last_step_fused()
     if fused:   # one kernel did the work of the first two slots
@@ -258,7 +306,8 @@ def main():
                    "params": sum(m * n for m, n in shapes), "state_bytes": ctx.state_bytes,
                    "gradient_sets": n_sets, "norm_mode": args.norm_mode, "fused_projection_adam": fused, "ld": "n" if not args.pad_ld else f"n rounded up to {args.pad_ld}", "finite": finite,
                    "matrices_limited_last_step": limited, "matrices_limited_last_warmup_step": limited_at_start,
-                   "projector_install_ms": round(install_ms, 3), "settle_steps": args.settle_steps},
+                   "projector_install_ms": round(install_ms, 3), "settle_steps": args.settle_steps,
+                   "socket_power_w": power.mean(), "socket_power_cap_w": power.cap()},
         "roofline": roof, "kernels": kernels,
     }
     if args.limited_steps > 0:
@@ -294,6 +343,41 @@ def main():
                                      make_z_ms=round(ms_l["make_z"] / max(rec_l, 1), 4),
                                      finite=all(bool(torch.isfinite(w).all()) for w in W[:7]))
         del Gspike, prep_spike
+    if args.power_seconds > 0:
+        # What the step draws against the socket's power cap, next to a plain copy and the vendor library's bf16
+        # matrix product measured the same way: the chip lowers its clock to stay under the cap, so the energy
+        # of a step, not the occupancy of one unit, is what its time follows.
+        def powered(fn, work_per_call):
+            fn()
+            torch.cuda.synchronize()
+            with PowerSampler(0.05) as ps:
+                t1, n = time.perf_counter(), 0
+                while time.perf_counter() - t1 < args.power_seconds:
+                    for _ in range(10):
+                        fn()
+                    torch.cuda.synchronize()
+                    n += 10
+                el = time.perf_counter() - t1
+            return dict(ms_per_call=round(1e3 * el / n, 4), rate=round(work_per_call * n / el, 1), socket_w=ps.mean(True))
+        state = {"s": 0}
+        def one_step():
+            ctx.fira_step(prepared=prepared[state["s"] % n_sets])
+            state["s"] += 1
+        pw = {"cap_w": PowerSampler().cap(), "seconds_each": args.power_seconds}
+        pw["fira_step"] = powered(one_step, 1.0)                                   # rate: steps/s
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        pw["copy_1GiB"] = powered(lambda: dst.copy_(src), 2.0 * (1 << 30) / 1e9)   # rate: GB/s read + written
+        del src, dst
+        A = torch.randn(8192, 8192, device=dev).to(torch.bfloat16)
+        B = torch.randn(8192, 8192, device=dev).to(torch.bfloat16)
+        pw["library_matmul_bf16_8192"] = powered(lambda: torch.matmul(A, B), 2.0 * 8192 ** 3 / 1e12)   # rate: TFLOP/s
+        del A, B
+        torch.cuda.synchronize()
+        with PowerSampler(0.05) as ps:      # nothing running (the clocks have not yet dropped to the low-power state)
+            time.sleep(2.0)
+        pw["idle_w"] = ps.mean(True)
+        out["power"] = pw
     if args.refresh_iters > 0:
         # projector refresh (Algorithm 1's "if t mod T = 0" branch) over every matrix, from the first gradient set
         idx_all = list(range(len(shapes)))
