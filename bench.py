@@ -5,13 +5,17 @@ A "step" is one fira_step call over ALL weight matrices of the workload (default
 shape set, 168 matrices, r = 512, bf16 W/G with fp32 state): projection, Adam on the low-rank
 gradient, factor norms, residual norm, limiter, back-projection and weight update.  Inputs are
 synthetic and resident in HBM before the timed region; three gradient sets rotate so that no step
-finds its gradient in the last-level cache.
+finds its gradient in the last-level cache.  Before the warm-up steps asked for, 40 untimed settling steps
+bring the optimizer state from its zero start to the steady state (the limiter acts on the first steps of a run).
 
 Prints ONE JSON line: whole-job optimizer steps/s, plus
   "roofline":     achieved vs peak for the kernel that takes the most time (HIP events recorded by
                   the library around every kernel of every timed step), and "kernels" with the same
                   figures for all of them;
-  "cpu_baseline": the CPU oracle timed on this machine's host cores on a bounded sample.
+  "limiter_active": the same step timed with the limiter acting on every matrix (not part of value);
+  "cpu_baseline": the CPU oracle timed on this box's host cores on a bounded sample;
+  "power" (--power-seconds): socket power of the step, of a plain copy and of the vendor library's bf16
+                  matrix product against the power cap; config.socket_power_w is sampled over the timed steps.
 """
 import argparse
 import json
