@@ -189,7 +189,7 @@ def main():
                          "first 30 or so steps of a run, which belong to the limiter-active regime that is timed "
                          "separately (--limited-steps), not to the steady state that `value` reports; whatever "
                          "--warmup says, the timed region then starts with no matrix limited "
-                         "(config.matrices_limited_last_warmup_step)")
+                         "(config.matrices_limited_after_settling)")
     ap.add_argument("--limited-steps", type=int, default=30,
                     help="after the timed steps, also time this many steps in which the limiter acts on every matrix "
                          "(gradients whose part outside the subspace is eight times larger; reported under "
@@ -204,10 +204,10 @@ def main():
     ap.add_argument("--refresh-iters", type=int, default=0,
                     help="also time fira_refresh_projectors over all matrices with this many rounds of subspace "
                          "iteration (after the timed steps; reported under \"refresh\", not part of value)")
-    ap.add_argument("--power-seconds", type=float, default=0.0,
+    ap.add_argument("--power-seconds", type=float, default=3.0,
                     help="after the timed steps, keep stepping for this many seconds while the socket power is sampled "
                          "(reported under \"power\", together with a plain copy and a library bf16 matrix product "
-                         "run the same way for comparison; not part of value)")
+                         "run the same way for comparison; not part of value; 0 = skip)")
     ap.add_argument("--no-fusion", action="store_true",
                     help="run the projection and Adam as two kernels with R in memory")
     ap.add_argument("--norm-mode", choices=["gram", "residual"], default="gram",
@@ -264,15 +264,21 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    for s in range(args.settle_steps + args.warmup):
+    for s in range(args.settle_steps):
         ctx.fira_step(prepared=prepared[s % n_sets])
     torch.cuda.synchronize()
-    limited_at_start = sum(1 for i in range(len(shapes)) if ctx.fira_get_diag(i)[2] < 1.0)   # last warm-up step
+    # (read here, not between the warm-up and the timed steps: 168 small copies with a synchronisation each are a
+    # pause of some milliseconds, after which the chip takes a few steps to bring its clock up again)
+    limited_at_start = sum(1 for i in range(len(shapes)) if ctx.fira_get_diag(i)[2] < 1.0)
+    power = PowerSampler()
+    for s in range(args.warmup):
+        ctx.fira_step(prepared=prepared[(args.settle_steps + s) % n_sets])
+    torch.cuda.synchronize()
     ctx.fira_profile_begin(args.steps)
-    with PowerSampler() as power:
+    with power:
         t0 = time.perf_counter()
         for s in range(args.steps):
-            ctx.fira_step(prepared=prepared[s % n_sets])
+            ctx.fira_step(prepared=prepared[(args.settle_steps + args.warmup + s) % n_sets])
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
     ms_sum, rec = ctx.fira_profile_end()
@@ -309,7 +315,7 @@ def main():
         "config": {"workload": name, "matrices": len(shapes), "rank": wl.rank,
                    "params": sum(m * n for m, n in shapes), "state_bytes": ctx.state_bytes,
                    "gradient_sets": n_sets, "norm_mode": args.norm_mode, "fused_projection_adam": fused, "ld": "n" if not args.pad_ld else f"n rounded up to {args.pad_ld}", "finite": finite,
-                   "matrices_limited_last_step": limited, "matrices_limited_last_warmup_step": limited_at_start,
+                   "matrices_limited_last_step": limited, "matrices_limited_after_settling": limited_at_start,
                    "projector_install_ms": round(install_ms, 3), "settle_steps": args.settle_steps,
                    "socket_power_w": power.mean(), "socket_power_cap_w": power.cap()},
         "roofline": roof, "kernels": kernels,
@@ -348,40 +354,43 @@ def main():
                                      finite=all(bool(torch.isfinite(w).all()) for w in W[:7]))
         del Gspike, prep_spike
     if args.power_seconds > 0:
-        # What the step draws against the socket's power cap, next to a plain copy and the vendor library's bf16
-        # matrix product measured the same way: the chip lowers its clock to stay under the cap, so the energy
-        # of a step, not the occupancy of one unit, is what its time follows.
-        def powered(fn, work_per_call):
-            fn()
+        try:
+            # What the step draws against the socket's power cap, next to a plain copy and the vendor library's bf16
+            # matrix product measured the same way: the chip lowers its clock to stay under the cap, so the energy
+            # of a step, not the occupancy of one unit, is what its time follows.
+            def powered(fn, work_per_call):
+                fn()
+                torch.cuda.synchronize()
+                with PowerSampler(0.05) as ps:
+                    t1, n = time.perf_counter(), 0
+                    while time.perf_counter() - t1 < args.power_seconds:
+                        for _ in range(10):
+                            fn()
+                        torch.cuda.synchronize()
+                        n += 10
+                    el = time.perf_counter() - t1
+                return dict(ms_per_call=round(1e3 * el / n, 4), rate=round(work_per_call * n / el, 1), socket_w=ps.mean(True))
+            state = {"s": 0}
+            def one_step():
+                ctx.fira_step(prepared=prepared[state["s"] % n_sets])
+                state["s"] += 1
+            pw = {"cap_w": PowerSampler().cap(), "seconds_each": args.power_seconds}
+            pw["fira_step"] = powered(one_step, 1.0)                                   # rate: steps/s
+            src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+            dst = torch.empty_like(src)
+            pw["copy_1GiB"] = powered(lambda: dst.copy_(src), 2.0 * (1 << 30) / 1e9)   # rate: GB/s read + written
+            del src, dst
+            A = torch.randn(8192, 8192, device=dev).to(torch.bfloat16)
+            B = torch.randn(8192, 8192, device=dev).to(torch.bfloat16)
+            pw["library_matmul_bf16_8192"] = powered(lambda: torch.matmul(A, B), 2.0 * 8192 ** 3 / 1e12)   # rate: TFLOP/s
+            del A, B
             torch.cuda.synchronize()
-            with PowerSampler(0.05) as ps:
-                t1, n = time.perf_counter(), 0
-                while time.perf_counter() - t1 < args.power_seconds:
-                    for _ in range(10):
-                        fn()
-                    torch.cuda.synchronize()
-                    n += 10
-                el = time.perf_counter() - t1
-            return dict(ms_per_call=round(1e3 * el / n, 4), rate=round(work_per_call * n / el, 1), socket_w=ps.mean(True))
-        state = {"s": 0}
-        def one_step():
-            ctx.fira_step(prepared=prepared[state["s"] % n_sets])
-            state["s"] += 1
-        pw = {"cap_w": PowerSampler().cap(), "seconds_each": args.power_seconds}
-        pw["fira_step"] = powered(one_step, 1.0)                                   # rate: steps/s
-        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
-        dst = torch.empty_like(src)
-        pw["copy_1GiB"] = powered(lambda: dst.copy_(src), 2.0 * (1 << 30) / 1e9)   # rate: GB/s read + written
-        del src, dst
-        A = torch.randn(8192, 8192, device=dev).to(torch.bfloat16)
-        B = torch.randn(8192, 8192, device=dev).to(torch.bfloat16)
-        pw["library_matmul_bf16_8192"] = powered(lambda: torch.matmul(A, B), 2.0 * 8192 ** 3 / 1e12)   # rate: TFLOP/s
-        del A, B
-        torch.cuda.synchronize()
-        with PowerSampler(0.05) as ps:      # nothing running (the clocks have not yet dropped to the low-power state)
-            time.sleep(2.0)
-        pw["idle_w"] = ps.mean(True)
-        out["power"] = pw
+            with PowerSampler(0.05) as ps:      # nothing running (the clocks have not yet dropped to the low-power state)
+                time.sleep(2.0)
+            pw["idle_w"] = ps.mean(True)
+            out["power"] = pw
+        except Exception as e:   # a reported comparison, never a reason to lose the line
+            out["power"] = {"error": repr(e)}
     if args.refresh_iters > 0:
         # projector refresh (Algorithm 1's "if t mod T = 0" branch) over every matrix, from the first gradient set
         idx_all = list(range(len(shapes)))
