@@ -707,3 +707,40 @@ def test_projector_switch_keeps_state_and_errors_are_reported():
     ctx.fira_step([0, 1, 2], W, G)
     for a, b in zip(before, W):
         assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("dtype", [fira.FIRA_BF16, fira.FIRA_F32], ids=["bf16", "f32"])
+def test_learning_rate_schedule_against_the_oracle(dtype):
+    """eta and alpha change before every step (a warm-up and decay schedule, as in the paper's experiments):
+    the library reads eta * alpha from device memory, which fira_set_hparams rewrites in stream order, and every
+    step must take the value set just before it.  Three matrices, one of them on the fused kernel's rank."""
+    import dataclasses
+    shapes = [(192, 320), (320, 192), (256, 512)]
+    ranks = [32, 32, 128]
+    rng = np.random.default_rng(4242)
+    bf = dtype == fira.FIRA_BF16
+    val = (lambda x: synth.as_bf16_values(x)) if bf else (lambda x: x.astype(np.float32))
+    base = orc.OracleHparams()
+    ctx = fira.FiraContext(shapes, ranks, dtype, fira.make_hparams(), device=H.DEV)
+    W0 = [val(0.02 * rng.standard_normal(s)) for s in shapes]
+    Wd = [H.to_device(w, dtype) for w in W0]
+    Wref = [w.astype(np.float64) for w in W0]
+    st = [orc.OracleState.zeros(m, n, r) for (m, n), r in zip(shapes, ranks)]
+    P = []
+    for i, ((m, n), r) in enumerate(zip(shapes, ranks)):
+        q, _ = np.linalg.qr(rng.standard_normal((min(m, n), r)))
+        P.append(val(q).astype(np.float64))
+        ctx.fira_set_projector(i, H.to_device(P[i].astype(np.float32), dtype))
+    schedule = [(2e-4, 1.0), (6e-4, 1.0), (1e-3, 1.0), (9e-4, 0.25), (7e-4, 0.25), (4e-4, 0.5), (2e-4, 0.5), (0.0, 1.0), (5e-4, 1.0), (1e-4, 1.0)]
+    worst = 0.0
+    for t, (lr, alpha) in enumerate(schedule):
+        ctx.fira_set_hparams(fira.make_hparams(lr=lr, alpha=alpha))
+        hp = dataclasses.replace(base, lr=lr, alpha=alpha)
+        G = [val(1e-2 * rng.standard_normal(s)) for s in shapes]
+        ctx.fira_step([0, 1, 2], Wd, [H.to_device(g, dtype) for g in G])
+        for i in range(3):
+            out = orc.fira_step(Wref[i], G[i].astype(np.float64), P[i], st[i], hp, store_bf16=bf)
+            Wref[i] = out["W"]
+            worst = max(worst, H.rel_max(H.to_host(Wd[i]), Wref[i]))
+    print(f"schedule: worst W error over {len(schedule)} steps {worst:.3g}", flush=True)
+    assert worst <= (2e-2 if bf else 1e-4)
