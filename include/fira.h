@@ -29,7 +29,10 @@
  *   - Every function returns a fira_status (0 = OK, negative = error); errors detectable on the
  *     host are reported before anything is enqueued and leave the state untouched.
  *     fira_last_error() gives a message for the last failure (ctx may be NULL for failures of
- *     fira_init_state).  Non-finite inputs are not checked; they propagate.
+ *     fira_init_state).  Non-finite inputs are not checked; they propagate: a non-finite gradient
+ *     entry makes the state and the weights of its factor (its column; its row when m > n)
+ *     non-finite for good, the limiter's factor is 1 on a step whose norm is not finite, and the other
+ *     factors and the other matrices of the call are what they are without it.
  *   - Not thread-safe per context; two contexts are independent.
  */
 #ifndef FIRA_H_

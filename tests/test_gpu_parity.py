@@ -744,3 +744,36 @@ def test_learning_rate_schedule_against_the_oracle(dtype):
             worst = max(worst, H.rel_max(H.to_host(Wd[i]), Wref[i]))
     print(f"schedule: worst W error over {len(schedule)} steps {worst:.3g}", flush=True)
     assert worst <= (2e-2 if bf else 1e-4)
+
+
+@pytest.mark.parametrize("fusion", [True, False], ids=["fused", "two_kernels"])
+def test_a_non_finite_gradient_stays_in_its_matrix(fusion):
+    """Non-finite inputs are not checked and propagate (the paper is silent): a NaN in one gradient entry makes
+    that factor's column of R, M, V and W non-finite, the call returns normally, and the other matrices of the
+    same grouped launch are bit for bit what they are without it."""
+    shapes = [(256, 512), (256, 512), (512, 256)]
+    r = 128
+    gen = torch.Generator(device=H.DEV)
+    gen.manual_seed(11)
+    ctxs = [fira.FiraContext(shapes, r, fira.FIRA_BF16, device=H.DEV) for _ in range(2)]
+    P = [torch.linalg.qr(torch.randn((256, r), device=H.DEV, generator=gen))[0].to(torch.bfloat16).contiguous() for _ in shapes]
+    for c in ctxs:
+        c.fira_set_fusion(fusion)
+        c.fira_set_projectors(range(3), P)
+    W = [[(0.02 * torch.randn(s, device=H.DEV, generator=gen)).to(torch.bfloat16) for s in shapes]]
+    W.append([w.clone() for w in W[0]])
+    for step in range(3):
+        G = [(1e-2 * torch.randn(s, device=H.DEV, generator=gen)).to(torch.bfloat16) for s in shapes]
+        Gbad = [g.clone() for g in G]
+        if step == 1:
+            Gbad[0][17, 300] = float("nan")
+        ctxs[0].fira_step([0, 1, 2], W[0], G)
+        ctxs[1].fira_step([0, 1, 2], W[1], Gbad)
+        torch.cuda.synchronize()
+    assert not torch.isfinite(W[1][0][:, 300]).any(), "the poisoned factor's column of W"
+    clean = torch.ones(512, dtype=torch.bool, device=H.DEV)
+    clean[300] = False
+    assert torch.isfinite(W[1][0][:, clean]).all(), "the other columns of that matrix"
+    for i in (1, 2):
+        assert torch.equal(W[0][i], W[1][i]), f"matrix {i} must not see matrix 0's NaN"
+    assert all(bool(torch.isfinite(w).all()) for w in W[0])
