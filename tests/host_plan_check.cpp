@@ -118,6 +118,13 @@ void check_plan(const std::vector<fira_matrix_desc>& descs, std::mt19937_64& rng
   pieces.push_back({plan.off_partial, parts * 4, "tile partials", -1});
   pieces.push_back({plan.off_ortho, (size_t)max_S * 16, "orthonormality estimate y", -1});
   pieces.push_back({plan.off_ortho + plan.ortho_z, (size_t)FIRA_ORTHO_SPLITS * max_r * 16, "orthonormality estimate z", -1});
+  // the batched installation's pieces: one per matrix of a batch, [S][4] directly followed by [splits][r][4]
+  for (int k = 1; k < std::min(count, kInstallBatch); ++k)
+    pieces.push_back({plan.off_ortho + plan.ortho_slot * k, (size_t)max_S * 16 + (size_t)FIRA_ORTHO_SPLITS * max_r * 16,
+                      "orthonormality estimate of a batch", k});
+  CHECK(plan.ortho_slot >= plan.ortho_z + (size_t)FIRA_ORTHO_SPLITS * max_r * 16, "a batch piece is smaller than the single estimate's");
+  pieces.push_back({plan.off_install, sizeof(FiraRefreshEnt) * (size_t)count, "installation table", -1});
+  pieces.push_back({plan.off_dyn, 4, "step size", -1});
   for (int k = 0; k < kSlots; ++k) pieces.push_back({plan.off_slots + plan.slot_bytes * k, plan.slot_bytes, "work-list slot", k});
   check_pieces(pieces, plan.total, "slab");
 
@@ -213,6 +220,7 @@ void check_plan(const std::vector<fira_matrix_desc>& descs, std::mt19937_64& rng
       const size_t inst = std::max((size_t)m.S * 16 + (size_t)FIRA_ORTHO_SPLITS * m.r * 16,
                                    (size_t)((m.r + FIRA_SOLVE_JB - 1) / FIRA_SOLVE_JB) * FIRA_SOLVE_JB * FIRA_SOLVE_JB * 8);
       wp.push_back({rp.off_linv[e], inst, "block inverses / gate scratch", ridx[e]});
+      if (m.kx != 1) wp.push_back({rp.off_gb[e], (size_t)m.m * refresh_gb_ld(m.n) * 2, "bf16 rounding of the gradient", ridx[e]});
       CHECK(rp.off_top[e] >= rp.top_begin && rp.off_top[e] + Lp * m.rq * 2 <= rp.top_end, "packed operand outside the cleared range");
     }
     check_pieces(wp, rp.total, "refresh workspace");
