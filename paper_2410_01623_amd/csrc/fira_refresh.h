@@ -64,13 +64,65 @@ __global__ __launch_bounds__(256) void fira_refresh_pack_kernel(const FiraRefres
   }
 }
 
-// 64 x 64 tile of a product accumulated in fp64, 256 threads, 4 x 4 outputs per thread.
-// A[k][i] and B[k][j] come from row-major arrays with leading dimension r (k is the slow index).
-struct RefreshAcc { double v[4][4]; };
+// 64 x 64 tile of a product accumulated in fp64 on the matrix pipe (v_mfma_f64_16x16x4_f64): 256 threads, wave w
+// owns the 32 x 32 block at rows 32 (w >> 1), columns 32 (w & 1), as 2 x 2 blocks of 16 x 16.  Operand layout of
+// the instruction: lane l supplies A[m = l % 16][k = l / 16] and B[k = l / 16][n = l % 16]; of its four result
+// values, number v is D[m = l / 16 + 4 v][n = l % 16] (checked on the device against a plain product).  The products are fp64 multiply-adds like the vector
+// unit's; the matrix pipe has the same peak on this chip but takes one instruction for 2048 of them, which
+// frees the issue slots that the vector form spends on conversions and LDS reads.
+typedef double f64x4_t __attribute__((ext_vector_type(4)));
+struct RefreshAcc { f64x4_t v[2][2]; };
+__device__ __forceinline__ void refresh_acc_zero(RefreshAcc& acc) {
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) acc.v[i][j] = f64x4_t{0.0, 0.0, 0.0, 0.0};
+}
+// K steps [0, KN) of a staged pair of operands: A(k, m) = sa[k * ak + m * am], B(k, n) = sb[k * bk + n * bn],
+// m and n counted inside the workgroup's 64 x 64 tile.
+template <int KN, typename TA, typename TB>
+__device__ __forceinline__ void refresh_acc_steps(RefreshAcc& acc, const TA* sa, int ak, int am, const TB* sb, int bk, int bn) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int m0 = 32 * (wave >> 1) + (lane & 15), n0 = 32 * (wave & 1) + (lane & 15), kq = lane >> 4;
+#pragma unroll
+  for (int k4 = 0; k4 < KN; k4 += 4) {
+    const int k = k4 + kq;
+    const double a0 = (double)sa[k * ak + m0 * am], a1 = (double)sa[k * ak + (m0 + 16) * am];
+    const double b0 = (double)sb[k * bk + n0 * bn], b1 = (double)sb[k * bk + (n0 + 16) * bn];
+    acc.v[0][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b0, acc.v[0][0], 0, 0, 0);
+    acc.v[0][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b1, acc.v[0][1], 0, 0, 0);
+    acc.v[1][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b0, acc.v[1][0], 0, 0, 0);
+    acc.v[1][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b1, acc.v[1][1], 0, 0, 0);
+  }
+}
+// Calls f(row, col, value) for every element of the workgroup's tile that this lane holds.
+template <typename F>
+__device__ __forceinline__ void refresh_acc_foreach(const RefreshAcc& acc, F f) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int v = 0; v < 4; ++v)
+        f(32 * (wave >> 1) + 16 * i + (lane >> 4) + 4 * v, 32 * (wave & 1) + 16 * j + (lane & 15), acc.v[i][j][v]);
+}
+#define FIRA_STAGE_LD 80   // floats per staged K row of 64: the four K rows that one load instruction touches fall on distinct banks
 
-// C = Y^T Y (lower triangle tiles only), fp64.
+// Four consecutive floats of a row-major fp32 array (row `row`, columns col .. col + 3, leading dimension ld,
+// `rows` x `cols` valid): one 16-byte load when ld is a multiple of 4 (col is), else element by element.
+__device__ __forceinline__ f32x4 refresh_load4(gptr<const float> A, int row, int col, int rows, int cols, int ld) {
+  if (row >= rows || col >= cols) return f32x4{0.f, 0.f, 0.f, 0.f};
+  gptr<const float> p = A + (long long)row * ld + col;
+  if ((ld & 3) == 0) return *reinterpret_cast<gptr<const f32x4>>(p);
+  return f32x4{p[0], col + 1 < cols ? p[1] : 0.f, col + 2 < cols ? p[2] : 0.f, col + 3 < cols ? p[3] : 0.f};
+}
+
+// C = Y^T Y (lower triangle tiles only), fp64.  K stages of 32 rows; the next stage's rows are requested into
+// registers before the current one is multiplied.
+#define FIRA_GRAM_KS 32
 __global__ __launch_bounds__(256) void fira_refresh_gram_kernel(const FiraRefreshEnt* __restrict__ ents) {
-  __shared__ float sa[16][64], sb[16][64];
+  __shared__ __attribute__((aligned(16))) float sa[FIRA_GRAM_KS * FIRA_STAGE_LD], sb[FIRA_GRAM_KS * FIRA_STAGE_LD];
   const FiraRefreshEnt e = ents[blockIdx.y];
   const int nt = (e.r + 63) / 64;
   // linear index -> (ta >= tb)
@@ -79,42 +131,36 @@ __global__ __launch_bounds__(256) void fira_refresh_gram_kernel(const FiraRefres
   if (ta >= nt) return;
   const int tb = rem;
   gptr<const float> Y = as_global<const float>(e.Y);
-  const int t = threadIdx.x, tx = t & 15, ty = t >> 4;
+  const int t = threadIdx.x;
   RefreshAcc acc;
+  refresh_acc_zero(acc);
+  f32x4 ra[2], rb[2];
+  auto fetch = [&](int s0) {
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+    for (int p = 0; p < 2; ++p) {
+      const int x = t + 256 * p, sl = x >> 4, c4 = (x & 15) * 4;
+      ra[p] = refresh_load4(Y, s0 + sl, ta * 64 + c4, e.S, e.r, e.r);
+      rb[p] = refresh_load4(Y, s0 + sl, tb * 64 + c4, e.S, e.r, e.r);
+    }
+  };
+  fetch(0);
+  for (int s0 = 0; s0 < e.S; s0 += FIRA_GRAM_KS) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) acc.v[i][j] = 0.0;
-  for (int s0 = 0; s0 < e.S; s0 += 16) {
-#pragma unroll
-    for (int p = 0; p < 4; ++p) {
-      const int sl = (t >> 6) + 4 * p, c = t & 63;
-      const int s = s0 + sl;
-      const int ca = ta * 64 + c, cb = tb * 64 + c;
-      sa[sl][c] = (s < e.S && ca < e.r) ? Y[(long long)s * e.r + ca] : 0.0f;
-      sb[sl][c] = (s < e.S && cb < e.r) ? Y[(long long)s * e.r + cb] : 0.0f;
+    for (int p = 0; p < 2; ++p) {
+      const int x = t + 256 * p, sl = x >> 4, c4 = (x & 15) * 4;
+      *reinterpret_cast<f32x4*>(&sa[sl * FIRA_STAGE_LD + c4]) = ra[p];
+      *reinterpret_cast<f32x4*>(&sb[sl * FIRA_STAGE_LD + c4]) = rb[p];
     }
     __syncthreads();
-#pragma unroll
-    for (int sl = 0; sl < 16; ++sl) {
-      double a[4], b[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) { a[i] = (double)sa[sl][4 * ty + i]; b[i] = (double)sb[sl][4 * tx + i]; }
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) acc.v[i][j] += a[i] * b[j];
-    }
+    if (s0 + FIRA_GRAM_KS < e.S) fetch(s0 + FIRA_GRAM_KS);
+    refresh_acc_steps<FIRA_GRAM_KS>(acc, sa, FIRA_STAGE_LD, 1, sb, FIRA_STAGE_LD, 1);
     __syncthreads();
   }
   gptr<double> C = as_global(e.C);
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int ra = ta * 64 + 4 * ty + i, cb = tb * 64 + 4 * tx + j;
-      if (ra < e.r && cb < e.r && cb <= ra) C[(long long)ra * e.r + cb] = acc.v[i][j];
-    }
+  refresh_acc_foreach(acc, [&](int row, int col, double v) {
+    const int ra_ = ta * 64 + row, cb = tb * 64 + col;
+    if (ra_ < e.r && cb < e.r && cb <= ra_) C[(long long)ra_ * e.r + cb] = v;
+  });
 }
 
 // In-place Cholesky factorisation of the lower triangle of C (fp64), one workgroup per matrix,
@@ -252,14 +298,14 @@ __global__ __launch_bounds__(FIRA_CHOL_THREADS) void fira_refresh_chol_kernel(co
 // Q = Y L^-T, i.e. every row solves  q L^T = y  by forward substitution, done in column blocks of 64:
 //     Q_J = (Y_J - Q_{<J} L_{J,<J}^T) inv(L_JJ)^T.
 // Everything but the 64 x 64 inverses of the diagonal blocks is a dense product, so the work is tiled like
-// the Gram kernel (64 x 64 output tile, fp64 accumulation, 4 x 4 outputs per thread, operands staged through
-// LDS): one launch per column block J, in order, each reading the blocks of Q written by the launches
+// the Gram kernel (64 x 64 output tile, fp64 on the matrix pipe, operands staged through LDS with the next
+// stage's values requested into registers meanwhile): one launch per column block J, in order, each reading the blocks of Q written by the launches
 // before it (fp32, as the result is stored).  The inverses of the diagonal blocks come from a small
 // kernel of their own (one thread per column of an inverse) and live in the scratch of the installation,
 // which is idle until the solves are done.  (Forms that kept a workgroup's rows in LDS and walked along
 // the columns, one row per lane with L read from memory or staged in LDS, ran at a tenth of the fp64
 // rate: bound by the latency, or the LDS bandwidth, of the operand every lane shares.)
-#define FIRA_SOLVE_LDS (16 * 64 * 4 + 16 * 64 * 8 + 64 * 65 * 8 + 64 * 64 * 8)
+#define FIRA_SOLVE_LDS (16 * 80 * 4 + 16 * 64 * 8 + 64 * 65 * 8 + 64 * 64 * 8)   // staged Q (rows of FIRA_STAGE_LD floats), staged L, T, inverse
 
 // inv(L_JJ) for every diagonal block J of a matrix: inv[J][k][c], k >= c (zero above the diagonal).
 // Rows and columns beyond r act as an identity.
@@ -293,10 +339,10 @@ __global__ __launch_bounds__(64) void fira_refresh_diaginv_kernel(const FiraRefr
 // Column block J of Q for 64 rows.
 __global__ __launch_bounds__(256) void fira_refresh_solve_kernel(const FiraRefreshEnt* __restrict__ ents, int J) {
   extern __shared__ __attribute__((aligned(16))) char solve_lds[];
-  float (*sa)[64] = reinterpret_cast<float (*)[64]>(solve_lds);                       // [16][64]  Q[s0 + i][k0 + kk]
-  double (*sb)[64] = reinterpret_cast<double (*)[64]>(solve_lds + 16 * 64 * 4);        // [16][64]  L[j0 + j][k0 + kk]
-  double (*st)[65] = reinterpret_cast<double (*)[65]>(solve_lds + 16 * 64 * 4 + 16 * 64 * 8);   // [64][65] Y_J - update
-  double (*invT)[64] = reinterpret_cast<double (*)[64]>(solve_lds + 16 * 64 * 4 + 16 * 64 * 8 + 64 * 65 * 8);   // [c][k]
+  float* sa = reinterpret_cast<float*>(solve_lds);                                   // [16][FIRA_STAGE_LD]  Q[s0 + i][k0 + kk]
+  double* sb = reinterpret_cast<double*>(solve_lds + 16 * FIRA_STAGE_LD * 4);        // [16][64]  L[j0 + j][k0 + kk]
+  double (*st)[65] = reinterpret_cast<double (*)[65]>(solve_lds + 16 * FIRA_STAGE_LD * 4 + 16 * 64 * 8);   // [64][65] Y_J - update
+  double* invT = reinterpret_cast<double*>(solve_lds + 16 * FIRA_STAGE_LD * 4 + 16 * 64 * 8 + 64 * 65 * 8);   // [c][k]
   const FiraRefreshEnt e = ents[blockIdx.y];
   const int r = e.r, s0 = blockIdx.x * 64, j0 = J * FIRA_SOLVE_JB;
   if (s0 >= e.S || j0 >= r) return;
@@ -304,67 +350,60 @@ __global__ __launch_bounds__(256) void fira_refresh_solve_kernel(const FiraRefre
   gptr<const double> Lm = as_global<const double>(e.C);
   gptr<float> Q = as_global(e.Q);
   gptr<const double> inv = reinterpret_cast<gptr<const double>>(as_global(e.inst)) + (size_t)J * 64 * 64;
-  const int t = threadIdx.x, tx = t & 15, ty = t >> 4;
+  const int t = threadIdx.x;
   RefreshAcc acc;
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j) acc.v[i][j] = 0.0;
+  refresh_acc_zero(acc);
   const int lr = t >> 2, lk = (t & 3) * 4;      // staging: row (or column of the block) lr, four k from lk
-  for (int k0 = 0; k0 < j0; k0 += 16) {         // j0 is a multiple of 64: whole tiles, all inside the matrix
+  // (j0 is a multiple of 64: whole tiles along k, all inside the matrix.)  The next stage's values are requested
+  // into registers before the current one is multiplied.
+  f32x4 rq;
+  double rl[4];
+  auto fetch = [&](int k0) {
+    rq = refresh_load4(Q, s0 + lr, k0 + lk, e.S, r, r);
+    if (j0 + lr < r) {
+      gptr<const double> pl = Lm + (long long)(j0 + lr) * r + k0 + lk;
+      if ((r & 1) == 0) {
+        typedef double f64x2_t __attribute__((ext_vector_type(2)));
+        const f64x2_t u = *reinterpret_cast<gptr<const f64x2_t>>(pl), w = *reinterpret_cast<gptr<const f64x2_t>>(pl + 2);
+        rl[0] = u.x; rl[1] = u.y; rl[2] = w.x; rl[3] = w.y;
+      } else {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) rl[q] = pl[q];
+      }
+    } else {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) rl[q] = 0.0;
+    }
+  };
+  if (j0 > 0) fetch(0);
+  for (int k0 = 0; k0 < j0; k0 += 16) {
+    const float qv[4] = {rq.x, rq.y, rq.z, rq.w};
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-      sa[lk + q][lr] = (s0 + lr < e.S) ? Q[(long long)(s0 + lr) * r + k0 + lk + q] : 0.0f;
-      sb[lk + q][lr] = (j0 + lr < r) ? Lm[(long long)(j0 + lr) * r + k0 + lk + q] : 0.0;
+      sa[(lk + q) * FIRA_STAGE_LD + lr] = qv[q];
+      sb[(lk + q) * 64 + lr] = rl[q];
     }
     __syncthreads();
-#pragma unroll
-    for (int kk = 0; kk < 16; ++kk) {
-      double a[4], b[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) { a[i] = (double)sa[kk][4 * ty + i]; b[i] = sb[kk][4 * tx + i]; }
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) acc.v[i][j] += a[i] * b[j];
-    }
+    if (k0 + 16 < j0) fetch(k0 + 16);
+    refresh_acc_steps<16>(acc, sa, FIRA_STAGE_LD, 1, sb, 64, 1);   // sum_k Q[row][k] L[j0 + col][k]
     __syncthreads();
   }
   // T = Y_J - update, and the inverse of the diagonal block (transposed: invT[c][k] = inv[k][c])
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int row = 4 * ty + i, col = 4 * tx + j;
-      const double y = (s0 + row < e.S && j0 + col < r) ? (double)Y[(long long)(s0 + row) * r + j0 + col] : 0.0;
-      st[row][col] = y - acc.v[i][j];
-    }
+  refresh_acc_foreach(acc, [&](int row, int col, double v) {
+    const double y = (s0 + row < e.S && j0 + col < r) ? (double)Y[(long long)(s0 + row) * r + j0 + col] : 0.0;
+    st[row][col] = y - v;
+  });
   for (int x = t; x < 64 * 64; x += 256) {
     const int k = x >> 6, c = x & 63;
-    invT[c][k] = inv[x];
+    invT[c * 64 + k] = inv[x];
   }
   __syncthreads();
   // Q_J = T inv^T:  q[row][k] = sum_{c <= k} T[row][c] inv[k][c]
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j) acc.v[i][j] = 0.0;
-  for (int c = 0; c < 64; ++c) {
-    double a[4], b[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) { a[i] = st[4 * ty + i][c]; b[i] = invT[c][4 * tx + i]; }
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-      for (int j = 0; j < 4; ++j) acc.v[i][j] += a[i] * b[j];
-  }
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int row = 4 * ty + i, k = 4 * tx + j;
-      if (s0 + row < e.S && j0 + k < r) Q[(long long)(s0 + row) * r + j0 + k] = (float)acc.v[i][j];
-    }
+  refresh_acc_zero(acc);
+  refresh_acc_steps<64>(acc, &st[0][0], 1, 65, invT, 64, 1);
+  refresh_acc_foreach(acc, [&](int row, int k, double v) {
+    if (s0 + row < e.S && j0 + k < r) Q[(long long)(s0 + row) * r + j0 + k] = (float)v;
+  });
 }
 
 // ------------------------------------------------------------------------------------------------
