@@ -258,6 +258,40 @@ __global__ __launch_bounds__(FIRA_CHOL_THREADS) void fira_refresh_chol_kernel(co
     }
     __syncthreads();   // (HIP's barrier also waits for this wave's global stores)
     // (3) trailing triangle: C[i][k] -= sum_p P[i][p] P[k][p],  jb+nb <= k <= i < r,  P = the panel
+    if (in_lds && below > 0) {
+      // on the matrix pipe: 32 x 32 blocks of the triangle dealt out to the wavefronts, operands from the panel in
+      // LDS (rows past the end are clamped to the last row; what they produce is not stored)
+      const int lane = t & 63, wave = t >> 6, nb32 = (below + 31) / 32;
+      int cnt = 0;
+      for (int bi = 0; bi < nb32; ++bi)
+        for (int bk = 0; bk <= bi; ++bk, ++cnt) {
+          if (cnt % (FIRA_CHOL_THREADS / 64) != wave) continue;
+          const int m0 = min(32 * bi + (lane & 15), below - 1), m1 = min(32 * bi + 16 + (lane & 15), below - 1);
+          const int n0 = min(32 * bk + (lane & 15), below - 1), n1 = min(32 * bk + 16 + (lane & 15), below - 1);
+          RefreshAcc acc;
+          refresh_acc_zero(acc);
+#pragma unroll
+          for (int k4 = 0; k4 < FIRA_CHOL_NB; k4 += 4) {
+            const int k = k4 + (lane >> 4);
+            const bool kin = k < nb;
+            const double a0 = kin ? chol_pan[m0 * PP + k] : 0.0, a1 = kin ? chol_pan[m1 * PP + k] : 0.0;
+            const double b0 = kin ? chol_pan[n0 * PP + k] : 0.0, b1 = kin ? chol_pan[n1 * PP + k] : 0.0;
+            acc.v[0][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b0, acc.v[0][0], 0, 0, 0);
+            acc.v[0][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b1, acc.v[0][1], 0, 0, 0);
+            acc.v[1][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b0, acc.v[1][0], 0, 0, 0);
+            acc.v[1][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b1, acc.v[1][1], 0, 0, 0);
+          }
+#pragma unroll
+          for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+              for (int v = 0; v < 4; ++v) {
+                const int ri = 32 * bi + 16 * i + (lane >> 4) + 4 * v, ck = 32 * bk + 16 * j + (lane & 15);
+                if (ri < below && ck <= ri) C[(long long)(jb + nb + ri) * r + jb + nb + ck] -= acc.v[i][j][v];
+              }
+        }
+    } else {
     const int nt4 = (below + 3) / 4;
     for (int x = t; x < nt4 * nt4; x += FIRA_CHOL_THREADS) {
       const int bi = x / nt4, bk = x % nt4;
@@ -272,13 +306,8 @@ __global__ __launch_bounds__(FIRA_CHOL_THREADS) void fira_refresh_chol_kernel(co
         double a[4], b[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          if (in_lds) {
-            a[i] = (i0 + i < r) ? chol_pan[(4 * bi + i) * PP + p] : 0.0;
-            b[i] = (k0 + i < r) ? chol_pan[(4 * bk + i) * PP + p] : 0.0;
-          } else {
-            a[i] = (i0 + i < r) ? C[(long long)(i0 + i) * r + jb + p] : 0.0;
-            b[i] = (k0 + i < r) ? C[(long long)(k0 + i) * r + jb + p] : 0.0;
-          }
+          a[i] = (i0 + i < r) ? C[(long long)(i0 + i) * r + jb + p] : 0.0;
+          b[i] = (k0 + i < r) ? C[(long long)(k0 + i) * r + jb + p] : 0.0;
         }
 #pragma unroll
         for (int i = 0; i < 4; ++i)
@@ -290,6 +319,7 @@ __global__ __launch_bounds__(FIRA_CHOL_THREADS) void fira_refresh_chol_kernel(co
 #pragma unroll
         for (int k = 0; k < 4; ++k)
           if (i0 + i < r && k0 + k <= i0 + i) C[(long long)(i0 + i) * r + k0 + k] -= acc[i][k];
+    }
     }
     __syncthreads();
   }
