@@ -5,11 +5,19 @@
 //   mfma                : v_mfma_f32_32x32x16_bf16 on register operands, 8 independent accumulator blocks
 //                         per wavefront (the shape of the step's contractions), 1 or 2 wavefronts per SIMD
 //   lds                 : ds_read_b128 fragment reads, all wavefronts of a CU at once
+//   power               : socket power (amdgpu hwmon file) while the copy and the mfma loop run for two seconds each,
+//                         the latter with constant and with pseudo-random operands: what a byte moved and a
+//                         multiply-add cost above the idle chip when nothing else is done
 // Prints one line per measurement.  Everything is in bounds and every loop has a fixed trip count.
 #include <hip/hip_runtime.h>
 
+#include <glob.h>
+#include <unistd.h>
+
+#include <chrono>
 #include <cstdio>
 #include <cstdlib>
+#include <string>
 #include <vector>
 
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
@@ -155,6 +163,85 @@ __global__ __launch_bounds__(256) void lds_kernel(int iters, unsigned* __restric
   if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9e3779b9u) sink[0] = 1u;
 }
 
+// The same loop with operands that change from one multiply to the next: two sets of pseudo-random bf16 fragments
+// (values in [-1, 1)) used in turn, so that the operand inputs of the matrix pipe toggle as they do on real data.
+__global__ __launch_bounds__(256) void mfma_random_kernel(int iters, float* __restrict__ sink) {
+  f32x16_t acc[4][2];
+#pragma unroll
+  for (int a = 0; a < 4; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.0f;
+  bf16x8_t fa[2][4], fb[2][2];
+  unsigned h = (blockIdx.x * 256u + threadIdx.x) * 2654435761u + 12345u;
+  auto next = [&]() { h = h * 1664525u + 1013904223u; return (__bf16)((float)(int)(h >> 8) * (1.0f / 8388608.0f) - 1.0f); };
+#pragma unroll
+  for (int s = 0; s < 2; ++s) {
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) fa[s][a][e] = next();
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) fb[s][b][e] = next();
+  }
+  for (int it = 0; it < iters; it += 2) {
+#pragma unroll
+    for (int s = 0; s < 2; ++s)
+#pragma unroll
+      for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[s][a], fb[s][b], acc[a][b], 0, 0, 0);
+  }
+  float sum = 0.0f;
+#pragma unroll
+  for (int a = 0; a < 4; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b) sum += acc[a][b][0];
+  if (sum == 12345.678f) sink[0] = sum;
+}
+
+// Socket power in watts from the amdgpu hwmon file, or a negative value when it cannot be read.
+static std::string g_power_file;
+static double read_power_w() {
+  if (g_power_file.empty()) {
+    glob_t g;
+    if (glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_input", 0, nullptr, &g) == 0 && g.gl_pathc > 0) g_power_file = g.gl_pathv[0];
+    globfree(&g);
+    if (g_power_file.empty()) return -1.0;
+  }
+  FILE* f = std::fopen(g_power_file.c_str(), "r");
+  if (!f) return -1.0;
+  long long uw = -1;
+  if (std::fscanf(f, "%lld", &uw) != 1) uw = -1;
+  std::fclose(f);
+  return uw < 0 ? -1.0 : uw / 1e6;
+}
+// Runs `launch` in batches for `seconds`, reading the power after every batch; the mean leaves out the first third.
+template <typename F>
+static void power_run(F launch, double seconds, double* watts, double* launches_per_s) {
+  launch();
+  CHECK(hipDeviceSynchronize());
+  std::vector<double> w;
+  const auto t0 = std::chrono::steady_clock::now();
+  long long n = 0;
+  double el = 0.0;
+  while (el < seconds) {
+    for (int i = 0; i < 8; ++i) launch();
+    CHECK(hipDeviceSynchronize());
+    n += 8;
+    w.push_back(read_power_w());
+    el = std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
+  }
+  double sum = 0.0;
+  size_t cnt = 0;
+  for (size_t i = w.size() / 3; i < w.size(); ++i) { sum += w[i]; ++cnt; }
+  *watts = cnt ? sum / cnt : -1.0;
+  *launches_per_s = n / el;
+}
+
 template <typename F>
 static double time_ms(F launch, int reps) {
   hipEvent_t e0, e1;
@@ -242,6 +329,33 @@ int main() {
     const double by = (double)grid.x * 256 * iters * 8 * 16;
     std::printf("lds ds_read_b128, 8 wavefronts per CU: %.1f TB/s (%.0f bytes per clock per CU at %.0f MHz)\n", by / t / 1e9,
                 by / t / 1e3 / cus / (prop.clockRate / 1e3) * 1e3 / 1e3, prop.clockRate / 1e3);
+  }
+  if (read_power_w() > 0.0) {
+    CHECK(hipDeviceSynchronize());
+    std::vector<double> idle;
+    for (int i = 0; i < 20; ++i) { usleep(50000); idle.push_back(read_power_w()); }
+    double idle_w = 0.0;
+    for (size_t i = idle.size() / 3; i < idle.size(); ++i) idle_w += idle[i];
+    idle_w /= (double)(idle.size() - idle.size() / 3);
+    std::printf("power, nothing running (clocks still up): %.0f W\n", idle_w);
+    double w, lps;
+    {
+      const dim3 grid(cus * 4), blk(256);
+      power_run([&] { hipLaunchKernelGGL(stream_kernel<2>, grid, blk, 0, 0, a, b, n16, sink); }, 2.0, &w, &lps);
+      const double bps = 2.0 * bytes * lps;
+      std::printf("power, copy 4 GiB: %.0f W at %.0f GB/s read + written: %.0f pJ per byte above idle\n", w, bps / 1e9, (w - idle_w) / bps * 1e12);
+    }
+    const int iters = 4000;
+    const dim3 grid(cus * 2), blk(256);
+    const double flop = (double)grid.x * 4 * iters * 8 * (2.0 * 32 * 32 * 16);
+    power_run([&] { hipLaunchKernelGGL(mfma_kernel, grid, blk, 0, 0, iters, (float*)sink); }, 2.0, &w, &lps);
+    std::printf("power, mfma 32x32x16 bf16 on constant operands: %.0f W at %.0f TFLOP/s: %.2f pJ per flop above idle\n", w, flop * lps / 1e12,
+                (w - idle_w) / (flop * lps) * 1e12);
+    power_run([&] { hipLaunchKernelGGL(mfma_random_kernel, grid, blk, 0, 0, iters, (float*)sink); }, 2.0, &w, &lps);
+    std::printf("power, mfma 32x32x16 bf16 on pseudo-random operands that change every multiply: %.0f W at %.0f TFLOP/s: %.2f pJ per flop above idle\n",
+                w, flop * lps / 1e12, (w - idle_w) / (flop * lps) * 1e12);
+  } else {
+    std::printf("power: no readable hwmon power file\n");
   }
   CHECK(hipFree(a));
   CHECK(hipFree(b));
