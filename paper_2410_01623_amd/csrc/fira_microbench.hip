@@ -163,6 +163,14 @@ __global__ __launch_bounds__(256) void lds_kernel(int iters, unsigned* __restric
   if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9e3779b9u) sink[0] = 1u;
 }
 
+// Every workgroup reads the same n16 16-byte pieces `rounds` times: after the first touch they come from L2.
+__global__ __launch_bounds__(256) void reread_kernel(const u32x4* __restrict__ src, size_t n16, int rounds, unsigned* __restrict__ sink) {
+  u32x4 acc = u32x4{0u, 0u, 0u, 0u};
+  for (int r = 0; r < rounds; ++r)
+    for (size_t i = threadIdx.x; i < n16; i += 256) acc ^= src[(i + 64 * (size_t)blockIdx.x) % n16];
+  if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9e3779b9u) sink[0] = 1u;
+}
+
 // The same loop with operands that change from one multiply to the next: two sets of pseudo-random bf16 fragments
 // (values in [-1, 1)) used in turn, so that the operand inputs of the matrix pipe toggle as they do on real data.
 __global__ __launch_bounds__(256) void mfma_random_kernel(int iters, float* __restrict__ sink) {
@@ -354,6 +362,22 @@ int main() {
     power_run([&] { hipLaunchKernelGGL(mfma_random_kernel, grid, blk, 0, 0, iters, (float*)sink); }, 2.0, &w, &lps);
     std::printf("power, mfma 32x32x16 bf16 on pseudo-random operands that change every multiply: %.0f W at %.0f TFLOP/s: %.2f pJ per flop above idle\n",
                 w, flop * lps / 1e12, (w - idle_w) / (flop * lps) * 1e12);
+    {
+      const dim3 g2(cus * 2), b2(256);
+      const int it2 = 4000;
+      power_run([&] { hipLaunchKernelGGL(lds_kernel, g2, b2, 0, 0, it2, sink); }, 2.0, &w, &lps);
+      const double bps = (double)g2.x * 256 * it2 * 8 * 16 * lps;
+      std::printf("power, lds ds_read_b128: %.0f W at %.1f TB/s: %.1f pJ per byte above idle\n", w, bps / 1e12, (w - idle_w) / bps * 1e12);
+    }
+    {
+      // reads that hit in L2: every workgroup walks the same 2 MiB again and again (16 MiB per workgroup and launch)
+      const size_t n16_small = ((size_t)2 << 20) / 16;
+      const dim3 g3(cus * 8), b3(256);
+      power_run([&] { hipLaunchKernelGGL(reread_kernel, g3, b3, 0, 0, (const u32x4*)a, n16_small, 8, sink); }, 2.0, &w, &lps);
+      const double bps = (double)g3.x * 8 * ((size_t)2 << 20) * lps;
+      std::printf("power, reads served by L2 (2 MiB re-read by every workgroup): %.0f W at %.1f TB/s: %.1f pJ per byte above idle\n", w, bps / 1e12,
+                  (w - idle_w) / bps * 1e12);
+    }
   } else {
     std::printf("power: no readable hwmon power file\n");
   }
