@@ -873,6 +873,9 @@ fira_status refresh_run(fira_ctx* ctx, int count, const int* idx, const void* co
     re.inst = (float*)(ws + rp.off_linv[e]);
     ents2[e] = re;                       // second orthonormalisation pass of the last round: Q -> Y
     std::swap(ents2[e].Y, ents2[e].Q);
+    // ... which is left out for a matrix whose basis is orthonormal already, to the accuracy its storage can hold
+    ents2[e].done = (int*)(ws + rp.off_done) + e;
+    ents2[e].done_tol = m.kx == 1 ? 1e-4f : 1e-6f;
     max_S = std::max(max_S, m.S); max_r = std::max(max_r, m.r); max_Lp = std::max(max_Lp, re.Lp);
     // The way back, Y[s][a] = sum_i G(s, i) T[i][a], is the projection kernel on the other orientation
     // of the same gradient: long side L' = S, contraction over S' = L, operand "PT" = Top, output "Rt" = Y.
@@ -938,6 +941,7 @@ fira_status refresh_run(fira_ctx* ctx, int count, const int* idx, const void* co
   const int prep_blocks = (int)std::min<long long>(((long long)max_S * max_r + 255) / 256, 4096);
   auto orthonormalise = [&](const FiraRefreshEnt* de) {
     hipLaunchKernelGGL(fira_refresh_gram_kernel, dim3(nt64 * (nt64 + 1) / 2, count), dim3(256), 0, q, de);
+    hipLaunchKernelGGL(fira_refresh_orthocheck_kernel, dim3(count), dim3(256), 0, q, de);   // (second pass only; else it leaves at once)
     {
       const int pan_rows = std::min(FIRA_CHOL_PAN_ROWS, std::max(max_r - FIRA_CHOL_NB, 0));
       hipLaunchKernelGGL(fira_refresh_chol_kernel, dim3(count), dim3(FIRA_CHOL_THREADS), (size_t)pan_rows * (FIRA_CHOL_NB + 1) * 8, q, de, pan_rows);

@@ -163,6 +163,11 @@ struct FiraRefreshEnt {
   double* C;           // [r][r]            Gram matrix, then its Cholesky factor (lower triangle)
   float* inst;         // scratch: inverses of the solve's diagonal blocks ([r/64][64][64] fp64), later the
                        // orthonormality estimate's [S][4] and [FIRA_ORTHO_SPLITS][r][4]
+  int* done;           // second orthonormalisation pass only (else null): set to 1 by the check of its Gram matrix when
+                       // the basis it was given (Y) is orthonormal already; the pass's other kernels then leave, and
+                       // the installation takes Y instead of Q
+  float done_tol;      // ... when max |Y^T Y - I| is at most this
+  int pad1;
 };
 
 

@@ -195,6 +195,7 @@ void build_work_list(const Plan& p, int count, const int* idx, void* const* W, c
 struct RefreshPlan {
   size_t total = 0;
   size_t off_ents = 0, off_ents2 = 0, off_vmats = 0, off_vents = 0, off_vtiles[2] = {0, 0};
+  size_t off_done = 0;                    // one int per listed matrix: the second pass found its input orthonormal
   int ntiles[2] = {0, 0};                 // virtual launches: [0] K-contiguous (real left), [1] K-slow (real right)
   std::vector<size_t> off_top, off_y, off_q, off_c, off_linv;
   std::vector<size_t> off_gb;             // fp32 matrices: bf16 rounding of the gradient, rows of gb_ld elements (else unused)
@@ -213,6 +214,7 @@ bool make_refresh_plan(const Plan& plan, int count, const int* idx, RefreshPlan*
   rp->off_ents2 = take(sizeof(FiraRefreshEnt) * count);
   rp->off_vmats = take(sizeof(FiraMat) * count);
   rp->off_vents = take(sizeof(FiraEnt) * count);
+  rp->off_done = take(sizeof(int) * (size_t)count);
   rp->ntiles[0] = rp->ntiles[1] = 0;
   for (int e = 0; e < count; ++e) {
     if (idx[e] < 0 || idx[e] >= nmat) return false;

@@ -163,6 +163,37 @@ __global__ __launch_bounds__(256) void fira_refresh_gram_kernel(const FiraRefres
   });
 }
 
+// Second pass only: is the basis that the pass was given orthonormal already?  max |C - I| over the lower triangle
+// of its Gram matrix (just computed) against the entry's tolerance; one workgroup per matrix.
+__global__ __launch_bounds__(256) void fira_refresh_orthocheck_kernel(const FiraRefreshEnt* __restrict__ ents) {
+  __shared__ double red[4];
+  const FiraRefreshEnt e = ents[blockIdx.x];
+  if (!e.done) return;
+  gptr<const double> C = as_global<const double>(e.C);
+  const int r = e.r, t = threadIdx.x;
+  double worst = 0.0;
+  for (long long x = t; x < (long long)r * r; x += 256) {
+    const int i = (int)(x / r), k = (int)(x - (long long)i * r);
+    if (k <= i) {
+      const double d = fabs(C[x] - (i == k ? 1.0 : 0.0));
+      worst = (d > worst || d != d) ? d : worst;      // a NaN stays
+    }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const double other = __shfl_xor(worst, o, 64);
+    worst = (other > worst || other != other) ? other : worst;
+  }
+  if ((t & 63) == 0) red[t >> 6] = worst;
+  __syncthreads();
+  if (t == 0) {
+    double w = red[0];
+    for (int i = 1; i < 4; ++i) w = (red[i] > w || red[i] != red[i]) ? red[i] : w;
+    *as_global(e.done) = (w <= (double)e.done_tol) ? 1 : 0;     // false for a NaN
+  }
+}
+__device__ __forceinline__ bool refresh_pass_done(const FiraRefreshEnt& e) { return e.done && *as_global<const int>(e.done) != 0; }
+
 // In-place Cholesky factorisation of the lower triangle of C (fp64), one workgroup per matrix,
 // blocked by 32 columns: factor the diagonal block in LDS, solve the panel below it one row per
 // thread, update the trailing triangle from the panel.  A pivot that is not safely positive (Y
@@ -180,6 +211,7 @@ __global__ __launch_bounds__(FIRA_CHOL_THREADS) void fira_refresh_chol_kernel(co
   extern __shared__ __attribute__((aligned(16))) double chol_pan[];
   constexpr int PP = FIRA_CHOL_NB + 1;
   const FiraRefreshEnt e = ents[blockIdx.x];
+  if (refresh_pass_done(e)) return;
   const int r = e.r, t = threadIdx.x;
   gptr<double> C = as_global(e.C);
   if (t == 0) {
@@ -343,7 +375,7 @@ __global__ __launch_bounds__(64) void fira_refresh_diaginv_kernel(const FiraRefr
   __shared__ double Ld[64][65];
   const FiraRefreshEnt e = ents[blockIdx.y];
   const int r = e.r, j0 = blockIdx.x * FIRA_SOLVE_JB, c = threadIdx.x;
-  if (j0 >= r) return;
+  if (j0 >= r || refresh_pass_done(e)) return;
   gptr<const double> Lm = as_global<const double>(e.C);
   for (int x = c; x < 64 * 64; x += 64) {
     const int i = x >> 6, k = x & 63;
@@ -375,7 +407,7 @@ __global__ __launch_bounds__(256) void fira_refresh_solve_kernel(const FiraRefre
   double* invT = reinterpret_cast<double*>(solve_lds + 16 * FIRA_STAGE_LD * 4 + 16 * 64 * 8 + 64 * 65 * 8);   // [c][k]
   const FiraRefreshEnt e = ents[blockIdx.y];
   const int r = e.r, s0 = blockIdx.x * 64, j0 = J * FIRA_SOLVE_JB;
-  if (s0 >= e.S || j0 >= r) return;
+  if (s0 >= e.S || j0 >= r || refresh_pass_done(e)) return;
   gptr<const float> Y = as_global<const float>(e.Y);
   gptr<const double> Lm = as_global<const double>(e.C);
   gptr<float> Q = as_global(e.Q);
@@ -445,7 +477,7 @@ __global__ __launch_bounds__(256) void fira_refresh_solve_kernel(const FiraRefre
 __global__ __launch_bounds__(256) void fira_refresh_prep_kernel(const FiraMat* __restrict__ mats, const FiraRefreshEnt* __restrict__ ents) {
   const FiraRefreshEnt e = ents[blockIdx.y];
   if (e.q_dtype == 1) prep_projector_body<bf16_raw>(mats[e.mat], reinterpret_cast<const bf16_raw*>(e.Q));
-  else prep_projector_body<float>(mats[e.mat], e.Q);
+  else prep_projector_body<float>(mats[e.mat], refresh_pass_done(e) ? e.Y : e.Q);   // (a second pass that had nothing to do left its input as the result)
 }
 __global__ __launch_bounds__(256) void fira_refresh_ortho_y_kernel(const FiraMat* __restrict__ mats, const FiraRefreshEnt* __restrict__ ents) {
   const FiraRefreshEnt e = ents[blockIdx.y];

@@ -208,6 +208,7 @@ void check_plan(const std::vector<fira_matrix_desc>& descs, std::mt19937_64& rng
     wp.push_back({rp.off_ents2, sizeof(FiraRefreshEnt) * (size_t)rc, "refresh entries 2", -1});
     wp.push_back({rp.off_vmats, sizeof(FiraMat) * (size_t)rc, "virtual matrices", -1});
     wp.push_back({rp.off_vents, sizeof(FiraEnt) * (size_t)rc, "virtual entries", -1});
+    wp.push_back({rp.off_done, sizeof(int) * (size_t)rc, "second-pass flags", -1});
     wp.push_back({rp.off_vtiles[0], sizeof(FiraTile) * (size_t)std::max(rp.ntiles[0], 1), "virtual tiles 0", -1});
     wp.push_back({rp.off_vtiles[1], sizeof(FiraTile) * (size_t)std::max(rp.ntiles[1], 1), "virtual tiles 1", -1});
     for (int e = 0; e < rc; ++e) {

@@ -39,8 +39,11 @@ def test_refreshed_projector_spans_the_leading_singular_subspace(m, n, r):
     torch.cuda.synchronize()
     P = ctx.fira_get_projector(0).numpy().astype(np.float64)
     assert P.shape == (min(m, n), r) and np.all(np.isfinite(P))
-    # orthonormal to the bf16 rounding of its entries
-    assert np.max(np.abs(P.T @ P - np.eye(r))) < 2e-2
+    # orthonormal to the bf16 rounding of its entries (whether or not the second orthonormalisation pass, which
+    # the library leaves out when the first one's result passes its check, had to run)
+    defect = np.max(np.abs(P.T @ P - np.eye(r)))
+    print(f"max |P^T P - I| = {defect:.2e}", flush=True)
+    assert defect < 3e-3
     Pref = orc.top_r_projector(G, r)
     sines = orc.subspace_sines(Pref, P)
     e_ref, e_gpu = orc.captured_energy(G, Pref), orc.captured_energy(G, P)
@@ -98,24 +101,31 @@ def test_refresh_of_a_gradient_without_a_gap_keeps_nearly_the_optimal_energy():
     del ws
 
 
-def test_refresh_survives_a_steep_spectrum():
+@pytest.mark.parametrize("dtype", [fira.FIRA_BF16, fira.FIRA_F32], ids=["bf16", "f32"])
+def test_refresh_survives_a_steep_spectrum(dtype):
     """Singular values falling by eight decades across the short side: Y = G G^T Q then has a
     condition number near 1e4 after one round, whose Gram matrix (1e8) an fp32 Cholesky would not
-    survive; the fp64 CholeskyQR must still return an orthonormal basis that keeps the optimal energy."""
+    survive; the fp64 CholeskyQR must still return an orthonormal basis that keeps the optimal energy.
+    Here the first orthonormalisation pass of the last round leaves a defect far above what an fp32 projector
+    holds, so the second pass has to run (it is left out only when a check of its Gram matrix allows it): the
+    fp32 case asserts the accuracy that only the second pass gives."""
     m, n, r = 256, 700, 64
     rng = np.random.default_rng(9)
     U, _ = np.linalg.qr(rng.standard_normal((m, m)))
     V, _ = np.linalg.qr(rng.standard_normal((n, m)))
     s = 10.0 ** (-8.0 * np.arange(m) / m)
-    G = synth.as_bf16_values((U * s) @ V.T)
-    ctx = fira.FiraContext([(m, n)], r, fira.FIRA_BF16, device=H.DEV)
-    ws = ctx.fira_refresh_projectors([0], [H.to_device(G, fira.FIRA_BF16)], iters=3, seed=1)
+    bf = dtype == fira.FIRA_BF16
+    G = synth.as_bf16_values((U * s) @ V.T) if bf else ((U * s) @ V.T).astype(np.float32)
+    ctx = fira.FiraContext([(m, n)], r, dtype, device=H.DEV)
+    ws = ctx.fira_refresh_projectors([0], [H.to_device(G, dtype)], iters=3, seed=1)
     torch.cuda.synchronize()
     P = ctx.fira_get_projector(0).numpy().astype(np.float64)
     assert np.all(np.isfinite(P))
-    assert np.max(np.abs(P.T @ P - np.eye(r))) < 2e-2
-    e_ref, e_gpu = orc.captured_energy(G, orc.top_r_projector(G, r)), orc.captured_energy(G, P)
-    print(f"energy kept: svd {e_ref:.8f} device {e_gpu:.8f}", flush=True)
+    defect = np.max(np.abs(P.T @ P - np.eye(r)))
+    Gd = G.astype(np.float64)
+    e_ref, e_gpu = orc.captured_energy(Gd, orc.top_r_projector(Gd, r)), orc.captured_energy(Gd, P)
+    print(f"max |P^T P - I| = {defect:.2e}  energy kept: svd {e_ref:.8f} device {e_gpu:.8f}", flush=True)
+    assert defect < (3e-3 if bf else 1e-5)
     assert e_gpu > e_ref - 5e-5      # the bf16 entries of P tilt the basis by ~2e-3 rad
     del ws
 
